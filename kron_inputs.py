@@ -1,0 +1,64 @@
+"""Seeded synthetic inputs for Kron-Matmul, shared by the tests, the benchmark and the smoke run.
+
+This module holds no arithmetic of the method itself: it only draws matrices.  Every tensor is a
+function of (seed, tag) through numpy's counter-based Philox generator, so the CPU oracle and the GPU
+library are fed bit-identical data.
+
+The five named workloads are the ones the build is measured on (shape families of the paper's
+microbenchmarks: M = 1024 with P^N as large as fits, and M = 16 for the small-M / double case;
+section 6.2.2 and Tables 1 and 3), with synthetic values.
+"""
+import numpy as np
+
+CONFIGS = {
+    # name: dtype, M, list of (P, Q), X distribution, F distribution
+    "c1_f32_m16_8x8x3": dict(dtype="float32", M=16, shapes=[(8, 8)] * 3, x="uniform", f="uniform"),
+    "c2_f32_m1024_8x8x6": dict(dtype="float32", M=1024, shapes=[(8, 8)] * 6, x="uniform", f="uniform"),
+    "c3_f32_m1024_32x32x4": dict(dtype="float32", M=1024, shapes=[(32, 32)] * 4, x="uniform", f="uniform"),
+    "c4_f64_m16_128x128x3": dict(dtype="float64", M=16, shapes=[(128, 128)] * 3, x="normal", f="normal"),
+    "c5_f32_m256_16x32x4": dict(dtype="float32", M=256, shapes=[(16, 32)] * 4, x="uniform", f="normal0.25"),
+}
+
+
+def _rng(seed, tag):
+    return np.random.Generator(np.random.Philox(key=[int(seed) & (2**64 - 1), int(tag)]))
+
+
+def draw(shape, dtype, dist, seed, tag):
+    """One matrix.  dist: 'uniform' in [-1,1), 'normal' N(0,1), 'normal0.25' N(0, 0.25^2),
+    'int2' integers in {-2..2}, 'int1' integers in {-1,0,1}."""
+    dtype = np.dtype(dtype)
+    rng = _rng(seed, tag)
+    if dist == "uniform":
+        a = rng.random(shape, dtype=dtype)
+        a *= 2
+        a -= 1
+        return a
+    if dist == "normal":
+        return rng.standard_normal(shape, dtype=dtype)
+    if dist == "normal0.25":
+        a = rng.standard_normal(shape, dtype=dtype)
+        a *= 0.25
+        return a
+    if dist == "int2":
+        return rng.integers(-2, 3, size=shape).astype(dtype)
+    if dist == "int1":
+        return rng.integers(-1, 2, size=shape).astype(dtype)
+    raise ValueError("unknown distribution %r" % (dist,))
+
+
+def make_problem(M, shapes, dtype="float32", x="uniform", f="uniform", seed=1):
+    """X (M x prod P) and the factor list for a list of (P, Q) shapes."""
+    K = 1
+    for p, _ in shapes:
+        K *= p
+    X = draw((M, K), dtype, x, seed, 0)
+    Fs = [draw(s, dtype, f, seed, 1 + i) for i, s in enumerate(shapes)]
+    return X, Fs
+
+
+def make_config(name, seed=1, x=None, f=None, M=None):
+    """A named workload; x / f / M override the distribution or the row count."""
+    c = CONFIGS[name]
+    return make_problem(c["M"] if M is None else M, c["shapes"], c["dtype"],
+                        x or c["x"], f or c["f"], seed)
