@@ -1,0 +1,158 @@
+#!/usr/bin/env python3
+"""Benchmark of the Kron-Matmul hot path on one MI355X.
+
+A step is one whole Kron-Matmul Y = X (F_1 (x) ... (x) F_N) through the C-ABI library (all planned
+launches) on a synthetic workload that already sits in HBM.  Prints ONE JSON line:
+whole-job GFLOP/s (flops = 2*M*sum_f K_f*Q_f, one multiply-add = 2), the roofline of the dominant
+kernel from HIP-event durations taken inside the timed region, and the CPU oracle timed on the host.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
+PEAKS_TFLOPS = {"float32": 157.3, "float64": 78.6}   # dense MFMA / vector peaks, published
+
+# Paper's own figure for the same shape on one V100 (Table 1: 5.76 ms for M=1024, 8^6, fp32), turned
+# into GFLOP/s with the same flop count.  Other hardware: context only.
+PAPER_GFLOPS = {"c2_f32_m1024_8x8x6": 25769803776 / 5.76e-3 / 1e9,
+                "c3_f32_m1024_32x32x4": 274877906944 / 38.8e-3 / 1e9}
+
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# (summaries under profiles/); None until measured.
+MEASURED_TRAFFIC = {}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c2_f32_m1024_8x8x6")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--seed", type=int, default=1)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.exit("bench.py: this build measures one GPU only (rows shard across GPUs without "
+                 "communication; see DESIGN.md); run with --gpus 1")
+
+    import numpy as np
+    import torch
+    import kron_inputs
+    import paper_2401_10187_amd as km
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    km.lib()
+    cfg = kron_inputs.CONFIGS[args.workload]
+    X, Fs = kron_inputs.make_config(args.workload, seed=args.seed)
+    M = X.shape[0]
+    P = [F.shape[0] for F in Fs]
+    Q = [F.shape[1] for F in Fs]
+    dev = torch.device("cuda:0")
+    Xd = torch.from_numpy(X).to(dev)
+    Fd = [torch.from_numpy(F).to(dev) for F in Fs]
+    Yd = torch.empty((M, int(np.prod(Q, dtype=np.int64))), dtype=Xd.dtype, device=dev)
+    ws_bytes = km.workspace_size(M, P, Q, cfg["dtype"])
+    ws = torch.empty(max(ws_bytes, 1), dtype=torch.uint8, device=dev)
+    steps = km.plan(M, P, Q, cfg["dtype"])
+    flops, planned_bytes = km.cost(M, P, Q, cfg["dtype"])
+    es = Xd.element_size()
+
+    stream = torch.cuda.current_stream(dev)
+    for _ in range(args.warmup):
+        km.kronmatmul(Xd, Fd, Y=Yd, workspace=ws)
+    torch.cuda.synchronize()
+    km.set_option(km.KM_OPT_PROFILE, 1)     # HIP events around every launch, on the launch stream
+    t0 = torch.cuda.Event(enable_timing=True)
+    t1 = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    wall0 = time.perf_counter()
+    t0.record(stream)
+    for _ in range(args.steps):
+        km.kronmatmul(Xd, Fd, Y=Yd, workspace=ws)
+    t1.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - wall0
+    ms_total = t0.elapsed_time(t1)
+    per_launch_ms, ncalls = km.mean_profile()
+    km.set_option(km.KM_OPT_PROFILE, 0)
+    ms_per_step = ms_total / args.steps
+    gflops = flops / (ms_per_step * 1e-3) / 1e9
+
+    # dominant kernel = the launch kind with the largest share of the step
+    launches = []
+    for st, ms in zip(steps, per_launch_ms):
+        nb = es * M * (st["k_in"] + st["k_out"])
+        f0, nf = st["first_factor"], st["num_factors"]
+        nb += es * sum(P[i] * Q[i] for i in range(f0, f0 + nf))
+        k, fl = st["k_in"], 0
+        for i in range(f0 + nf - 1, f0 - 1, -1):
+            fl += 2 * M * k * Q[i]
+            k = k // P[i] * Q[i]
+        key = (st["kernel"], st["variant"], st["k_in"], st["k_out"])
+        launches.append(dict(key=key, ms=ms, bytes=nb, flops=fl,
+                             name="%s[%dx(%dx%d)]" % (km.kernel_name(st["kernel"]), nf, P[f0], Q[f0])))
+    groups = {}
+    for l in launches:
+        g = groups.setdefault(l["key"], dict(ms=0.0, n=0, bytes=l["bytes"], flops=l["flops"], name=l["name"]))
+        g["ms"] += l["ms"]
+        g["n"] += 1
+    dom = max(groups.values(), key=lambda g: g["ms"])
+    dom_ms = dom["ms"] / dom["n"]
+    gbs = dom["bytes"] / (dom_ms * 1e-3) / 1e9
+    tfl = dom["flops"] / (dom_ms * 1e-3) / 1e12
+    peak_tf = PEAKS_TFLOPS[cfg["dtype"]]
+    if gbs / HBM_PEAK_GBS >= tfl / peak_tf:
+        roofline = dict(bound="hbm", achieved=round(gbs, 1), peak=HBM_PEAK_GBS, unit="GB/s",
+                        frac=round(gbs / HBM_PEAK_GBS, 4))
+    else:
+        roofline = dict(bound="mfma", achieved=round(tfl, 2), peak=peak_tf, unit="TFLOP/s",
+                        frac=round(tfl / peak_tf, 4))
+    roofline.update(traffic=MEASURED_TRAFFIC.get(args.workload), kernel=dom["name"],
+                    kernel_ms=round(dom_ms, 4), launches_per_step=dom["n"],
+                    algorithmic_bytes_per_launch=dom["bytes"], flops_per_launch=dom["flops"],
+                    alt_frac_hbm=round(gbs / HBM_PEAK_GBS, 4), alt_frac_flops=round(tfl / peak_tf, 4))
+
+    out = {
+        "metric": "kron_matmul_gflops", "value": round(gflops, 1), "unit": "GFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": (round(gflops / PAPER_GFLOPS[args.workload], 2)
+                        if args.workload in PAPER_GFLOPS else None),
+        "dtype": "f32" if cfg["dtype"] == "float32" else "f64", "data": "synthetic",
+        "config": {"workload": args.workload, "M": M, "factors": "%dx(%dx%d)" % (len(P), P[0], Q[0]),
+                   "launches": [l["name"] for l in launches],
+                   "per_launch_ms": [round(l["ms"], 4) for l in launches],
+                   "planned_bytes": planned_bytes, "flops": flops,
+                   "end_to_end_gbs": round(planned_bytes / (ms_per_step * 1e-3) / 1e9, 1),
+                   "wall_ms_per_step": round(wall * 1e3 / args.steps, 4),
+                   "paper_baseline": "one V100, Table 1" if args.workload in PAPER_GFLOPS else None},
+        "roofline": roofline,
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        # bounded sample: enough rows of the same workload for roughly 10-30 s of CPU work
+        macs_per_row = flops / 2 / M
+        rows = int(max(1, min(M, 1.2e10 // macs_per_row)))
+        c0 = time.perf_counter()
+        ref = oracle.kron_matmul(X[:rows], Fs)
+        cpu_s = time.perf_counter() - c0
+        got = Yd[:rows].cpu().numpy()
+        err = float(np.abs(got.astype(np.float64) - ref.astype(np.float64)).max() / np.abs(ref).max())
+        out["cpu_baseline"] = {"value": round(flops * rows / M / cpu_s / 1e9, 2), "unit": "GFLOP/s",
+                               "cores": oracle.threads(), "kind": "oracle",
+                               "sample": "%d of %d rows of the same X, %.2f s wall" % (rows, M, cpu_s),
+                               "max_rel_err_gpu_vs_oracle": err}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

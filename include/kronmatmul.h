@@ -1,0 +1,134 @@
+/*
+ * kronmatmul -- Kronecker matrix-matrix multiplication on AMD MI355X (gfx950).
+ *
+ *     Y = X * (F[0] (x) F[1] (x) ... (x) F[N-1])
+ *
+ * X is M x prod(P[i]), F[i] is P[i] x Q[i], Y is M x prod(Q[i]) (the "Kron-Matmul" of the paper's
+ * section 2).  The product is evaluated by the paper's sliced-multiply iteration (section 3,
+ * Algorithm 1): factors are applied from the last to the first; applying a P x Q factor to a row of
+ * width K contracts each of the K/P contiguous length-P slices with each factor column and stores
+ * the value for (slice s, column q) at column q*(K/P)+s, which is already the layout the next
+ * iteration reads.  Runs of consecutive factors are fused into one kernel whose intermediates stay
+ * in LDS (section 4.2).
+ *
+ * Conventions for every entry point
+ *   - All matrices are dense, row-major, without padding.
+ *   - P, Q and the array F itself are HOST memory; X, Y, the workspace and every F[i] are DEVICE
+ *     memory on the current HIP device.  F[0] is the leftmost factor (slowest index digit).
+ *   - The caller owns every buffer.  X and the factors are only read.  Y may be used as scratch
+ *     for intermediates before it receives the result.  X, Y and the workspace must not overlap.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is enqueued
+ *     on it; no entry point synchronises with the device unless stated.
+ *   - Errors are returned, never thrown; nothing calls exit().  M == 0 is a successful no-op.
+ *   - Entry points are thread-safe with respect to each other; concurrent calls that share the
+ *     library-managed workspace (kronmatmul) on different streams are serialised by the caller.
+ */
+#ifndef KRONMATMUL_H
+#define KRONMATMUL_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { KM_F32 = 0, KM_F64 = 1 } km_dtype;
+
+typedef enum {
+    KM_OK = 0,
+    KM_EINVAL = 1,       /* bad shape, null pointer, unknown dtype/option, size overflow          */
+    KM_ENOMEM = 2,       /* workspace too small, or the library could not allocate its own        */
+    KM_ELAUNCH = 3,      /* HIP reported an error on launch / event / query                        */
+    KM_EUNSUPPORTED = 4  /* no kernel can run this shape on this device                            */
+} km_status;
+
+/* Kernel families a plan step can use. */
+typedef enum {
+    KM_KERNEL_GENERIC = 0,  /* one factor, any P and Q: LDS-tiled FMA kernel                       */
+    KM_KERNEL_FUSED = 1,    /* 1..3 consecutive small factors, tile resident in LDS (section 4.2)  */
+    KM_KERNEL_MFMA = 2      /* one factor with P and Q multiples of 16: slice contraction on MFMA  */
+} km_kernel;
+
+/* Buffers a plan step reads or writes. */
+typedef enum { KM_BUF_X = 0, KM_BUF_Y = 1, KM_BUF_WS0 = 2, KM_BUF_WS1 = 3 } km_buffer;
+
+/* One kernel launch of a plan.  Factors first_factor .. first_factor+num_factors-1 (indices into
+ * F, applied last to first) map rows of width k_in to rows of width k_out. */
+typedef struct {
+    int kernel;            /* km_kernel                                                            */
+    int first_factor;      /* lowest factor index in this step                                     */
+    int num_factors;       /* factors fused in this launch (N_fused of section 4.2)                */
+    int tile_slices;       /* contiguous output run per tile and fused column (T_K / prod P)       */
+    long long k_in;        /* row width read                                                       */
+    long long k_out;       /* row width written                                                    */
+    int src;               /* km_buffer read                                                       */
+    int dst;               /* km_buffer written                                                    */
+    long long grid;        /* workgroups launched                                                  */
+    int block;             /* threads per workgroup                                                */
+    int lds_bytes;         /* LDS per workgroup                                                    */
+    int variant;           /* index of the compiled kernel instance, for reports                   */
+} km_plan_step;
+
+/* Bytes of device workspace kronmatmul_ws needs for this problem (0 when one launch suffices).
+ * Follows Algorithm 1's two swapped intermediates, except that Y stands in for one of them when it
+ * is wide enough and X is read in place.  Pure host computation. */
+km_status kronmatmul_workspace_size(int M, int N, const int* P, const int* Q, km_dtype dtype,
+                                    size_t* bytes);
+
+/* Y = X * (F[0] (x) ... (x) F[N-1]) with a workspace the library allocates on first use and keeps
+ * (one per device, grown on demand with hipMalloc, which may synchronise the device; freed by
+ * kronmatmul_release). */
+km_status kronmatmul(int M, int N, const int* P, const int* Q,
+                     const void* X, const void* const* F, void* Y,
+                     km_dtype dtype, void* stream);
+
+/* Same, with a caller-provided device workspace of at least kronmatmul_workspace_size bytes
+ * (may be NULL when that size is 0).  Never allocates.  KM_ENOMEM if workspace_bytes is too small. */
+km_status kronmatmul_ws(int M, int N, const int* P, const int* Q,
+                        const void* X, const void* const* F, void* Y,
+                        km_dtype dtype, void* workspace, size_t workspace_bytes, void* stream);
+
+/* The launches kronmatmul would issue for this problem, in order.  Writes at most `cap` steps and
+ * the total count to *nsteps.  Pure host computation (no device needed). */
+km_status kronmatmul_plan(int M, int N, const int* P, const int* Q, km_dtype dtype,
+                          km_plan_step* steps, int cap, int* nsteps);
+
+/* Output column, within a row of the intermediate, of element `local_col` of a tile after a fused
+ * group of factors with prod(P) = p_group was applied to a row of width k_in cut into contiguous
+ * tiles of tile_k elements (section 4.2, the store of Figure 7; with one factor it is the store of
+ * Figure 3).  local_col counts the tile's final contents in (fused column, slice) order.  Returns -1
+ * on invalid arguments.  Pure host computation, exported so the index map can be tested. */
+long long kronmatmul_store_column(long long k_in, long long p_group, long long tile_k,
+                                  long long tile_index, long long local_col);
+
+/* Floating-point operations (2 per multiply-add, summed over the N iterations of Algorithm 1) and
+ * the bytes the planned launches must move (rows read + rows written per launch, plus factors). */
+km_status kronmatmul_cost(int M, int N, const int* P, const int* Q, km_dtype dtype,
+                          double* flops, double* planned_bytes);
+
+/* Options.  KM_OPT_KERNELS: bit mask of km_kernel families the planner may use (bit k = family k;
+ * the generic family is always allowed).  KM_OPT_MAX_FUSE: upper limit on factors per launch.
+ * KM_OPT_PROFILE: when 1, every launch is bracketed by HIP events on the caller's stream. */
+typedef enum { KM_OPT_KERNELS = 0, KM_OPT_MAX_FUSE = 1, KM_OPT_PROFILE = 2 } km_option;
+km_status kronmatmul_set_option(km_option option, int value);
+km_status kronmatmul_get_option(km_option option, int* value);
+
+/* Per-launch durations (milliseconds) of the most recent profiled call on the current device, in
+ * plan order.  Synchronises with the events of that call.  KM_EINVAL if nothing was profiled. */
+km_status kronmatmul_last_profile(float* ms, int cap, int* nsteps);
+
+/* Per-launch durations averaged over every call made on the current device since KM_OPT_PROFILE was
+ * last switched from 0 to 1 (at most 4096 calls are kept; later ones run unprofiled).  All those
+ * calls must have had the same number of launches, else KM_EINVAL.  *ncalls receives their count. */
+km_status kronmatmul_mean_profile(float* ms, int cap, int* nsteps, int* ncalls);
+
+/* Frees the library-managed workspaces and profiling events (synchronises the device). */
+km_status kronmatmul_release(void);
+
+const char* kronmatmul_status_string(km_status status);
+const char* kronmatmul_kernel_name(int kernel);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KRONMATMUL_H */

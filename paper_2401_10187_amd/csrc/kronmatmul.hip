@@ -1,0 +1,368 @@
+// C-ABI of the Kron-Matmul library (see include/kronmatmul.h) and the launch loop of Algorithm 1:
+// one launch per plan step, buffers swapped between launches, everything on the caller's stream.
+#include <hip/hip_runtime.h>
+#include <mutex>
+#include <vector>
+#include <string.h>
+
+#include "../../include/kronmatmul.h"
+#include "plan.hpp"
+#include "generic_kernel.hpp"
+
+namespace km {
+
+// ---------------------------------------------------------------------------------------------
+// compiled kernel instances
+// ---------------------------------------------------------------------------------------------
+struct LaunchArgs {
+    const void* src;
+    void* dst;
+    const void* const* factors;   // host array of device pointers, all N of the problem
+    const Problem* pr;
+    const km_plan_step* st;
+    hipStream_t stream;
+};
+typedef hipError_t (*LaunchFn)(const LaunchArgs&);
+
+static const Variant g_variants[] = {
+    {KM_KERNEL_GENERIC, -1, 0, 0, 1, GEN_TS, GEN_THREADS, 0, 1, "placeholder"},
+};
+static const LaunchFn g_launchers[] = { nullptr };
+static const int g_num_variants = 0;
+
+template <typename T>
+static hipError_t launch_generic(const LaunchArgs& a)
+{
+    const km_plan_step& st = *a.st;
+    const int f = st.first_factor;
+    const int P = a.pr->P[f], Q = a.pr->Q[f];
+    const int64_t S = st.k_in / P;
+    const int64_t tiles = (S + GEN_TS - 1) / GEN_TS;
+    hipLaunchKernelGGL((sliced_multiply_generic<T>), dim3((unsigned)st.grid), dim3(GEN_THREADS), 0, a.stream,
+                       (const T*)a.src, (const T*)a.factors[f], (T*)a.dst, st.k_in, P, Q, tiles);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// library state
+// ---------------------------------------------------------------------------------------------
+struct DeviceState {
+    void* ws = nullptr;
+    size_t ws_bytes = 0;
+    // Profiling history since KM_OPT_PROFILE was last switched on: call c with n launches owns
+    // events [first[c], first[c] + n].  Events are pooled and reused after the history is cleared.
+    std::vector<hipEvent_t> events;
+    std::vector<int> call_first, call_steps;
+    int events_used = 0;
+};
+constexpr int MAX_PROFILED_CALLS = 4096;
+
+static std::mutex g_mutex;
+static Options g_options;
+static int g_profile = 0;
+static DeviceState g_dev[64];
+
+static int generic_lds(int dtype)
+{
+    const int e = dtype == KM_F32 ? 4 : 8;
+    return e * (GEN_TS * (GEN_TP + 1) + GEN_TP * GEN_TQ);
+}
+
+static km_status plan_for(const Problem& pr, Plan& plan)
+{
+    Options opt;
+    {
+        std::lock_guard<std::mutex> lock(g_mutex);
+        opt = g_options;
+    }
+    km_status s = make_plan(pr, opt, g_variants, g_num_variants, GEN_THREADS, GEN_TS, generic_lds(pr.dtype), plan);
+    if (s != KM_OK) return s;
+    for (const km_plan_step& st : plan.steps)
+        if (st.grid <= 0 || st.grid > 0x7fffffffLL) return KM_EUNSUPPORTED;
+    return KM_OK;
+}
+
+static km_status run(const Problem& pr, const Plan& plan, const void* X, const void* const* F, void* Y,
+                     void* ws, hipStream_t stream)
+{
+    char* ws0 = (char*)ws;
+    char* ws1 = ws0 + plan.ws0_bytes;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return KM_ELAUNCH;
+    DeviceState& ds = g_dev[dev];
+    const int n = (int)plan.steps.size();
+    int profile;
+    int ev0 = 0;
+    {
+        std::lock_guard<std::mutex> lock(g_mutex);
+        profile = g_profile && (int)ds.call_first.size() < MAX_PROFILED_CALLS;
+        if (profile) {
+            ev0 = ds.events_used;
+            while ((int)ds.events.size() < ev0 + n + 1) {
+                hipEvent_t e;
+                if (hipEventCreate(&e) != hipSuccess) return KM_ELAUNCH;
+                ds.events.push_back(e);
+            }
+            ds.events_used = ev0 + n + 1;
+        }
+    }
+    if (profile && hipEventRecord(ds.events[ev0], stream) != hipSuccess) return KM_ELAUNCH;
+    for (int i = 0; i < n; ++i) {
+        const km_plan_step& st = plan.steps[i];
+        auto buf = [&](int b) -> void* {
+            switch (b) {
+                case KM_BUF_X: return (void*)X;
+                case KM_BUF_Y: return Y;
+                case KM_BUF_WS0: return ws0;
+                default: return ws1;
+            }
+        };
+        LaunchArgs a{buf(st.src), buf(st.dst), F, &pr, &st, stream};
+        hipError_t e;
+        if (st.kernel == KM_KERNEL_GENERIC)
+            e = pr.dtype == KM_F32 ? launch_generic<float>(a) : launch_generic<double>(a);
+        else
+            e = g_launchers[st.variant](a);
+        if (e != hipSuccess) return KM_ELAUNCH;
+        if (profile && hipEventRecord(ds.events[ev0 + i + 1], stream) != hipSuccess) return KM_ELAUNCH;
+    }
+    if (profile) {
+        std::lock_guard<std::mutex> lock(g_mutex);
+        ds.call_first.push_back(ev0);
+        ds.call_steps.push_back(n);
+    }
+    return KM_OK;
+}
+
+static km_status check_pointers(const Problem& pr, const void* X, const void* const* F, void* Y)
+{
+    if (!F) return KM_EINVAL;
+    if (pr.M == 0) return KM_OK;
+    if (!X || !Y) return KM_EINVAL;
+    for (int i = 0; i < pr.N; ++i)
+        if (!F[i]) return KM_EINVAL;
+    return KM_OK;
+}
+
+}  // namespace km
+
+using namespace km;
+
+extern "C" {
+
+km_status kronmatmul_workspace_size(int M, int N, const int* P, const int* Q, km_dtype dtype, size_t* bytes)
+{
+    if (!bytes) return KM_EINVAL;
+    Problem pr;
+    km_status s = make_problem(M, N, P, Q, (int)dtype, pr);
+    if (s != KM_OK) return s;
+    *bytes = 0;
+    if (pr.M == 0) return KM_OK;
+    Plan plan;
+    s = plan_for(pr, plan);
+    if (s != KM_OK) return s;
+    *bytes = plan.ws0_bytes + plan.ws1_bytes;
+    return KM_OK;
+}
+
+km_status kronmatmul_ws(int M, int N, const int* P, const int* Q, const void* X, const void* const* F,
+                        void* Y, km_dtype dtype, void* workspace, size_t workspace_bytes, void* stream)
+{
+    Problem pr;
+    km_status s = make_problem(M, N, P, Q, (int)dtype, pr);
+    if (s != KM_OK) return s;
+    s = check_pointers(pr, X, F, Y);
+    if (s != KM_OK) return s;
+    if (pr.M == 0) return KM_OK;
+    Plan plan;
+    s = plan_for(pr, plan);
+    if (s != KM_OK) return s;
+    const size_t need = plan.ws0_bytes + plan.ws1_bytes;
+    if (need > 0 && (!workspace || workspace_bytes < need)) return KM_ENOMEM;
+    return run(pr, plan, X, F, Y, workspace, (hipStream_t)stream);
+}
+
+km_status kronmatmul(int M, int N, const int* P, const int* Q, const void* X, const void* const* F,
+                     void* Y, km_dtype dtype, void* stream)
+{
+    Problem pr;
+    km_status s = make_problem(M, N, P, Q, (int)dtype, pr);
+    if (s != KM_OK) return s;
+    s = check_pointers(pr, X, F, Y);
+    if (s != KM_OK) return s;
+    if (pr.M == 0) return KM_OK;
+    Plan plan;
+    s = plan_for(pr, plan);
+    if (s != KM_OK) return s;
+    const size_t need = plan.ws0_bytes + plan.ws1_bytes;
+    void* ws = nullptr;
+    if (need > 0) {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return KM_ELAUNCH;
+        std::lock_guard<std::mutex> lock(g_mutex);
+        DeviceState& ds = g_dev[dev];
+        if (ds.ws_bytes < need) {
+            if (ds.ws) {
+                // work already enqueued may still read the old buffer
+                if (hipDeviceSynchronize() != hipSuccess) return KM_ELAUNCH;
+                (void)hipFree(ds.ws);
+                ds.ws = nullptr; ds.ws_bytes = 0;
+            }
+            if (hipMalloc(&ds.ws, need) != hipSuccess) { (void)hipGetLastError(); ds.ws = nullptr; return KM_ENOMEM; }
+            ds.ws_bytes = need;
+        }
+        ws = ds.ws;
+    }
+    return run(pr, plan, X, F, Y, ws, (hipStream_t)stream);
+}
+
+km_status kronmatmul_plan(int M, int N, const int* P, const int* Q, km_dtype dtype,
+                          km_plan_step* steps, int cap, int* nsteps)
+{
+    if (!nsteps || cap < 0 || (cap > 0 && !steps)) return KM_EINVAL;
+    Problem pr;
+    km_status s = make_problem(M, N, P, Q, (int)dtype, pr);
+    if (s != KM_OK) return s;
+    Plan plan;
+    s = plan_for(pr, plan);
+    if (s != KM_OK) return s;
+    *nsteps = (int)plan.steps.size();
+    for (int i = 0; i < *nsteps && i < cap; ++i) steps[i] = plan.steps[i];
+    return KM_OK;
+}
+
+long long kronmatmul_store_column(long long k_in, long long p_group, long long tile_k,
+                                  long long tile_index, long long local_col)
+{
+    if (tile_k > 0 && p_group > 0 && local_col >= tile_k) {
+        // a tile never holds more than (tile_k / p_group) * q_group elements; the caller's q_group is
+        // not known here, so only reject what is impossible for every q_group: negative handled below
+    }
+    return store_column(k_in, p_group, tile_k, tile_index, local_col);
+}
+
+km_status kronmatmul_cost(int M, int N, const int* P, const int* Q, km_dtype dtype,
+                          double* flops, double* planned_bytes)
+{
+    Problem pr;
+    km_status s = make_problem(M, N, P, Q, (int)dtype, pr);
+    if (s != KM_OK) return s;
+    Plan plan;
+    s = plan_for(pr, plan);
+    if (s != KM_OK) return s;
+    if (flops) *flops = plan.flops;
+    if (planned_bytes) *planned_bytes = plan.bytes;
+    return KM_OK;
+}
+
+km_status kronmatmul_set_option(km_option option, int value)
+{
+    std::lock_guard<std::mutex> lock(g_mutex);
+    switch (option) {
+        case KM_OPT_KERNELS:
+            if (value < 0 || value > 7) return KM_EINVAL;
+            g_options.kernels = value | 1;
+            return KM_OK;
+        case KM_OPT_MAX_FUSE:
+            if (value < 1 || value > 8) return KM_EINVAL;
+            g_options.max_fuse = value;
+            return KM_OK;
+        case KM_OPT_PROFILE:
+            if (value != 0 && value != 1) return KM_EINVAL;
+            if (value == 1 && g_profile == 0)      // a fresh history on every device
+                for (DeviceState& ds : g_dev) { ds.call_first.clear(); ds.call_steps.clear(); ds.events_used = 0; }
+            g_profile = value;
+            return KM_OK;
+    }
+    return KM_EINVAL;
+}
+
+km_status kronmatmul_get_option(km_option option, int* value)
+{
+    if (!value) return KM_EINVAL;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    switch (option) {
+        case KM_OPT_KERNELS: *value = g_options.kernels; return KM_OK;
+        case KM_OPT_MAX_FUSE: *value = g_options.max_fuse; return KM_OK;
+        case KM_OPT_PROFILE: *value = g_profile; return KM_OK;
+    }
+    return KM_EINVAL;
+}
+
+static km_status profile_query(bool mean, float* ms, int cap, int* nsteps, int* ncalls)
+{
+    if (!nsteps || cap < 0 || (cap > 0 && !ms)) return KM_EINVAL;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return KM_ELAUNCH;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    DeviceState& ds = g_dev[dev];
+    const int calls = (int)ds.call_first.size();
+    if (calls == 0) return KM_EINVAL;
+    const int n = ds.call_steps[calls - 1];
+    const int c0 = mean ? 0 : calls - 1;
+    for (int c = c0; c < calls; ++c)
+        if (ds.call_steps[c] != n) return KM_EINVAL;     // a mean needs calls of one plan
+    if (hipEventSynchronize(ds.events[ds.call_first[calls - 1] + n]) != hipSuccess) return KM_ELAUNCH;
+    *nsteps = n;
+    if (ncalls) *ncalls = calls - c0;
+    for (int i = 0; i < n && i < cap; ++i) {
+        double sum = 0;
+        for (int c = c0; c < calls; ++c) {
+            float t = 0;
+            const int e = ds.call_first[c] + i;
+            if (hipEventElapsedTime(&t, ds.events[e], ds.events[e + 1]) != hipSuccess) return KM_ELAUNCH;
+            sum += t;
+        }
+        ms[i] = (float)(sum / (calls - c0));
+    }
+    return KM_OK;
+}
+
+km_status kronmatmul_last_profile(float* ms, int cap, int* nsteps)
+{
+    return profile_query(false, ms, cap, nsteps, nullptr);
+}
+
+km_status kronmatmul_mean_profile(float* ms, int cap, int* nsteps, int* ncalls)
+{
+    return profile_query(true, ms, cap, nsteps, ncalls);
+}
+
+km_status kronmatmul_release(void)
+{
+    std::lock_guard<std::mutex> lock(g_mutex);
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return KM_ELAUNCH;
+    DeviceState& ds = g_dev[dev];
+    if (hipDeviceSynchronize() != hipSuccess) return KM_ELAUNCH;
+    if (ds.ws) (void)hipFree(ds.ws);
+    ds.ws = nullptr; ds.ws_bytes = 0;
+    for (hipEvent_t e : ds.events) (void)hipEventDestroy(e);
+    ds.events.clear();
+    ds.call_first.clear(); ds.call_steps.clear(); ds.events_used = 0;
+    return KM_OK;
+}
+
+const char* kronmatmul_status_string(km_status status)
+{
+    switch (status) {
+        case KM_OK: return "ok";
+        case KM_EINVAL: return "invalid argument";
+        case KM_ENOMEM: return "workspace too small or allocation failed";
+        case KM_ELAUNCH: return "HIP launch or runtime error";
+        case KM_EUNSUPPORTED: return "shape not supported";
+    }
+    return "unknown status";
+}
+
+const char* kronmatmul_kernel_name(int kernel)
+{
+    switch (kernel) {
+        case KM_KERNEL_GENERIC: return "generic";
+        case KM_KERNEL_FUSED: return "fused";
+        case KM_KERNEL_MFMA: return "mfma";
+    }
+    return "unknown";
+}
+
+}  // extern "C"

@@ -1,0 +1,185 @@
+// Host-side planner: turns a problem (M, factor shapes, dtype) into the list of kernel launches
+// that evaluates Algorithm 1, last factor first, and assigns the buffers the launches read and
+// write (the two swapped intermediates of Algorithm 1; Y stands in for one of them when it is wide
+// enough, and the first launch reads X in place).  Pure host code, no HIP calls.
+#pragma once
+#include <stdint.h>
+#include <stddef.h>
+#include <vector>
+#include "../../include/kronmatmul.h"
+
+namespace km {
+
+// One compiled kernel instance the planner can choose.
+struct Variant {
+    int kernel;        // km_kernel family
+    int dtype;         // km_dtype
+    int P, Q;          // factor shape it is compiled for (0 = any)
+    int num_factors;   // factors per launch
+    int tile_slices;   // S_t: run of consecutive output columns a tile produces per fused column
+    int threads;       // workgroup size
+    int lds_bytes;     // LDS per workgroup
+    int rows_per_tile; // rows of X a workgroup handles together
+    const char* name;
+};
+
+struct Problem {
+    int64_t M = 0;
+    int N = 0;
+    std::vector<int> P, Q;
+    int dtype = 0;
+    int64_t k_in = 1, k_out = 1;   // prod P, prod Q
+    size_t esize = 4;
+};
+
+struct Plan {
+    std::vector<km_plan_step> steps;
+    size_t ws0_bytes = 0, ws1_bytes = 0;   // the two intermediates (ws1 unused when Y can serve)
+    double flops = 0, bytes = 0;
+};
+
+struct Options {
+    int kernels = 0x7;    // bit mask of km_kernel families
+    int max_fuse = 3;
+};
+
+inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Validates the shapes and fills the derived sizes.  Products must stay below 2^62 elements.
+inline km_status make_problem(int M, int N, const int* P, const int* Q, int dtype, Problem& pr)
+{
+    if (M < 0 || N < 1 || N > 64 || !P || !Q) return KM_EINVAL;
+    if (dtype != KM_F32 && dtype != KM_F64) return KM_EINVAL;
+    pr.M = M; pr.N = N; pr.dtype = dtype; pr.esize = dtype == KM_F32 ? 4 : 8;
+    pr.P.assign(P, P + N); pr.Q.assign(Q, Q + N);
+    const int64_t lim = (int64_t)1 << 40;   // elements per row; M * width * esize must fit in int64
+    int64_t kin = 1, kout = 1;
+    for (int i = 0; i < N; ++i) {
+        if (P[i] < 1 || Q[i] < 1) return KM_EINVAL;
+        if (kin > lim / P[i] || kout > lim / Q[i]) return KM_EINVAL;
+        kin *= P[i]; kout *= Q[i];
+    }
+    // every intermediate width Q_N..Q_f * P_1..P_{f-1}
+    int64_t w = kin;
+    for (int f = N - 1; f >= 0; --f) {
+        w = w / P[f];
+        if (w > lim / Q[f]) return KM_EINVAL;
+        w *= Q[f];
+        if (M > 0 && w > ((int64_t)1 << 59) / M) return KM_EINVAL;
+    }
+    if (M > 0 && kin > ((int64_t)1 << 59) / M) return KM_EINVAL;
+    pr.k_in = kin; pr.k_out = kout;
+    return KM_OK;
+}
+
+// Output column of local element c of tile `tile_index` after a fused group (section 4.2): the
+// tile's final contents are ordered (fused column qq, slice r) with r < S_t = tile_k / p_group, and
+// the row of the intermediate holds, for each qq, all K_in / p_group slices contiguously.
+inline int64_t store_column(int64_t k_in, int64_t p_group, int64_t tile_k, int64_t tile_index,
+                            int64_t local_col)
+{
+    if (k_in <= 0 || p_group <= 0 || tile_k <= 0 || k_in % p_group || tile_k % p_group ||
+        k_in % tile_k || tile_index < 0 || tile_index >= k_in / tile_k || local_col < 0)
+        return -1;
+    const int64_t s_tile = tile_k / p_group;      // slices of the fused group inside the tile
+    const int64_t s_row = k_in / p_group;         // ... inside the whole row
+    const int64_t qq = local_col / s_tile;
+    const int64_t r = local_col % s_tile;
+    return qq * s_row + tile_index * s_tile + r;
+}
+
+// Picks the variant for factors [f - nf + 1, f] or nullptr.
+inline const Variant* find_variant(const Variant* table, int count, const Problem& pr, int f, int nf,
+                                   int64_t k_cur, const Options& opt)
+{
+    const Variant* best = nullptr;
+    int64_t pg = 1;
+    for (int i = f - nf + 1; i <= f; ++i) {
+        if (pr.P[i] != pr.P[f] || pr.Q[i] != pr.Q[f]) return nullptr;   // equal shapes within a group
+        pg *= pr.P[i];
+    }
+    if (k_cur % pg) return nullptr;
+    const int64_t s_row = k_cur / pg;
+    for (int v = 0; v < count; ++v) {
+        const Variant& c = table[v];
+        if (!(opt.kernels >> c.kernel & 1)) continue;
+        if (c.dtype != pr.dtype || c.num_factors != nf) continue;
+        if (c.P != pr.P[f] || c.Q != pr.Q[f]) continue;
+        if (s_row % c.tile_slices) continue;
+        if (pr.M % c.rows_per_tile) continue;
+        if (!best || c.tile_slices > best->tile_slices) best = &c;   // table order breaks ties
+    }
+    return best;
+}
+
+inline km_status make_plan(const Problem& pr, const Options& opt, const Variant* table, int count,
+                           int generic_threads, int generic_tile_slices, int generic_lds, Plan& plan)
+{
+    plan = Plan();
+    int64_t k_cur = pr.k_in;
+    int f = pr.N - 1;
+    while (f >= 0) {
+        km_plan_step st = {};
+        const Variant* var = nullptr;
+        int nf = 1;
+        for (int tryn = opt.max_fuse < f + 1 ? opt.max_fuse : f + 1; tryn >= 1 && !var; --tryn) {
+            var = find_variant(table, count, pr, f, tryn, k_cur, opt);
+            if (var) nf = tryn;
+        }
+        int64_t pg = 1, qg = 1;
+        for (int i = f - nf + 1; i <= f; ++i) { pg *= pr.P[i]; qg *= pr.Q[i]; }
+        st.first_factor = f - nf + 1;
+        st.num_factors = nf;
+        st.k_in = k_cur;
+        st.k_out = k_cur / pg * qg;
+        if (var) {
+            st.kernel = var->kernel;
+            st.variant = (int)(var - table);
+            st.tile_slices = var->tile_slices;
+            st.block = var->threads;
+            st.lds_bytes = var->lds_bytes;
+            st.grid = (pr.M / var->rows_per_tile) * (k_cur / pg / var->tile_slices);
+        } else {
+            st.kernel = KM_KERNEL_GENERIC;
+            st.variant = -1;
+            st.tile_slices = generic_tile_slices;
+            st.block = generic_threads;
+            st.lds_bytes = generic_lds;
+            const int64_t S = k_cur / pr.P[f];
+            st.grid = pr.M * ((S + generic_tile_slices - 1) / generic_tile_slices);
+        }
+        // flops of the iterations this launch covers
+        int64_t w = k_cur;
+        for (int i = f; i >= f - nf + 1; --i) {
+            plan.flops += 2.0 * (double)pr.M * (double)w * pr.Q[i];
+            w = w / pr.P[i] * pr.Q[i];
+            plan.bytes += (double)pr.P[i] * pr.Q[i] * pr.esize;
+        }
+        plan.bytes += (double)pr.M * ((double)st.k_in + (double)st.k_out) * pr.esize;
+        plan.steps.push_back(st);
+        k_cur = st.k_out;
+        f -= nf;
+    }
+    // Buffers, assigned backwards from Y: the last launch writes Y, the one before it writes WS0,
+    // the one before that writes "B", and so on alternately.  B is Y itself when every row written
+    // there fits in a row of Y, otherwise the second workspace.
+    const int n = (int)plan.steps.size();
+    bool b_is_y = true;
+    for (int i = n - 3; i >= 0; i -= 2)
+        if (plan.steps[i].k_out > pr.k_out) b_is_y = false;
+    int64_t w0 = 0, w1 = 0;
+    for (int i = n - 1; i >= 0; --i) {
+        const int back = n - 1 - i;
+        int dst = back == 0 ? KM_BUF_Y : (back % 2 == 1 ? KM_BUF_WS0 : (b_is_y ? KM_BUF_Y : KM_BUF_WS1));
+        plan.steps[i].dst = dst;
+        if (dst == KM_BUF_WS0 && plan.steps[i].k_out > w0) w0 = plan.steps[i].k_out;
+        if (dst == KM_BUF_WS1 && plan.steps[i].k_out > w1) w1 = plan.steps[i].k_out;
+        if (i + 1 < n) plan.steps[i + 1].src = dst;
+    }
+    plan.steps[0].src = KM_BUF_X;
+    plan.ws0_bytes = round_up((size_t)(pr.M * w0) * pr.esize, 256);
+    plan.ws1_bytes = round_up((size_t)(pr.M * w1) * pr.esize, 256);
+    return KM_OK;
+}
+
+}  // namespace km

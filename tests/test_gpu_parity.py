@@ -1,0 +1,256 @@
+"""GPU parity: the HIP library (through its C-ABI) against the CPU oracle on the same seeded inputs.
+
+Bars (written out here): bit-exact when inputs are small integers (every partial sum is exactly
+representable); otherwise max|Y_gpu - Y_ref| / max|Y_ref| <= 1e-5 for fp32 and 1e-12 for fp64, with
+Y_ref from the wide-accumulator oracle.  A second, per-element bound is also checked:
+|Y_gpu - Y_ref| <= 2 u (sum_i P_i + N) * (|X| (x)|F_i|), the standard forward error of the chained dot
+products, evaluated by running the oracle on absolute values.
+"""
+import numpy as np
+import pytest
+
+import kron_inputs
+import oracle
+
+torch = pytest.importorskip("torch")
+import paper_2401_10187_amd as km  # noqa: E402
+
+pytestmark = pytest.mark.gpu
+
+REL_TOL = {np.dtype("float32"): 1e-5, np.dtype("float64"): 1e-12}
+UNIT = {np.dtype("float32"): 2.0 ** -24, np.dtype("float64"): 2.0 ** -53}
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _device():
+    if not torch.cuda.is_available():
+        pytest.fail("gpu-marked tests need a GPU (torch.cuda.is_available() is False)")
+    km.lib()   # fails loudly if the HIP library has not been built
+    yield
+    km.release()
+
+
+class options:
+    """Temporarily restrict the planner (kernel families bit mask, fusion depth)."""
+
+    def __init__(self, kernels=None, max_fuse=None):
+        self.new = {km.KM_OPT_KERNELS: kernels, km.KM_OPT_MAX_FUSE: max_fuse}
+
+    def __enter__(self):
+        self.old = {k: km.get_option(k) for k in self.new}
+        for k, v in self.new.items():
+            if v is not None:
+                km.set_option(k, v)
+
+    def __exit__(self, *exc):
+        for k, v in self.old.items():
+            km.set_option(k, v)
+
+
+def run_gpu(X, Fs, use_ws=False):
+    Xd = torch.from_numpy(X).cuda()
+    Fd = [torch.from_numpy(F).cuda() for F in Fs]
+    ws = None
+    if use_ws:
+        nbytes = km.workspace_size(X.shape[0], [F.shape[0] for F in Fs], [F.shape[1] for F in Fs], X.dtype)
+        ws = torch.empty(max(nbytes, 1), dtype=torch.uint8, device="cuda")
+    Y = km.kronmatmul(Xd, Fd, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(Xd.cpu(), torch.from_numpy(X)), "X was modified"
+    return Y.cpu().numpy()
+
+
+def assert_close(got, X, Fs, exact=False):
+    ref = oracle.kron_matmul(X, Fs)
+    assert got.shape == ref.shape and got.dtype == ref.dtype
+    if exact:
+        assert np.array_equal(got, ref)
+        return
+    scale = float(np.abs(ref).max())
+    err = float(np.abs(got.astype(np.float64) - ref.astype(np.float64)).max())
+    assert err <= REL_TOL[ref.dtype] * scale, (err, scale)
+    bound = oracle.kron_matmul(np.abs(X), [np.abs(F) for F in Fs]).astype(np.float64)
+    n_terms = sum(F.shape[0] for F in Fs) + len(Fs)
+    slack = 2 * UNIT[ref.dtype] * n_terms * bound + np.finfo(np.float64).tiny
+    assert np.all(np.abs(got.astype(np.float64) - ref.astype(np.float64)) <= slack)
+
+
+# shapes that span several tiles, ragged tails and the degenerate cases
+SMALL_CASES = [
+    ("float32", 16, [(8, 8)] * 3),                       # config 1
+    ("float32", 5, [(8, 8)] * 4),
+    ("float32", 3, [(8, 8)] * 2),
+    ("float32", 2, [(8, 8)]),
+    ("float32", 3, [(4, 4)] * 5),
+    ("float32", 7, [(3, 5), (4, 2), (6, 6), (2, 3)]),    # distinct rectangular factors
+    ("float64", 4, [(5, 2), (5, 2), (5, 2)]),
+    ("float32", 2, [(1, 3), (7, 1), (2, 2)]),            # P = 1 and Q = 1
+    ("float32", 1, [(130, 70)]),                         # N = 1, ragged everything
+    ("float64", 3, [(33, 17), (2, 65)]),
+    ("float32", 9, [(16, 32)] * 3),                      # growing intermediates
+    ("float32", 4, [(32, 16)] * 3),                      # shrinking intermediates
+    ("float32", 6, [(32, 32)] * 3),
+    ("float32", 2, [(16, 16)] * 4),
+    ("float64", 2, [(128, 128)] * 2),
+    ("float64", 3, [(16, 16)] * 3),
+    ("float32", 2, [(64, 64)] * 2),
+    ("float64", 1, [(8, 8)] * 5),
+    ("float32", 1, [(2, 2)] * 11),                       # many tiny factors, M = 1
+    ("float32", 5, [(8, 8), (8, 8), (8, 8), (32, 32), (32, 32)]),
+]
+
+
+@pytest.mark.parametrize("dtype,M,shapes", SMALL_CASES, ids=lambda v: str(v).replace(" ", ""))
+@pytest.mark.parametrize("mode", ["auto", "unfused", "generic"])
+def test_small_float(dtype, M, shapes, mode):
+    kw = {"auto": {}, "unfused": {"max_fuse": 1}, "generic": {"kernels": 0}}[mode]
+    X, Fs = kron_inputs.make_problem(M, shapes, dtype, "uniform", "normal", seed=len(shapes) * 100 + M)
+    with options(**kw):
+        got = run_gpu(X, Fs, use_ws=(mode == "unfused"))
+    assert_close(got, X, Fs)
+
+
+@pytest.mark.parametrize("dtype,M,shapes", SMALL_CASES, ids=lambda v: str(v).replace(" ", ""))
+def test_small_integer_bit_exact(dtype, M, shapes):
+    width = int(np.prod([max(p, 1) for p, _ in shapes], dtype=np.int64))
+    fdist = "int2" if 2 * 2 ** len(shapes) * width < 2 ** 24 else "int1"
+    if 2 * width >= 2 ** 24 and dtype == "float32":
+        pytest.skip("sums not exactly representable in fp32")
+    X, Fs = kron_inputs.make_problem(M, shapes, dtype, "int2", fdist, seed=7)
+    assert_close(run_gpu(X, Fs), X, Fs, exact=True)
+
+
+def test_config1_integer_and_float():
+    """fp32, M=16, three 8x8 factors: the float variant and the {-2..2} bit-exact variant."""
+    X, Fs = kron_inputs.make_config("c1_f32_m16_8x8x3", seed=1)
+    assert_close(run_gpu(X, Fs), X, Fs)
+    X, Fs = kron_inputs.make_config("c1_f32_m16_8x8x3", seed=1, x="int2", f="int2")
+    assert_close(run_gpu(X, Fs), X, Fs, exact=True)
+    assert np.array_equal(run_gpu(X, Fs), oracle.kron_bruteforce(X, Fs))
+
+
+def test_identity_factors_return_x_bit_exact():
+    X = kron_inputs.draw((6, 8 * 8 * 8 * 8), "float32", "uniform", 3, 0)
+    Fs = [np.eye(8, dtype=np.float32)] * 4
+    assert np.array_equal(run_gpu(X, Fs), X)
+
+
+def test_empty_rows_and_library_workspace_reuse():
+    Fs = [np.ones((8, 8), np.float32)] * 3
+    Y = km.kronmatmul(torch.empty((0, 512), device="cuda"), [torch.from_numpy(F).cuda() for F in Fs])
+    assert tuple(Y.shape) == (0, 512)
+    # a small problem after a larger one reuses the cached workspace; a larger one regrows it
+    for M in (2, 64, 3):
+        X, Fs = kron_inputs.make_problem(M, [(8, 8)] * 4, "float32", seed=M)
+        assert_close(run_gpu(X, Fs), X, Fs)
+
+
+def test_profiled_call_reports_each_launch():
+    X, Fs = kron_inputs.make_problem(8, [(8, 8)] * 4, "float32", seed=5)
+    steps = km.plan(8, [8] * 4, [8] * 4, "float32")
+    km.set_option(km.KM_OPT_PROFILE, 1)
+    try:
+        got = run_gpu(X, Fs)
+        ms = km.last_profile()
+    finally:
+        km.set_option(km.KM_OPT_PROFILE, 0)
+    assert len(ms) == len(steps) and all(t > 0 for t in ms)
+    assert_close(got, X, Fs)
+
+
+def test_caller_stream_is_used():
+    X, Fs = kron_inputs.make_problem(32, [(8, 8)] * 4, "float32", seed=9)
+    Xd = torch.from_numpy(X).cuda()
+    Fd = [torch.from_numpy(F).cuda() for F in Fs]
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        Y = km.kronmatmul(Xd, Fd)
+    side.synchronize()
+    ref = oracle.kron_matmul(X, Fs)
+    assert np.abs(Y.cpu().numpy() - ref).max() <= 1e-5 * np.abs(ref).max()
+
+
+# ------------------------------------------------------------------ full-size workloads
+# Checked on sampled rows (rows are independent, so the oracle computes exactly those rows) plus
+# properties that hold at any size.
+
+FULL = ["c2_f32_m1024_8x8x6", "c3_f32_m1024_32x32x4", "c4_f64_m16_128x128x3", "c5_f32_m256_16x32x4"]
+
+
+def _sample_rows(M):
+    rng = np.random.default_rng(M)
+    rows = {0, 1, M // 2, M - 2, M - 1} | set(int(r) for r in rng.integers(0, M, 3))
+    return sorted(rows)
+
+
+@pytest.mark.parametrize("name", FULL)
+def test_full_size_sampled_rows(name):
+    X, Fs = kron_inputs.make_config(name, seed=2)
+    Xd = torch.from_numpy(X).cuda()
+    Fd = [torch.from_numpy(F).cuda() for F in Fs]
+    Y = km.kronmatmul(Xd, Fd)
+    torch.cuda.synchronize()
+    rows = _sample_rows(X.shape[0])
+    got = Y[rows].cpu().numpy()
+    assert_close(got, X[rows], Fs)
+    # second call into the same Y gives the same bits (no dependence on stale contents)
+    Y2 = km.kronmatmul(Xd, Fd, Y=torch.full_like(Y, float("nan")))
+    torch.cuda.synchronize()
+    assert torch.equal(Y, Y2)
+    del Y, Y2, Xd
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("name", FULL)
+def test_full_size_integer_rows_bit_exact(name):
+    X, Fs = kron_inputs.make_config(name, seed=4, x="int2", f="int1")
+    Xd = torch.from_numpy(X).cuda()
+    Y = km.kronmatmul(Xd, [torch.from_numpy(F).cuda() for F in Fs])
+    torch.cuda.synchronize()
+    rows = _sample_rows(X.shape[0])
+    assert_close(Y[rows].cpu().numpy(), X[rows], Fs, exact=True)
+    del Y, Xd
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("name", FULL)
+def test_full_size_all_ones_factors_give_row_sums(name):
+    """All-ones factors: every output of a row is that row's sum (exact for small-integer X)."""
+    c = kron_inputs.CONFIGS[name]
+    X, _ = kron_inputs.make_config(name, seed=6, x="int1")
+    Fs = [np.ones(s, dtype=c["dtype"]) for s in c["shapes"]]
+    Xd = torch.from_numpy(X).cuda()
+    Y = km.kronmatmul(Xd, [torch.from_numpy(F).cuda() for F in Fs])
+    torch.cuda.synchronize()
+    sums = torch.from_numpy(X.sum(axis=1, dtype=np.float64).astype(c["dtype"])).cuda()
+    assert bool((Y == sums[:, None]).all())
+    del Y, Xd
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("name", ["c2_f32_m1024_8x8x6", "c3_f32_m1024_32x32x4", "c4_f64_m16_128x128x3"])
+def test_full_size_permutation_factors_move_columns_bit_exact(name):
+    """Permutation-matrix factors: Y is a known column permutation of X, bit for bit, for float X."""
+    c = kron_inputs.CONFIGS[name]
+    X, _ = kron_inputs.make_config(name, seed=8)
+    rng = np.random.default_rng(8)
+    sig, Fs = [], []
+    for p, q in c["shapes"]:
+        s = rng.permutation(p)
+        F = np.zeros((p, q), dtype=c["dtype"])
+        F[np.arange(p), s] = 1
+        sig.append(s)
+        Fs.append(F)
+    Xd = torch.from_numpy(X).cuda()
+    Y = km.kronmatmul(Xd, [torch.from_numpy(F).cuda() for F in Fs])
+    torch.cuda.synchronize()
+    # destination column of every source column: digits (p1..pN) -> (sigma1(p1)..sigmaN(pN))
+    dest = np.zeros(1, dtype=np.int64)
+    for s, (p, _) in zip(sig, c["shapes"]):
+        dest = (dest[:, None] * p + s[None, :]).reshape(-1)
+    want = torch.empty_like(Xd)
+    want[:, torch.from_numpy(dest).cuda()] = Xd
+    assert torch.equal(Y, want)
+    del Y, Xd, want
+    torch.cuda.empty_cache()

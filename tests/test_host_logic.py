@@ -1,0 +1,197 @@
+"""Host-side logic of the HIP library: exported symbols, planner, index maps, argument checks.
+Nothing here launches a kernel, so it runs without a GPU."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2401_10187_amd as km
+from conftest import ROOT, read_golden
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "kronmatmul.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(kronmatmul\w*)\s*\(", header))
+    assert declared == set(km.EXPORTS)
+    L = km.lib()
+    for name in declared:
+        assert getattr(L, name) is not None
+
+
+def test_status_and_kernel_names():
+    assert km.status_string(km.KM_OK) == "ok"
+    assert "invalid" in km.status_string(km.KM_EINVAL)
+    assert km.kernel_name(km.KM_KERNEL_GENERIC) == "generic"
+    assert km.kernel_name(km.KM_KERNEL_FUSED) == "fused"
+    assert km.kernel_name(km.KM_KERNEL_MFMA) == "mfma"
+
+
+def test_store_column_matches_fused_store_example():
+    g = read_golden("fused_store_example.txt")
+    k, p, tk, nf = int(g["k"][0]), int(g["p"][0]), int(g["tile_k"][0]), int(g["n_fused"][0])
+    assert k // p == g["slices_row"][0] and tk // p == g["slices_tile"][0]
+    assert k // p ** nf == g["fused_slices_row"][0] and tk // p ** nf == g["fused_slices_tile"][0]
+    assert km.store_column(k, p ** nf, tk, int(g["block"][0]), int(g["element"][0])) == g["column"][0]
+
+
+def test_store_column_matches_single_factor_example():
+    g = read_golden("fig4_store_index.txt")
+    k, p, tk = int(g["k"][0]), int(g["p"][0]), int(g["tile_k"][0])
+    s = tk // p
+    assert km.store_column(k, p, tk, 0, 0 * s) == g["column0_start"][0]
+    assert km.store_column(k, p, tk, 0, 1 * s) == g["column1_start"][0]
+    # run lengths inside a fused tile: consecutive local elements stay consecutive for exactly T_K/P^i
+    tk, p = int(g["fig6_tile_k"][0]), int(g["fig6_p"][0])
+    for i, key in ((1, "fig6_run_after_1"), (2, "fig6_run_after_2")):
+        cols = [km.store_column(256, p ** i, tk, 1, c) for c in range(tk)]
+        runs = np.split(np.array(cols), np.where(np.diff(cols) != 1)[0] + 1)
+        assert {len(r) for r in runs} == {int(g[key][0])}
+        assert len(runs) == p ** i
+
+
+def test_store_column_is_the_composition_of_single_steps():
+    """A fused group's store equals applying the single-factor output map once per factor to the
+    whole row (a6: local tile index -> global column)."""
+    K, P, nf, tile_k = 4 ** 4, 4, 3, 4 ** 3 * 2
+    cols = np.arange(K)
+    # follow every input column's *slice group* through nf single steps with square factors: after one
+    # step the element made from slice s and column q sits at q*(K/P)+s.
+    # Enumerate outputs: output digit string (q1..qnf, a) <-> a*P^nf + (p-digits) block of inputs.
+    s_t = tile_k // P ** nf
+    for tile in range(K // tile_k):
+        for c in range(tile_k):
+            qq, r = divmod(c, s_t)
+            a = tile * s_t + r
+            assert km.store_column(K, P ** nf, tile_k, tile, c) == qq * (K // P ** nf) + a
+    assert km.store_column(K, P ** nf, tile_k, K // tile_k, 0) == -1
+    assert km.store_column(K, 3, tile_k, 0, 0) == -1
+
+
+@pytest.mark.parametrize("M,shapes,dtype", [
+    (16, [(8, 8)] * 3, "float32"),
+    (1024, [(8, 8)] * 6, "float32"),
+    (1024, [(32, 32)] * 4, "float32"),
+    (16, [(128, 128)] * 3, "float64"),
+    (256, [(16, 32)] * 4, "float32"),
+    (7, [(3, 5), (4, 2), (6, 6), (2, 3)], "float64"),
+    (3, [(5, 2), (5, 2), (5, 2)], "float32"),
+])
+def test_plan_is_consistent(M, shapes, dtype):
+    P = [s[0] for s in shapes]
+    Q = [s[1] for s in shapes]
+    steps = km.plan(M, P, Q, dtype)
+    es = 4 if dtype == "float32" else 8
+    # factors are consumed last to first, each exactly once
+    f = len(shapes)
+    k = int(np.prod(P, dtype=np.int64))
+    widths = {km.KM_BUF_WS0: 0, km.KM_BUF_WS1: 0}
+    for i, st in enumerate(steps):
+        assert st["first_factor"] + st["num_factors"] == f
+        f = st["first_factor"]
+        assert st["k_in"] == k
+        for j in range(st["num_factors"]):
+            k = k // P[f + st["num_factors"] - 1 - j] * Q[f + st["num_factors"] - 1 - j]
+        assert st["k_out"] == k
+        assert st["src"] == (km.KM_BUF_X if i == 0 else steps[i - 1]["dst"])
+        assert st["dst"] != st["src"] and st["dst"] != km.KM_BUF_X
+        if st["dst"] == km.KM_BUF_Y:
+            assert st["k_out"] <= int(np.prod(Q, dtype=np.int64))
+        else:
+            widths[st["dst"]] = max(widths[st["dst"]], st["k_out"])
+        assert st["grid"] > 0 and st["block"] > 0
+        assert st["lds_bytes"] <= 160 * 1024
+    assert f == 0
+    assert steps[-1]["dst"] == km.KM_BUF_Y
+    need = sum((M * w * es + 255) // 256 * 256 for w in widths.values())
+    assert km.workspace_size(M, P, Q, dtype) == need
+    # flops: 2 * M * sum_f K_f * Q_f (section 3, counted as multiply-add = 2)
+    flops, nbytes = km.cost(M, P, Q, dtype)
+    kk, want = int(np.prod(P, dtype=np.int64)), 0
+    for p, q in reversed(shapes):
+        want += 2 * M * kk * q
+        kk = kk // p * q
+    assert flops == want
+    assert nbytes >= es * M * (steps[0]["k_in"] + steps[-1]["k_out"])
+
+
+def test_workspace_follows_algorithm_1_buffers():
+    """Two swapped intermediates of M x max-width (Algorithm 1, line 3) are an upper bound."""
+    M, P, Q = 5, [4, 2, 3, 2], [2, 6, 3, 5]
+    ws = km.workspace_size(M, P, Q, "float64")
+    k, widest = int(np.prod(P)), 0
+    for p, q in reversed(list(zip(P, Q))):
+        k = k // p * q
+        widest = max(widest, k)
+    assert ws <= 2 * ((M * widest * 8 + 255) // 256 * 256)
+    assert km.workspace_size(M, [4], [7], "float32") == 0
+
+
+def test_options_round_trip():
+    old = km.get_option(km.KM_OPT_MAX_FUSE)
+    try:
+        km.set_option(km.KM_OPT_MAX_FUSE, 1)
+        assert km.get_option(km.KM_OPT_MAX_FUSE) == 1
+        assert all(st["num_factors"] == 1 for st in km.plan(16, [8] * 3, [8] * 3, "float32"))
+        with pytest.raises(km.KronMatmulError):
+            km.set_option(km.KM_OPT_MAX_FUSE, 0)
+        with pytest.raises(km.KronMatmulError):
+            km.set_option(99, 0)
+    finally:
+        km.set_option(km.KM_OPT_MAX_FUSE, old)
+    old = km.get_option(km.KM_OPT_KERNELS)
+    try:
+        km.set_option(km.KM_OPT_KERNELS, 0)
+        assert km.get_option(km.KM_OPT_KERNELS) & 1
+        assert all(st["kernel"] == km.KM_KERNEL_GENERIC for st in km.plan(1024, [8] * 6, [8] * 6, "float32"))
+    finally:
+        km.set_option(km.KM_OPT_KERNELS, old)
+
+
+def _raw(M, P, Q, X, F, Y, dtype=0, with_ws=False):
+    L = km.lib()
+    n = len(P)
+    p = (ctypes.c_int * max(n, 1))(*P)
+    q = (ctypes.c_int * max(n, 1))(*Q)
+    f = None if F is None else ctypes.cast((ctypes.c_void_p * max(n, 1))(*F), ctypes.c_void_p)
+    if with_ws:
+        return L.kronmatmul_ws(M, n, p, q, X, f, Y, dtype, None, 0, None)
+    return L.kronmatmul(M, n, p, q, X, f, Y, dtype, None)
+
+
+def test_argument_errors_are_status_codes():
+    """Validation happens before any HIP call, so these never touch a device."""
+    bad = 0x1000   # never dereferenced: the calls below must fail before any launch
+    assert _raw(-1, [2], [2], bad, [bad], bad) == km.KM_EINVAL
+    assert _raw(4, [], [], bad, [], bad) == km.KM_EINVAL
+    assert _raw(4, [0], [2], bad, [bad], bad) == km.KM_EINVAL
+    assert _raw(4, [2], [-3], bad, [bad], bad) == km.KM_EINVAL
+    assert _raw(4, [2], [2], None, [bad], bad) == km.KM_EINVAL
+    assert _raw(4, [2], [2], bad, [bad], None) == km.KM_EINVAL
+    assert _raw(4, [2], [2], bad, [None], bad) == km.KM_EINVAL
+    assert _raw(4, [2], [2], bad, None, bad) == km.KM_EINVAL
+    assert _raw(4, [2], [2], bad, [bad], bad, dtype=7) == km.KM_EINVAL
+    assert _raw(4, [2 ** 20] * 3, [2] * 3, bad, [bad] * 3, bad) == km.KM_EINVAL      # width overflow
+    assert _raw(2 ** 31 - 1, [2 ** 15] * 2, [2 ** 15] * 2, bad, [bad] * 2, bad) == km.KM_EINVAL
+    # M == 0 is a successful no-op, with or without buffers
+    assert _raw(0, [2, 3], [2, 3], None, [bad, bad], None) == km.KM_OK
+    assert _raw(0, [2, 3], [2, 3], None, [bad, bad], None, with_ws=True) == km.KM_OK
+    # a workspace that is too small is refused before any launch
+    assert _raw(4, [2, 2], [2, 2], bad, [bad, bad], bad, with_ws=True) == km.KM_ENOMEM
+
+
+def test_workspace_size_errors():
+    L = km.lib()
+    p = (ctypes.c_int * 1)(2)
+    assert L.kronmatmul_workspace_size(1, 1, p, p, 0, None) == km.KM_EINVAL
+    out = ctypes.c_size_t(123)
+    assert L.kronmatmul_workspace_size(1, 0, p, p, 0, ctypes.byref(out)) == km.KM_EINVAL
+    assert L.kronmatmul_workspace_size(0, 1, p, p, 1, ctypes.byref(out)) == km.KM_OK and out.value == 0
+
+
+def test_last_profile_without_a_call_is_an_error_or_needs_device():
+    L = km.lib()
+    cnt = ctypes.c_int(0)
+    assert L.kronmatmul_last_profile(None, 0, None) == km.KM_EINVAL
