@@ -8,6 +8,7 @@
 #include "../../include/kronmatmul.h"
 #include "plan.hpp"
 #include "generic_kernel.hpp"
+#include "fused_kernel.hpp"
 
 namespace km {
 
@@ -24,11 +25,48 @@ struct LaunchArgs {
 };
 typedef hipError_t (*LaunchFn)(const LaunchArgs&);
 
-static const Variant g_variants[] = {
-    {KM_KERNEL_GENERIC, -1, 0, 0, 1, GEN_TS, GEN_THREADS, 0, 1, "placeholder"},
-};
-static const LaunchFn g_launchers[] = { nullptr };
-static const int g_num_variants = 0;
+template <typename T, int P, int Q, int NF, int ST, int NT>
+static hipError_t launch_fused(const LaunchArgs& a)
+{
+    typedef FusedShape<T, P, Q, NF, ST, NT> Sh;
+    const km_plan_step& st = *a.st;
+    auto kern = fused_sliced_multiply<T, P, Q, NF, ST, NT>;
+    if (Sh::LDS_BYTES > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, Sh::LDS_BYTES);
+        if (e != hipSuccess) return e;
+    }
+    const T* f[3] = {nullptr, nullptr, nullptr};
+    for (int j = 0; j < NF; ++j) f[j] = (const T*)a.factors[st.first_factor + NF - 1 - j];   // order of application
+    const int64_t tiles_per_row = st.k_in / Sh::TK;
+    hipLaunchKernelGGL(kern, dim3((unsigned)st.grid), dim3(NT), Sh::LDS_BYTES, a.stream,
+                       (const T*)a.src, (T*)a.dst, f[0], f[1], f[2], st.k_in, st.k_out, tiles_per_row,
+                       (int64_t)st.grid);
+    return hipGetLastError();
+}
+
+// (type, dtype code, P, Q, factors per launch, tile_slices, threads)
+#define KM_FUSED_INSTANCES(X)                 \
+    X(float, KM_F32, 8, 8, 3, 32, 256)        \
+    X(float, KM_F32, 8, 8, 3, 16, 256)        \
+    X(float, KM_F32, 8, 8, 3, 16, 128)        \
+    X(float, KM_F32, 8, 8, 3, 8, 128)         \
+    X(float, KM_F32, 8, 8, 3, 1, 64)          \
+    X(float, KM_F32, 8, 8, 2, 256, 256)       \
+    X(float, KM_F32, 8, 8, 2, 64, 256)        \
+    X(float, KM_F32, 8, 8, 2, 8, 64)          \
+    X(float, KM_F32, 8, 8, 2, 1, 64)          \
+    X(float, KM_F32, 8, 8, 1, 2048, 256)      \
+    X(float, KM_F32, 8, 8, 1, 64, 64)         \
+    X(float, KM_F32, 8, 8, 1, 8, 64)          \
+    X(float, KM_F32, 8, 8, 1, 1, 64)
+
+#define KM_VARIANT_ROW(T, DT, P, Q, NF, ST, NT) \
+    {KM_KERNEL_FUSED, DT, P, Q, NF, ST, NT, FusedShape<T, P, Q, NF, ST, NT>::LDS_BYTES, 1, "fused"},
+#define KM_LAUNCHER_ROW(T, DT, P, Q, NF, ST, NT) launch_fused<T, P, Q, NF, ST, NT>,
+
+static const Variant g_variants[] = { KM_FUSED_INSTANCES(KM_VARIANT_ROW) };
+static const LaunchFn g_launchers[] = { KM_FUSED_INSTANCES(KM_LAUNCHER_ROW) };
+static const int g_num_variants = (int)(sizeof(g_variants) / sizeof(g_variants[0]));
 
 template <typename T>
 static hipError_t launch_generic(const LaunchArgs& a)
@@ -267,6 +305,14 @@ km_status kronmatmul_set_option(km_option option, int value)
             if (value < 1 || value > 8) return KM_EINVAL;
             g_options.max_fuse = value;
             return KM_OK;
+        case KM_OPT_PREFER_TILE:
+            if (value < 0) return KM_EINVAL;
+            g_options.prefer_tile = value;
+            return KM_OK;
+        case KM_OPT_PREFER_THREADS:
+            if (value < 0 || value > 1024) return KM_EINVAL;
+            g_options.prefer_threads = value;
+            return KM_OK;
         case KM_OPT_PROFILE:
             if (value != 0 && value != 1) return KM_EINVAL;
             if (value == 1 && g_profile == 0)      // a fresh history on every device
@@ -285,6 +331,8 @@ km_status kronmatmul_get_option(km_option option, int* value)
         case KM_OPT_KERNELS: *value = g_options.kernels; return KM_OK;
         case KM_OPT_MAX_FUSE: *value = g_options.max_fuse; return KM_OK;
         case KM_OPT_PROFILE: *value = g_profile; return KM_OK;
+        case KM_OPT_PREFER_TILE: *value = g_options.prefer_tile; return KM_OK;
+        case KM_OPT_PREFER_THREADS: *value = g_options.prefer_threads; return KM_OK;
     }
     return KM_EINVAL;
 }

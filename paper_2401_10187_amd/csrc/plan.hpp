@@ -41,6 +41,8 @@ struct Plan {
 struct Options {
     int kernels = 0x7;    // bit mask of km_kernel families
     int max_fuse = 3;
+    int prefer_tile = 0;      // tuning: choose instances with this tile_slices when one fits
+    int prefer_threads = 0;   // tuning: ... with this workgroup size
 };
 
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -107,7 +109,14 @@ inline const Variant* find_variant(const Variant* table, int count, const Proble
         if (c.P != pr.P[f] || c.Q != pr.Q[f]) continue;
         if (s_row % c.tile_slices) continue;
         if (pr.M % c.rows_per_tile) continue;
-        if (!best || c.tile_slices > best->tile_slices) best = &c;   // table order breaks ties
+        // preference: the tuning options first, then the longest output run; table order breaks ties
+        auto score = [&](const Variant& x) {
+            int64_t sc = x.tile_slices;
+            if (opt.prefer_tile && x.tile_slices == opt.prefer_tile) sc += (int64_t)1 << 40;
+            if (opt.prefer_threads && x.threads == opt.prefer_threads) sc += (int64_t)1 << 32;
+            return sc;
+        };
+        if (!best || score(c) > score(*best)) best = &c;
     }
     return best;
 }
