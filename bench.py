@@ -26,7 +26,10 @@ PAPER_GFLOPS = {"c2_f32_m1024_8x8x6": 25769803776 / 5.76e-3 / 1e9,
 
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (summaries under profiles/); None until measured.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {
+    # profiles/fused_f32_8x8_nf3_c2_m1024_8x8x6.md: (524327.29 * 1.99987 + 1048576.0) KiB
+    "c2_f32_m1024_8x8x6": 2147494700,
+}
 
 
 def main():
@@ -37,6 +40,8 @@ def main():
     ap.add_argument("--workload", default="c2_f32_m1024_8x8x6")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=1)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain elementwise copy of X's size (for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build measures one GPU only (rows shard across GPUs without "
@@ -66,6 +71,12 @@ def main():
     es = Xd.element_size()
 
     stream = torch.cuda.current_stream(dev)
+    if args.calibrate_copy:
+        # a plain elementwise kernel that reads X once and writes the same number of bytes once
+        cal = torch.empty_like(Xd)
+        torch.mul(Xd, 1.0, out=cal)
+        torch.cuda.synchronize()
+        del cal
     for _ in range(args.warmup):
         km.kronmatmul(Xd, Fd, Y=Yd, workspace=ws)
     torch.cuda.synchronize()

@@ -46,9 +46,9 @@ static hipError_t launch_fused(const LaunchArgs& a)
 
 // (type, dtype code, P, Q, factors per launch, tile_slices, threads)
 #define KM_FUSED_INSTANCES(X)                 \
+    X(float, KM_F32, 8, 8, 3, 32, 1024)       \
     X(float, KM_F32, 8, 8, 3, 32, 256)        \
     X(float, KM_F32, 8, 8, 3, 16, 256)        \
-    X(float, KM_F32, 8, 8, 3, 16, 128)        \
     X(float, KM_F32, 8, 8, 3, 8, 128)         \
     X(float, KM_F32, 8, 8, 3, 1, 64)          \
     X(float, KM_F32, 8, 8, 2, 256, 256)       \

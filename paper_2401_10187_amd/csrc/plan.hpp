@@ -94,7 +94,6 @@ inline int64_t store_column(int64_t k_in, int64_t p_group, int64_t tile_k, int64
 inline const Variant* find_variant(const Variant* table, int count, const Problem& pr, int f, int nf,
                                    int64_t k_cur, const Options& opt)
 {
-    const Variant* best = nullptr;
     int64_t pg = 1;
     for (int i = f - nf + 1; i <= f; ++i) {
         if (pr.P[i] != pr.P[f] || pr.Q[i] != pr.Q[f]) return nullptr;   // equal shapes within a group
@@ -102,6 +101,14 @@ inline const Variant* find_variant(const Variant* table, int count, const Proble
     }
     if (k_cur % pg) return nullptr;
     const int64_t s_row = k_cur / pg;
+    // The table is in order of preference (fastest instance on a full machine first).  Take the first
+    // instance that fits the shape and still gives the chip enough workgroups; failing that, the
+    // fitting instance with the most workgroups.  The tuning options override both.
+    const int64_t enough = 2 * 256;
+    const Variant* first_big = nullptr;
+    const Variant* most = nullptr;
+    const Variant* wanted = nullptr;
+    int64_t most_grid = 0, wanted_score = 0;
     for (int v = 0; v < count; ++v) {
         const Variant& c = table[v];
         if (!(opt.kernels >> c.kernel & 1)) continue;
@@ -109,16 +116,19 @@ inline const Variant* find_variant(const Variant* table, int count, const Proble
         if (c.P != pr.P[f] || c.Q != pr.Q[f]) continue;
         if (s_row % c.tile_slices) continue;
         if (pr.M % c.rows_per_tile) continue;
-        // preference: the tuning options first, then the longest output run; table order breaks ties
-        auto score = [&](const Variant& x) {
-            int64_t sc = x.tile_slices;
-            if (opt.prefer_tile && x.tile_slices == opt.prefer_tile) sc += (int64_t)1 << 40;
-            if (opt.prefer_threads && x.threads == opt.prefer_threads) sc += (int64_t)1 << 32;
-            return sc;
-        };
-        if (!best || score(c) > score(*best)) best = &c;
+        const int64_t grid = (pr.M / c.rows_per_tile) * (s_row / c.tile_slices);
+        if (!first_big && grid >= enough) first_big = &c;
+        // among small launches prefer output runs of at least 32 bytes over more workgroups
+        const bool longer = most && c.tile_slices >= 8 && most->tile_slices < 8;
+        const bool shorter = most && c.tile_slices < 8 && most->tile_slices >= 8;
+        if (!most || longer || (!shorter && grid > most_grid)) { most = &c; most_grid = grid; }
+        int64_t sc = 0;
+        if (opt.prefer_tile && c.tile_slices == opt.prefer_tile) sc += 2;
+        if (opt.prefer_threads && c.threads == opt.prefer_threads) sc += 1;
+        if (sc > wanted_score) { wanted = &c; wanted_score = sc; }
     }
-    return best;
+    if (wanted) return wanted;
+    return first_big ? first_big : most;
 }
 
 inline km_status make_plan(const Problem& pr, const Options& opt, const Variant* table, int count,
