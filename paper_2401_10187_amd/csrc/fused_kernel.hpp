@@ -25,9 +25,10 @@ namespace km {
 constexpr int64_t ipow(int64_t b, int e) { return e <= 0 ? 1 : b * ipow(b, e - 1); }
 constexpr int64_t cmax(int64_t a, int64_t b) { return a > b ? a : b; }
 
+// 16-byte vectors (native vector types, so that arrays of them stay in registers)
 template <typename T> struct Vec16;
-template <> struct Vec16<float> { typedef float4 type; static constexpr int N = 4; };
-template <> struct Vec16<double> { typedef double2 type; static constexpr int N = 2; };
+template <> struct Vec16<float> { typedef float type __attribute__((ext_vector_type(4))); static constexpr int N = 4; };
+template <> struct Vec16<double> { typedef double type __attribute__((ext_vector_type(2))); static constexpr int N = 2; };
 
 // read-only data that is uniform across a wavefront: scalar loads
 #pragma clang diagnostic push
@@ -81,8 +82,8 @@ __device__ __forceinline__ void fused_stage(T* __restrict__ tile, const T* Fg, T
 #pragma unroll
                 for (int c = 0; c < P / VN; ++c) {
                     const V v = src[c];
-                    if constexpr (VN == 4) { x[4 * c] = v.x; x[4 * c + 1] = v.y; x[4 * c + 2] = v.z; x[4 * c + 3] = v.w; }
-                    else { x[2 * c] = v.x; x[2 * c + 1] = v.y; }
+#pragma unroll
+                    for (int e = 0; e < VN; ++e) x[VN * c + e] = v[e];
                 }
             } else {
 #pragma unroll
@@ -113,14 +114,16 @@ __device__ __forceinline__ void fused_stage(T* __restrict__ tile, const T* Fg, T
         __syncthreads();
     } else {
         // local (q, s) with s = qq_rest*ST + r  ->  column (q*Q^(NF-1) + qq_rest)*s_row + h*ST + r
+        // (in-row offsets fit 32 bits: the planner only picks this kernel for rows below 2^31 bytes)
         constexpr int QREST = (int)ipow(Q, NF - 1);
+        const int sr = (int)s_row;
 #pragma unroll
         for (int i = 0; i < R; ++i) {
             const int s = tid + i * NT;
             if (FULL || s < SJ) {
-                T* dst = Yrow + (int64_t)(s / ST) * s_row + h * ST + (s % ST);
+                const int off = (s / ST) * sr + (int)h * ST + (s % ST);
 #pragma unroll
-                for (int q = 0; q < Q; ++q) dst[(int64_t)(q * QREST) * s_row] = out[i][q];
+                for (int q = 0; q < Q; ++q) Yrow[off + q * QREST * sr] = out[i][q];
             }
         }
     }

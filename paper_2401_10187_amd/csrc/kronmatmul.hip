@@ -9,6 +9,7 @@
 #include "plan.hpp"
 #include "generic_kernel.hpp"
 #include "fused_kernel.hpp"
+#include "mfma_kernel.hpp"
 
 namespace km {
 
@@ -22,6 +23,7 @@ struct LaunchArgs {
     const Problem* pr;
     const km_plan_step* st;
     hipStream_t stream;
+    int tiles_per_wg_hint;
 };
 typedef hipError_t (*LaunchFn)(const LaunchArgs&);
 
@@ -44,28 +46,63 @@ static hipError_t launch_fused(const LaunchArgs& a)
     return hipGetLastError();
 }
 
-// (type, dtype code, P, Q, factors per launch, tile_slices, threads)
-#define KM_FUSED_INSTANCES(X)                 \
-    X(float, KM_F32, 8, 8, 3, 32, 1024)       \
-    X(float, KM_F32, 8, 8, 3, 32, 256)        \
-    X(float, KM_F32, 8, 8, 3, 16, 256)        \
-    X(float, KM_F32, 8, 8, 3, 8, 128)         \
-    X(float, KM_F32, 8, 8, 3, 1, 64)          \
-    X(float, KM_F32, 8, 8, 2, 256, 256)       \
-    X(float, KM_F32, 8, 8, 2, 64, 256)        \
-    X(float, KM_F32, 8, 8, 2, 8, 64)          \
-    X(float, KM_F32, 8, 8, 2, 1, 64)          \
-    X(float, KM_F32, 8, 8, 1, 2048, 256)      \
-    X(float, KM_F32, 8, 8, 1, 64, 64)         \
-    X(float, KM_F32, 8, 8, 1, 8, 64)          \
-    X(float, KM_F32, 8, 8, 1, 1, 64)
+template <class OP, int P, int Q, int NF, int ST, int NW, int QSPLIT>
+static hipError_t launch_mfma(const LaunchArgs& a)
+{
+    typedef MfmaShape<OP, P, Q, NF, ST, NW, QSPLIT> Sh;
+    typedef typename OP::T T;
+    const km_plan_step& st = *a.st;
+    auto kern = mfma_sliced_multiply<OP, P, Q, NF, ST, NW, QSPLIT>;
+    if (Sh::LDS_BYTES > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, Sh::LDS_BYTES);
+        if (e != hipSuccess) return e;
+    }
+    const T* f[2] = {nullptr, nullptr};
+    for (int j = 0; j < NF; ++j) f[j] = (const T*)a.factors[st.first_factor + NF - 1 - j];   // order of application
+    const int64_t tiles_per_row = st.k_in / Sh::TK;
+    const int64_t num_tiles = a.pr->M * tiles_per_row;
+    const int64_t tpw = tiles_per_wg(num_tiles, a.tiles_per_wg_hint);
+    if ((num_tiles + tpw - 1) / tpw != st.grid) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(kern, dim3((unsigned)st.grid), dim3(Sh::NT), Sh::LDS_BYTES, a.stream,
+                       (const T*)a.src, (T*)a.dst, f[0], f[1], st.k_in, st.k_out, tiles_per_row, num_tiles, tpw);
+    return hipGetLastError();
+}
 
-#define KM_VARIANT_ROW(T, DT, P, Q, NF, ST, NT) \
-    {KM_KERNEL_FUSED, DT, P, Q, NF, ST, NT, FusedShape<T, P, Q, NF, ST, NT>::LDS_BYTES, 1, "fused"},
-#define KM_LAUNCHER_ROW(T, DT, P, Q, NF, ST, NT) launch_fused<T, P, Q, NF, ST, NT>,
+// Fused FMA instances: X(type, dtype code, P, Q, factors per launch, tile_slices, threads).
+// MFMA instances: Y(op, dtype code, P, Q, factors per launch, tile_slices, wavefronts, q split).
+// Order = preference among instances that fit a shape.
+#define KM_INSTANCES(X, Y)                              \
+    X(float, KM_F32, 8, 8, 3, 32, 1024)                 \
+    X(float, KM_F32, 8, 8, 3, 32, 256)                  \
+    X(float, KM_F32, 8, 8, 3, 16, 256)                  \
+    X(float, KM_F32, 8, 8, 3, 8, 128)                   \
+    X(float, KM_F32, 8, 8, 3, 1, 64)                    \
+    X(float, KM_F32, 8, 8, 2, 256, 256)                 \
+    X(float, KM_F32, 8, 8, 2, 64, 256)                  \
+    X(float, KM_F32, 8, 8, 2, 8, 64)                    \
+    X(float, KM_F32, 8, 8, 2, 1, 64)                    \
+    X(float, KM_F32, 8, 8, 1, 2048, 256)                \
+    X(float, KM_F32, 8, 8, 1, 64, 64)                   \
+    X(float, KM_F32, 8, 8, 1, 8, 64)                    \
+    X(float, KM_F32, 8, 8, 1, 1, 64)                    \
+    Y(MfmaF32x32, KM_F32, 32, 32, 2, 16, 4, 1)          \
+    Y(MfmaF32x32, KM_F32, 32, 32, 1, 512, 4, 1)         \
+    Y(MfmaF32x32, KM_F32, 32, 32, 1, 128, 4, 1)         \
+    Y(MfmaF32x32, KM_F32, 16, 32, 2, 32, 4, 1)          \
+    Y(MfmaF32x32, KM_F32, 16, 32, 2, 16, 4, 1)          \
+    Y(MfmaF32x32, KM_F32, 16, 32, 1, 512, 4, 1)         \
+    Y(MfmaF32x32, KM_F32, 16, 32, 1, 128, 4, 1)         \
+    Y(MfmaF64x16, KM_F64, 128, 128, 1, 16, 4, 4)
 
-static const Variant g_variants[] = { KM_FUSED_INSTANCES(KM_VARIANT_ROW) };
-static const LaunchFn g_launchers[] = { KM_FUSED_INSTANCES(KM_LAUNCHER_ROW) };
+#define KM_FUSED_ROW(T, DT, P, Q, NF, ST, NT) \
+    {KM_KERNEL_FUSED, DT, P, Q, NF, ST, NT, FusedShape<T, P, Q, NF, ST, NT>::LDS_BYTES, 1, 0, "fused"},
+#define KM_MFMA_ROW(OP, DT, P, Q, NF, ST, NW, QS) \
+    {KM_KERNEL_MFMA, DT, P, Q, NF, ST, NW * 64, MfmaShape<OP, P, Q, NF, ST, NW, QS>::LDS_BYTES, 1, 1, "mfma"},
+#define KM_FUSED_FN(T, DT, P, Q, NF, ST, NT) launch_fused<T, P, Q, NF, ST, NT>,
+#define KM_MFMA_FN(OP, DT, P, Q, NF, ST, NW, QS) launch_mfma<OP, P, Q, NF, ST, NW, QS>,
+
+static const Variant g_variants[] = { KM_INSTANCES(KM_FUSED_ROW, KM_MFMA_ROW) };
+static const LaunchFn g_launchers[] = { KM_INSTANCES(KM_FUSED_FN, KM_MFMA_FN) };
 static const int g_num_variants = (int)(sizeof(g_variants) / sizeof(g_variants[0]));
 
 template <typename T>
@@ -131,8 +168,10 @@ static km_status run(const Problem& pr, const Plan& plan, const void* X, const v
     const int n = (int)plan.steps.size();
     int profile;
     int ev0 = 0;
+    int tpw_hint;
     {
         std::lock_guard<std::mutex> lock(g_mutex);
+        tpw_hint = g_options.tiles_per_wg;
         profile = g_profile && (int)ds.call_first.size() < MAX_PROFILED_CALLS;
         if (profile) {
             ev0 = ds.events_used;
@@ -155,7 +194,7 @@ static km_status run(const Problem& pr, const Plan& plan, const void* X, const v
                 default: return ws1;
             }
         };
-        LaunchArgs a{buf(st.src), buf(st.dst), F, &pr, &st, stream};
+        LaunchArgs a{buf(st.src), buf(st.dst), F, &pr, &st, stream, tpw_hint};
         hipError_t e;
         if (st.kernel == KM_KERNEL_GENERIC)
             e = pr.dtype == KM_F32 ? launch_generic<float>(a) : launch_generic<double>(a);
@@ -313,6 +352,10 @@ km_status kronmatmul_set_option(km_option option, int value)
             if (value < 0 || value > 1024) return KM_EINVAL;
             g_options.prefer_threads = value;
             return KM_OK;
+        case KM_OPT_TILES_PER_WG:
+            if (value < 0 || value > 4096) return KM_EINVAL;
+            g_options.tiles_per_wg = value;
+            return KM_OK;
         case KM_OPT_PROFILE:
             if (value != 0 && value != 1) return KM_EINVAL;
             if (value == 1 && g_profile == 0)      // a fresh history on every device
@@ -333,6 +376,7 @@ km_status kronmatmul_get_option(km_option option, int* value)
         case KM_OPT_PROFILE: *value = g_profile; return KM_OK;
         case KM_OPT_PREFER_TILE: *value = g_options.prefer_tile; return KM_OK;
         case KM_OPT_PREFER_THREADS: *value = g_options.prefer_threads; return KM_OK;
+        case KM_OPT_TILES_PER_WG: *value = g_options.tiles_per_wg; return KM_OK;
     }
     return KM_EINVAL;
 }

@@ -1,0 +1,221 @@
+// Sliced multiplies on the matrix cores (MFMA), for factors whose P and Q are multiples of the MFMA
+// block: the contraction of a slice with the factor (Algorithm 1's inner loop) is a dense product
+//     D[q][s] = sum_p F[p][q] * X[s*P + p]            (Q x S) = F^T (Q x P) * Xslices^T (P x S)
+// The factor is the A operand and stays in registers; slices are the B operand, so the lane
+// dimension of the accumulator runs along the slice index and one accumulator register of a
+// wavefront is a contiguous run of the output row (output column of (s, q) is q*(K/P)+s).
+//
+// The MFMA contraction index is split over lane groups (KG groups) and over issue steps.  Which
+// element p a (group, step) pair stands for is free as long as A and B agree, so group g takes the
+// contiguous range p in [g*P/KG, (g+1)*P/KG): every lane reads one contiguous piece of its slice
+// from LDS with 16-byte reads.  LDS rows (one slice each) are padded so that eight consecutive
+// lanes of such a read fall into different banks.
+//
+// A workgroup walks over `tiles_per_wg` consecutive tiles.  A tile is ST*P^NF contiguous elements of
+// one row; NF = 1 or 2 factors are applied with the intermediate kept in LDS (section 4.2) and the
+// result is scattered exactly as in the non-MFMA fused kernel.  The next tile is fetched from
+// global memory into registers while the current one is being multiplied.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "fused_kernel.hpp"   // ipow, Vec16
+
+namespace km {
+
+typedef float mfma_f32x4 __attribute__((ext_vector_type(4)));
+typedef float mfma_f32x16 __attribute__((ext_vector_type(16)));
+typedef double mfma_f64x4 __attribute__((ext_vector_type(4)));
+
+// v_mfma_f32_32x32x2_f32: A is 32x2, B is 2x32; lane l holds A[l%32][l/32], B[l/32][l%32];
+// accumulator register v of lane l is D[8*(v/4) + 4*(l/32) + v%4][l%32]
+// (row = row_lane(l) + row_reg(v)).
+struct MfmaF32x32 {
+    typedef float T;
+    typedef mfma_f32x16 Acc;
+    static constexpr int MB = 32, NB = 32, KG = 2, NACC = 16;
+    static __device__ __forceinline__ int row_lane(int lane) { return 4 * (lane / 32); }
+    static constexpr int row_reg(int v) { return 8 * (v / 4) + (v % 4); }
+    static __device__ __forceinline__ Acc mma(float a, float b, Acc c) { return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0); }
+};
+// v_mfma_f32_16x16x4_f32: lane l holds A[l%16][l/16], B[l/16][l%16]; register v is D[4*(l/16) + v][l%16].
+struct MfmaF32x16 {
+    typedef float T;
+    typedef mfma_f32x4 Acc;
+    static constexpr int MB = 16, NB = 16, KG = 4, NACC = 4;
+    static __device__ __forceinline__ int row_lane(int lane) { return 4 * (lane / 16); }
+    static constexpr int row_reg(int v) { return v; }
+    static __device__ __forceinline__ Acc mma(float a, float b, Acc c) { return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0); }
+};
+// v_mfma_f64_16x16x4_f64: same operand layout; register v is D[4*v + l/16][l%16].
+struct MfmaF64x16 {
+    typedef double T;
+    typedef mfma_f64x4 Acc;
+    static constexpr int MB = 16, NB = 16, KG = 4, NACC = 4;
+    static __device__ __forceinline__ int row_lane(int lane) { return lane / 16; }
+    static constexpr int row_reg(int v) { return 4 * v; }
+    static __device__ __forceinline__ Acc mma(double a, double b, Acc c) { return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0); }
+};
+
+// NW wavefronts per workgroup; the factor's column blocks are dealt to QSPLIT wave groups and the
+// slice blocks of a stage to the NW/QSPLIT wave groups along the other axis.
+template <class OP, int P, int Q, int NF, int ST, int NW, int QSPLIT>
+struct MfmaShape {
+    typedef typename OP::T T;
+    static constexpr int NT = NW * 64;
+    static constexpr int PL = P / OP::KG;              // slice elements per lane
+    static constexpr int QT = Q / OP::MB;              // column blocks of the factor
+    static constexpr int QTW = QT / QSPLIT;            // ... per wavefront
+    static constexpr int SG = NW / QSPLIT;             // wave groups along the slice axis
+    static constexpr int VN = Vec16<T>::N;
+    static constexpr int UNITS = P * (int)sizeof(T) / 16;                  // 16-byte units per slice
+    static constexpr int PAD = (UNITS % 2 == 0 && UNITS != 2) ? VN : 0;    // make the row stride odd in units
+    static constexpr int RS = P + PAD;                 // LDS row stride in elements
+    static constexpr int size(int j) { return (int)(ST * ipow(P, NF - j) * ipow(Q, j)); }
+    static constexpr int TK = size(0);
+    static constexpr int lds_elems()
+    {
+        int m = 0;
+        for (int j = 0; j < NF; ++j) m = size(j) / P * RS > m ? size(j) / P * RS : m;
+        return m;
+    }
+    static constexpr int LDS_BYTES = lds_elems() * (int)sizeof(T);
+    static constexpr int RV = TK / VN / NT;            // 16-byte vectors of a tile per thread
+    static_assert(P % OP::KG == 0 && Q % OP::MB == 0 && QT % QSPLIT == 0 && NW % QSPLIT == 0, "shape");
+    static_assert((PL * sizeof(T)) % 16 == 0, "a lane's piece of a slice must be whole 16-byte vectors");
+    static_assert(TK % (VN * NT) == 0, "tile must be a whole number of vectors per thread");
+};
+
+template <class OP, int P, int Q, int NF, int ST, int NW, int QSPLIT, int J>
+__device__ __forceinline__ void mfma_stage(typename OP::T* __restrict__ tile,
+                                           const typename OP::T (&a)[MfmaShape<OP, P, Q, NF, ST, NW, QSPLIT>::QTW][MfmaShape<OP, P, Q, NF, ST, NW, QSPLIT>::PL],
+                                           typename OP::T* __restrict__ Yrow, int64_t s_row, int64_t h)
+{
+    typedef MfmaShape<OP, P, Q, NF, ST, NW, QSPLIT> Sh;
+    typedef typename OP::T T;
+    typedef typename Vec16<T>::type V;
+    constexpr int VN = Sh::VN, PL = Sh::PL, QTW = Sh::QTW, SG = Sh::SG, RS = Sh::RS;
+    constexpr int SJ = Sh::size(J) / P;                // slices at this stage
+    constexpr int NBLK = SJ / OP::NB;                  // slice blocks
+    constexpr int BPW = NBLK / SG;                     // ... per wave group
+    static_assert(SJ % OP::NB == 0 && NBLK % SG == 0, "slice blocks must divide among the wave groups");
+    constexpr bool LAST = J == NF - 1;
+    const int lane = threadIdx.x % 64, wave = threadIdx.x / 64;
+    const int j = lane % OP::NB, g = lane / OP::NB;
+    const int wq = wave % QSPLIT, ws = wave / QSPLIT;
+
+    typename OP::Acc acc[LAST ? 1 : BPW][QTW];
+#pragma unroll
+    for (int bi = 0; bi < BPW; ++bi) {
+        const int s0 = (ws + bi * SG) * OP::NB;
+        T b[PL];
+        const V* src = reinterpret_cast<const V*>(tile + (s0 + j) * RS + g * PL);
+#pragma unroll
+        for (int c = 0; c < PL / VN; ++c) {
+            const V v = src[c];
+#pragma unroll
+            for (int e = 0; e < VN; ++e) b[VN * c + e] = v[e];
+        }
+        const int ai = LAST ? 0 : bi;
+#pragma unroll
+        for (int qt = 0; qt < QTW; ++qt) {
+#pragma unroll
+            for (int v = 0; v < OP::NACC; ++v) acc[ai][qt][v] = T(0);
+#pragma unroll
+            for (int t = 0; t < PL; ++t) acc[ai][qt] = OP::mma(a[qt][t], b[t], acc[ai][qt]);
+        }
+        if constexpr (LAST) {
+            // local (q, s), s = qrest*ST + r  ->  column (q*Q^(NF-1) + qrest)*s_row + h*ST + r
+            // (in-row offsets fit 32 bits: the planner only picks this kernel for rows below 2^31 bytes)
+            constexpr int QREST = (int)ipow(Q, NF - 1);
+            const int s = s0 + j;
+            const int sr = (int)s_row;
+            const int off = (s / ST) * sr + (int)h * ST + (s % ST) + (wq * QTW * OP::MB + OP::row_lane(lane)) * QREST * sr;
+#pragma unroll
+            for (int qt = 0; qt < QTW; ++qt)
+#pragma unroll
+                for (int v = 0; v < OP::NACC; ++v)
+                    Yrow[off + (qt * OP::MB + OP::row_reg(v)) * QREST * sr] = acc[0][qt][v];
+        }
+    }
+    if constexpr (!LAST) {
+        __syncthreads();                               // the whole tile has been read
+#pragma unroll
+        for (int bi = 0; bi < BPW; ++bi) {
+            const int s = (ws + bi * SG) * OP::NB + j;
+#pragma unroll
+            for (int qt = 0; qt < QTW; ++qt)
+#pragma unroll
+                for (int v = 0; v < OP::NACC; ++v) {
+                    const int q = (wq * QTW + qt) * OP::MB + OP::row_lane(lane) + OP::row_reg(v);
+                    const int c = q * SJ + s;          // position in the next stage's row of the tile
+                    tile[(c / P) * RS + (c % P)] = acc[bi][qt][v];
+                }
+        }
+        __syncthreads();
+    }
+}
+
+template <class OP, int P, int Q, int NF, int ST, int NW, int QSPLIT>
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2)))
+void mfma_sliced_multiply(const typename OP::T* __restrict__ Xg, typename OP::T* __restrict__ Yg,
+                          const typename OP::T* __restrict__ F0, const typename OP::T* __restrict__ F1,
+                          int64_t k_in, int64_t k_out, int64_t tiles_per_row, int64_t num_tiles,
+                          int64_t tiles_per_wg)
+{
+    typedef MfmaShape<OP, P, Q, NF, ST, NW, QSPLIT> Sh;
+    typedef typename OP::T T;
+    typedef typename Vec16<T>::type V;
+    constexpr int VN = Sh::VN, PL = Sh::PL, QTW = Sh::QTW, RS = Sh::RS, NT = Sh::NT, RV = Sh::RV;
+    extern __shared__ __attribute__((aligned(16))) unsigned char mfma_lds[];
+    T* tile = reinterpret_cast<T*>(mfma_lds);
+
+    const int tid = threadIdx.x;
+    const int lane = tid % 64, wave = tid / 64;
+    const int wq = wave % QSPLIT;
+    const int ai = lane % OP::MB, ag = lane / OP::MB;
+
+    // factor pieces of this lane: A[i][k] = F[p][q] with q = column block + ai, p = ag*PL + t
+    T a0[QTW][PL], a1[NF > 1 ? QTW : 1][NF > 1 ? PL : 1];
+#pragma unroll
+    for (int qt = 0; qt < QTW; ++qt)
+#pragma unroll
+        for (int t = 0; t < PL; ++t) {
+            const int q = (wq * QTW + qt) * OP::MB + ai;
+            a0[qt][t] = F0[(ag * PL + t) * Q + q];
+            if constexpr (NF > 1) a1[qt][t] = F1[(ag * PL + t) * Q + q];
+        }
+
+    const int64_t s_row = tiles_per_row * ST;
+    const int64_t t_begin = (int64_t)blockIdx.x * tiles_per_wg;
+    int64_t t_end = t_begin + tiles_per_wg;
+    if (t_end > num_tiles) t_end = num_tiles;
+
+    V pf[RV];
+    if (t_begin < t_end) {
+        const V* src = reinterpret_cast<const V*>(Xg + (t_begin / tiles_per_row) * k_in + (t_begin % tiles_per_row) * Sh::TK);
+#pragma unroll
+        for (int i = 0; i < RV; ++i) pf[i] = src[tid + i * NT];
+    }
+    for (int64_t t = t_begin; t < t_end; ++t) {
+        // registers -> LDS rows of P elements with stride RS
+#pragma unroll
+        for (int i = 0; i < RV; ++i) {
+            const int e = (tid + i * NT) * VN;
+            *reinterpret_cast<V*>(tile + (e / P) * RS + (e % P)) = pf[i];
+        }
+        __syncthreads();
+        if (t + 1 < t_end) {
+            const int64_t tn = t + 1;
+            const V* src = reinterpret_cast<const V*>(Xg + (tn / tiles_per_row) * k_in + (tn % tiles_per_row) * Sh::TK);
+#pragma unroll
+            for (int i = 0; i < RV; ++i) pf[i] = src[tid + i * NT];
+        }
+        const int64_t row = t / tiles_per_row, h = t % tiles_per_row;
+        T* Yrow = Yg + row * k_out;
+        mfma_stage<OP, P, Q, NF, ST, NW, QSPLIT, 0>(tile, a0, Yrow, s_row, h);
+        if constexpr (NF > 1) mfma_stage<OP, P, Q, NF, ST, NW, QSPLIT, 1>(tile, a1, Yrow, s_row, h);
+        __syncthreads();                               // tile fully consumed before it is overwritten
+    }
+}
+
+}  // namespace km

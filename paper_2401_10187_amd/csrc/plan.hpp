@@ -20,8 +20,17 @@ struct Variant {
     int threads;       // workgroup size
     int lds_bytes;     // LDS per workgroup
     int rows_per_tile; // rows of X a workgroup handles together
+    int persistent;    // 1: a workgroup walks over several consecutive tiles (see tiles_per_wg)
     const char* name;
 };
+
+// Consecutive tiles handled by one workgroup of a persistent instance; `hint` > 0 forces the value.
+inline int64_t tiles_per_wg(int64_t num_tiles, int hint)
+{
+    if (hint > 0) return hint;
+    int64_t t = num_tiles / 2048;
+    return t < 1 ? 1 : (t > 16 ? 16 : t);
+}
 
 struct Problem {
     int64_t M = 0;
@@ -43,6 +52,7 @@ struct Options {
     int max_fuse = 3;
     int prefer_tile = 0;      // tuning: choose instances with this tile_slices when one fits
     int prefer_threads = 0;   // tuning: ... with this workgroup size
+    int tiles_per_wg = 0;     // tuning: tiles per workgroup of persistent instances (0 = automatic)
 };
 
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -101,6 +111,12 @@ inline const Variant* find_variant(const Variant* table, int count, const Proble
     }
     if (k_cur % pg) return nullptr;
     const int64_t s_row = k_cur / pg;
+    {   // the tiled kernels address within a row with 32-bit offsets
+        int64_t qg = 1;
+        for (int i = f - nf + 1; i <= f; ++i) qg *= pr.Q[i];
+        if ((double)s_row * (double)qg * (double)pr.esize >= 2147483648.0) return nullptr;
+        if ((double)k_cur * (double)pr.esize >= 2147483648.0) return nullptr;
+    }
     // The table is in order of preference (fastest instance on a full machine first).  Take the first
     // instance that fits the shape and still gives the chip enough workgroups; failing that, the
     // fitting instance with the most workgroups.  The tuning options override both.
@@ -158,6 +174,10 @@ inline km_status make_plan(const Problem& pr, const Options& opt, const Variant*
             st.block = var->threads;
             st.lds_bytes = var->lds_bytes;
             st.grid = (pr.M / var->rows_per_tile) * (k_cur / pg / var->tile_slices);
+            if (var->persistent) {
+                const int64_t tpw = tiles_per_wg(st.grid, opt.tiles_per_wg);
+                st.grid = (st.grid + tpw - 1) / tpw;
+            }
         } else {
             st.kernel = KM_KERNEL_GENERIC;
             st.variant = -1;
