@@ -61,7 +61,7 @@ static hipError_t launch_mfma(const LaunchArgs& a)
     for (int j = 0; j < NF; ++j) f[j] = (const T*)a.factors[st.first_factor + NF - 1 - j];   // order of application
     const int64_t tiles_per_row = st.k_in / Sh::TK;
     const int64_t num_tiles = a.pr->M * tiles_per_row;
-    const int64_t tpw = tiles_per_wg(num_tiles, a.tiles_per_wg_hint);
+    const int64_t tpw = tiles_per_wg(num_tiles, a.tiles_per_wg_hint, (int64_t)NF * P * Q, (int64_t)Sh::TK);
     if ((num_tiles + tpw - 1) / tpw != st.grid) return hipErrorInvalidValue;
     hipLaunchKernelGGL(kern, dim3((unsigned)st.grid), dim3(Sh::NT), Sh::LDS_BYTES, a.stream,
                        (const T*)a.src, (T*)a.dst, f[0], f[1], st.k_in, st.k_out, tiles_per_row, num_tiles, tpw);
@@ -85,12 +85,14 @@ static hipError_t launch_mfma(const LaunchArgs& a)
     X(float, KM_F32, 8, 8, 1, 64, 64)                   \
     X(float, KM_F32, 8, 8, 1, 8, 64)                    \
     X(float, KM_F32, 8, 8, 1, 1, 64)                    \
+    Y(MfmaF32x32, KM_F32, 32, 32, 2, 32, 8, 1)          \
+    Y(MfmaF32x32, KM_F32, 32, 32, 2, 32, 16, 1)         \
     Y(MfmaF32x32, KM_F32, 32, 32, 2, 16, 4, 1)          \
-    Y(MfmaF32x32, KM_F32, 32, 32, 1, 512, 4, 1)         \
+    Y(MfmaF32x32, KM_F32, 32, 32, 1, 256, 4, 1)         \
     Y(MfmaF32x32, KM_F32, 32, 32, 1, 128, 4, 1)         \
     Y(MfmaF32x32, KM_F32, 16, 32, 2, 32, 4, 1)          \
     Y(MfmaF32x32, KM_F32, 16, 32, 2, 16, 4, 1)          \
-    Y(MfmaF32x32, KM_F32, 16, 32, 1, 512, 4, 1)         \
+    Y(MfmaF32x32, KM_F32, 16, 32, 1, 256, 4, 1)         \
     Y(MfmaF32x32, KM_F32, 16, 32, 1, 128, 4, 1)         \
     Y(MfmaF64x16, KM_F64, 128, 128, 1, 16, 4, 4)
 

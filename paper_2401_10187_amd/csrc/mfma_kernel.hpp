@@ -156,7 +156,7 @@ __device__ __forceinline__ void mfma_stage(typename OP::T* __restrict__ tile,
 }
 
 template <class OP, int P, int Q, int NF, int ST, int NW, int QSPLIT>
-__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2)))
+__global__ __launch_bounds__(NW * 64, (NW >= 16 ? 4 : 2))   // second bound: wavefronts per SIMD to fit
 void mfma_sliced_multiply(const typename OP::T* __restrict__ Xg, typename OP::T* __restrict__ Yg,
                           const typename OP::T* __restrict__ F0, const typename OP::T* __restrict__ F1,
                           int64_t k_in, int64_t k_out, int64_t tiles_per_row, int64_t num_tiles,

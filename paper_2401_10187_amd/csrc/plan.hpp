@@ -25,11 +25,16 @@ struct Variant {
 };
 
 // Consecutive tiles handled by one workgroup of a persistent instance; `hint` > 0 forces the value.
-inline int64_t tiles_per_wg(int64_t num_tiles, int hint)
+// A workgroup loads its factors once, so it should move at least ten times as many tile bytes as
+// factor bytes, but the launch must keep two workgroups for each of the 256 compute units.
+inline int64_t tiles_per_wg(int64_t num_tiles, int hint, int64_t factor_elems, int64_t tile_elems)
 {
     if (hint > 0) return hint;
-    int64_t t = num_tiles / 2048;
-    return t < 1 ? 1 : (t > 16 ? 16 : t);
+    int64_t t = (10 * factor_elems + tile_elems - 1) / tile_elems;
+    if (t < 4) t = 4;
+    const int64_t cap = num_tiles / 512;
+    if (t > cap) t = cap;
+    return t < 1 ? 1 : t;
 }
 
 struct Problem {
@@ -175,7 +180,8 @@ inline km_status make_plan(const Problem& pr, const Options& opt, const Variant*
             st.lds_bytes = var->lds_bytes;
             st.grid = (pr.M / var->rows_per_tile) * (k_cur / pg / var->tile_slices);
             if (var->persistent) {
-                const int64_t tpw = tiles_per_wg(st.grid, opt.tiles_per_wg);
+                const int64_t tpw = tiles_per_wg(st.grid, opt.tiles_per_wg, (int64_t)nf * var->P * var->Q,
+                                                 (int64_t)var->tile_slices * pg);
                 st.grid = (st.grid + tpw - 1) / tpw;
             }
         } else {
