@@ -111,9 +111,11 @@ km_status kronmatmul_cost(int M, int N, const int* P, const int* Q, km_dtype dty
  * KM_OPT_PROFILE: when 1, every launch is bracketed by HIP events on the caller's stream.
  * KM_OPT_PREFER_TILE / KM_OPT_PREFER_THREADS: tuning aids; when non-zero the planner prefers compiled
  * instances with that tile_slices / workgroup size where one fits the shape (0 = automatic).
- * KM_OPT_TILES_PER_WG: tuning aid; consecutive tiles per workgroup of the MFMA kernels (0 = automatic). */
+ * KM_OPT_TILES_PER_WG: tuning aid; consecutive tiles per workgroup of the MFMA kernels (0 = automatic).
+ * KM_OPT_PAIR_INTERLEAVE: tuning aid (default 1); MFMA kernels whose output runs are shorter than a
+ * cache line give alternate tiles to pairs of workgroups that share an XCD. */
 typedef enum { KM_OPT_KERNELS = 0, KM_OPT_MAX_FUSE = 1, KM_OPT_PROFILE = 2, KM_OPT_PREFER_TILE = 3,
-               KM_OPT_PREFER_THREADS = 4, KM_OPT_TILES_PER_WG = 5 } km_option;
+               KM_OPT_PREFER_THREADS = 4, KM_OPT_TILES_PER_WG = 5, KM_OPT_PAIR_INTERLEAVE = 6 } km_option;
 km_status kronmatmul_set_option(km_option option, int value);
 km_status kronmatmul_get_option(km_option option, int* value);
 

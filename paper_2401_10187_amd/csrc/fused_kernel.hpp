@@ -114,16 +114,16 @@ __device__ __forceinline__ void fused_stage(T* __restrict__ tile, const T* Fg, T
         __syncthreads();
     } else {
         // local (q, s) with s = qq_rest*ST + r  ->  column (q*Q^(NF-1) + qq_rest)*s_row + h*ST + r
-        // (in-row offsets fit 32 bits: the planner only picks this kernel for rows below 2^31 bytes)
+        // One 64-bit pointer per slice, advanced by a wave-uniform stride per column (measured faster
+        // than 32-bit offsets from the row base).
         constexpr int QREST = (int)ipow(Q, NF - 1);
-        const int sr = (int)s_row;
 #pragma unroll
         for (int i = 0; i < R; ++i) {
             const int s = tid + i * NT;
             if (FULL || s < SJ) {
-                const int off = (s / ST) * sr + (int)h * ST + (s % ST);
+                T* dst = Yrow + (int64_t)(s / ST) * s_row + h * ST + (s % ST);
 #pragma unroll
-                for (int q = 0; q < Q; ++q) Yrow[off + q * QREST * sr] = out[i][q];
+                for (int q = 0; q < Q; ++q) dst[(int64_t)(q * QREST) * s_row] = out[i][q];
             }
         }
     }

@@ -24,6 +24,7 @@ struct LaunchArgs {
     const km_plan_step* st;
     hipStream_t stream;
     int tiles_per_wg_hint;
+    int pair_interleave;
 };
 typedef hipError_t (*LaunchFn)(const LaunchArgs&);
 
@@ -61,10 +62,12 @@ static hipError_t launch_mfma(const LaunchArgs& a)
     for (int j = 0; j < NF; ++j) f[j] = (const T*)a.factors[st.first_factor + NF - 1 - j];   // order of application
     const int64_t tiles_per_row = st.k_in / Sh::TK;
     const int64_t num_tiles = a.pr->M * tiles_per_row;
-    const int64_t tpw = tiles_per_wg(num_tiles, a.tiles_per_wg_hint, (int64_t)NF * P * Q, (int64_t)Sh::TK);
+    const int64_t tpw = tiles_per_wg(num_tiles, a.tiles_per_wg_hint, (int64_t)NF * P * Q, (int64_t)Sh::TK, Sh::LDS_BYTES);
     if ((num_tiles + tpw - 1) / tpw != st.grid) return hipErrorInvalidValue;
+    // output runs shorter than a 128-byte line: let neighbouring tiles be written together
+    const int pair = (ST * sizeof(T) < 128 && st.grid % 16 == 0 && num_tiles % (2 * tpw) == 0 && a.pair_interleave) ? 1 : 0;
     hipLaunchKernelGGL(kern, dim3((unsigned)st.grid), dim3(Sh::NT), Sh::LDS_BYTES, a.stream,
-                       (const T*)a.src, (T*)a.dst, f[0], f[1], st.k_in, st.k_out, tiles_per_row, num_tiles, tpw);
+                       (const T*)a.src, (T*)a.dst, f[0], f[1], st.k_in, st.k_out, tiles_per_row, num_tiles, tpw, pair);
     return hipGetLastError();
 }
 
@@ -170,10 +173,11 @@ static km_status run(const Problem& pr, const Plan& plan, const void* X, const v
     const int n = (int)plan.steps.size();
     int profile;
     int ev0 = 0;
-    int tpw_hint;
+    int tpw_hint, pair_hint;
     {
         std::lock_guard<std::mutex> lock(g_mutex);
         tpw_hint = g_options.tiles_per_wg;
+        pair_hint = g_options.pair_interleave;
         profile = g_profile && (int)ds.call_first.size() < MAX_PROFILED_CALLS;
         if (profile) {
             ev0 = ds.events_used;
@@ -196,7 +200,7 @@ static km_status run(const Problem& pr, const Plan& plan, const void* X, const v
                 default: return ws1;
             }
         };
-        LaunchArgs a{buf(st.src), buf(st.dst), F, &pr, &st, stream, tpw_hint};
+        LaunchArgs a{buf(st.src), buf(st.dst), F, &pr, &st, stream, tpw_hint, pair_hint};
         hipError_t e;
         if (st.kernel == KM_KERNEL_GENERIC)
             e = pr.dtype == KM_F32 ? launch_generic<float>(a) : launch_generic<double>(a);
@@ -358,6 +362,10 @@ km_status kronmatmul_set_option(km_option option, int value)
             if (value < 0 || value > 4096) return KM_EINVAL;
             g_options.tiles_per_wg = value;
             return KM_OK;
+        case KM_OPT_PAIR_INTERLEAVE:
+            if (value != 0 && value != 1) return KM_EINVAL;
+            g_options.pair_interleave = value;
+            return KM_OK;
         case KM_OPT_PROFILE:
             if (value != 0 && value != 1) return KM_EINVAL;
             if (value == 1 && g_profile == 0)      // a fresh history on every device
@@ -379,6 +387,7 @@ km_status kronmatmul_get_option(km_option option, int* value)
         case KM_OPT_PREFER_TILE: *value = g_options.prefer_tile; return KM_OK;
         case KM_OPT_PREFER_THREADS: *value = g_options.prefer_threads; return KM_OK;
         case KM_OPT_TILES_PER_WG: *value = g_options.tiles_per_wg; return KM_OK;
+        case KM_OPT_PAIR_INTERLEAVE: *value = g_options.pair_interleave; return KM_OK;
     }
     return KM_EINVAL;
 }

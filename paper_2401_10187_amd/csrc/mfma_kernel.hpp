@@ -125,9 +125,9 @@ __device__ __forceinline__ void mfma_stage(typename OP::T* __restrict__ tile,
         }
         if constexpr (LAST) {
             // local (q, s), s = qrest*ST + r  ->  column (q*Q^(NF-1) + qrest)*s_row + h*ST + r
-            // (in-row offsets fit 32 bits: the planner only picks this kernel for rows below 2^31 bytes)
             constexpr int QREST = (int)ipow(Q, NF - 1);
             const int s = s0 + j;
+            // (in-row offsets fit 32 bits: the planner only picks this kernel for rows below 2^31 bytes)
             const int sr = (int)s_row;
             const int off = (s / ST) * sr + (int)h * ST + (s % ST) + (wq * QTW * OP::MB + OP::row_lane(lane)) * QREST * sr;
 #pragma unroll
@@ -160,7 +160,7 @@ __global__ __launch_bounds__(NW * 64, (NW >= 16 ? 4 : 2))   // second bound: wav
 void mfma_sliced_multiply(const typename OP::T* __restrict__ Xg, typename OP::T* __restrict__ Yg,
                           const typename OP::T* __restrict__ F0, const typename OP::T* __restrict__ F1,
                           int64_t k_in, int64_t k_out, int64_t tiles_per_row, int64_t num_tiles,
-                          int64_t tiles_per_wg)
+                          int64_t tiles_per_wg, int pair_interleave)
 {
     typedef MfmaShape<OP, P, Q, NF, ST, NW, QSPLIT> Sh;
     typedef typename OP::T T;
@@ -186,8 +186,19 @@ void mfma_sliced_multiply(const typename OP::T* __restrict__ Xg, typename OP::T*
         }
 
     const int64_t s_row = tiles_per_row * ST;
-    const int64_t t_begin = (int64_t)blockIdx.x * tiles_per_wg;
+    // Tiles of this workgroup: t_begin, t_begin + t_step, ...  Normally a contiguous range.  With
+    // pair_interleave, two workgroups that the dispatcher places on the same XCD one after the other
+    // (ids b and b + 8) share a range of 2*tiles_per_wg tiles and take alternate ones, so that
+    // neighbouring tiles, whose short output runs fill the same cache lines, are written at about the
+    // same time into the same L2.
+    int64_t t_begin = (int64_t)blockIdx.x * tiles_per_wg, t_step = 1;
     int64_t t_end = t_begin + tiles_per_wg;
+    if (pair_interleave) {
+        const int64_t b = blockIdx.x, xcd = b % 8, k = b / 8;
+        t_begin = ((k >> 1) * 8 + xcd) * tiles_per_wg * 2 + (k & 1);
+        t_step = 2;
+        t_end = t_begin + 2 * tiles_per_wg;
+    }
     if (t_end > num_tiles) t_end = num_tiles;
 
     V pf[RV];
@@ -196,7 +207,7 @@ void mfma_sliced_multiply(const typename OP::T* __restrict__ Xg, typename OP::T*
 #pragma unroll
         for (int i = 0; i < RV; ++i) pf[i] = src[tid + i * NT];
     }
-    for (int64_t t = t_begin; t < t_end; ++t) {
+    for (int64_t t = t_begin; t < t_end; t += t_step) {
         // registers -> LDS rows of P elements with stride RS
 #pragma unroll
         for (int i = 0; i < RV; ++i) {
@@ -204,16 +215,28 @@ void mfma_sliced_multiply(const typename OP::T* __restrict__ Xg, typename OP::T*
             *reinterpret_cast<V*>(tile + (e / P) * RS + (e % P)) = pf[i];
         }
         __syncthreads();
-        if (t + 1 < t_end) {
-            const int64_t tn = t + 1;
-            const V* src = reinterpret_cast<const V*>(Xg + (tn / tiles_per_row) * k_in + (tn % tiles_per_row) * Sh::TK);
-#pragma unroll
-            for (int i = 0; i < RV; ++i) pf[i] = src[tid + i * NT];
-        }
         const int64_t row = t / tiles_per_row, h = t % tiles_per_row;
         T* Yrow = Yg + row * k_out;
-        mfma_stage<OP, P, Q, NF, ST, NW, QSPLIT, 0>(tile, a0, Yrow, s_row, h);
-        if constexpr (NF > 1) mfma_stage<OP, P, Q, NF, ST, NW, QSPLIT, 1>(tile, a1, Yrow, s_row, h);
+        // With two factors the fetch of the next tile is issued after the first stage: its registers
+        // then only coexist with the streaming second stage, not with the held accumulators.
+        if constexpr (NF == 1) {
+            if (t + t_step < t_end) {
+                const int64_t tn = t + t_step;
+                const V* src = reinterpret_cast<const V*>(Xg + (tn / tiles_per_row) * k_in + (tn % tiles_per_row) * Sh::TK);
+#pragma unroll
+                for (int i = 0; i < RV; ++i) pf[i] = src[tid + i * NT];
+            }
+            mfma_stage<OP, P, Q, NF, ST, NW, QSPLIT, 0>(tile, a0, Yrow, s_row, h);
+        } else {
+            mfma_stage<OP, P, Q, NF, ST, NW, QSPLIT, 0>(tile, a0, Yrow, s_row, h);
+            if (t + t_step < t_end) {
+                const int64_t tn = t + t_step;
+                const V* src = reinterpret_cast<const V*>(Xg + (tn / tiles_per_row) * k_in + (tn % tiles_per_row) * Sh::TK);
+#pragma unroll
+                for (int i = 0; i < RV; ++i) pf[i] = src[tid + i * NT];
+            }
+            mfma_stage<OP, P, Q, NF, ST, NW, QSPLIT, 1>(tile, a1, Yrow, s_row, h);
+        }
         __syncthreads();                               // tile fully consumed before it is overwritten
     }
 }

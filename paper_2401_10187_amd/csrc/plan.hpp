@@ -27,11 +27,14 @@ struct Variant {
 // Consecutive tiles handled by one workgroup of a persistent instance; `hint` > 0 forces the value.
 // A workgroup loads its factors once, so it should move at least ten times as many tile bytes as
 // factor bytes, but the launch must keep two workgroups for each of the 256 compute units.
-inline int64_t tiles_per_wg(int64_t num_tiles, int hint, int64_t factor_elems, int64_t tile_elems)
+// Instances so large that one workgroup fills a compute unit's LDS gain from longer walks (measured).
+inline int64_t tiles_per_wg(int64_t num_tiles, int hint, int64_t factor_elems, int64_t tile_elems,
+                            int lds_bytes)
 {
     if (hint > 0) return hint;
     int64_t t = (10 * factor_elems + tile_elems - 1) / tile_elems;
     if (t < 4) t = 4;
+    if (lds_bytes > 80 * 1024 && t < 32) t = 32;
     const int64_t cap = num_tiles / 512;
     if (t > cap) t = cap;
     return t < 1 ? 1 : t;
@@ -58,6 +61,7 @@ struct Options {
     int prefer_tile = 0;      // tuning: choose instances with this tile_slices when one fits
     int prefer_threads = 0;   // tuning: ... with this workgroup size
     int tiles_per_wg = 0;     // tuning: tiles per workgroup of persistent instances (0 = automatic)
+    int pair_interleave = 1;  // neighbouring tiles with short output runs go to workgroup pairs
 };
 
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -181,7 +185,7 @@ inline km_status make_plan(const Problem& pr, const Options& opt, const Variant*
             st.grid = (pr.M / var->rows_per_tile) * (k_cur / pg / var->tile_slices);
             if (var->persistent) {
                 const int64_t tpw = tiles_per_wg(st.grid, opt.tiles_per_wg, (int64_t)nf * var->P * var->Q,
-                                                 (int64_t)var->tile_slices * pg);
+                                                 (int64_t)var->tile_slices * pg, var->lds_bytes);
                 st.grid = (st.grid + tpw - 1) / tpw;
             }
         } else {

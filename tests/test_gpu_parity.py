@@ -33,8 +33,10 @@ def _device():
 class options:
     """Temporarily restrict the planner (kernel families bit mask, fusion depth)."""
 
-    def __init__(self, kernels=None, max_fuse=None):
-        self.new = {km.KM_OPT_KERNELS: kernels, km.KM_OPT_MAX_FUSE: max_fuse}
+    def __init__(self, kernels=None, max_fuse=None, tile=None, threads=None, tiles_per_wg=None, pair=None):
+        self.new = {km.KM_OPT_KERNELS: kernels, km.KM_OPT_MAX_FUSE: max_fuse, km.KM_OPT_PREFER_TILE: tile,
+                    km.KM_OPT_PREFER_THREADS: threads, km.KM_OPT_TILES_PER_WG: tiles_per_wg,
+                    km.KM_OPT_PAIR_INTERLEAVE: pair}
 
     def __enter__(self):
         self.old = {k: km.get_option(k) for k in self.new}
@@ -118,6 +120,49 @@ def test_small_integer_bit_exact(dtype, M, shapes):
         pytest.skip("sums not exactly representable in fp32")
     X, Fs = kron_inputs.make_problem(M, shapes, dtype, "int2", fdist, seed=7)
     assert_close(run_gpu(X, Fs), X, Fs, exact=True)
+
+
+# every compiled instance and launch mode, forced through the tuning options, on mid-size inputs
+FORCED = [
+    ("float32", 64, [(32, 32)] * 3, dict(tile=16, threads=256, tiles_per_wg=1, pair=1)),
+    ("float32", 64, [(32, 32)] * 3, dict(tile=16, threads=256, tiles_per_wg=4, pair=1)),
+    ("float32", 64, [(32, 32)] * 3, dict(tile=16, threads=256, tiles_per_wg=4, pair=0)),
+    ("float32", 16, [(32, 32)] * 3, dict(tile=32, threads=512, tiles_per_wg=3)),
+    ("float32", 16, [(32, 32)] * 3, dict(tile=32, threads=1024, tiles_per_wg=2)),
+    ("float32", 16, [(32, 32)] * 3, dict(max_fuse=1, tile=128)),
+    ("float32", 16, [(32, 32)] * 3, dict(max_fuse=1, tile=256, tiles_per_wg=5)),
+    ("float32", 32, [(16, 32)] * 3, dict(tile=16, tiles_per_wg=2, pair=1)),
+    ("float32", 4, [(16, 32)] * 4, dict(tile=32, tiles_per_wg=2)),
+    ("float32", 8, [(16, 32)] * 3, dict(max_fuse=1, tile=128)),
+    ("float64", 8, [(128, 128)] * 2, dict(tiles_per_wg=7)),
+    ("float64", 8, [(128, 128)] * 2, dict(tiles_per_wg=1)),
+    ("float32", 8, [(8, 8)] * 6, dict(tile=32, threads=256)),
+    ("float32", 8, [(8, 8)] * 6, dict(tile=32, threads=1024)),
+    ("float32", 8, [(8, 8)] * 6, dict(tile=16, threads=256)),
+    ("float32", 8, [(8, 8)] * 6, dict(tile=8, threads=128)),
+    ("float32", 8, [(8, 8)] * 6, dict(tile=1)),
+    ("float32", 8, [(8, 8)] * 6, dict(max_fuse=2, tile=256)),
+    ("float32", 8, [(8, 8)] * 6, dict(max_fuse=2, tile=64)),
+    ("float32", 8, [(8, 8)] * 6, dict(max_fuse=2, tile=8)),
+    ("float32", 8, [(8, 8)] * 6, dict(max_fuse=1, tile=2048)),
+    ("float32", 8, [(8, 8)] * 6, dict(max_fuse=1, tile=64)),
+    ("float32", 8, [(8, 8)] * 6, dict(max_fuse=1, tile=8)),
+]
+
+
+@pytest.mark.parametrize("dtype,M,shapes,opts", FORCED, ids=lambda v: str(v).replace(" ", ""))
+def test_forced_instances(dtype, M, shapes, opts):
+    P = [s[0] for s in shapes]
+    Q = [s[1] for s in shapes]
+    with options(**opts):
+        steps = km.plan(M, P, Q, dtype)
+        if "tile" in opts:
+            assert any(st["tile_slices"] == opts["tile"] for st in steps), steps
+        X, Fs = kron_inputs.make_problem(M, shapes, dtype, "uniform", "normal", seed=17)
+        got = run_gpu(X, Fs)
+        assert_close(got, X, Fs)
+        Xi, Fi = kron_inputs.make_problem(M, shapes, dtype, "int2", "int1", seed=18)
+        assert_close(run_gpu(Xi, Fi), Xi, Fi, exact=True)
 
 
 def test_config1_integer_and_float():
