@@ -10,6 +10,7 @@
 #include "generic_kernel.hpp"
 #include "fused_kernel.hpp"
 #include "mfma_kernel.hpp"
+#include "mfma_pair_kernel.hpp"
 
 namespace km {
 
@@ -71,10 +72,30 @@ static hipError_t launch_mfma(const LaunchArgs& a)
     return hipGetLastError();
 }
 
+template <int P, int ST, int NW>
+static hipError_t launch_mfma_pair(const LaunchArgs& a)
+{
+    typedef MfmaPairShape<P, ST, NW> Sh;
+    const km_plan_step& st = *a.st;
+    auto kern = mfma_pair_sliced_multiply<P, ST, NW>;
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, Sh::LDS_BYTES);
+    if (e != hipSuccess) return e;
+    const float* f0 = (const float*)a.factors[st.first_factor + 1];    // applied first
+    const float* f1 = (const float*)a.factors[st.first_factor];
+    const int64_t tiles_per_row = st.k_in / Sh::TK;
+    const int64_t num_tiles = a.pr->M * tiles_per_row;
+    const int64_t tpw = tiles_per_wg(num_tiles, a.tiles_per_wg_hint, (int64_t)2 * P * Sh::Q, (int64_t)Sh::TK, Sh::LDS_BYTES);
+    if ((num_tiles + tpw - 1) / tpw != st.grid) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(kern, dim3((unsigned)st.grid), dim3(Sh::NT), Sh::LDS_BYTES, a.stream,
+                       (const float*)a.src, (float*)a.dst, f0, f1, st.k_in, st.k_out, tiles_per_row, num_tiles, tpw);
+    return hipGetLastError();
+}
+
 // Fused FMA instances: X(type, dtype code, P, Q, factors per launch, tile_slices, threads).
+// Register-resident MFMA pairs: Z(P, tile_slices, wavefronts) (fp32, Q = 32, two factors).
 // MFMA instances: Y(op, dtype code, P, Q, factors per launch, tile_slices, wavefronts, q split).
 // Order = preference among instances that fit a shape.
-#define KM_INSTANCES(X, Y)                              \
+#define KM_INSTANCES(X, Y, Z)                            \
     X(float, KM_F32, 8, 8, 3, 32, 1024)                 \
     X(float, KM_F32, 8, 8, 3, 32, 256)                  \
     X(float, KM_F32, 8, 8, 3, 16, 256)                  \
@@ -88,11 +109,13 @@ static hipError_t launch_mfma(const LaunchArgs& a)
     X(float, KM_F32, 8, 8, 1, 64, 64)                   \
     X(float, KM_F32, 8, 8, 1, 8, 64)                    \
     X(float, KM_F32, 8, 8, 1, 1, 64)                    \
+    Z(32, 32, 4)                                        \
     Y(MfmaF32x32, KM_F32, 32, 32, 2, 32, 8, 1)          \
     Y(MfmaF32x32, KM_F32, 32, 32, 2, 32, 16, 1)         \
     Y(MfmaF32x32, KM_F32, 32, 32, 2, 16, 4, 1)          \
     Y(MfmaF32x32, KM_F32, 32, 32, 1, 256, 4, 1)         \
     Y(MfmaF32x32, KM_F32, 32, 32, 1, 128, 4, 1)         \
+    Z(16, 32, 4)                                        \
     Y(MfmaF32x32, KM_F32, 16, 32, 2, 32, 4, 1)          \
     Y(MfmaF32x32, KM_F32, 16, 32, 2, 16, 4, 1)          \
     Y(MfmaF32x32, KM_F32, 16, 32, 1, 256, 4, 1)         \
@@ -103,11 +126,14 @@ static hipError_t launch_mfma(const LaunchArgs& a)
     {KM_KERNEL_FUSED, DT, P, Q, NF, ST, NT, FusedShape<T, P, Q, NF, ST, NT>::LDS_BYTES, 1, 0, "fused"},
 #define KM_MFMA_ROW(OP, DT, P, Q, NF, ST, NW, QS) \
     {KM_KERNEL_MFMA, DT, P, Q, NF, ST, NW * 64, MfmaShape<OP, P, Q, NF, ST, NW, QS>::LDS_BYTES, 1, 1, "mfma"},
+#define KM_PAIR_ROW(P, ST, NW) \
+    {KM_KERNEL_MFMA, KM_F32, P, 32, 2, ST, NW * 64, MfmaPairShape<P, ST, NW>::LDS_BYTES, 1, 1, "mfma-pair"},
+#define KM_PAIR_FN(P, ST, NW) launch_mfma_pair<P, ST, NW>,
 #define KM_FUSED_FN(T, DT, P, Q, NF, ST, NT) launch_fused<T, P, Q, NF, ST, NT>,
 #define KM_MFMA_FN(OP, DT, P, Q, NF, ST, NW, QS) launch_mfma<OP, P, Q, NF, ST, NW, QS>,
 
-static const Variant g_variants[] = { KM_INSTANCES(KM_FUSED_ROW, KM_MFMA_ROW) };
-static const LaunchFn g_launchers[] = { KM_INSTANCES(KM_FUSED_FN, KM_MFMA_FN) };
+static const Variant g_variants[] = { KM_INSTANCES(KM_FUSED_ROW, KM_MFMA_ROW, KM_PAIR_ROW) };
+static const LaunchFn g_launchers[] = { KM_INSTANCES(KM_FUSED_FN, KM_MFMA_FN, KM_PAIR_FN) };
 static const int g_num_variants = (int)(sizeof(g_variants) / sizeof(g_variants[0]));
 
 template <typename T>

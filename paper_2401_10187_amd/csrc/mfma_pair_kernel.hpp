@@ -1,0 +1,177 @@
+// Two fused sliced multiplies on the matrix cores with the intermediate kept in registers
+// (fusion of section 4.2 of the paper with N_fused = 2; fp32, P x 32 factors, P = 16 or 32).
+//
+// A tile is ST*P*P contiguous elements of one row: X[a][p1][p2], a < ST.  The pair of factors maps
+// it to Y[(q1, q2)][a], stored at column (q1*Q + q2)*(K_in/P^2) + h*ST + a of the output row (h =
+// tile index in the row), exactly as the LDS-resident fused kernels do.
+//
+// For one `a` both contractions are dense products and the accumulator layout of the first is the
+// B-operand layout of the second:
+//   stage 0   D0[p1][q2] = sum_p2 X[a][p1][p2] * F0[p2][q2]      A = X_a  (rows p1), B = F0
+//   stage 1   D1[q1][q2] = sum_p1 F1[p1][q1]   * D0[p1][q2]      A = F1^T (rows q1), B = D0
+// v_mfma_f32_32x32x2_f32 leaves D0 with column q2 on lane%32 and row 8*(v/4) + 4*(lane/32) + v%4 in
+// register v; taken as a B operand, register t of lane half g therefore supplies k = p1 =
+// 8*(t/4) + 4*g + t%4, and the A operand (F1) is loaded in that same order.  The intermediate never
+// leaves the registers: no LDS, no barrier, no transposition between the two stages.
+// With P = 16 one 32-row stage-0 product covers two values of `a`.
+//
+// X is read straight from global memory into the A-operand registers (each lane takes P/2
+// contiguous elements of its slice).  Only the result passes through LDS, to turn "one a per
+// wavefront pass" into contiguous runs of ST elements along `a`: D1 of all the tile's `a` is written
+// as rows (q1, q2) of ST elements, then read back 16 bytes per lane and stored with 16-byte global
+// stores, half of the q1 range at a time so that two workgroups fit a compute unit.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "fused_kernel.hpp"   // Vec16
+
+namespace km {
+
+template <int P, int ST, int NW>
+struct MfmaPairShape {
+    static constexpr int Q = 32;
+    static constexpr int NT = NW * 64;
+    static constexpr int AP = 32 / P;                 // values of `a` per 32-row stage-0 product
+    static constexpr int KS = P / 2;                  // MFMA steps per product (2 k values per step)
+    static constexpr int UNITS = ST / AP;             // stage-0 products per tile
+    static constexpr int UPW = UNITS / NW;            // ... per wavefront
+    static constexpr int APW = UPW * AP;              // values of `a` per wavefront
+    static constexpr int TK = ST * P * P;
+    static constexpr int STP = ST + 4;                // padded row of the output staging buffer
+    static constexpr int PASS_ROWS = 16 * Q;          // rows (q1_local, q2) of one output pass
+    static constexpr int LDS_BYTES = PASS_ROWS * STP * 4;
+    static constexpr int RD = PASS_ROWS * (ST / 4) / NT;   // 16-byte reads per thread and pass
+    static_assert(P == 16 || P == 32, "P must be 16 or 32");
+    static_assert(ST % (AP * NW) == 0 && ST % 4 == 0, "tile must split evenly over the wavefronts");
+    static_assert((PASS_ROWS * (ST / 4)) % NT == 0, "output pass must split evenly over the threads");
+    static_assert(UPW % 2 == 0, "the operand double buffer alternates per unit and must wrap per tile");
+    static_assert(RD % 4 == 0, "output reads are issued four at a time");
+};
+
+typedef float pair_f32x16 __attribute__((ext_vector_type(16)));
+typedef float pair_f32x4 __attribute__((ext_vector_type(4)));
+
+template <int P, int ST, int NW>
+__global__ __launch_bounds__(NW * 64, 2)
+void mfma_pair_sliced_multiply(const float* __restrict__ Xg, float* __restrict__ Yg,
+                               const float* __restrict__ F0, const float* __restrict__ F1,   // in order of application
+                               int64_t k_in, int64_t k_out, int64_t tiles_per_row, int64_t num_tiles,
+                               int64_t tiles_per_wg)
+{
+    typedef MfmaPairShape<P, ST, NW> Sh;
+    constexpr int Q = Sh::Q, KS = Sh::KS, AP = Sh::AP, UPW = Sh::UPW, STP = Sh::STP, NT = Sh::NT;
+    extern __shared__ __attribute__((aligned(16))) unsigned char pair_lds[];
+    float* stage = reinterpret_cast<float*>(pair_lds);
+
+    const int tid = threadIdx.x;
+    const int lane = tid % 64, wave = tid / 64;
+    const int col = lane % 32;        // stage 0: row (a_loc, p1) of A, column q2 of B; stage 1: row q1 of A
+    const int g = lane / 32;          // which of the two k values of an MFMA step this lane holds
+
+    // B operand of stage 0: F0[p2][q2], p2 = g*KS + t.   A operand of stage 1: F1[p1][q1] with
+    // p1 = 8*(t/4) + 4*g + t%4, the row that accumulator register t of lane half g holds.
+    float b0[KS], a1[KS];
+#pragma unroll
+    for (int t = 0; t < KS; ++t) {
+        b0[t] = F0[(g * KS + t) * Q + col];
+        a1[t] = F1[(8 * (t / 4) + 4 * g + (t % 4)) * Q + col];
+    }
+
+    const int64_t s_row = tiles_per_row * ST;
+    const int64_t t_begin = (int64_t)blockIdx.x * tiles_per_wg;
+    int64_t t_end = t_begin + tiles_per_wg;
+    if (t_end > num_tiles) t_end = num_tiles;
+
+    // element offset, inside a tile, of this lane's piece of unit u of this wavefront
+    const int lane_off = col * P + g * KS;
+    auto tile_src = [&](int64_t t) { return Xg + (t / tiles_per_row) * k_in + (t % tiles_per_row) * Sh::TK; };
+
+    pair_f32x4 xa[2][KS / 4];         // double-buffered A operand of stage 0
+    if (t_begin < t_end) {
+        const pair_f32x4* src = reinterpret_cast<const pair_f32x4*>(tile_src(t_begin) + (wave * AP) * P * P + lane_off);
+#pragma unroll
+        for (int c = 0; c < KS / 4; ++c) xa[0][c] = src[c];
+    }
+
+    for (int64_t t = t_begin; t < t_end; ++t) {
+        const float* Xt = tile_src(t);
+        // Registers 0-7 of a stage-1 accumulator hold q1 < 16 and go to the staging buffer at once
+        // (it is free: the previous tile's last pass ended with a barrier); registers 8-15 (q1 >= 16)
+        // wait here for the second pass.
+        float keep[Sh::APW][8];
+#pragma unroll
+        for (int u = 0; u < UPW; ++u) {
+            // fetch the next unit (of this tile, or the first one of the next tile)
+            if (u + 1 < UPW) {
+                const pair_f32x4* src = reinterpret_cast<const pair_f32x4*>(Xt + ((wave + (u + 1) * NW) * AP) * P * P + lane_off);
+#pragma unroll
+                for (int c = 0; c < KS / 4; ++c) xa[(u + 1) % 2][c] = src[c];
+            } else if (t + 1 < t_end) {
+                const pair_f32x4* src = reinterpret_cast<const pair_f32x4*>(tile_src(t + 1) + (wave * AP) * P * P + lane_off);
+#pragma unroll
+                for (int c = 0; c < KS / 4; ++c) xa[(u + 1) % 2][c] = src[c];
+            }
+            pair_f32x16 d0;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) d0[v] = 0.f;
+#pragma unroll
+            for (int s = 0; s < KS; ++s)
+                d0 = __builtin_amdgcn_mfma_f32_32x32x2f32(xa[u % 2][s / 4][s % 4], b0[s], d0, 0, 0, 0);
+#pragma unroll
+            for (int al = 0; al < AP; ++al) {
+                pair_f32x16 acc;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+#pragma unroll
+                for (int s = 0; s < KS; ++s)
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[s], d0[al * KS + s], acc, 0, 0, 0);
+                const int a = (wave + u * NW) * AP + al;
+#pragma unroll
+                for (int w = 0; w < 8; ++w) {
+                    const int q1l = 8 * (w / 4) + 4 * g + (w % 4);           // q1 of register w (and of 8 + w, minus 16)
+                    stage[(q1l * Q + col) * STP + a] = acc[w];
+                    keep[u * AP + al][w] = acc[8 + w];
+                }
+            }
+        }
+
+        const int64_t row = t / tiles_per_row, h = t % tiles_per_row;
+        float* Yrow = Yg + row * k_out + h * ST;
+#pragma unroll
+        for (int pass = 0; pass < 2; ++pass) {
+            if (pass == 1) {
+#pragma unroll
+                for (int u = 0; u < UPW; ++u)
+#pragma unroll
+                    for (int al = 0; al < AP; ++al) {
+                        const int a = (wave + u * NW) * AP + al;
+#pragma unroll
+                        for (int w = 0; w < 8; ++w) {
+                            const int q1l = 8 * (w / 4) + 4 * g + (w % 4);
+                            stage[(q1l * Q + col) * STP + a] = keep[u * AP + al][w];
+                        }
+                    }
+            }
+            __syncthreads();
+            // row r = (q1l, q2) of the staging buffer -> output column ((16*pass + q1l)*Q + q2)*s_row + h*ST + a
+            float* Ypass = Yrow + (int64_t)(16 * pass * Q) * s_row;
+#pragma unroll
+            for (int i0 = 0; i0 < Sh::RD; i0 += 4) {
+                pair_f32x4 v[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int idx = tid + (i0 + i) * NT;
+                    v[i] = *reinterpret_cast<const pair_f32x4*>(stage + (idx / (ST / 4)) * STP + 4 * (idx % (ST / 4)));
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int idx = tid + (i0 + i) * NT;
+                    *reinterpret_cast<pair_f32x4*>(Ypass + (int64_t)(idx / (ST / 4)) * s_row + 4 * (idx % (ST / 4))) = v[i];
+                }
+            }
+            __syncthreads();
+        }
+    }
+}
+
+}  // namespace km
