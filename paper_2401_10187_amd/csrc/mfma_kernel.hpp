@@ -134,7 +134,7 @@ __device__ __forceinline__ void mfma_stage(typename OP::T* __restrict__ tile,
             for (int qt = 0; qt < QTW; ++qt)
 #pragma unroll
                 for (int v = 0; v < OP::NACC; ++v)
-                    Yrow[off + (qt * OP::MB + OP::row_reg(v)) * QREST * sr] = acc[0][qt][v];
+                    stream_store(acc[0][qt][v], &Yrow[off + (qt * OP::MB + OP::row_reg(v)) * QREST * sr]);
         }
     }
     if constexpr (!LAST) {
@@ -205,7 +205,7 @@ void mfma_sliced_multiply(const typename OP::T* __restrict__ Xg, typename OP::T*
     if (t_begin < t_end) {
         const V* src = reinterpret_cast<const V*>(Xg + (t_begin / tiles_per_row) * k_in + (t_begin % tiles_per_row) * Sh::TK);
 #pragma unroll
-        for (int i = 0; i < RV; ++i) pf[i] = src[tid + i * NT];
+        for (int i = 0; i < RV; ++i) pf[i] = stream_load(&src[tid + i * NT]);
     }
     for (int64_t t = t_begin; t < t_end; t += t_step) {
         // registers -> LDS rows of P elements with stride RS
@@ -224,7 +224,7 @@ void mfma_sliced_multiply(const typename OP::T* __restrict__ Xg, typename OP::T*
                 const int64_t tn = t + t_step;
                 const V* src = reinterpret_cast<const V*>(Xg + (tn / tiles_per_row) * k_in + (tn % tiles_per_row) * Sh::TK);
 #pragma unroll
-                for (int i = 0; i < RV; ++i) pf[i] = src[tid + i * NT];
+                for (int i = 0; i < RV; ++i) pf[i] = stream_load(&src[tid + i * NT]);
             }
             mfma_stage<OP, P, Q, NF, ST, NW, QSPLIT, 0>(tile, a0, Yrow, s_row, h);
         } else {
@@ -233,7 +233,7 @@ void mfma_sliced_multiply(const typename OP::T* __restrict__ Xg, typename OP::T*
                 const int64_t tn = t + t_step;
                 const V* src = reinterpret_cast<const V*>(Xg + (tn / tiles_per_row) * k_in + (tn % tiles_per_row) * Sh::TK);
 #pragma unroll
-                for (int i = 0; i < RV; ++i) pf[i] = src[tid + i * NT];
+                for (int i = 0; i < RV; ++i) pf[i] = stream_load(&src[tid + i * NT]);
             }
             mfma_stage<OP, P, Q, NF, ST, NW, QSPLIT, 1>(tile, a1, Yrow, s_row, h);
         }

@@ -166,7 +166,7 @@ void mfma_pair_sliced_multiply(const float* __restrict__ Xg, float* __restrict__
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const int idx = tid + (i0 + i) * NT;
-                    *reinterpret_cast<pair_f32x4*>(Ypass + (int64_t)(idx / (ST / 4)) * s_row + 4 * (idx % (ST / 4))) = v[i];
+                    stream_store(v[i], reinterpret_cast<pair_f32x4*>(Ypass + (int64_t)(idx / (ST / 4)) * s_row + 4 * (idx % (ST / 4))));
                 }
             }
             __syncthreads();
