@@ -28,11 +28,11 @@ PAPER_GFLOPS = {"c2_f32_m1024_8x8x6": 25769803776 / 5.76e-3 / 1e9,
 # (summaries under profiles/); None until measured.
 MEASURED_TRAFFIC = {
     # scaled FETCH_SIZE + WRITE_SIZE of the dominant kernel, from the summaries under profiles/
-    "c1_f32_m16_8x8x3": 89276,             # fused_f32_8x8_nf3_c1_m16_8x8x3.md
-    "c2_f32_m1024_8x8x6": 2147495012,      # fused_f32_8x8_nf3_c2_m1024_8x8x6.md
-    "c3_f32_m1024_32x32x4": 8590280454,    # mfma_f32_32x32_nf2_c3_m1024_32x32x4.md
-    "c4_f64_m16_128x128x3": 537961194,     # mfma_f64_128x128_nf1_c4_m16_128x128x3.md
-    "c5_f32_m256_16x32x4": 1342433236,     # mfma_f32_16x32_nf2_c5_m256_16x32x4.md
+    "c1_f32_m16_8x8x3": 84950,             # fused_f32_8x8_nf3_c1_m16_8x8x3.md
+    "c2_f32_m1024_8x8x6": 2147944301,      # fused_f32_8x8_nf3_c2_m1024_8x8x6.md
+    "c3_f32_m1024_32x32x4": 8936075954,    # mfma_f32_32x32_nf2_c3_m1024_32x32x4.md
+    "c4_f64_m16_128x128x3": 537968780,     # mfma_f64_128x128_nf1_c4_m16_128x128x3.md
+    "c5_f32_m256_16x32x4": 1342570435,     # mfma_f32_16x32_nf2_c5_m256_16x32x4.md
 }
 
 
@@ -156,7 +156,7 @@ def main():
         import oracle
         # bounded sample: enough rows of the same workload for roughly 10-30 s of CPU work
         macs_per_row = flops / 2 / M
-        rows = int(max(1, min(M, 1.2e10 // macs_per_row)))
+        rows = int(max(1, min(M, 4e10 // macs_per_row)))
         c0 = time.perf_counter()
         ref = oracle.kron_matmul(X[:rows], Fs)
         cpu_s = time.perf_counter() - c0

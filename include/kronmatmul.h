@@ -15,6 +15,8 @@
  *   - All matrices are dense, row-major, without padding.
  *   - P, Q and the array F itself are HOST memory; X, Y, the workspace and every F[i] are DEVICE
  *     memory on the current HIP device.  F[0] is the leftmost factor (slowest index digit).
+ *   - X, Y and the workspace must be 16-byte aligned (hipMalloc and torch allocations are); factors
+ *     need only their element's alignment.  KM_EINVAL otherwise.
  *   - The caller owns every buffer.  X and the factors are only read.  Y may be used as scratch
  *     for intermediates before it receives the result.  X, Y and the workspace must not overlap.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is enqueued

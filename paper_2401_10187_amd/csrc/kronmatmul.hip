@@ -243,13 +243,16 @@ static km_status run(const Problem& pr, const Plan& plan, const void* X, const v
     return KM_OK;
 }
 
+static bool aligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
+
 static km_status check_pointers(const Problem& pr, const void* X, const void* const* F, void* Y)
 {
     if (!F) return KM_EINVAL;
     if (pr.M == 0) return KM_OK;
     if (!X || !Y) return KM_EINVAL;
+    if (!aligned(X, 16) || !aligned(Y, 16)) return KM_EINVAL;      // kernels use 16-byte accesses
     for (int i = 0; i < pr.N; ++i)
-        if (!F[i]) return KM_EINVAL;
+        if (!F[i] || !aligned(F[i], pr.esize)) return KM_EINVAL;
     return KM_OK;
 }
 
@@ -288,6 +291,7 @@ km_status kronmatmul_ws(int M, int N, const int* P, const int* Q, const void* X,
     if (s != KM_OK) return s;
     const size_t need = plan.ws0_bytes + plan.ws1_bytes;
     if (need > 0 && (!workspace || workspace_bytes < need)) return KM_ENOMEM;
+    if (need > 0 && !aligned(workspace, 16)) return KM_EINVAL;
     return run(pr, plan, X, F, Y, workspace, (hipStream_t)stream);
 }
 

@@ -129,6 +129,44 @@ def test_workspace_follows_algorithm_1_buffers():
     assert km.workspace_size(M, [4], [7], "float32") == 0
 
 
+def test_tuning_options_round_trip():
+    for opt, good, bad in ((km.KM_OPT_PREFER_TILE, 16, -1), (km.KM_OPT_PREFER_THREADS, 256, 5000),
+                           (km.KM_OPT_TILES_PER_WG, 8, -2), (km.KM_OPT_PAIR_INTERLEAVE, 0, 2),
+                           (km.KM_OPT_PROFILE, 1, 3)):
+        old = km.get_option(opt)
+        try:
+            km.set_option(opt, good)
+            assert km.get_option(opt) == good
+            with pytest.raises(km.KronMatmulError):
+                km.set_option(opt, bad)
+            assert km.get_option(opt) == good
+        finally:
+            km.set_option(opt, old)
+
+
+def test_planner_prefers_fusion_and_mfma_for_the_measured_workloads():
+    import kron_inputs
+    want = {"c1_f32_m16_8x8x3": [(km.KM_KERNEL_FUSED, 3)],
+            "c2_f32_m1024_8x8x6": [(km.KM_KERNEL_FUSED, 3)] * 2,
+            "c3_f32_m1024_32x32x4": [(km.KM_KERNEL_MFMA, 2)] * 2,
+            "c4_f64_m16_128x128x3": [(km.KM_KERNEL_MFMA, 1)] * 3,
+            "c5_f32_m256_16x32x4": [(km.KM_KERNEL_MFMA, 2)] * 2}
+    for name, steps in want.items():
+        c = kron_inputs.CONFIGS[name]
+        got = km.plan(c["M"], [s[0] for s in c["shapes"]], [s[1] for s in c["shapes"]], c["dtype"])
+        assert [(st["kernel"], st["num_factors"]) for st in got] == steps, name
+        # 128-byte output runs wherever the row is long enough
+        if name != "c1_f32_m16_8x8x3":
+            es = 4 if c["dtype"] == "float32" else 8
+            assert all(st["tile_slices"] * es >= 128 for st in got), name
+
+
+def test_tile_instances_are_skipped_for_rows_beyond_32_bit_offsets():
+    # 2^31 bytes per row and more: only the generic kernel addresses such rows
+    steps = km.plan(1, [8] * 10, [8] * 10, "float32")
+    assert all(st["kernel"] == km.KM_KERNEL_GENERIC for st in steps)
+
+
 def test_options_round_trip():
     old = km.get_option(km.KM_OPT_MAX_FUSE)
     try:
@@ -175,6 +213,9 @@ def test_argument_errors_are_status_codes():
     assert _raw(4, [2], [2], bad, [bad], bad, dtype=7) == km.KM_EINVAL
     assert _raw(4, [2 ** 20] * 3, [2] * 3, bad, [bad] * 3, bad) == km.KM_EINVAL      # width overflow
     assert _raw(2 ** 31 - 1, [2 ** 15] * 2, [2 ** 15] * 2, bad, [bad] * 2, bad) == km.KM_EINVAL
+    assert _raw(4, [2], [2], bad + 4, [bad], bad) == km.KM_EINVAL            # X not 16-byte aligned
+    assert _raw(4, [2], [2], bad, [bad], bad + 8) == km.KM_EINVAL            # Y not 16-byte aligned
+    assert _raw(4, [2], [2], bad, [bad + 2], bad) == km.KM_EINVAL            # factor not element aligned
     # M == 0 is a successful no-op, with or without buffers
     assert _raw(0, [2, 3], [2, 3], None, [bad, bad], None) == km.KM_OK
     assert _raw(0, [2, 3], [2, 3], None, [bad, bad], None, with_ws=True) == km.KM_OK
