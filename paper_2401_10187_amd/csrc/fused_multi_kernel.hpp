@@ -1,0 +1,197 @@
+// Fused sliced multiplies for very small factors (P, Q <= 8): several factors per LDS pass.
+//
+// Same tile and same final scatter as fused_kernel.hpp (section 4.2 of the paper), but a thread
+// now owns a group of P^G contiguous elements and applies G factors to it entirely in registers
+// before anything goes back to LDS.  Applying the sliced-multiply rule of Algorithm 1 G times to the
+// P^G elements seen as a tiny row gives them the order (q_1, ..., q_G), i.e. exactly the column
+// index qq of the G-factor group, so the LDS write of a "super-stage" is the ordinary rule with
+// Q^G columns: (group s, column qq) -> qq*S + s.  With P = 2 three factors cost one LDS round trip
+// instead of three; with P = 4 two factors do.
+//
+// Up to three super-stages (G0, G1, G2 factors; 0 = unused) per launch.  Factor elements are read
+// with scalar loads, as in fused_kernel.hpp.  LDS rows (one group each) are padded when their
+// length is an even number of 16-byte units above two, which would otherwise put the 16-byte reads
+// of eight consecutive lanes into the same banks.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "fused_kernel.hpp"   // ipow, Vec16, as_constant, stream_load/stream_store
+
+namespace km {
+
+template <int N> struct FactorPtrs { const void* f[N]; };
+
+// STMAX bounds the tile (LDS, registers, unrolled trip counts); the number of slices actually in a
+// tile, st <= STMAX, is a launch parameter so that one instance serves every row length whose
+// K/P^NF has a divisor in range (rows of 3^7 or 6^7 elements, M = 1 problems, ...).
+template <typename T, int P, int Q, int G0, int G1, int G2, int STMAX, int NT>
+struct MultiShape {
+    static constexpr int NS = (G0 > 0) + (G1 > 0) + (G2 > 0);
+    static constexpr int NF = G0 + G1 + G2;
+    static constexpr int VN = Vec16<T>::N;
+    static constexpr int g(int j) { return j == 0 ? G0 : (j == 1 ? G1 : G2); }
+    static constexpr int done(int j) { return (j > 0 ? G0 : 0) + (j > 1 ? G1 : 0) + (j > 2 ? G2 : 0); }
+    static constexpr int per_slice(int j) { return (int)(ipow(P, NF - done(j)) * ipow(Q, done(j))); }   // tile elements per unit of st
+    static constexpr int pg(int j) { return (int)ipow(P, g(j)); }      // elements a thread reads per group
+    static constexpr int qg(int j) { return (int)ipow(Q, g(j)); }      // elements it produces
+    static constexpr int wmax(int j) { return (int)ipow(P > Q ? P : Q, g(j)); }
+    static constexpr int pad(int j)
+    {
+        const int bytes = pg(j) * (int)sizeof(T);
+        if (bytes % 16) return 0;
+        const int units = bytes / 16;
+        return (units % 2 == 0 && units > 2) ? VN : 0;
+    }
+    static constexpr int rows_per_slice(int j) { return per_slice(j) / pg(j); }     // groups per unit of st
+    static constexpr int max_rows(int j) { return STMAX * rows_per_slice(j); }
+    static constexpr int lds_elems()
+    {
+        int m = 0;
+        for (int j = 0; j < NS; ++j) {
+            const int e = max_rows(j) * (pg(j) + pad(j));
+            m = e > m ? e : m;
+        }
+        return m;
+    }
+    static constexpr int LDS_BYTES = (lds_elems() * (int)sizeof(T) + 15) / 16 * 16;
+    static constexpr bool VEC_ROWS = pg(0) % VN == 0;
+    static_assert(G0 > 0 && (G1 > 0 || G2 == 0), "super-stages are filled from the first");
+};
+
+// position in LDS of flat tile index c when rows of `PGN` elements are padded by `PADN`
+template <int PGN, int PADN>
+__device__ __forceinline__ int multi_lds_index(int c) { return PADN == 0 ? c : c + (c / PGN) * PADN; }
+
+template <typename T, int P, int Q, int G0, int G1, int G2, int STMAX, int NT, int J>
+__device__ __forceinline__ void multi_stage(T* __restrict__ tile, const FactorPtrs<G0 + G1 + G2>& fp,
+                                            T* __restrict__ Yrow, int64_t s_row, int64_t h, int st)
+{
+    typedef MultiShape<T, P, Q, G0, G1, G2, STMAX, NT> Sh;
+    typedef typename Vec16<T>::type V;
+    constexpr int VN = Sh::VN;
+    constexpr int GJ = Sh::g(J), PGJ = Sh::pg(J), QGJ = Sh::qg(J), PADJ = Sh::pad(J), WMAX = Sh::wmax(J);
+    constexpr int R = (Sh::max_rows(J) + NT - 1) / NT;
+    constexpr bool LAST = J == Sh::NS - 1;
+    const int SJ = st * Sh::rows_per_slice(J);           // groups in the tile at this super-stage
+    const int tid = threadIdx.x;
+
+    T out[R][QGJ];
+#pragma unroll
+    for (int i = 0; i < R; ++i) {
+        const int s = tid + i * NT;
+        T x[WMAX], y[WMAX];
+        if (s < SJ) {
+            const T* src = tile + s * (PGJ + PADJ);
+            if constexpr ((PGJ * sizeof(T)) % 16 == 0) {
+#pragma unroll
+                for (int c = 0; c < PGJ / VN; ++c) {
+                    const V v = reinterpret_cast<const V*>(src)[c];
+#pragma unroll
+                    for (int e = 0; e < VN; ++e) x[VN * c + e] = v[e];
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < PGJ; ++e) x[e] = src[e];
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < PGJ; ++e) x[e] = T(0);
+        }
+        // G factors in registers: the rule of Algorithm 1 on a row of W = P^(G-gi) * Q^gi elements
+#pragma unroll
+        for (int gi = 0; gi < GJ; ++gi) {
+            const auto Fc = as_constant(static_cast<const T*>(fp.f[Sh::done(J) + gi]));
+            const int W = (int)(ipow(P, GJ - gi) * ipow(Q, gi));
+            const int S = W / P;
+#pragma unroll
+            for (int sp = 0; sp < S; ++sp)
+#pragma unroll
+                for (int q = 0; q < Q; ++q) {
+                    T acc = x[sp * P] * Fc[q];
+#pragma unroll
+                    for (int p = 1; p < P; ++p) acc += x[sp * P + p] * Fc[p * Q + q];
+                    y[q * S + sp] = acc;
+                }
+#pragma unroll
+            for (int e = 0; e < S * Q; ++e) x[e] = y[e];
+        }
+#pragma unroll
+        for (int qq = 0; qq < QGJ; ++qq) out[i][qq] = x[qq];
+    }
+    if constexpr (!LAST) {
+        constexpr int PGN = Sh::pg(J + 1), PADN = Sh::pad(J + 1);
+        __syncthreads();                                 // every group has been read
+#pragma unroll
+        for (int i = 0; i < R; ++i) {
+            const int s = tid + i * NT;
+            if (s < SJ) {
+#pragma unroll
+                for (int qq = 0; qq < QGJ; ++qq) tile[multi_lds_index<PGN, PADN>(qq * SJ + s)] = out[i][qq];
+            }
+        }
+        __syncthreads();
+    } else {
+        // local (qq, s) with s = qrest*st + r  ->  column (qq*Q^done + qrest)*s_row + h*st + r
+        constexpr int QREST = (int)ipow(Q, Sh::done(J));
+#pragma unroll
+        for (int i = 0; i < R; ++i) {
+            const int s = tid + i * NT;
+            if (s < SJ) {
+                T* dst = Yrow + (int64_t)(s / st) * s_row + h * st + (s % st);
+#pragma unroll
+                for (int qq = 0; qq < QGJ; ++qq) stream_store(out[i][qq], &dst[(int64_t)(qq * QREST) * s_row]);
+            }
+        }
+    }
+}
+
+template <typename T, int P, int Q, int G0, int G1, int G2, int STMAX, int NT>
+__global__ __launch_bounds__(NT)
+void fused_multi_sliced_multiply(const T* __restrict__ Xg, T* __restrict__ Yg,
+                                 const FactorPtrs<G0 + G1 + G2> fp,     // in order of application
+                                 int64_t k_in, int64_t k_out, int64_t tiles_per_row, int64_t num_tiles, int st)
+{
+    typedef MultiShape<T, P, Q, G0, G1, G2, STMAX, NT> Sh;
+    typedef typename Vec16<T>::type V;
+    constexpr int VN = Sh::VN;
+    extern __shared__ __attribute__((aligned(16))) unsigned char multi_lds[];
+    T* tile = reinterpret_cast<T*>(multi_lds);
+
+    // XCD-aware order: workgroup b runs on XCD b % 8; give each XCD a contiguous range of tiles
+    int64_t t = blockIdx.x;
+    if (num_tiles % 8 == 0) t = (t % 8) * (num_tiles / 8) + t / 8;
+    const int64_t row = t / tiles_per_row;
+    const int64_t h = t % tiles_per_row;
+    const int tk = st * Sh::per_slice(0);                // elements in this tile
+    const T* src = Xg + row * k_in + h * tk;
+    T* Yrow = Yg + row * k_out;
+    const int64_t s_row = tiles_per_row * st;
+    const int tid = threadIdx.x;
+    constexpr int PG0 = Sh::pg(0), PAD0 = Sh::pad(0);
+
+    // 16-byte loads need every tile to start on a 16-byte boundary and rows of whole vectors
+    if (Sh::VEC_ROWS && tk % VN == 0 && k_in % VN == 0) {
+        const int nv = tk / VN;
+        constexpr int RV = (STMAX * Sh::per_slice(0) / VN + NT - 1) / NT;
+        V tmp[RV];
+#pragma unroll
+        for (int i = 0; i < RV; ++i) {
+            const int v = tid + i * NT;
+            if (v < nv) tmp[i] = stream_load(&reinterpret_cast<const V*>(src)[v]);
+        }
+#pragma unroll
+        for (int i = 0; i < RV; ++i) {
+            const int v = tid + i * NT;
+            if (v < nv) *reinterpret_cast<V*>(tile + multi_lds_index<PG0, PAD0>(v * VN)) = tmp[i];
+        }
+    } else {
+        for (int e = tid; e < tk; e += NT) tile[multi_lds_index<PG0, PAD0>(e)] = src[e];
+    }
+    __syncthreads();
+
+    multi_stage<T, P, Q, G0, G1, G2, STMAX, NT, 0>(tile, fp, Yrow, s_row, h, st);
+    if constexpr (Sh::NS > 1) multi_stage<T, P, Q, G0, G1, G2, STMAX, NT, 1>(tile, fp, Yrow, s_row, h, st);
+    if constexpr (Sh::NS > 2) multi_stage<T, P, Q, G0, G1, G2, STMAX, NT, 2>(tile, fp, Yrow, s_row, h, st);
+}
+
+}  // namespace km

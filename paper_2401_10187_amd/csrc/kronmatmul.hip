@@ -9,6 +9,7 @@
 #include "plan.hpp"
 #include "generic_kernel.hpp"
 #include "fused_kernel.hpp"
+#include "fused_multi_kernel.hpp"
 #include "mfma_kernel.hpp"
 #include "mfma_pair_kernel.hpp"
 
@@ -45,6 +46,28 @@ static hipError_t launch_fused(const LaunchArgs& a)
     hipLaunchKernelGGL(kern, dim3((unsigned)st.grid), dim3(NT), Sh::LDS_BYTES, a.stream,
                        (const T*)a.src, (T*)a.dst, f[0], f[1], f[2], st.k_in, st.k_out, tiles_per_row,
                        (int64_t)st.grid);
+    return hipGetLastError();
+}
+
+template <typename T, int P, int Q, int G0, int G1, int G2, int STMAX, int NT>
+static hipError_t launch_multi(const LaunchArgs& a)
+{
+    typedef MultiShape<T, P, Q, G0, G1, G2, STMAX, NT> Sh;
+    const km_plan_step& st = *a.st;
+    auto kern = fused_multi_sliced_multiply<T, P, Q, G0, G1, G2, STMAX, NT>;
+    if (Sh::LDS_BYTES > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, Sh::LDS_BYTES);
+        if (e != hipSuccess) return e;
+    }
+    if (st.tile_slices < 1 || st.tile_slices > STMAX) return hipErrorInvalidValue;
+    FactorPtrs<Sh::NF> fp;
+    for (int j = 0; j < Sh::NF; ++j) fp.f[j] = a.factors[st.first_factor + Sh::NF - 1 - j];   // order of application
+    const int64_t tk = (int64_t)st.tile_slices * Sh::per_slice(0);
+    if (st.k_in % tk) return hipErrorInvalidValue;
+    const int64_t tiles_per_row = st.k_in / tk;
+    hipLaunchKernelGGL(kern, dim3((unsigned)st.grid), dim3(NT), Sh::LDS_BYTES, a.stream,
+                       (const T*)a.src, (T*)a.dst, fp, st.k_in, st.k_out, tiles_per_row, (int64_t)st.grid,
+                       st.tile_slices);
     return hipGetLastError();
 }
 
@@ -93,9 +116,11 @@ static hipError_t launch_mfma_pair(const LaunchArgs& a)
 
 // Fused FMA instances: X(type, dtype code, P, Q, factors per launch, tile_slices, threads).
 // Register-resident MFMA pairs: Z(P, tile_slices, wavefronts) (fp32, Q = 32, two factors).
+// Small-factor instances with several factors per LDS pass and a run-time tile length:
+// W(type, dtype code, P, Q, G0, G1, G2, largest tile_slices, threads).
 // MFMA instances: Y(op, dtype code, P, Q, factors per launch, tile_slices, wavefronts, q split).
 // Order = preference among instances that fit a shape.
-#define KM_INSTANCES(X, Y, Z)                            \
+#define KM_INSTANCES(X, Y, Z, W)                            \
     X(float, KM_F32, 8, 8, 3, 32, 1024)                 \
     X(float, KM_F32, 8, 8, 3, 32, 256)                  \
     X(float, KM_F32, 8, 8, 3, 16, 256)                  \
@@ -120,20 +145,52 @@ static hipError_t launch_mfma_pair(const LaunchArgs& a)
     Y(MfmaF32x32, KM_F32, 16, 32, 2, 16, 4, 1)          \
     Y(MfmaF32x32, KM_F32, 16, 32, 1, 256, 4, 1)         \
     Y(MfmaF32x32, KM_F32, 16, 32, 1, 128, 4, 1)         \
-    Y(MfmaF64x16, KM_F64, 128, 128, 1, 16, 4, 4)
+    Y(MfmaF64x16, KM_F64, 128, 128, 1, 16, 4, 4)         \
+    W(float, KM_F32, 2, 2, 3, 3, 3, 32, 256)            \
+    W(float, KM_F32, 2, 2, 3, 3, 0, 256, 256)           \
+    W(float, KM_F32, 2, 2, 3, 0, 0, 2048, 256)          \
+    W(float, KM_F32, 2, 2, 2, 0, 0, 4096, 256)          \
+    W(float, KM_F32, 2, 2, 1, 0, 0, 8192, 256)          \
+    W(float, KM_F32, 4, 4, 2, 2, 0, 64, 256)            \
+    W(float, KM_F32, 4, 4, 2, 1, 0, 256, 256)           \
+    W(float, KM_F32, 4, 4, 2, 0, 0, 1024, 256)          \
+    W(float, KM_F32, 4, 4, 1, 0, 0, 4096, 256)          \
+    W(float, KM_F32, 3, 3, 2, 2, 0, 81, 256)            \
+    W(float, KM_F32, 3, 3, 2, 1, 0, 243, 256)           \
+    W(float, KM_F32, 3, 3, 2, 0, 0, 729, 256)           \
+    W(float, KM_F32, 3, 3, 1, 0, 0, 2187, 256)          \
+    W(float, KM_F32, 5, 5, 2, 1, 0, 125, 256)           \
+    W(float, KM_F32, 5, 5, 2, 0, 0, 625, 256)           \
+    W(float, KM_F32, 5, 5, 1, 0, 0, 3125, 256)          \
+    W(float, KM_F32, 6, 6, 1, 1, 1, 72, 256)            \
+    W(float, KM_F32, 6, 6, 1, 1, 0, 432, 256)           \
+    W(float, KM_F32, 6, 6, 1, 0, 0, 2592, 256)          \
+    W(double, KM_F64, 2, 2, 3, 3, 3, 16, 256)           \
+    W(double, KM_F64, 2, 2, 3, 3, 0, 128, 256)          \
+    W(double, KM_F64, 2, 2, 3, 0, 0, 1024, 256)         \
+    W(double, KM_F64, 2, 2, 1, 0, 0, 4096, 256)         \
+    W(double, KM_F64, 4, 4, 2, 2, 0, 32, 256)           \
+    W(double, KM_F64, 4, 4, 2, 0, 0, 512, 256)          \
+    W(double, KM_F64, 4, 4, 1, 0, 0, 2048, 256)         \
+    W(double, KM_F64, 8, 8, 1, 1, 1, 16, 256)           \
+    W(double, KM_F64, 8, 8, 1, 1, 0, 128, 256)          \
+    W(double, KM_F64, 8, 8, 1, 0, 0, 1024, 256)
 
 #define KM_FUSED_ROW(T, DT, P, Q, NF, ST, NT) \
-    {KM_KERNEL_FUSED, DT, P, Q, NF, ST, NT, FusedShape<T, P, Q, NF, ST, NT>::LDS_BYTES, 1, 0, "fused"},
+    {KM_KERNEL_FUSED, DT, P, Q, NF, ST, NT, FusedShape<T, P, Q, NF, ST, NT>::LDS_BYTES, 1, 0, 0, "fused"},
 #define KM_MFMA_ROW(OP, DT, P, Q, NF, ST, NW, QS) \
-    {KM_KERNEL_MFMA, DT, P, Q, NF, ST, NW * 64, MfmaShape<OP, P, Q, NF, ST, NW, QS>::LDS_BYTES, 1, 1, "mfma"},
+    {KM_KERNEL_MFMA, DT, P, Q, NF, ST, NW * 64, MfmaShape<OP, P, Q, NF, ST, NW, QS>::LDS_BYTES, 1, 1, 0, "mfma"},
 #define KM_PAIR_ROW(P, ST, NW) \
-    {KM_KERNEL_MFMA, KM_F32, P, 32, 2, ST, NW * 64, MfmaPairShape<P, ST, NW>::LDS_BYTES, 1, 1, "mfma-pair"},
+    {KM_KERNEL_MFMA, KM_F32, P, 32, 2, ST, NW * 64, MfmaPairShape<P, ST, NW>::LDS_BYTES, 1, 1, 0, "mfma-pair"},
+#define KM_MULTI_ROW(T, DT, P, Q, G0, G1, G2, ST, NT) \
+    {KM_KERNEL_FUSED, DT, P, Q, G0 + G1 + G2, ST, NT, MultiShape<T, P, Q, G0, G1, G2, ST, NT>::LDS_BYTES, 1, 0, 1, "fused-multi"},
+#define KM_MULTI_FN(T, DT, P, Q, G0, G1, G2, ST, NT) launch_multi<T, P, Q, G0, G1, G2, ST, NT>,
 #define KM_PAIR_FN(P, ST, NW) launch_mfma_pair<P, ST, NW>,
 #define KM_FUSED_FN(T, DT, P, Q, NF, ST, NT) launch_fused<T, P, Q, NF, ST, NT>,
 #define KM_MFMA_FN(OP, DT, P, Q, NF, ST, NW, QS) launch_mfma<OP, P, Q, NF, ST, NW, QS>,
 
-static const Variant g_variants[] = { KM_INSTANCES(KM_FUSED_ROW, KM_MFMA_ROW, KM_PAIR_ROW) };
-static const LaunchFn g_launchers[] = { KM_INSTANCES(KM_FUSED_FN, KM_MFMA_FN, KM_PAIR_FN) };
+static const Variant g_variants[] = { KM_INSTANCES(KM_FUSED_ROW, KM_MFMA_ROW, KM_PAIR_ROW, KM_MULTI_ROW) };
+static const LaunchFn g_launchers[] = { KM_INSTANCES(KM_FUSED_FN, KM_MFMA_FN, KM_PAIR_FN, KM_MULTI_FN) };
 static const int g_num_variants = (int)(sizeof(g_variants) / sizeof(g_variants[0]));
 
 template <typename T>
@@ -377,7 +434,7 @@ km_status kronmatmul_set_option(km_option option, int value)
             g_options.kernels = value | 1;
             return KM_OK;
         case KM_OPT_MAX_FUSE:
-            if (value < 1 || value > 8) return KM_EINVAL;
+            if (value < 1 || value > 16) return KM_EINVAL;
             g_options.max_fuse = value;
             return KM_OK;
         case KM_OPT_PREFER_TILE:

@@ -21,6 +21,7 @@ struct Variant {
     int lds_bytes;     // LDS per workgroup
     int rows_per_tile; // rows of X a workgroup handles together
     int persistent;    // 1: a workgroup walks over several consecutive tiles (see tiles_per_wg)
+    int flexible;      // 1: tile_slices is an upper limit; the launch picks a divisor of K/prod(P)
     const char* name;
 };
 
@@ -57,7 +58,7 @@ struct Plan {
 
 struct Options {
     int kernels = 0x7;    // bit mask of km_kernel families
-    int max_fuse = 3;
+    int max_fuse = 9;
     int prefer_tile = 0;      // tuning: choose instances with this tile_slices when one fits
     int prefer_threads = 0;   // tuning: ... with this workgroup size
     int tiles_per_wg = 0;     // tuning: tiles per workgroup of persistent instances (0 = automatic)
@@ -109,83 +110,136 @@ inline int64_t store_column(int64_t k_in, int64_t p_group, int64_t tile_k, int64
     return qq * s_row + tile_index * s_tile + r;
 }
 
-// Picks the variant for factors [f - nf + 1, f] or nullptr.
-inline const Variant* find_variant(const Variant* table, int count, const Problem& pr, int f, int nf,
-                                   int64_t k_cur, const Options& opt)
+// A compiled instance chosen for one group of factors, with the slices per tile it will run with.
+struct Choice {
+    const Variant* var = nullptr;
+    int tile_slices = 0;
+    int64_t grid = 0;        // tiles (before the persistent-walk division)
+};
+
+// Picks the instance for factors [f - nf + 1, f] applied to rows of width k_cur (var == nullptr: none).
+// The table is in order of preference (fastest instance on a full machine first).  The first instance
+// that fits the shape and still gives the chip enough workgroups wins; failing that, the fitting
+// instance with the most workgroups among those whose output runs are at least 32 bytes.  The tuning
+// options override both.
+inline Choice find_variant(const Variant* table, int count, const Problem& pr, int f, int nf,
+                           int64_t k_cur, const Options& opt)
 {
-    int64_t pg = 1;
+    Choice none;
+    int64_t pg = 1, qg = 1;
     for (int i = f - nf + 1; i <= f; ++i) {
-        if (pr.P[i] != pr.P[f] || pr.Q[i] != pr.Q[f]) return nullptr;   // equal shapes within a group
+        if (pr.P[i] != pr.P[f] || pr.Q[i] != pr.Q[f]) return none;   // equal shapes within a group
         pg *= pr.P[i];
+        qg *= pr.Q[i];
+        if (pg > ((int64_t)1 << 40) || qg > ((int64_t)1 << 40)) return none;
     }
-    if (k_cur % pg) return nullptr;
+    if (k_cur % pg) return none;
     const int64_t s_row = k_cur / pg;
-    {   // the tiled kernels address within a row with 32-bit offsets
-        int64_t qg = 1;
-        for (int i = f - nf + 1; i <= f; ++i) qg *= pr.Q[i];
-        if ((double)s_row * (double)qg * (double)pr.esize >= 2147483648.0) return nullptr;
-        if ((double)k_cur * (double)pr.esize >= 2147483648.0) return nullptr;
-    }
-    // The table is in order of preference (fastest instance on a full machine first).  Take the first
-    // instance that fits the shape and still gives the chip enough workgroups; failing that, the
-    // fitting instance with the most workgroups.  The tuning options override both.
+    // the tiled kernels address within a row with 32-bit offsets
+    if ((double)s_row * (double)qg * (double)pr.esize >= 2147483648.0) return none;
+    if ((double)k_cur * (double)pr.esize >= 2147483648.0) return none;
+
     const int64_t enough = 2 * 256;
-    const Variant* first_big = nullptr;
-    const Variant* most = nullptr;
-    const Variant* wanted = nullptr;
-    int64_t most_grid = 0, wanted_score = 0;
+    Choice first_big, most, wanted;
+    int64_t wanted_score = 0;
     for (int v = 0; v < count; ++v) {
         const Variant& c = table[v];
         if (!(opt.kernels >> c.kernel & 1)) continue;
         if (c.dtype != pr.dtype || c.num_factors != nf) continue;
         if (c.P != pr.P[f] || c.Q != pr.Q[f]) continue;
-        if (s_row % c.tile_slices) continue;
         if (pr.M % c.rows_per_tile) continue;
-        const int64_t grid = (pr.M / c.rows_per_tile) * (s_row / c.tile_slices);
-        if (!first_big && grid >= enough) first_big = &c;
-        // among small launches prefer output runs of at least 32 bytes over more workgroups
-        const bool longer = most && c.tile_slices >= 8 && most->tile_slices < 8;
-        const bool shorter = most && c.tile_slices < 8 && most->tile_slices >= 8;
-        if (!most || longer || (!shorter && grid > most_grid)) { most = &c; most_grid = grid; }
-        int64_t sc = 0;
-        if (opt.prefer_tile && c.tile_slices == opt.prefer_tile) sc += 2;
-        if (opt.prefer_threads && c.threads == opt.prefer_threads) sc += 1;
-        if (sc > wanted_score) { wanted = &c; wanted_score = sc; }
+        // slices per tile: fixed, or the best divisor of s_row up to the instance's limit
+        int cand[3] = {0, 0, 0};
+        if (!c.flexible) {
+            if (s_row % c.tile_slices) continue;
+            cand[0] = c.tile_slices;
+        } else {
+            // largest divisor; largest divisor that still leaves enough workgroups; the tuning wish
+            const int64_t lim = s_row < c.tile_slices ? s_row : c.tile_slices;
+            for (int64_t d = lim; d >= 1 && !cand[0]; --d)
+                if (s_row % d == 0) cand[0] = (int)d;
+            for (int64_t d = lim; d >= 1 && !cand[1]; --d)
+                if (s_row % d == 0 && (pr.M / c.rows_per_tile) * (s_row / d) >= enough) cand[1] = (int)d;
+            if (opt.prefer_tile > 0 && opt.prefer_tile <= lim && s_row % opt.prefer_tile == 0) cand[2] = opt.prefer_tile;
+        }
+        for (int k = 0; k < 3; ++k) {
+            if (!cand[k]) continue;
+            Choice ch;
+            ch.var = &c;
+            ch.tile_slices = cand[k];
+            ch.grid = (pr.M / c.rows_per_tile) * (s_row / cand[k]);
+            if (!first_big.var && ch.grid >= enough) first_big = ch;
+            // among small launches prefer output runs of at least 32 bytes over more workgroups
+            const bool long_run = (int64_t)ch.tile_slices * (int64_t)pr.esize >= 32;
+            const bool most_long = most.var && (int64_t)most.tile_slices * (int64_t)pr.esize >= 32;
+            if (!most.var || (long_run && !most_long) || (long_run == most_long && ch.grid > most.grid)) most = ch;
+            int64_t sc = 0;
+            if (opt.prefer_tile && ch.tile_slices == opt.prefer_tile) sc += 2;
+            if (opt.prefer_threads && c.threads == opt.prefer_threads) sc += 1;
+            if (sc > wanted_score) { wanted = ch; wanted_score = sc; }
+        }
     }
-    if (wanted) return wanted;
-    return first_big ? first_big : most;
+    if (wanted.var) return wanted;
+    return first_big.var ? first_big : most;
+}
+
+// Estimated cost of one launch in "bytes moved at full speed": rows read and written, scaled up for
+// short output runs and for the generic kernel, plus a constant per launch.
+inline double launch_cost(const Problem& pr, int64_t k_in, int64_t k_out, const Choice& ch)
+{
+    const double bytes = (double)pr.M * ((double)k_in + (double)k_out) * (double)pr.esize;
+    double slow = 3.0;                                   // generic kernel
+    if (ch.var) {
+        const int64_t run = (int64_t)ch.tile_slices * (int64_t)pr.esize;
+        slow = run >= 128 ? 1.0 : (run >= 64 ? 1.25 : (run >= 32 ? 1.6 : 2.5));
+    }
+    return bytes * slow + 2.5e7;                         // ~5 us of launch latency at 5 TB/s
 }
 
 inline km_status make_plan(const Problem& pr, const Options& opt, const Variant* table, int count,
                            int generic_threads, int generic_tile_slices, int generic_lds, Plan& plan)
 {
     plan = Plan();
-    int64_t k_cur = pr.k_in;
-    int f = pr.N - 1;
-    while (f >= 0) {
-        km_plan_step st = {};
-        const Variant* var = nullptr;
-        int nf = 1;
-        for (int tryn = opt.max_fuse < f + 1 ? opt.max_fuse : f + 1; tryn >= 1 && !var; --tryn) {
-            var = find_variant(table, count, pr, f, tryn, k_cur, opt);
-            if (var) nf = tryn;
+    const int N = pr.N;
+    // width[r]: row width when factors 0..r-1 are still to be applied (the others already were)
+    std::vector<int64_t> width(N + 1);
+    width[N] = pr.k_in;
+    for (int r = N; r >= 1; --r) width[r - 1] = width[r] / pr.P[r - 1] * pr.Q[r - 1];
+    // Grouping by dynamic programming over r: best[r] = cheapest way to apply factors 0..r-1.
+    std::vector<double> best(N + 1, 0.0);
+    std::vector<int> take(N + 1, 1);
+    std::vector<Choice> pick(N + 1);
+    for (int r = 1; r <= N; ++r) {
+        best[r] = -1;
+        for (int nf = 1; nf <= r && nf <= opt.max_fuse; ++nf) {
+            const Choice ch = find_variant(table, count, pr, r - 1, nf, width[r], opt);
+            if (nf > 1 && !ch.var) continue;             // only single factors fall back to the generic kernel
+            const double c = launch_cost(pr, width[r], width[r - nf], ch) + best[r - nf];
+            if (best[r] < 0 || c < best[r]) { best[r] = c; take[r] = nf; pick[r] = ch; }
         }
-        int64_t pg = 1, qg = 1;
-        for (int i = f - nf + 1; i <= f; ++i) { pg *= pr.P[i]; qg *= pr.Q[i]; }
+    }
+    for (int r = N; r >= 1; r -= take[r]) {
+        const int nf = take[r];
+        const int f = r - 1;
+        const Choice& ch = pick[r];
+        km_plan_step st = {};
         st.first_factor = f - nf + 1;
         st.num_factors = nf;
-        st.k_in = k_cur;
-        st.k_out = k_cur / pg * qg;
-        if (var) {
+        st.k_in = width[r];
+        st.k_out = width[r - nf];
+        if (ch.var) {
+            const Variant* var = ch.var;
+            int64_t pg = 1;
+            for (int i = f - nf + 1; i <= f; ++i) pg *= pr.P[i];
             st.kernel = var->kernel;
             st.variant = (int)(var - table);
-            st.tile_slices = var->tile_slices;
+            st.tile_slices = ch.tile_slices;
             st.block = var->threads;
             st.lds_bytes = var->lds_bytes;
-            st.grid = (pr.M / var->rows_per_tile) * (k_cur / pg / var->tile_slices);
+            st.grid = ch.grid;
             if (var->persistent) {
                 const int64_t tpw = tiles_per_wg(st.grid, opt.tiles_per_wg, (int64_t)nf * var->P * var->Q,
-                                                 (int64_t)var->tile_slices * pg, var->lds_bytes);
+                                                 (int64_t)ch.tile_slices * pg, var->lds_bytes);
                 st.grid = (st.grid + tpw - 1) / tpw;
             }
         } else {
@@ -194,11 +248,11 @@ inline km_status make_plan(const Problem& pr, const Options& opt, const Variant*
             st.tile_slices = generic_tile_slices;
             st.block = generic_threads;
             st.lds_bytes = generic_lds;
-            const int64_t S = k_cur / pr.P[f];
+            const int64_t S = st.k_in / pr.P[f];
             st.grid = pr.M * ((S + generic_tile_slices - 1) / generic_tile_slices);
         }
         // flops of the iterations this launch covers
-        int64_t w = k_cur;
+        int64_t w = st.k_in;
         for (int i = f; i >= f - nf + 1; --i) {
             plan.flops += 2.0 * (double)pr.M * (double)w * pr.Q[i];
             w = w / pr.P[i] * pr.Q[i];
@@ -206,8 +260,6 @@ inline km_status make_plan(const Problem& pr, const Options& opt, const Variant*
         }
         plan.bytes += (double)pr.M * ((double)st.k_in + (double)st.k_out) * pr.esize;
         plan.steps.push_back(st);
-        k_cur = st.k_out;
-        f -= nf;
     }
     // Buffers, assigned backwards from Y: the last launch writes Y, the one before it writes WS0,
     // the one before that writes "B", and so on alternately.  B is Y itself when every row written

@@ -99,6 +99,18 @@ SMALL_CASES = [
     ("float64", 1, [(8, 8)] * 5),
     ("float32", 1, [(2, 2)] * 11),                       # many tiny factors, M = 1
     ("float32", 5, [(8, 8), (8, 8), (8, 8), (32, 32), (32, 32)]),
+    # very small factors: several factors per LDS pass, tile length chosen at launch
+    ("float32", 3, [(3, 3)] * 7),
+    ("float32", 2, [(6, 6)] * 4),
+    ("float32", 3, [(5, 5)] * 4),
+    ("float32", 1, [(5, 5), (5, 5), (5, 5), (2, 2)]),
+    ("float32", 20, [(2, 2)] * 7),
+    ("float32", 5, [(4, 4)] * 7),
+    ("float32", 4, [(2, 2)] * 12),
+    ("float64", 2, [(2, 2)] * 10),
+    ("float64", 3, [(4, 4)] * 5),
+    ("float64", 2, [(8, 8)] * 4),
+    ("float32", 7, [(4, 4), (4, 4), (2, 2), (2, 2), (2, 2), (3, 3)]),
 ]
 
 
