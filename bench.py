@@ -42,6 +42,9 @@ def main():
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--workload", default="c2_f32_m1024_8x8x6")
+    ap.add_argument("--shape", default=None,
+                    help="ad-hoc workload instead of a named one: M:PxQ^N[,PxQ^N...]:f32|f64, "
+                         "e.g. 1024:3x3^7:f32 or 10:52x50^1,65x20^1:f32 (uniform X and factors)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -59,8 +62,19 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     km.lib()
-    cfg = kron_inputs.CONFIGS[args.workload]
-    X, Fs = kron_inputs.make_config(args.workload, seed=args.seed)
+    if args.shape:
+        m_s, f_s, d_s = args.shape.split(":")
+        shapes = []
+        for part in f_s.split(","):
+            pq, _, n = part.partition("^")
+            p_, q_ = pq.split("x")
+            shapes += [(int(p_), int(q_))] * int(n or 1)
+        cfg = dict(dtype={"f32": "float32", "f64": "float64"}[d_s], M=int(m_s), shapes=shapes)
+        args.workload = "shape_" + args.shape
+        X, Fs = kron_inputs.make_problem(cfg["M"], shapes, cfg["dtype"], "uniform", "uniform", args.seed)
+    else:
+        cfg = kron_inputs.CONFIGS[args.workload]
+        X, Fs = kron_inputs.make_config(args.workload, seed=args.seed)
     M = X.shape[0]
     P = [F.shape[0] for F in Fs]
     Q = [F.shape[1] for F in Fs]
@@ -142,7 +156,9 @@ def main():
         "vs_baseline": (round(gflops / PAPER_GFLOPS[args.workload], 2)
                         if args.workload in PAPER_GFLOPS else None),
         "dtype": "f32" if cfg["dtype"] == "float32" else "f64", "data": "synthetic",
-        "config": {"workload": args.workload, "M": M, "factors": "%dx(%dx%d)" % (len(P), P[0], Q[0]),
+        "config": {"workload": args.workload, "M": M,
+                   "factors": ",".join("%dx%d" % pq for pq in zip(P, Q)) if len(set(zip(P, Q))) > 1
+                   else "%dx(%dx%d)" % (len(P), P[0], Q[0]),
                    "launches": [l["name"] for l in launches],
                    "per_launch_ms": [round(l["ms"], 4) for l in launches],
                    "planned_bytes": planned_bytes, "flops": flops,

@@ -146,6 +146,16 @@ static hipError_t launch_mfma_pair(const LaunchArgs& a)
     Y(MfmaF32x32, KM_F32, 16, 32, 1, 256, 4, 1)         \
     Y(MfmaF32x32, KM_F32, 16, 32, 1, 128, 4, 1)         \
     Y(MfmaF64x16, KM_F64, 128, 128, 1, 16, 4, 4)         \
+    Y(MfmaF32x16, KM_F32, 16, 16, 2, 32, 4, 1)          \
+    Y(MfmaF32x16, KM_F32, 16, 16, 1, 256, 4, 1)         \
+    Y(MfmaF32x16, KM_F32, 16, 16, 1, 64, 4, 1)          \
+    Y(MfmaF32x32, KM_F32, 64, 64, 1, 128, 4, 1)         \
+    Y(MfmaF32x32, KM_F32, 128, 128, 1, 32, 4, 4)        \
+    Y(MfmaF64x16, KM_F64, 16, 16, 2, 16, 4, 1)          \
+    Y(MfmaF64x16, KM_F64, 16, 16, 1, 256, 4, 1)         \
+    Y(MfmaF64x16, KM_F64, 16, 16, 1, 64, 4, 1)          \
+    Y(MfmaF64x16, KM_F64, 32, 32, 1, 128, 4, 1)         \
+    Y(MfmaF64x16, KM_F64, 64, 64, 1, 64, 4, 1)          \
     W(float, KM_F32, 2, 2, 3, 3, 3, 32, 256)            \
     W(float, KM_F32, 2, 2, 3, 3, 0, 256, 256)           \
     W(float, KM_F32, 2, 2, 3, 0, 0, 2048, 256)          \

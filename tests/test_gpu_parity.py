@@ -99,6 +99,11 @@ SMALL_CASES = [
     ("float64", 1, [(8, 8)] * 5),
     ("float32", 1, [(2, 2)] * 11),                       # many tiny factors, M = 1
     ("float32", 5, [(8, 8), (8, 8), (8, 8), (32, 32), (32, 32)]),
+    ("float32", 2, [(128, 128)] * 2),
+    ("float64", 2, [(64, 64)] * 2),
+    ("float64", 2, [(32, 32)] * 3),
+    ("float32", 3, [(16, 16)] * 5),
+    ("float64", 1, [(16, 16)] * 4),
     # very small factors: several factors per LDS pass, tile length chosen at launch
     ("float32", 3, [(3, 3)] * 7),
     ("float32", 2, [(6, 6)] * 4),
