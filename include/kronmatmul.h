@@ -115,9 +115,11 @@ km_status kronmatmul_cost(int M, int N, const int* P, const int* Q, km_dtype dty
  * instances with that tile_slices / workgroup size where one fits the shape (0 = automatic).
  * KM_OPT_TILES_PER_WG: tuning aid; consecutive tiles per workgroup of the MFMA kernels (0 = automatic).
  * KM_OPT_PAIR_INTERLEAVE: tuning aid (default 1); MFMA kernels whose output runs are shorter than a
- * cache line give alternate tiles to pairs of workgroups that share an XCD. */
+ * cache line give alternate tiles to pairs of workgroups that share an XCD.
+ * KM_OPT_TILE_ORDER: tuning aid (default 2); persistent MFMA kernels walk over a contiguous range of
+ * tiles (0) or over tiles strided by the grid size (2). */
 typedef enum { KM_OPT_KERNELS = 0, KM_OPT_MAX_FUSE = 1, KM_OPT_PROFILE = 2, KM_OPT_PREFER_TILE = 3,
-               KM_OPT_PREFER_THREADS = 4, KM_OPT_TILES_PER_WG = 5, KM_OPT_PAIR_INTERLEAVE = 6 } km_option;
+               KM_OPT_PREFER_THREADS = 4, KM_OPT_TILES_PER_WG = 5, KM_OPT_PAIR_INTERLEAVE = 6, KM_OPT_TILE_ORDER = 7 } km_option;
 km_status kronmatmul_set_option(km_option option, int value);
 km_status kronmatmul_get_option(km_option option, int* value);
 

@@ -27,6 +27,7 @@ struct LaunchArgs {
     hipStream_t stream;
     int tiles_per_wg_hint;
     int pair_interleave;
+    int tile_order;
 };
 typedef hipError_t (*LaunchFn)(const LaunchArgs&);
 
@@ -88,8 +89,10 @@ static hipError_t launch_mfma(const LaunchArgs& a)
     const int64_t num_tiles = a.pr->M * tiles_per_row;
     const int64_t tpw = tiles_per_wg(num_tiles, a.tiles_per_wg_hint, (int64_t)NF * P * Q, (int64_t)Sh::TK, Sh::LDS_BYTES);
     if ((num_tiles + tpw - 1) / tpw != st.grid) return hipErrorInvalidValue;
-    // output runs shorter than a 128-byte line: let neighbouring tiles be written together
-    const int pair = (ST * sizeof(T) < 128 && st.grid % 16 == 0 && num_tiles % (2 * tpw) == 0 && a.pair_interleave) ? 1 : 0;
+    // output runs shorter than a 128-byte line: let neighbouring tiles be written together (order 1);
+    // otherwise let the resident workgroups work on consecutive tiles (order 2)
+    int pair = (ST * sizeof(T) < 128 && st.grid % 16 == 0 && num_tiles % (2 * tpw) == 0 && a.pair_interleave) ? 1 : 0;
+    if (!pair && a.tile_order == 2) pair = 2;
     hipLaunchKernelGGL(kern, dim3((unsigned)st.grid), dim3(Sh::NT), Sh::LDS_BYTES, a.stream,
                        (const T*)a.src, (T*)a.dst, f[0], f[1], st.k_in, st.k_out, tiles_per_row, num_tiles, tpw, pair);
     return hipGetLastError();
@@ -110,7 +113,8 @@ static hipError_t launch_mfma_pair(const LaunchArgs& a)
     const int64_t tpw = tiles_per_wg(num_tiles, a.tiles_per_wg_hint, (int64_t)2 * P * Sh::Q, (int64_t)Sh::TK, Sh::LDS_BYTES);
     if ((num_tiles + tpw - 1) / tpw != st.grid) return hipErrorInvalidValue;
     hipLaunchKernelGGL(kern, dim3((unsigned)st.grid), dim3(Sh::NT), Sh::LDS_BYTES, a.stream,
-                       (const float*)a.src, (float*)a.dst, f0, f1, st.k_in, st.k_out, tiles_per_row, num_tiles, tpw);
+                       (const float*)a.src, (float*)a.dst, f0, f1, st.k_in, st.k_out, tiles_per_row, num_tiles, tpw,
+                       a.tile_order);
     return hipGetLastError();
 }
 
@@ -266,11 +270,12 @@ static km_status run(const Problem& pr, const Plan& plan, const void* X, const v
     const int n = (int)plan.steps.size();
     int profile;
     int ev0 = 0;
-    int tpw_hint, pair_hint;
+    int tpw_hint, pair_hint, order_hint;
     {
         std::lock_guard<std::mutex> lock(g_mutex);
         tpw_hint = g_options.tiles_per_wg;
         pair_hint = g_options.pair_interleave;
+        order_hint = g_options.tile_order;
         profile = g_profile && (int)ds.call_first.size() < MAX_PROFILED_CALLS;
         if (profile) {
             ev0 = ds.events_used;
@@ -293,7 +298,7 @@ static km_status run(const Problem& pr, const Plan& plan, const void* X, const v
                 default: return ws1;
             }
         };
-        LaunchArgs a{buf(st.src), buf(st.dst), F, &pr, &st, stream, tpw_hint, pair_hint};
+        LaunchArgs a{buf(st.src), buf(st.dst), F, &pr, &st, stream, tpw_hint, pair_hint, order_hint};
         hipError_t e;
         if (st.kernel == KM_KERNEL_GENERIC)
             e = pr.dtype == KM_F32 ? launch_generic<float>(a) : launch_generic<double>(a);
@@ -463,6 +468,10 @@ km_status kronmatmul_set_option(km_option option, int value)
             if (value != 0 && value != 1) return KM_EINVAL;
             g_options.pair_interleave = value;
             return KM_OK;
+        case KM_OPT_TILE_ORDER:
+            if (value != 0 && value != 2) return KM_EINVAL;
+            g_options.tile_order = value;
+            return KM_OK;
         case KM_OPT_PROFILE:
             if (value != 0 && value != 1) return KM_EINVAL;
             if (value == 1 && g_profile == 0)      // a fresh history on every device
@@ -485,6 +494,7 @@ km_status kronmatmul_get_option(km_option option, int* value)
         case KM_OPT_PREFER_THREADS: *value = g_options.prefer_threads; return KM_OK;
         case KM_OPT_TILES_PER_WG: *value = g_options.tiles_per_wg; return KM_OK;
         case KM_OPT_PAIR_INTERLEAVE: *value = g_options.pair_interleave; return KM_OK;
+        case KM_OPT_TILE_ORDER: *value = g_options.tile_order; return KM_OK;
     }
     return KM_EINVAL;
 }

@@ -78,7 +78,11 @@ struct MfmaShape {
         for (int j = 0; j < NF; ++j) m = size(j) / P * RS > m ? size(j) / P * RS : m;
         return m;
     }
-    static constexpr int LDS_BYTES = lds_elems() * (int)sizeof(T);
+    static constexpr int BUF_ELEMS = lds_elems();
+    // Single factors stream through two tile buffers, except when the factor is split over the
+    // wavefronts (large factors, MFMA-bound): there one buffer measured slightly faster.
+    static constexpr int NBUF = (NF == 1 && QSPLIT == 1) ? 2 : 1;
+    static constexpr int LDS_BYTES = NBUF * BUF_ELEMS * (int)sizeof(T);
     static constexpr int RV = TK / VN / NT;            // 16-byte vectors of a tile per thread
     static_assert(P % OP::KG == 0 && Q % OP::MB == 0 && QT % QSPLIT == 0 && NW % QSPLIT == 0, "shape");
     static_assert((PL * sizeof(T)) % 16 == 0, "a lane's piece of a slice must be whole 16-byte vectors");
@@ -155,12 +159,76 @@ __device__ __forceinline__ void mfma_stage(typename OP::T* __restrict__ tile,
     }
 }
 
+// Single factor, split in two so that the caller can refill the other tile buffer between them:
+// all products of this wavefront's slice blocks first (accumulators stay in registers) ...
+template <class OP, int P, int Q, int ST, int NW, int QSPLIT>
+__device__ __forceinline__ void mfma_single_compute(
+    const typename OP::T* __restrict__ tile,
+    const typename OP::T (&a)[MfmaShape<OP, P, Q, 1, ST, NW, QSPLIT>::QTW][MfmaShape<OP, P, Q, 1, ST, NW, QSPLIT>::PL],
+    typename OP::Acc (&acc)[ST / OP::NB / MfmaShape<OP, P, Q, 1, ST, NW, QSPLIT>::SG][MfmaShape<OP, P, Q, 1, ST, NW, QSPLIT>::QTW])
+{
+    typedef MfmaShape<OP, P, Q, 1, ST, NW, QSPLIT> Sh;
+    typedef typename OP::T T;
+    typedef typename Vec16<T>::type V;
+    constexpr int VN = Sh::VN, PL = Sh::PL, QTW = Sh::QTW, SG = Sh::SG, RS = Sh::RS;
+    constexpr int BPW = ST / OP::NB / SG;
+    static_assert(ST % OP::NB == 0 && (ST / OP::NB) % SG == 0, "slice blocks must divide among the wave groups");
+    const int lane = threadIdx.x % 64, wave = threadIdx.x / 64;
+    const int j = lane % OP::NB, g = lane / OP::NB;
+    const int ws = wave / QSPLIT;
+#pragma unroll
+    for (int bi = 0; bi < BPW; ++bi) {
+        const int s0 = (ws + bi * SG) * OP::NB;
+        T b[PL];
+        const V* src = reinterpret_cast<const V*>(tile + (s0 + j) * RS + g * PL);
+#pragma unroll
+        for (int c = 0; c < PL / VN; ++c) {
+            const V v = src[c];
+#pragma unroll
+            for (int e = 0; e < VN; ++e) b[VN * c + e] = v[e];
+        }
+#pragma unroll
+        for (int qt = 0; qt < QTW; ++qt) {
+#pragma unroll
+            for (int v = 0; v < OP::NACC; ++v) acc[bi][qt][v] = T(0);
+#pragma unroll
+            for (int t = 0; t < PL; ++t) acc[bi][qt] = OP::mma(a[qt][t], b[t], acc[bi][qt]);
+        }
+    }
+}
+
+// ... then the permuted store: (q, s) -> column q*s_row + h*ST + s.
+template <class OP, int P, int Q, int ST, int NW, int QSPLIT>
+__device__ __forceinline__ void mfma_single_store(
+    const typename OP::Acc (&acc)[ST / OP::NB / MfmaShape<OP, P, Q, 1, ST, NW, QSPLIT>::SG][MfmaShape<OP, P, Q, 1, ST, NW, QSPLIT>::QTW],
+    typename OP::T* __restrict__ Yrow, int64_t s_row, int64_t h)
+{
+    typedef MfmaShape<OP, P, Q, 1, ST, NW, QSPLIT> Sh;
+    constexpr int QTW = Sh::QTW, SG = Sh::SG;
+    constexpr int BPW = ST / OP::NB / SG;
+    const int lane = threadIdx.x % 64, wave = threadIdx.x / 64;
+    const int j = lane % OP::NB;
+    const int wq = wave % QSPLIT, ws = wave / QSPLIT;
+    // (in-row offsets fit 32 bits: the planner only picks this kernel for rows below 2^31 bytes)
+    const int sr = (int)s_row;
+#pragma unroll
+    for (int bi = 0; bi < BPW; ++bi) {
+        const int s = (ws + bi * SG) * OP::NB + j;
+        const int off = (int)h * ST + s + (wq * QTW * OP::MB + OP::row_lane(lane)) * sr;
+#pragma unroll
+        for (int qt = 0; qt < QTW; ++qt)
+#pragma unroll
+            for (int v = 0; v < OP::NACC; ++v)
+                stream_store(acc[bi][qt][v], &Yrow[off + (qt * OP::MB + OP::row_reg(v)) * sr]);
+    }
+}
+
 template <class OP, int P, int Q, int NF, int ST, int NW, int QSPLIT>
 __global__ __launch_bounds__(NW * 64, (NW >= 16 ? 4 : 2))   // second bound: wavefronts per SIMD to fit
 void mfma_sliced_multiply(const typename OP::T* __restrict__ Xg, typename OP::T* __restrict__ Yg,
                           const typename OP::T* __restrict__ F0, const typename OP::T* __restrict__ F1,
                           int64_t k_in, int64_t k_out, int64_t tiles_per_row, int64_t num_tiles,
-                          int64_t tiles_per_wg, int pair_interleave)
+                          int64_t tiles_per_wg, int tile_order)
 {
     typedef MfmaShape<OP, P, Q, NF, ST, NW, QSPLIT> Sh;
     typedef typename OP::T T;
@@ -186,58 +254,114 @@ void mfma_sliced_multiply(const typename OP::T* __restrict__ Xg, typename OP::T*
         }
 
     const int64_t s_row = tiles_per_row * ST;
-    // Tiles of this workgroup: t_begin, t_begin + t_step, ...  Normally a contiguous range.  With
-    // pair_interleave, two workgroups that the dispatcher places on the same XCD one after the other
-    // (ids b and b + 8) share a range of 2*tiles_per_wg tiles and take alternate ones, so that
-    // neighbouring tiles, whose short output runs fill the same cache lines, are written at about the
-    // same time into the same L2.
+    // Tiles of this workgroup: t_begin, t_begin + t_step, ... below t_end.
+    //  order 0: a contiguous range of tiles_per_wg tiles.
+    //  order 1: two workgroups that the dispatcher places on the same XCD one after the other (ids b
+    //           and b + 8) share a range of 2*tiles_per_wg tiles and take alternate ones, so that
+    //           neighbouring tiles, whose short output runs fill the same cache lines, are written at
+    //           about the same time into the same L2.
+    //  order 2: tiles b, b + grid, b + 2*grid, ...: the workgroups resident at any moment work on
+    //           consecutive tiles, so their output runs (one per factor column, a power-of-two stride
+    //           apart within a tile) tile whole stretches of each output row instead of all falling
+    //           on the same few memory channels.
     int64_t t_begin = (int64_t)blockIdx.x * tiles_per_wg, t_step = 1;
     int64_t t_end = t_begin + tiles_per_wg;
-    if (pair_interleave) {
+    if (tile_order == 1) {
         const int64_t b = blockIdx.x, xcd = b % 8, k = b / 8;
         t_begin = ((k >> 1) * 8 + xcd) * tiles_per_wg * 2 + (k & 1);
         t_step = 2;
         t_end = t_begin + 2 * tiles_per_wg;
+    } else if (tile_order == 2) {
+        t_begin = blockIdx.x;
+        t_step = gridDim.x;
+        t_end = num_tiles;
     }
     if (t_end > num_tiles) t_end = num_tiles;
 
+    auto tile_ptr = [&](int64_t t) {
+        return reinterpret_cast<const V*>(Xg + (t / tiles_per_row) * k_in + (t % tiles_per_row) * Sh::TK);
+    };
     V pf[RV];
     if (t_begin < t_end) {
-        const V* src = reinterpret_cast<const V*>(Xg + (t_begin / tiles_per_row) * k_in + (t_begin % tiles_per_row) * Sh::TK);
+        const V* src = tile_ptr(t_begin);
 #pragma unroll
         for (int i = 0; i < RV; ++i) pf[i] = stream_load(&src[tid + i * NT]);
     }
-    for (int64_t t = t_begin; t < t_end; t += t_step) {
-        // registers -> LDS rows of P elements with stride RS
+
+    if constexpr (Sh::NBUF == 2) {
+        // Two tile buffers, one barrier per tile.  While tile t is multiplied out of one buffer, tile
+        // t+1 waits in registers; after the products it moves to the other buffer and the loads of
+        // tile t+2 are issued, and only then are the results stored, so that waiting for a fetched
+        // tile never means waiting for stores that were issued a moment ago.
+        constexpr int BPW = ST / OP::NB / Sh::SG;
+        if (t_begin < t_end) {
 #pragma unroll
-        for (int i = 0; i < RV; ++i) {
-            const int e = (tid + i * NT) * VN;
-            *reinterpret_cast<V*>(tile + (e / P) * RS + (e % P)) = pf[i];
+            for (int i = 0; i < RV; ++i) {
+                const int e = (tid + i * NT) * VN;
+                *reinterpret_cast<V*>(tile + (e / P) * RS + (e % P)) = pf[i];
+            }
+            if (t_begin + t_step < t_end) {
+                const V* src = tile_ptr(t_begin + t_step);
+#pragma unroll
+                for (int i = 0; i < RV; ++i) pf[i] = stream_load(&src[tid + i * NT]);
+            }
         }
         __syncthreads();
-        const int64_t row = t / tiles_per_row, h = t % tiles_per_row;
-        T* Yrow = Yg + row * k_out;
-        // With two factors the fetch of the next tile is issued after the first stage: its registers
-        // then only coexist with the streaming second stage, not with the held accumulators.
-        if constexpr (NF == 1) {
+        int cur = 0;
+        for (int64_t t = t_begin; t < t_end; t += t_step) {
+            T* buf = tile + cur * Sh::BUF_ELEMS;
+            T* other = tile + (cur ^ 1) * Sh::BUF_ELEMS;
+            typename OP::Acc acc[BPW][QTW];
+            mfma_single_compute<OP, P, Q, ST, NW, QSPLIT>(buf, a0, acc);
             if (t + t_step < t_end) {
-                const int64_t tn = t + t_step;
-                const V* src = reinterpret_cast<const V*>(Xg + (tn / tiles_per_row) * k_in + (tn % tiles_per_row) * Sh::TK);
 #pragma unroll
-                for (int i = 0; i < RV; ++i) pf[i] = stream_load(&src[tid + i * NT]);
-            }
-            mfma_stage<OP, P, Q, NF, ST, NW, QSPLIT, 0>(tile, a0, Yrow, s_row, h);
-        } else {
-            mfma_stage<OP, P, Q, NF, ST, NW, QSPLIT, 0>(tile, a0, Yrow, s_row, h);
-            if (t + t_step < t_end) {
-                const int64_t tn = t + t_step;
-                const V* src = reinterpret_cast<const V*>(Xg + (tn / tiles_per_row) * k_in + (tn % tiles_per_row) * Sh::TK);
+                for (int i = 0; i < RV; ++i) {
+                    const int e = (tid + i * NT) * VN;
+                    *reinterpret_cast<V*>(other + (e / P) * RS + (e % P)) = pf[i];
+                }
+                if (t + 2 * t_step < t_end) {
+                    const V* src = tile_ptr(t + 2 * t_step);
 #pragma unroll
-                for (int i = 0; i < RV; ++i) pf[i] = stream_load(&src[tid + i * NT]);
+                    for (int i = 0; i < RV; ++i) pf[i] = stream_load(&src[tid + i * NT]);
+                }
             }
-            mfma_stage<OP, P, Q, NF, ST, NW, QSPLIT, 1>(tile, a1, Yrow, s_row, h);
+            const int64_t row = t / tiles_per_row, h = t % tiles_per_row;
+            mfma_single_store<OP, P, Q, ST, NW, QSPLIT>(acc, Yg + row * k_out, s_row, h);
+            __syncthreads();      // the other buffer is complete; this one has been read by everybody
+            cur ^= 1;
         }
-        __syncthreads();                               // tile fully consumed before it is overwritten
+    } else {
+        for (int64_t t = t_begin; t < t_end; t += t_step) {
+            // registers -> LDS rows of P elements with stride RS
+#pragma unroll
+            for (int i = 0; i < RV; ++i) {
+                const int e = (tid + i * NT) * VN;
+                *reinterpret_cast<V*>(tile + (e / P) * RS + (e % P)) = pf[i];
+            }
+            __syncthreads();
+            const int64_t row = t / tiles_per_row, h = t % tiles_per_row;
+            T* Yrow = Yg + row * k_out;
+            // With two factors the fetch of the next tile is issued after the first stage: its
+            // registers then only coexist with the streaming second stage, not with the held
+            // accumulators.
+            if constexpr (NF == 1) {
+                if (t + t_step < t_end) {
+                    const V* src = tile_ptr(t + t_step);
+#pragma unroll
+                    for (int i = 0; i < RV; ++i) pf[i] = stream_load(&src[tid + i * NT]);
+                }
+                mfma_stage<OP, P, Q, NF, ST, NW, QSPLIT, 0>(tile, a0, Yrow, s_row, h);
+            } else {
+                mfma_stage<OP, P, Q, NF, ST, NW, QSPLIT, 0>(tile, a0, Yrow, s_row, h);
+                if (t + t_step < t_end) {
+                    const V* src = tile_ptr(t + t_step);
+#pragma unroll
+                    for (int i = 0; i < RV; ++i) pf[i] = stream_load(&src[tid + i * NT]);
+                }
+                mfma_stage<OP, P, Q, NF, ST, NW, QSPLIT, 1>(tile, a1, Yrow, s_row, h);
+            }
+            __syncthreads();                           // tile fully consumed before it is overwritten
+        }
     }
 }
 

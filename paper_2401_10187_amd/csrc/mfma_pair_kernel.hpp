@@ -56,7 +56,7 @@ __global__ __launch_bounds__(NW * 64, 2)
 void mfma_pair_sliced_multiply(const float* __restrict__ Xg, float* __restrict__ Yg,
                                const float* __restrict__ F0, const float* __restrict__ F1,   // in order of application
                                int64_t k_in, int64_t k_out, int64_t tiles_per_row, int64_t num_tiles,
-                               int64_t tiles_per_wg)
+                               int64_t tiles_per_wg, int tile_order)
 {
     typedef MfmaPairShape<P, ST, NW> Sh;
     constexpr int Q = Sh::Q, KS = Sh::KS, AP = Sh::AP, UPW = Sh::UPW, STP = Sh::STP, NT = Sh::NT;
@@ -78,8 +78,14 @@ void mfma_pair_sliced_multiply(const float* __restrict__ Xg, float* __restrict__
     }
 
     const int64_t s_row = tiles_per_row * ST;
-    const int64_t t_begin = (int64_t)blockIdx.x * tiles_per_wg;
+    // tile_order 0: a contiguous range of tiles per workgroup; 2: tiles b, b + grid, b + 2*grid, ...
+    int64_t t_begin = (int64_t)blockIdx.x * tiles_per_wg, t_step = 1;
     int64_t t_end = t_begin + tiles_per_wg;
+    if (tile_order == 2) {
+        t_begin = blockIdx.x;
+        t_step = gridDim.x;
+        t_end = num_tiles;
+    }
     if (t_end > num_tiles) t_end = num_tiles;
 
     // element offset, inside a tile, of this lane's piece of unit u of this wavefront
@@ -93,7 +99,7 @@ void mfma_pair_sliced_multiply(const float* __restrict__ Xg, float* __restrict__
         for (int c = 0; c < KS / 4; ++c) xa[0][c] = src[c];
     }
 
-    for (int64_t t = t_begin; t < t_end; ++t) {
+    for (int64_t t = t_begin; t < t_end; t += t_step) {
         const float* Xt = tile_src(t);
         // Registers 0-7 of a stage-1 accumulator hold q1 < 16 and go to the staging buffer at once
         // (it is free: the previous tile's last pass ended with a barrier); registers 8-15 (q1 >= 16)
@@ -106,8 +112,8 @@ void mfma_pair_sliced_multiply(const float* __restrict__ Xg, float* __restrict__
                 const pair_f32x4* src = reinterpret_cast<const pair_f32x4*>(Xt + ((wave + (u + 1) * NW) * AP) * P * P + lane_off);
 #pragma unroll
                 for (int c = 0; c < KS / 4; ++c) xa[(u + 1) % 2][c] = src[c];
-            } else if (t + 1 < t_end) {
-                const pair_f32x4* src = reinterpret_cast<const pair_f32x4*>(tile_src(t + 1) + (wave * AP) * P * P + lane_off);
+            } else if (t + t_step < t_end) {
+                const pair_f32x4* src = reinterpret_cast<const pair_f32x4*>(tile_src(t + t_step) + (wave * AP) * P * P + lane_off);
 #pragma unroll
                 for (int c = 0; c < KS / 4; ++c) xa[(u + 1) % 2][c] = src[c];
             }

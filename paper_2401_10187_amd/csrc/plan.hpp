@@ -63,6 +63,7 @@ struct Options {
     int prefer_threads = 0;   // tuning: ... with this workgroup size
     int tiles_per_wg = 0;     // tuning: tiles per workgroup of persistent instances (0 = automatic)
     int pair_interleave = 1;  // neighbouring tiles with short output runs go to workgroup pairs
+    int tile_order = 2;       // persistent kernels: 0 = contiguous tile ranges, 2 = tiles strided by the grid
 };
 
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }

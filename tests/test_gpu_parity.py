@@ -33,10 +33,11 @@ def _device():
 class options:
     """Temporarily restrict the planner (kernel families bit mask, fusion depth)."""
 
-    def __init__(self, kernels=None, max_fuse=None, tile=None, threads=None, tiles_per_wg=None, pair=None):
+    def __init__(self, kernels=None, max_fuse=None, tile=None, threads=None, tiles_per_wg=None, pair=None,
+                 order=None):
         self.new = {km.KM_OPT_KERNELS: kernels, km.KM_OPT_MAX_FUSE: max_fuse, km.KM_OPT_PREFER_TILE: tile,
                     km.KM_OPT_PREFER_THREADS: threads, km.KM_OPT_TILES_PER_WG: tiles_per_wg,
-                    km.KM_OPT_PAIR_INTERLEAVE: pair}
+                    km.KM_OPT_PAIR_INTERLEAVE: pair, km.KM_OPT_TILE_ORDER: order}
 
     def __enter__(self):
         self.old = {k: km.get_option(k) for k in self.new}
@@ -152,6 +153,10 @@ FORCED = [
     ("float32", 4, [(16, 32)] * 4, dict(tile=32, tiles_per_wg=2)),
     ("float32", 8, [(16, 32)] * 3, dict(max_fuse=1, tile=128)),
     ("float64", 8, [(128, 128)] * 2, dict(tiles_per_wg=7)),
+    ("float64", 8, [(128, 128)] * 2, dict(tiles_per_wg=7, order=0)),
+    ("float32", 16, [(32, 32)] * 3, dict(tile=32, threads=256, tiles_per_wg=3, order=0)),
+    ("float32", 16, [(32, 32)] * 3, dict(tile=32, threads=256, tiles_per_wg=3, order=2)),
+    ("float32", 4, [(16, 32)] * 4, dict(tile=32, tiles_per_wg=5, order=0)),
     ("float64", 8, [(128, 128)] * 2, dict(tiles_per_wg=1)),
     ("float32", 8, [(8, 8)] * 6, dict(tile=32, threads=256)),
     ("float32", 8, [(8, 8)] * 6, dict(tile=32, threads=1024)),
