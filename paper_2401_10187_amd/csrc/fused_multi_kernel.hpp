@@ -35,6 +35,15 @@ struct MultiShape {
     static constexpr int pg(int j) { return (int)ipow(P, g(j)); }      // elements a thread reads per group
     static constexpr int qg(int j) { return (int)ipow(Q, g(j)); }      // elements it produces
     static constexpr int wmax(int j) { return (int)ipow(P > Q ? P : Q, g(j)); }
+    static constexpr int qchunk()       // columns of one factor whose elements fit 64 scalar registers
+    {
+        int c = Q;
+        while (c > 1 && (P * c * (int)sizeof(T)) / 4 > 64) {
+            --c;
+            while (c > 1 && Q % c) --c;
+        }
+        return c;
+    }
     static constexpr int pad(int j)
     {
         const int bytes = pg(j) * (int)sizeof(T);
@@ -76,6 +85,64 @@ __device__ __forceinline__ void multi_stage(T* __restrict__ tile, const FactorPt
     const int tid = threadIdx.x;
 
     T out[R][QGJ];
+    if constexpr (GJ == 1 && (P * Q * (int)sizeof(T)) / 4 > 64) {
+        // One factor whose elements do not fit the scalar registers at once (8x8 doubles): take its
+        // columns in chunks that do, and run every slice of the thread against one chunk before the
+        // next chunk is fetched.
+        constexpr int QCH = Sh::qchunk();
+        T xs[R][P];
+#pragma unroll
+        for (int i = 0; i < R; ++i) {
+            const int s = tid + i * NT;
+            if (s < SJ) {
+                const T* src = tile + s * (PGJ + PADJ);
+                if constexpr ((PGJ * sizeof(T)) % 16 == 0) {
+#pragma unroll
+                    for (int c = 0; c < PGJ / VN; ++c) {
+                        const V v = reinterpret_cast<const V*>(src)[c];
+#pragma unroll
+                        for (int e = 0; e < VN; ++e) xs[i][VN * c + e] = v[e];
+                    }
+                } else {
+#pragma unroll
+                    for (int e = 0; e < PGJ; ++e) xs[i][e] = src[e];
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < PGJ; ++e) xs[i][e] = T(0);
+            }
+        }
+        // Results go straight to their destination, one chunk of columns per trip of a loop that is
+        // deliberately not unrolled (unrolled, all of the factor would be fetched up front again).
+        const auto Fc = as_constant(static_cast<const T*>(fp.f[Sh::done(J)]));
+        if constexpr (!LAST) __syncthreads();            // every slice has been read
+        constexpr int QREST1 = (int)ipow(Q, Sh::done(J));
+#pragma unroll 1
+        for (int q0 = 0; q0 < Q; q0 += QCH) {
+#pragma unroll
+            for (int i = 0; i < R; ++i) {
+                const int s = tid + i * NT;
+#pragma unroll
+                for (int qq = 0; qq < QCH; ++qq) {
+                    const int q = q0 + qq;
+                    T acc = xs[i][0] * Fc[q];
+#pragma unroll
+                    for (int p = 1; p < P; ++p) acc += xs[i][p] * Fc[p * Q + q];
+                    if (s < SJ) {
+                        if constexpr (!LAST) {
+                            constexpr int PGN1 = Sh::pg(J + 1 < Sh::NS ? J + 1 : J), PADN1 = Sh::pad(J + 1 < Sh::NS ? J + 1 : J);
+                            tile[multi_lds_index<PGN1, PADN1>(q * SJ + s)] = acc;
+                        } else {
+                            T* dst = Yrow + (int64_t)(s / st) * s_row + h * st + (s % st);
+                            stream_store(acc, &dst[(int64_t)(q * QREST1) * s_row]);
+                        }
+                    }
+                }
+            }
+        }
+        if constexpr (!LAST) __syncthreads();
+        return;
+    } else {
 #pragma unroll
     for (int i = 0; i < R; ++i) {
         const int s = tid + i * NT;
@@ -117,6 +184,7 @@ __device__ __forceinline__ void multi_stage(T* __restrict__ tile, const FactorPt
         }
 #pragma unroll
         for (int qq = 0; qq < QGJ; ++qq) out[i][qq] = x[qq];
+    }
     }
     if constexpr (!LAST) {
         constexpr int PGN = Sh::pg(J + 1), PADN = Sh::pad(J + 1);

@@ -31,16 +31,29 @@ struct LaunchArgs {
 };
 typedef hipError_t (*LaunchFn)(const LaunchArgs&);
 
+// Kernels that need more than 48 KB of dynamic LDS must raise their limit once per device.
+static hipError_t allow_lds(const void* kernel, int bytes, unsigned char (&done)[64])
+{
+    if (bytes <= 48 * 1024) return hipSuccess;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    if (done[dev]) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess) done[dev] = 1;     // racing threads at worst set the same value twice
+    return e;
+}
+
 template <typename T, int P, int Q, int NF, int ST, int NT>
 static hipError_t launch_fused(const LaunchArgs& a)
 {
     typedef FusedShape<T, P, Q, NF, ST, NT> Sh;
     const km_plan_step& st = *a.st;
     auto kern = fused_sliced_multiply<T, P, Q, NF, ST, NT>;
-    if (Sh::LDS_BYTES > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, Sh::LDS_BYTES);
-        if (e != hipSuccess) return e;
-    }
+    static unsigned char lds_ok[64];
+    hipError_t e = allow_lds((const void*)kern, Sh::LDS_BYTES, lds_ok);
+    if (e != hipSuccess) return e;
     const T* f[3] = {nullptr, nullptr, nullptr};
     for (int j = 0; j < NF; ++j) f[j] = (const T*)a.factors[st.first_factor + NF - 1 - j];   // order of application
     const int64_t tiles_per_row = st.k_in / Sh::TK;
@@ -56,10 +69,9 @@ static hipError_t launch_multi(const LaunchArgs& a)
     typedef MultiShape<T, P, Q, G0, G1, G2, STMAX, NT> Sh;
     const km_plan_step& st = *a.st;
     auto kern = fused_multi_sliced_multiply<T, P, Q, G0, G1, G2, STMAX, NT>;
-    if (Sh::LDS_BYTES > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, Sh::LDS_BYTES);
-        if (e != hipSuccess) return e;
-    }
+    static unsigned char lds_ok[64];
+    hipError_t e = allow_lds((const void*)kern, Sh::LDS_BYTES, lds_ok);
+    if (e != hipSuccess) return e;
     if (st.tile_slices < 1 || st.tile_slices > STMAX) return hipErrorInvalidValue;
     FactorPtrs<Sh::NF> fp;
     for (int j = 0; j < Sh::NF; ++j) fp.f[j] = a.factors[st.first_factor + Sh::NF - 1 - j];   // order of application
@@ -79,10 +91,9 @@ static hipError_t launch_mfma(const LaunchArgs& a)
     typedef typename OP::T T;
     const km_plan_step& st = *a.st;
     auto kern = mfma_sliced_multiply<OP, P, Q, NF, ST, NW, QSPLIT>;
-    if (Sh::LDS_BYTES > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, Sh::LDS_BYTES);
-        if (e != hipSuccess) return e;
-    }
+    static unsigned char lds_ok[64];
+    hipError_t e = allow_lds((const void*)kern, Sh::LDS_BYTES, lds_ok);
+    if (e != hipSuccess) return e;
     const T* f[2] = {nullptr, nullptr};
     for (int j = 0; j < NF; ++j) f[j] = (const T*)a.factors[st.first_factor + NF - 1 - j];   // order of application
     const int64_t tiles_per_row = st.k_in / Sh::TK;
@@ -104,7 +115,8 @@ static hipError_t launch_mfma_pair(const LaunchArgs& a)
     typedef MfmaPairShape<P, ST, NW> Sh;
     const km_plan_step& st = *a.st;
     auto kern = mfma_pair_sliced_multiply<P, ST, NW>;
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, Sh::LDS_BYTES);
+    static unsigned char lds_ok[64];
+    hipError_t e = allow_lds((const void*)kern, Sh::LDS_BYTES, lds_ok);
     if (e != hipSuccess) return e;
     const float* f0 = (const float*)a.factors[st.first_factor + 1];    // applied first
     const float* f1 = (const float*)a.factors[st.first_factor];
@@ -176,8 +188,9 @@ static hipError_t launch_mfma_pair(const LaunchArgs& a)
     W(float, KM_F32, 5, 5, 2, 1, 0, 125, 256)           \
     W(float, KM_F32, 5, 5, 2, 0, 0, 625, 256)           \
     W(float, KM_F32, 5, 5, 1, 0, 0, 3125, 256)          \
+    W(float, KM_F32, 6, 6, 2, 1, 0, 72, 256)            \
     W(float, KM_F32, 6, 6, 1, 1, 1, 72, 256)            \
-    W(float, KM_F32, 6, 6, 1, 1, 0, 432, 256)           \
+    W(float, KM_F32, 6, 6, 2, 0, 0, 432, 256)           \
     W(float, KM_F32, 6, 6, 1, 0, 0, 2592, 256)          \
     W(double, KM_F64, 2, 2, 3, 3, 3, 16, 256)           \
     W(double, KM_F64, 2, 2, 3, 3, 0, 128, 256)          \
@@ -191,13 +204,14 @@ static hipError_t launch_mfma_pair(const LaunchArgs& a)
     W(double, KM_F64, 8, 8, 1, 0, 0, 1024, 256)
 
 #define KM_FUSED_ROW(T, DT, P, Q, NF, ST, NT) \
-    {KM_KERNEL_FUSED, DT, P, Q, NF, ST, NT, FusedShape<T, P, Q, NF, ST, NT>::LDS_BYTES, 1, 0, 0, "fused"},
+    {KM_KERNEL_FUSED, DT, P, Q, NF, ST, NT, FusedShape<T, P, Q, NF, ST, NT>::LDS_BYTES, 1, 0, 0, 1.0f, "fused"},
 #define KM_MFMA_ROW(OP, DT, P, Q, NF, ST, NW, QS) \
-    {KM_KERNEL_MFMA, DT, P, Q, NF, ST, NW * 64, MfmaShape<OP, P, Q, NF, ST, NW, QS>::LDS_BYTES, 1, 1, 0, "mfma"},
+    {KM_KERNEL_MFMA, DT, P, Q, NF, ST, NW * 64, MfmaShape<OP, P, Q, NF, ST, NW, QS>::LDS_BYTES, 1, 1, 0, 1.0f, "mfma"},
 #define KM_PAIR_ROW(P, ST, NW) \
-    {KM_KERNEL_MFMA, KM_F32, P, 32, 2, ST, NW * 64, MfmaPairShape<P, ST, NW>::LDS_BYTES, 1, 1, 0, "mfma-pair"},
+    {KM_KERNEL_MFMA, KM_F32, P, 32, 2, ST, NW * 64, MfmaPairShape<P, ST, NW>::LDS_BYTES, 1, 1, 0, 1.0f, "mfma-pair"},
 #define KM_MULTI_ROW(T, DT, P, Q, G0, G1, G2, ST, NT) \
-    {KM_KERNEL_FUSED, DT, P, Q, G0 + G1 + G2, ST, NT, MultiShape<T, P, Q, G0, G1, G2, ST, NT>::LDS_BYTES, 1, 0, 1, "fused-multi"},
+    {KM_KERNEL_FUSED, DT, P, Q, G0 + G1 + G2, ST, NT, MultiShape<T, P, Q, G0, G1, G2, ST, NT>::LDS_BYTES, 1, 0, 1, \
+     (G0 == 1 && P < 8) ? 1.6f : 1.0f, "fused-multi"},   /* one tiny factor per LDS pass is instruction-bound */
 #define KM_MULTI_FN(T, DT, P, Q, G0, G1, G2, ST, NT) launch_multi<T, P, Q, G0, G1, G2, ST, NT>,
 #define KM_PAIR_FN(P, ST, NW) launch_mfma_pair<P, ST, NW>,
 #define KM_FUSED_FN(T, DT, P, Q, NF, ST, NT) launch_fused<T, P, Q, NF, ST, NT>,

@@ -22,6 +22,7 @@ struct Variant {
     int rows_per_tile; // rows of X a workgroup handles together
     int persistent;    // 1: a workgroup walks over several consecutive tiles (see tiles_per_wg)
     int flexible;      // 1: tile_slices is an upper limit; the launch picks a divisor of K/prod(P)
+    float slowdown;    // measured cost relative to an HBM-bound launch of the same bytes (planner weight)
     const char* name;
 };
 
@@ -193,6 +194,7 @@ inline double launch_cost(const Problem& pr, int64_t k_in, int64_t k_out, const 
     if (ch.var) {
         const int64_t run = (int64_t)ch.tile_slices * (int64_t)pr.esize;
         slow = run >= 128 ? 1.0 : (run >= 64 ? 1.25 : (run >= 32 ? 1.6 : 2.5));
+        slow *= ch.var->slowdown;
     }
     return bytes * slow + 2.5e7;                         // ~5 us of launch latency at 5 TB/s
 }
