@@ -321,3 +321,36 @@ def test_full_size_permutation_factors_move_columns_bit_exact(name):
     assert torch.equal(Y, want)
     del Y, Xd, want
     torch.cuda.empty_cache()
+
+
+def test_rows_beyond_32_bit_offsets_use_the_generic_kernel_and_stay_exact():
+    """Maximum sizes: one row of 8^10 floats (4 GiB) is past the 32-bit in-row offsets of the tiled
+    kernels, so every factor takes the generic kernel with 64-bit indexing.  Cyclic-shift factors
+    (F[p][(p+1) % 8] = 1) make Y an exactly known column permutation of X, checked bit for bit on
+    sampled columns: output digits (q_1..q_10) come from input digits ((q_i - 1) % 8)."""
+    n, P = 10, 8
+    steps = km.plan(1, [P] * n, [P] * n, "float32")
+    assert all(st["kernel"] == km.KM_KERNEL_GENERIC for st in steps)
+    K = P ** n
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(1234)
+    Xd = torch.rand((1, K), dtype=torch.float32, device="cuda", generator=gen)
+    F = np.zeros((P, P), dtype=np.float32)
+    F[np.arange(P), (np.arange(P) + 1) % P] = 1
+    Fd = [torch.from_numpy(F).cuda() for _ in range(n)]
+    Y = km.kronmatmul(Xd, Fd)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(99)
+    cols = np.unique(np.concatenate([rng.integers(0, K, 200000), [0, 1, K - 1, K - 2, K // 2, 2 ** 31 // 4, 2 ** 31 // 4 + 1]]))
+    src = np.zeros_like(cols)
+    rem = cols.copy()
+    for i in range(n):                       # peel digits from the fastest
+        q = rem % P
+        rem //= P
+        src += ((q - 1) % P) * P ** i
+    got = Y[0, torch.from_numpy(cols).cuda()].cpu().numpy()
+    want = Xd[0, torch.from_numpy(src).cuda()].cpu().numpy()
+    assert np.array_equal(got, want)
+    del Y, Xd
+    torch.cuda.empty_cache()
+    km.release()
