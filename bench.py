@@ -51,8 +51,8 @@ def main():
                     help="also run one plain elementwise copy of X's size (for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        sys.exit("bench.py: this build measures one GPU only (rows shard across GPUs without "
-                 "communication; see DESIGN.md); run with --gpus 1")
+        sys.exit("bench.py: this build measures one GPU only (rows of X are independent, so they would "
+                 "shard across GPUs without communication); run with --gpus 1")
 
     import numpy as np
     import torch

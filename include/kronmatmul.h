@@ -48,7 +48,8 @@ typedef enum {
 typedef enum {
     KM_KERNEL_GENERIC = 0,  /* one factor, any P and Q: LDS-tiled FMA kernel                       */
     KM_KERNEL_FUSED = 1,    /* 1..3 consecutive small factors, tile resident in LDS (section 4.2)  */
-    KM_KERNEL_MFMA = 2      /* one factor with P and Q multiples of 16: slice contraction on MFMA  */
+    KM_KERNEL_MFMA = 2,     /* factors with P and Q multiples of 16: slice contraction on MFMA     */
+    KM_KERNEL_SHUFFLE = 3   /* one 8x8 fp32 factor, no LDS: P-reduction by wavefront lane exchanges */
 } km_kernel;
 
 /* Buffers a plan step reads or writes. */
@@ -109,7 +110,8 @@ km_status kronmatmul_cost(int M, int N, const int* P, const int* Q, km_dtype dty
                           double* flops, double* planned_bytes);
 
 /* Options.  KM_OPT_KERNELS: bit mask of km_kernel families the planner may use (bit k = family k;
- * the generic family is always allowed).  KM_OPT_MAX_FUSE: upper limit on factors per launch.
+ * the generic family is always allowed; default 7: the shuffle family is off because the LDS-tiled
+ * kernels measured faster).  KM_OPT_MAX_FUSE: upper limit on factors per launch.
  * KM_OPT_PROFILE: when 1, every launch is bracketed by HIP events on the caller's stream.
  * KM_OPT_PREFER_TILE / KM_OPT_PREFER_THREADS: tuning aids; when non-zero the planner prefers compiled
  * instances with that tile_slices / workgroup size where one fits the shape (0 = automatic).

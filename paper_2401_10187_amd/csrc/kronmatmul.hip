@@ -12,6 +12,7 @@
 #include "fused_multi_kernel.hpp"
 #include "mfma_kernel.hpp"
 #include "mfma_pair_kernel.hpp"
+#include "shuffle_kernel.hpp"
 
 namespace km {
 
@@ -130,6 +131,16 @@ static hipError_t launch_mfma_pair(const LaunchArgs& a)
     return hipGetLastError();
 }
 
+static hipError_t launch_shuffle(const LaunchArgs& a)
+{
+    const km_plan_step& st = *a.st;
+    const int64_t tiles_per_row = st.k_in / ((int64_t)SHF_ST * SHF_P);
+    hipLaunchKernelGGL(shuffle_sliced_multiply_8x8, dim3((unsigned)st.grid), dim3(SHF_NT), 0, a.stream,
+                       (const float*)a.src, (float*)a.dst, (const float*)a.factors[st.first_factor], st.k_in,
+                       tiles_per_row, (int64_t)st.grid);
+    return hipGetLastError();
+}
+
 // Fused FMA instances: X(type, dtype code, P, Q, factors per launch, tile_slices, threads).
 // Register-resident MFMA pairs: Z(P, tile_slices, wavefronts) (fp32, Q = 32, two factors).
 // Small-factor instances with several factors per LDS pass and a run-time tile length:
@@ -217,8 +228,12 @@ static hipError_t launch_mfma_pair(const LaunchArgs& a)
 #define KM_FUSED_FN(T, DT, P, Q, NF, ST, NT) launch_fused<T, P, Q, NF, ST, NT>,
 #define KM_MFMA_FN(OP, DT, P, Q, NF, ST, NW, QS) launch_mfma<OP, P, Q, NF, ST, NW, QS>,
 
-static const Variant g_variants[] = { KM_INSTANCES(KM_FUSED_ROW, KM_MFMA_ROW, KM_PAIR_ROW, KM_MULTI_ROW) };
-static const LaunchFn g_launchers[] = { KM_INSTANCES(KM_FUSED_FN, KM_MFMA_FN, KM_PAIR_FN, KM_MULTI_FN) };
+static const Variant g_variants[] = {
+    {KM_KERNEL_SHUFFLE, KM_F32, SHF_P, SHF_Q, 1, SHF_ST, SHF_NT, 0, 1, 0, 0, 1.0f, "shuffle"},
+    KM_INSTANCES(KM_FUSED_ROW, KM_MFMA_ROW, KM_PAIR_ROW, KM_MULTI_ROW) };
+static const LaunchFn g_launchers[] = {
+    launch_shuffle,
+    KM_INSTANCES(KM_FUSED_FN, KM_MFMA_FN, KM_PAIR_FN, KM_MULTI_FN) };
 static const int g_num_variants = (int)(sizeof(g_variants) / sizeof(g_variants[0]));
 
 template <typename T>
@@ -459,7 +474,7 @@ km_status kronmatmul_set_option(km_option option, int value)
     std::lock_guard<std::mutex> lock(g_mutex);
     switch (option) {
         case KM_OPT_KERNELS:
-            if (value < 0 || value > 7) return KM_EINVAL;
+            if (value < 0 || value > 15) return KM_EINVAL;
             g_options.kernels = value | 1;
             return KM_OK;
         case KM_OPT_MAX_FUSE:
@@ -585,6 +600,7 @@ const char* kronmatmul_kernel_name(int kernel)
         case KM_KERNEL_GENERIC: return "generic";
         case KM_KERNEL_FUSED: return "fused";
         case KM_KERNEL_MFMA: return "mfma";
+        case KM_KERNEL_SHUFFLE: return "shuffle";
     }
     return "unknown";
 }

@@ -169,6 +169,8 @@ FORCED = [
     ("float32", 8, [(8, 8)] * 6, dict(max_fuse=1, tile=2048)),
     ("float32", 8, [(8, 8)] * 6, dict(max_fuse=1, tile=64)),
     ("float32", 8, [(8, 8)] * 6, dict(max_fuse=1, tile=8)),
+    ("float32", 8, [(8, 8)] * 6, dict(max_fuse=1, kernels=8 | 1)),      # shuffle family only
+    ("float32", 3, [(8, 8)] * 5, dict(max_fuse=1, kernels=8 | 1)),
 ]
 
 

@@ -27,6 +27,7 @@ def test_status_and_kernel_names():
     assert km.kernel_name(km.KM_KERNEL_GENERIC) == "generic"
     assert km.kernel_name(km.KM_KERNEL_FUSED) == "fused"
     assert km.kernel_name(km.KM_KERNEL_MFMA) == "mfma"
+    assert km.kernel_name(km.KM_KERNEL_SHUFFLE) == "shuffle"
 
 
 def test_store_column_matches_fused_store_example():
