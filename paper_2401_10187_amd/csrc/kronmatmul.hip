@@ -270,8 +270,24 @@ static DeviceState g_dev[64];
 
 static int generic_lds(int dtype)
 {
-    const int e = dtype == KM_F32 ? 4 : 8;
-    return e * (GEN_TS * (GEN_TP + 1) + GEN_TP * GEN_TQ);
+    return dtype == KM_F32 ? gen_lds_bytes<float>() : gen_lds_bytes<double>();
+}
+
+// Plans are memoised: iterative callers repeat the same small problem thousands of times and the
+// planner should not show up next to a 6-microsecond kernel.
+struct CachedPlan {
+    int64_t M; int N; int dtype;
+    std::vector<int> P, Q;
+    Options opt;
+    Plan plan;
+};
+static std::vector<CachedPlan> g_plan_cache;      // most recently used first, guarded by g_mutex
+
+static bool same_options(const Options& a, const Options& b)
+{
+    return a.kernels == b.kernels && a.max_fuse == b.max_fuse && a.prefer_tile == b.prefer_tile &&
+           a.prefer_threads == b.prefer_threads && a.tiles_per_wg == b.tiles_per_wg &&
+           a.pair_interleave == b.pair_interleave && a.tile_order == b.tile_order;
 }
 
 static km_status plan_for(const Problem& pr, Plan& plan)
@@ -280,11 +296,24 @@ static km_status plan_for(const Problem& pr, Plan& plan)
     {
         std::lock_guard<std::mutex> lock(g_mutex);
         opt = g_options;
+        for (size_t i = 0; i < g_plan_cache.size(); ++i) {
+            const CachedPlan& c = g_plan_cache[i];
+            if (c.M == pr.M && c.N == pr.N && c.dtype == pr.dtype && same_options(c.opt, opt) && c.P == pr.P && c.Q == pr.Q) {
+                plan = c.plan;
+                if (i) std::swap(g_plan_cache[0], g_plan_cache[i]);
+                return KM_OK;
+            }
+        }
     }
     km_status s = make_plan(pr, opt, g_variants, g_num_variants, GEN_THREADS, GEN_TS, generic_lds(pr.dtype), plan);
     if (s != KM_OK) return s;
     for (const km_plan_step& st : plan.steps)
         if (st.grid <= 0 || st.grid > 0x7fffffffLL) return KM_EUNSUPPORTED;
+    {
+        std::lock_guard<std::mutex> lock(g_mutex);
+        if (g_plan_cache.size() >= 16) g_plan_cache.pop_back();
+        g_plan_cache.insert(g_plan_cache.begin(), CachedPlan{pr.M, pr.N, pr.dtype, pr.P, pr.Q, opt, plan});
+    }
     return KM_OK;
 }
 
