@@ -239,3 +239,35 @@ def test_last_profile_without_a_call_is_an_error_or_needs_device():
     L = km.lib()
     cnt = ctypes.c_int(0)
     assert L.kronmatmul_last_profile(None, 0, None) == km.KM_EINVAL
+
+
+def test_missing_library_is_a_loud_error(monkeypatch):
+    """There is no CPU fallback: without the built HIP library the binding refuses to work."""
+    import paper_2401_10187_amd.binding as B
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", os.path.join(ROOT, "paper_2401_10187_amd", "no_such_library.so"))
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        B.lib()
+    with pytest.raises(RuntimeError):
+        B.plan(4, [2], [2], "float32")
+
+
+def test_oracle_and_product_do_not_import_each_other():
+    """The oracle is test infrastructure: the package never imports it, and it never imports the
+    package; only the input generators are shared, and they hold none of the method's arithmetic."""
+    def sources(folder, exts):
+        for base, _, files in os.walk(os.path.join(ROOT, folder)):
+            for f in files:
+                if f.endswith(exts):
+                    yield os.path.join(base, f)
+    for path in sources("paper_2401_10187_amd", (".py", ".hip", ".hpp", ".h")):
+        text = open(path).read()
+        assert "oracle" not in text.lower(), path
+    for path in sources("oracle", (".py", ".c", ".h")):
+        text = open(path).read()
+        assert "paper_2401_10187_amd" not in text and "kronmatmul.h" not in text, path
+        assert "#include <hip" not in text and "libkronmatmul" not in text and "import torch" not in text, path
+    gen = open(os.path.join(ROOT, "kron_inputs.py")).read()
+    assert "import oracle" not in gen and "paper_2401_10187_amd" not in gen
+    for needle in ("kron_matmul(", "sliced_multiply(", " @ ", "np.kron", "matmul"):
+        assert needle not in gen
