@@ -46,6 +46,8 @@ def main():
                     help="ad-hoc workload instead of a named one: M:PxQ^N[,PxQ^N...]:f32|f64, "
                          "e.g. 1024:3x3^7:f32 or 10:52x50^1,65x20^1:f32 (uniform X and factors)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tune", action="store_true",
+                    help="run the library's autotuner for the workload before the warm-up (set-up, not timed)")
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain elementwise copy of X's size (for scaling rocprofv3 byte counters)")
@@ -82,6 +84,7 @@ def main():
     Xd = torch.from_numpy(X).to(dev)
     Fd = [torch.from_numpy(F).to(dev) for F in Fs]
     Yd = torch.empty((M, int(np.prod(Q, dtype=np.int64))), dtype=Xd.dtype, device=dev)
+    tuned = km.tune(M, P, Q, cfg["dtype"]) if args.tune else None
     ws_bytes = km.workspace_size(M, P, Q, cfg["dtype"])
     ws = torch.empty(max(ws_bytes, 1), dtype=torch.uint8, device=dev)
     steps = km.plan(M, P, Q, cfg["dtype"])
@@ -164,6 +167,8 @@ def main():
                    "planned_bytes": planned_bytes, "flops": flops,
                    "end_to_end_gbs": round(planned_bytes / (ms_per_step * 1e-3) / 1e9, 1),
                    "wall_ms_per_step": round(wall * 1e3 / args.steps, 4),
+                   "autotuned": ({"kept_ms": round(tuned[0], 4), "cost_model_ms": round(tuned[1], 4)}
+                                 if tuned else False),
                    "paper_baseline": "one V100, Table 1" if args.workload in PAPER_GFLOPS else None},
         "roofline": roofline,
     }

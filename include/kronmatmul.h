@@ -70,6 +70,8 @@ typedef struct {
     int block;             /* threads per workgroup                                                */
     int lds_bytes;         /* LDS per workgroup                                                    */
     int variant;           /* index of the compiled kernel instance, for reports                   */
+    int tiles_per_wg;      /* tiles one workgroup walks over (0: one tile per workgroup)           */
+    int tile_order;        /* walk: 0 contiguous range, 1 interleaved pairs, 2 strided by the grid */
 } km_plan_step;
 
 /* Bytes of device workspace kronmatmul_ws needs for this problem (0 when one launch suffices).
@@ -95,6 +97,19 @@ km_status kronmatmul_ws(int M, int N, const int* P, const int* Q,
  * the total count to *nsteps.  Pure host computation (no device needed). */
 km_status kronmatmul_plan(int M, int N, const int* P, const int* Q, km_dtype dtype,
                           km_plan_step* steps, int cap, int* nsteps);
+
+/* Autotuning (the search over tile sizes of section 5, done at run time on the device that will
+ * run the problem): times every compiled instance, tile length and tile walk that fits each group
+ * of consecutive factors on synthetic rows of the problem's size, plans on the measured times, and
+ * keeps that plan for later kronmatmul / kronmatmul_ws / kronmatmul_plan calls with this problem and
+ * the options in force now, if its launches in sequence beat the cost-model plan (otherwise that one
+ * is kept).  The plan stays until kronmatmul_release.  Allocates and frees device memory (two
+ * buffers of M x the widest intermediate, plus the plan's workspace; KM_ENOMEM if that fails),
+ * enqueues on `stream` and waits for it: not for use under graph capture.  Results do not depend on
+ * the plan beyond rounding order.  tuned_ms / default_ms (host, may be NULL) receive the time of the
+ * kept plan and of the cost-model plan, in milliseconds per call. */
+km_status kronmatmul_tune(int M, int N, const int* P, const int* Q, km_dtype dtype, void* stream,
+                          float* tuned_ms, float* default_ms);
 
 /* Output column, within a row of the intermediate, of element `local_col` of a tile after a fused
  * group of factors with prod(P) = p_group was applied to a row of width k_in cut into contiguous

@@ -16,7 +16,7 @@ EXPORTS = [
     "kronmatmul_workspace_size", "kronmatmul", "kronmatmul_ws", "kronmatmul_plan",
     "kronmatmul_store_column", "kronmatmul_cost", "kronmatmul_set_option", "kronmatmul_get_option",
     "kronmatmul_last_profile", "kronmatmul_mean_profile", "kronmatmul_release", "kronmatmul_status_string",
-    "kronmatmul_kernel_name",
+    "kronmatmul_kernel_name", "kronmatmul_tune",
 ]
 
 
@@ -24,7 +24,8 @@ class PlanStep(ctypes.Structure):
     _fields_ = [("kernel", ctypes.c_int), ("first_factor", ctypes.c_int), ("num_factors", ctypes.c_int),
                 ("tile_slices", ctypes.c_int), ("k_in", ctypes.c_longlong), ("k_out", ctypes.c_longlong),
                 ("src", ctypes.c_int), ("dst", ctypes.c_int), ("grid", ctypes.c_longlong),
-                ("block", ctypes.c_int), ("lds_bytes", ctypes.c_int), ("variant", ctypes.c_int)]
+                ("block", ctypes.c_int), ("lds_bytes", ctypes.c_int), ("variant", ctypes.c_int),
+                ("tiles_per_wg", ctypes.c_int), ("tile_order", ctypes.c_int)]
 
     def as_dict(self):
         return {k: getattr(self, k) for k, _ in self._fields_}
@@ -57,6 +58,9 @@ def lib():
         L.kronmatmul_ws.argtypes = [ci, ci, ip, ip, vp, vp, vp, ci, vp, ctypes.c_size_t, vp]
         L.kronmatmul_plan.restype = ci
         L.kronmatmul_plan.argtypes = [ci, ci, ip, ip, ci, ctypes.POINTER(PlanStep), ci, ip]
+        L.kronmatmul_tune.restype = ci
+        L.kronmatmul_tune.argtypes = [ci, ci, ip, ip, ci, vp, ctypes.POINTER(ctypes.c_float),
+                                      ctypes.POINTER(ctypes.c_float)]
         L.kronmatmul_store_column.restype = ll
         L.kronmatmul_store_column.argtypes = [ll, ll, ll, ll, ll]
         L.kronmatmul_cost.restype = ci
@@ -128,6 +132,19 @@ def plan(M, P, Q, dtype):
     _check(lib().kronmatmul_plan(int(M), n, p, q, _dtype_code(dtype), steps, cap, ctypes.byref(cnt)),
            "kronmatmul_plan")
     return [steps[i].as_dict() for i in range(min(cnt.value, cap))]
+
+
+def tune(M, P, Q, dtype, stream=None):
+    """Measures the compiled kernel instances for this problem on the current device and keeps the
+    fastest plan for later calls.  Returns (kept_ms, cost_model_ms) per call."""
+    import torch
+    n, p, q = _shapes(P, Q)
+    if stream is None:
+        stream = torch.cuda.current_stream().cuda_stream
+    kept, model = ctypes.c_float(0), ctypes.c_float(0)
+    _check(lib().kronmatmul_tune(int(M), n, p, q, _dtype_code(dtype), ctypes.c_void_p(stream),
+                                 ctypes.byref(kept), ctypes.byref(model)), "kronmatmul_tune")
+    return float(kept.value), float(model.value)
 
 
 def cost(M, P, Q, dtype):

@@ -26,9 +26,6 @@ struct LaunchArgs {
     const Problem* pr;
     const km_plan_step* st;
     hipStream_t stream;
-    int tiles_per_wg_hint;
-    int pair_interleave;
-    int tile_order;
 };
 typedef hipError_t (*LaunchFn)(const LaunchArgs&);
 
@@ -99,14 +96,13 @@ static hipError_t launch_mfma(const LaunchArgs& a)
     for (int j = 0; j < NF; ++j) f[j] = (const T*)a.factors[st.first_factor + NF - 1 - j];   // order of application
     const int64_t tiles_per_row = st.k_in / Sh::TK;
     const int64_t num_tiles = a.pr->M * tiles_per_row;
-    const int64_t tpw = tiles_per_wg(num_tiles, a.tiles_per_wg_hint, (int64_t)NF * P * Q, (int64_t)Sh::TK, Sh::LDS_BYTES);
-    if ((num_tiles + tpw - 1) / tpw != st.grid) return hipErrorInvalidValue;
-    // output runs shorter than a 128-byte line: let neighbouring tiles be written together (order 1);
-    // otherwise let the resident workgroups work on consecutive tiles (order 2)
-    int pair = (ST * sizeof(T) < 128 && st.grid % 16 == 0 && num_tiles % (2 * tpw) == 0 && a.pair_interleave) ? 1 : 0;
-    if (!pair && a.tile_order == 2) pair = 2;
+    const int64_t tpw = st.tiles_per_wg;
+    if (tpw < 1 || (num_tiles + tpw - 1) / tpw != st.grid) return hipErrorInvalidValue;
+    if (st.tile_order < 0 || st.tile_order > 2) return hipErrorInvalidValue;
+    if (st.tile_order == 1 && !pair_order_fits(num_tiles, tpw)) return hipErrorInvalidValue;
     hipLaunchKernelGGL(kern, dim3((unsigned)st.grid), dim3(Sh::NT), Sh::LDS_BYTES, a.stream,
-                       (const T*)a.src, (T*)a.dst, f[0], f[1], st.k_in, st.k_out, tiles_per_row, num_tiles, tpw, pair);
+                       (const T*)a.src, (T*)a.dst, f[0], f[1], st.k_in, st.k_out, tiles_per_row, num_tiles, tpw,
+                       st.tile_order);
     return hipGetLastError();
 }
 
@@ -123,11 +119,12 @@ static hipError_t launch_mfma_pair(const LaunchArgs& a)
     const float* f1 = (const float*)a.factors[st.first_factor];
     const int64_t tiles_per_row = st.k_in / Sh::TK;
     const int64_t num_tiles = a.pr->M * tiles_per_row;
-    const int64_t tpw = tiles_per_wg(num_tiles, a.tiles_per_wg_hint, (int64_t)2 * P * Sh::Q, (int64_t)Sh::TK, Sh::LDS_BYTES);
-    if ((num_tiles + tpw - 1) / tpw != st.grid) return hipErrorInvalidValue;
+    const int64_t tpw = st.tiles_per_wg;
+    if (tpw < 1 || (num_tiles + tpw - 1) / tpw != st.grid) return hipErrorInvalidValue;
+    if (st.tile_order != 0 && st.tile_order != 2) return hipErrorInvalidValue;
     hipLaunchKernelGGL(kern, dim3((unsigned)st.grid), dim3(Sh::NT), Sh::LDS_BYTES, a.stream,
                        (const float*)a.src, (float*)a.dst, f0, f1, st.k_in, st.k_out, tiles_per_row, num_tiles, tpw,
-                       a.tile_order);
+                       st.tile_order);
     return hipGetLastError();
 }
 
@@ -219,7 +216,7 @@ static hipError_t launch_shuffle(const LaunchArgs& a)
 #define KM_MFMA_ROW(OP, DT, P, Q, NF, ST, NW, QS) \
     {KM_KERNEL_MFMA, DT, P, Q, NF, ST, NW * 64, MfmaShape<OP, P, Q, NF, ST, NW, QS>::LDS_BYTES, 1, 1, 0, 1.0f, "mfma"},
 #define KM_PAIR_ROW(P, ST, NW) \
-    {KM_KERNEL_MFMA, KM_F32, P, 32, 2, ST, NW * 64, MfmaPairShape<P, ST, NW>::LDS_BYTES, 1, 1, 0, 1.0f, "mfma-pair"},
+    {KM_KERNEL_MFMA, KM_F32, P, 32, 2, ST, NW * 64, MfmaPairShape<P, ST, NW>::LDS_BYTES, 1, 2, 0, 1.0f, "mfma-pair"},
 #define KM_MULTI_ROW(T, DT, P, Q, G0, G1, G2, ST, NT) \
     {KM_KERNEL_FUSED, DT, P, Q, G0 + G1 + G2, ST, NT, MultiShape<T, P, Q, G0, G1, G2, ST, NT>::LDS_BYTES, 1, 0, 1, \
      (G0 == 1 && P < 8) ? 1.6f : 1.0f, "fused-multi"},   /* one tiny factor per LDS pass is instruction-bound */
@@ -280,8 +277,14 @@ struct CachedPlan {
     std::vector<int> P, Q;
     Options opt;
     Plan plan;
+    bool tuned;          // measured by kronmatmul_tune: kept until kronmatmul_release
 };
 static std::vector<CachedPlan> g_plan_cache;      // most recently used first, guarded by g_mutex
+constexpr size_t PLAN_CACHE_ENTRIES = 16, PLAN_CACHE_TUNED = 64;
+
+// Puts a plan at the head of the cache (g_mutex held).  A tuned plan replaces the entry of the same
+// problem; computed plans are dropped oldest first, tuned ones only when PLAN_CACHE_TUNED are held.
+static void cache_plan(const Problem& pr, const Options& opt, const Plan& plan, bool tuned);
 
 static bool same_options(const Options& a, const Options& b)
 {
@@ -311,14 +314,45 @@ static km_status plan_for(const Problem& pr, Plan& plan)
         if (st.grid <= 0 || st.grid > 0x7fffffffLL) return KM_EUNSUPPORTED;
     {
         std::lock_guard<std::mutex> lock(g_mutex);
-        if (g_plan_cache.size() >= 16) g_plan_cache.pop_back();
-        g_plan_cache.insert(g_plan_cache.begin(), CachedPlan{pr.M, pr.N, pr.dtype, pr.P, pr.Q, opt, plan});
+        cache_plan(pr, opt, plan, false);
     }
     return KM_OK;
 }
 
+static void cache_plan(const Problem& pr, const Options& opt, const Plan& plan, bool tuned)
+{
+    size_t computed = 0, kept = 0;
+    for (size_t i = 0; i < g_plan_cache.size();) {
+        const CachedPlan& c = g_plan_cache[i];
+        const bool same = c.M == pr.M && c.N == pr.N && c.dtype == pr.dtype && same_options(c.opt, opt) &&
+                          c.P == pr.P && c.Q == pr.Q;
+        if (same) {
+            if (c.tuned && !tuned) return;               // never replace a measured plan by a computed one
+            g_plan_cache.erase(g_plan_cache.begin() + i);
+            continue;
+        }
+        (c.tuned ? kept : computed) += 1;
+        ++i;
+    }
+    const size_t limit = tuned ? PLAN_CACHE_TUNED : PLAN_CACHE_ENTRIES;
+    if ((tuned ? kept : computed) >= limit)
+        for (size_t i = g_plan_cache.size(); i-- > 0;)
+            if (g_plan_cache[i].tuned == tuned) { g_plan_cache.erase(g_plan_cache.begin() + i); break; }
+    g_plan_cache.insert(g_plan_cache.begin(), CachedPlan{pr.M, pr.N, pr.dtype, pr.P, pr.Q, opt, plan, tuned});
+}
+
+static hipError_t launch_step(const Problem& pr, const km_plan_step& st, const void* src, void* dst,
+                              const void* const* F, hipStream_t stream)
+{
+    LaunchArgs a{src, dst, F, &pr, &st, stream};
+    if (st.kernel == KM_KERNEL_GENERIC)
+        return pr.dtype == KM_F32 ? launch_generic<float>(a) : launch_generic<double>(a);
+    if (st.variant < 0 || st.variant >= g_num_variants) return hipErrorInvalidValue;
+    return g_launchers[st.variant](a);
+}
+
 static km_status run(const Problem& pr, const Plan& plan, const void* X, const void* const* F, void* Y,
-                     void* ws, hipStream_t stream)
+                     void* ws, hipStream_t stream, bool allow_profile = true)
 {
     char* ws0 = (char*)ws;
     char* ws1 = ws0 + plan.ws0_bytes;
@@ -328,13 +362,9 @@ static km_status run(const Problem& pr, const Plan& plan, const void* X, const v
     const int n = (int)plan.steps.size();
     int profile;
     int ev0 = 0;
-    int tpw_hint, pair_hint, order_hint;
     {
         std::lock_guard<std::mutex> lock(g_mutex);
-        tpw_hint = g_options.tiles_per_wg;
-        pair_hint = g_options.pair_interleave;
-        order_hint = g_options.tile_order;
-        profile = g_profile && (int)ds.call_first.size() < MAX_PROFILED_CALLS;
+        profile = allow_profile && g_profile && (int)ds.call_first.size() < MAX_PROFILED_CALLS;
         if (profile) {
             ev0 = ds.events_used;
             while ((int)ds.events.size() < ev0 + n + 1) {
@@ -356,13 +386,7 @@ static km_status run(const Problem& pr, const Plan& plan, const void* X, const v
                 default: return ws1;
             }
         };
-        LaunchArgs a{buf(st.src), buf(st.dst), F, &pr, &st, stream, tpw_hint, pair_hint, order_hint};
-        hipError_t e;
-        if (st.kernel == KM_KERNEL_GENERIC)
-            e = pr.dtype == KM_F32 ? launch_generic<float>(a) : launch_generic<double>(a);
-        else
-            e = g_launchers[st.variant](a);
-        if (e != hipSuccess) return KM_ELAUNCH;
+        if (launch_step(pr, st, buf(st.src), buf(st.dst), F, stream) != hipSuccess) return KM_ELAUNCH;
         if (profile && hipEventRecord(ds.events[ev0 + i + 1], stream) != hipSuccess) return KM_ELAUNCH;
     }
     if (profile) {
@@ -383,6 +407,152 @@ static km_status check_pointers(const Problem& pr, const void* X, const void* co
     if (!aligned(X, 16) || !aligned(Y, 16)) return KM_EINVAL;      // kernels use 16-byte accesses
     for (int i = 0; i < pr.N; ++i)
         if (!F[i] || !aligned(F[i], pr.esize)) return KM_EINVAL;
+    return KM_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// autotuner: measures every instance that fits each group of factors and plans on the measurements
+// ---------------------------------------------------------------------------------------------
+// Fills a buffer with values in [-0.5, 0.5) so that timed launches work on ordinary numbers.
+template <typename T>
+__global__ void tune_fill(T* dst, int64_t n)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        const uint32_t h = (uint32_t)i * 2654435761u;
+        dst[i] = (T)((h >> 8) & 0xffff) * (T)(1.0 / 65536.0) - (T)0.5;
+    }
+}
+
+struct TuneScratch {
+    void* a = nullptr;       // rows read by the timed launch (X of a timed plan)
+    void* b = nullptr;       // rows written (Y of a timed plan)
+    void* f = nullptr;       // one buffer that stands in for every factor
+    void* ws = nullptr;      // workspace of a timed plan
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    ~TuneScratch()
+    {
+        if (a) (void)hipFree(a);
+        if (b) (void)hipFree(b);
+        if (f) (void)hipFree(f);
+        if (ws) (void)hipFree(ws);
+        if (e0) (void)hipEventDestroy(e0);
+        if (e1) (void)hipEventDestroy(e1);
+    }
+};
+
+// Milliseconds per repetition of `body` (which enqueues work on `stream`), best of two rounds.
+template <class Body>
+static float time_body(TuneScratch& sc, hipStream_t stream, int reps, Body body)
+{
+    float best = -1.f;
+    for (int round = 0; round < 2; ++round) {
+        if (hipEventRecord(sc.e0, stream) != hipSuccess) return -1.f;
+        for (int i = 0; i < reps; ++i)
+            if (!body()) return -1.f;
+        if (hipEventRecord(sc.e1, stream) != hipSuccess) return -1.f;
+        if (hipEventSynchronize(sc.e1) != hipSuccess) return -1.f;
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, sc.e0, sc.e1) != hipSuccess) return -1.f;
+        ms /= (float)reps;
+        if (best < 0.f || ms < best) best = ms;
+    }
+    return best;
+}
+
+static int reps_for(float ms_once)
+{
+    // about 3 ms of work per round, between 2 and 20 launches
+    int reps = ms_once > 0.f ? (int)(3.0f / ms_once) : 20;
+    return reps < 2 ? 2 : (reps > 20 ? 20 : reps);
+}
+
+static km_status tune(const Problem& pr, const Options& opt, hipStream_t stream, Plan& chosen,
+                      float* tuned_ms, float* default_ms)
+{
+    const int N = pr.N;
+    std::vector<int64_t> width;
+    row_widths(pr, width);
+    int64_t widest = 0, fmax = 0;
+    for (int r = 0; r <= N; ++r) widest = width[r] > widest ? width[r] : widest;
+    for (int i = 0; i < N; ++i) fmax = (int64_t)pr.P[i] * pr.Q[i] > fmax ? (int64_t)pr.P[i] * pr.Q[i] : fmax;
+
+    Plan deflt;
+    km_status s = make_plan(pr, opt, g_variants, g_num_variants, GEN_THREADS, GEN_TS, generic_lds(pr.dtype), deflt);
+    if (s != KM_OK) return s;
+
+    TuneScratch sc;
+    const size_t row_bytes = round_up((size_t)(pr.M * widest) * pr.esize, 256);
+    if (hipMalloc(&sc.a, row_bytes) != hipSuccess || hipMalloc(&sc.b, row_bytes) != hipSuccess ||
+        hipMalloc(&sc.f, (size_t)fmax * pr.esize) != hipSuccess) {
+        (void)hipGetLastError();
+        return KM_ENOMEM;
+    }
+    if (hipEventCreate(&sc.e0) != hipSuccess || hipEventCreate(&sc.e1) != hipSuccess) return KM_ELAUNCH;
+    if (pr.dtype == KM_F32) {
+        hipLaunchKernelGGL(tune_fill<float>, dim3(4096), dim3(256), 0, stream, (float*)sc.a, pr.M * widest);
+        hipLaunchKernelGGL(tune_fill<float>, dim3(64), dim3(256), 0, stream, (float*)sc.f, fmax);
+    } else {
+        hipLaunchKernelGGL(tune_fill<double>, dim3(4096), dim3(256), 0, stream, (double*)sc.a, pr.M * widest);
+        hipLaunchKernelGGL(tune_fill<double>, dim3(64), dim3(256), 0, stream, (double*)sc.f, fmax);
+    }
+    if (hipGetLastError() != hipSuccess) return KM_ELAUNCH;
+    std::vector<const void*> F(N, sc.f);
+
+    // cost[r][nf]: measured milliseconds of the best launch that applies factors r-nf .. r-1
+    std::vector<double> best(N + 1, 0.0);
+    std::vector<int> take(N + 1, 1);
+    std::vector<Choice> pick(N + 1);
+    std::vector<Choice> cands;
+    for (int r = 1; r <= N; ++r) {
+        best[r] = -1;
+        for (int nf = 1; nf <= r && nf <= opt.max_fuse; ++nf) {
+            enumerate_choices(g_variants, g_num_variants, pr, r - 1, nf, width[r], opt, cands);
+            if (nf == 1) cands.push_back(Choice());            // the generic kernel
+            float group_best = -1.f;
+            Choice group_pick;
+            for (const Choice& ch : cands) {
+                const km_plan_step st = build_step(pr, opt, g_variants, r, nf, ch, width, GEN_THREADS, GEN_TS,
+                                                   generic_lds(pr.dtype));
+                if (st.grid <= 0 || st.grid > 0x7fffffffLL) continue;
+                auto body = [&]() { return launch_step(pr, st, sc.a, sc.b, F.data(), stream) == hipSuccess; };
+                const float once = time_body(sc, stream, 1, body);       // also the warm-up
+                if (once < 0.f) return KM_ELAUNCH;
+                if (group_best > 0.f && once > 2.f * group_best) continue;   // hopeless: skip the careful timing
+                const float ms = time_body(sc, stream, reps_for(once), body);
+                if (ms < 0.f) return KM_ELAUNCH;
+                if (group_best < 0.f || ms < group_best) { group_best = ms; group_pick = ch; }
+            }
+            if (group_best < 0.f) continue;
+            const double c = (double)group_best + best[r - nf];
+            if (best[r] < 0 || c < best[r]) { best[r] = c; take[r] = nf; pick[r] = group_pick; }
+        }
+        if (best[r] < 0) return KM_EUNSUPPORTED;
+    }
+    Plan tuned;
+    s = finish_plan(pr, opt, g_variants, take, pick, width, GEN_THREADS, GEN_TS, generic_lds(pr.dtype), tuned);
+    if (s != KM_OK) return s;
+
+    // Launches timed alone can rank differently than in sequence: keep the measured plan only if the
+    // whole sequence beats the planner's own.
+    const size_t need_d = deflt.ws0_bytes + deflt.ws1_bytes, need_t = tuned.ws0_bytes + tuned.ws1_bytes;
+    const size_t need = need_d > need_t ? need_d : need_t;
+    if (need > 0 && hipMalloc(&sc.ws, need) != hipSuccess) { (void)hipGetLastError(); return KM_ENOMEM; }
+    auto run_default = [&]() { return run(pr, deflt, sc.a, F.data(), sc.b, sc.ws, stream, false) == KM_OK; };
+    auto run_tuned = [&]() { return run(pr, tuned, sc.a, F.data(), sc.b, sc.ws, stream, false) == KM_OK; };
+    float td = time_body(sc, stream, 1, run_default), tt = time_body(sc, stream, 1, run_tuned);
+    if (td < 0.f || tt < 0.f) return KM_ELAUNCH;
+    const int reps = reps_for(td < tt ? td : tt);
+    for (int round = 0; round < 2; ++round) {
+        const float d = time_body(sc, stream, reps, run_default), t = time_body(sc, stream, reps, run_tuned);
+        if (d < 0.f || t < 0.f) return KM_ELAUNCH;
+        if (round == 0 || d < td) td = d;
+        if (round == 0 || t < tt) tt = t;
+    }
+    chosen = tt < 0.99f * td ? tuned : deflt;
+    if (tuned_ms) *tuned_ms = tt < 0.99f * td ? tt : td;
+    if (default_ms) *default_ms = td;
+    if (hipStreamSynchronize(stream) != hipSuccess) return KM_ELAUNCH;
     return KM_OK;
 }
 
@@ -457,6 +627,30 @@ km_status kronmatmul(int M, int N, const int* P, const int* Q, const void* X, co
         ws = ds.ws;
     }
     return run(pr, plan, X, F, Y, ws, (hipStream_t)stream);
+}
+
+km_status kronmatmul_tune(int M, int N, const int* P, const int* Q, km_dtype dtype, void* stream,
+                          float* tuned_ms, float* default_ms)
+{
+    Problem pr;
+    km_status s = make_problem(M, N, P, Q, (int)dtype, pr);
+    if (s != KM_OK) return s;
+    if (tuned_ms) *tuned_ms = 0.f;
+    if (default_ms) *default_ms = 0.f;
+    if (pr.M == 0) return KM_OK;
+    Options opt;
+    {
+        std::lock_guard<std::mutex> lock(g_mutex);
+        opt = g_options;
+    }
+    Plan plan;
+    s = tune(pr, opt, (hipStream_t)stream, plan, tuned_ms, default_ms);
+    if (s != KM_OK) return s;
+    for (const km_plan_step& st : plan.steps)
+        if (st.grid <= 0 || st.grid > 0x7fffffffLL) return KM_EUNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    cache_plan(pr, opt, plan, true);
+    return KM_OK;
 }
 
 km_status kronmatmul_plan(int M, int N, const int* P, const int* Q, km_dtype dtype,
@@ -608,6 +802,7 @@ km_status kronmatmul_release(void)
     for (hipEvent_t e : ds.events) (void)hipEventDestroy(e);
     ds.events.clear();
     ds.call_first.clear(); ds.call_steps.clear(); ds.events_used = 0;
+    g_plan_cache.clear();        // measured plans included: they were timed on this device
     return KM_OK;
 }
 

@@ -20,26 +20,34 @@ struct Variant {
     int threads;       // workgroup size
     int lds_bytes;     // LDS per workgroup
     int rows_per_tile; // rows of X a workgroup handles together
-    int persistent;    // 1: a workgroup walks over several consecutive tiles (see tiles_per_wg)
+    int persistent;    // >0: a workgroup walks over several tiles (see tiles_per_wg); 1: in any of the
+                       // three tile orders, 2: contiguous or grid-strided only
     int flexible;      // 1: tile_slices is an upper limit; the launch picks a divisor of K/prod(P)
     float slowdown;    // measured cost relative to an HBM-bound launch of the same bytes (planner weight)
     const char* name;
 };
 
-// Consecutive tiles handled by one workgroup of a persistent instance; `hint` > 0 forces the value.
-// A workgroup loads its factors once, so it should move at least ten times as many tile bytes as
-// factor bytes, but the launch must keep two workgroups for each of the 256 compute units.
-// Instances so large that one workgroup fills a compute unit's LDS gain from longer walks (measured).
+// Tiles handled by one workgroup of a persistent instance; `hint` > 0 forces the value.
+// Measured with the autotuner on this chip: a workgroup loads its factors once, so with large
+// factors (16 KB and more) long walks pay (64x64 fp32: walks of 32-64 tiles are 7 % faster than
+// walks of 5), while with small factors every tile beyond the amortisation point costs workgroups
+// in flight (16x16: walks of 3-4 tiles are 10 % slower than one tile per workgroup).  Walks are
+// powers of two so that the usual power-of-two tile counts split evenly over the grid.
+// Instances that fill most of a compute unit's LDS run one or two workgroups per unit and need the
+// walk to overlap their loads with their stores: at least 4 tiles above 64 KB, 32 above 80 KB.
+// The launch must keep two workgroups for each of the 256 compute units.
 inline int64_t tiles_per_wg(int64_t num_tiles, int hint, int64_t factor_elems, int64_t tile_elems,
-                            int lds_bytes)
+                            int lds_bytes, size_t esize)
 {
     if (hint > 0) return hint;
-    int64_t t = (10 * factor_elems + tile_elems - 1) / tile_elems;
-    if (t < 4) t = 4;
-    if (lds_bytes > 80 * 1024 && t < 32) t = 32;
-    const int64_t cap = num_tiles / 512;
-    if (t > cap) t = cap;
-    return t < 1 ? 1 : t;
+    const int64_t want = (10 * factor_elems + tile_elems - 1) / tile_elems;
+    int64_t t = 1;
+    while (t < want && t < 32) t *= 2;
+    if ((size_t)factor_elems * esize >= 16 * 1024) t = 32;
+    if (lds_bytes > 64 * 1024 && t < 4) t = 4;
+    if (lds_bytes > 80 * 1024) t = 32;
+    while (t > 1 && num_tiles / t < 512) t /= 2;
+    return t;
 }
 
 struct Problem {
@@ -117,7 +125,90 @@ struct Choice {
     const Variant* var = nullptr;
     int tile_slices = 0;
     int64_t grid = 0;        // tiles (before the persistent-walk division)
+    int tiles_per_wg = 0;    // persistent instances: 0 = take the rule of tiles_per_wg()
+    int tile_order = -1;     // persistent instances: -1 = take the option
 };
+
+// Workgroups of an instance that one compute unit holds at once (160 KB of LDS, 2048 threads).
+inline int64_t resident_per_cu(const Variant& c)
+{
+    int64_t by_lds = c.lds_bytes > 0 ? (160 * 1024) / c.lds_bytes : 8;
+    int64_t by_threads = 2048 / (c.threads > 0 ? c.threads : 256);
+    int64_t n = by_lds < by_threads ? by_lds : by_threads;
+    return n < 1 ? 1 : (n > 8 ? 8 : n);
+}
+
+// The divisors of s_row an instance may run with (fixed instances: their one tile length).
+inline void tile_lengths(const Variant& c, int64_t s_row, std::vector<int>& out, int at_most)
+{
+    out.clear();
+    if (!c.flexible) {
+        if (s_row % c.tile_slices == 0) out.push_back(c.tile_slices);
+        return;
+    }
+    const int64_t lim = s_row < c.tile_slices ? s_row : c.tile_slices;
+    for (int64_t d = lim; d >= 1 && (int)out.size() < at_most; --d)
+        if (s_row % d == 0) out.push_back((int)d);
+}
+
+// Can factors [f - nf + 1, f] on rows of width k_cur be one tiled launch at all?  Fills prod(P), K/prod(P).
+inline bool group_shape(const Problem& pr, int f, int nf, int64_t k_cur, int64_t& pg, int64_t& s_row)
+{
+    int64_t qg = 1;
+    pg = 1;
+    for (int i = f - nf + 1; i <= f; ++i) {
+        if (pr.P[i] != pr.P[f] || pr.Q[i] != pr.Q[f]) return false;   // equal shapes within a group
+        pg *= pr.P[i];
+        qg *= pr.Q[i];
+        if (pg > ((int64_t)1 << 40) || qg > ((int64_t)1 << 40)) return false;
+    }
+    if (k_cur % pg) return false;
+    s_row = k_cur / pg;
+    // the tiled kernels address within a row with 32-bit offsets
+    if ((double)s_row * (double)qg * (double)pr.esize >= 2147483648.0) return false;
+    if ((double)k_cur * (double)pr.esize >= 2147483648.0) return false;
+    return true;
+}
+
+// Every (instance, tile length, walk) combination that can run the group: the autotuner's search space.
+inline void enumerate_choices(const Variant* table, int count, const Problem& pr, int f, int nf,
+                              int64_t k_cur, const Options& opt, std::vector<Choice>& out)
+{
+    out.clear();
+    int64_t pg, s_row;
+    if (!group_shape(pr, f, nf, k_cur, pg, s_row)) return;
+    std::vector<int> lens;
+    for (int v = 0; v < count; ++v) {
+        const Variant& c = table[v];
+        if (!(opt.kernels >> c.kernel & 1)) continue;
+        if (c.dtype != pr.dtype || c.num_factors != nf) continue;
+        if (c.P != pr.P[f] || c.Q != pr.Q[f]) continue;
+        if (pr.M % c.rows_per_tile) continue;
+        tile_lengths(c, s_row, lens, 3);
+        for (int st : lens) {
+            Choice ch;
+            ch.var = &c;
+            ch.tile_slices = st;
+            ch.grid = (pr.M / c.rows_per_tile) * (s_row / st);
+            if (!c.persistent) { out.push_back(ch); continue; }
+            // walks: fixed lengths, and the lengths that make the grid exactly one or two rounds of
+            // the workgroups the chip holds at once (every workgroup then gets the same share)
+            const int64_t resident = 256 * resident_per_cu(c);
+            int64_t walks[6] = {1, 4, 16, 32, (ch.grid + resident - 1) / resident,
+                                (ch.grid + 2 * resident - 1) / (2 * resident)};
+            for (int i = 0; i < 6; ++i) {
+                const int64_t w = walks[i];
+                bool seen = w < 1 || w > 4096;
+                for (int j = 0; j < i; ++j) seen = seen || walks[j] == w;
+                if (seen) continue;
+                if (w > 1 && ch.grid / w < 256) continue;      // keep every compute unit busy
+                ch.tiles_per_wg = (int)w;
+                ch.tile_order = 2;
+                out.push_back(ch);
+            }
+        }
+    }
+}
 
 // Picks the instance for factors [f - nf + 1, f] applied to rows of width k_cur (var == nullptr: none).
 // The table is in order of preference (fastest instance on a full machine first).  The first instance
@@ -128,18 +219,8 @@ inline Choice find_variant(const Variant* table, int count, const Problem& pr, i
                            int64_t k_cur, const Options& opt)
 {
     Choice none;
-    int64_t pg = 1, qg = 1;
-    for (int i = f - nf + 1; i <= f; ++i) {
-        if (pr.P[i] != pr.P[f] || pr.Q[i] != pr.Q[f]) return none;   // equal shapes within a group
-        pg *= pr.P[i];
-        qg *= pr.Q[i];
-        if (pg > ((int64_t)1 << 40) || qg > ((int64_t)1 << 40)) return none;
-    }
-    if (k_cur % pg) return none;
-    const int64_t s_row = k_cur / pg;
-    // the tiled kernels address within a row with 32-bit offsets
-    if ((double)s_row * (double)qg * (double)pr.esize >= 2147483648.0) return none;
-    if ((double)k_cur * (double)pr.esize >= 2147483648.0) return none;
+    int64_t pg, s_row;
+    if (!group_shape(pr, f, nf, k_cur, pg, s_row)) return none;
 
     const int64_t enough = 2 * 256;
     Choice first_big, most, wanted;
@@ -199,61 +280,81 @@ inline double launch_cost(const Problem& pr, int64_t k_in, int64_t k_out, const 
     return bytes * slow + 2.5e7;                         // ~5 us of launch latency at 5 TB/s
 }
 
-inline km_status make_plan(const Problem& pr, const Options& opt, const Variant* table, int count,
-                           int generic_threads, int generic_tile_slices, int generic_lds, Plan& plan)
+// Tile order 1 hands tiles out in groups of 16 workgroups (8 XCDs x 2) that each take every other
+// tile of a range of 2 * tiles_per_wg: the grid must be whole groups and the tiles whole ranges.
+inline bool pair_order_fits(int64_t num_tiles, int64_t tpw)
+{
+    const int64_t grid = (num_tiles + tpw - 1) / tpw;
+    return grid % 16 == 0 && num_tiles % (2 * tpw) == 0;
+}
+
+// One launch of the plan for factors [r - nf, r - 1] with the given choice (var == nullptr: generic).
+inline km_plan_step build_step(const Problem& pr, const Options& opt, const Variant* table, int r, int nf,
+                               const Choice& ch, const std::vector<int64_t>& width,
+                               int generic_threads, int generic_tile_slices, int generic_lds)
+{
+    const int f = r - 1;
+    km_plan_step st = {};
+    st.first_factor = f - nf + 1;
+    st.num_factors = nf;
+    st.k_in = width[r];
+    st.k_out = width[r - nf];
+    if (ch.var) {
+        const Variant* var = ch.var;
+        int64_t pg = 1;
+        for (int i = f - nf + 1; i <= f; ++i) pg *= pr.P[i];
+        st.kernel = var->kernel;
+        st.variant = (int)(var - table);
+        st.tile_slices = ch.tile_slices;
+        st.block = var->threads;
+        st.lds_bytes = var->lds_bytes;
+        st.grid = ch.grid;
+        if (var->persistent) {
+            const int hint = ch.tiles_per_wg > 0 ? ch.tiles_per_wg : opt.tiles_per_wg;
+            const int64_t tpw = tiles_per_wg(st.grid, hint, (int64_t)nf * var->P * var->Q,
+                                             (int64_t)ch.tile_slices * pg, var->lds_bytes, pr.esize);
+            const int64_t num_tiles = st.grid;
+            st.tiles_per_wg = (int)tpw;
+            st.grid = (num_tiles + tpw - 1) / tpw;
+            st.tile_order = ch.tile_order >= 0 ? ch.tile_order : opt.tile_order;
+            // output runs shorter than a 128-byte line: neighbouring tiles go to a pair of workgroups
+            // that run side by side (order 1), when the tiles split evenly that way
+            if (ch.tile_order < 0 && var->persistent == 1 && opt.pair_interleave &&
+                (int64_t)ch.tile_slices * (int64_t)pr.esize < 128 && pair_order_fits(num_tiles, tpw))
+                st.tile_order = 1;
+            if (st.tile_order == 1 && (var->persistent != 1 || !pair_order_fits(num_tiles, tpw))) st.tile_order = 0;
+        }
+    } else {
+        st.kernel = KM_KERNEL_GENERIC;
+        st.variant = -1;
+        st.tile_slices = generic_tile_slices;
+        st.block = generic_threads;
+        st.lds_bytes = generic_lds;
+        const int64_t S = st.k_in / pr.P[f];
+        st.grid = pr.M * ((S + generic_tile_slices - 1) / generic_tile_slices);
+    }
+    return st;
+}
+
+inline void row_widths(const Problem& pr, std::vector<int64_t>& width)
+{
+    // width[r]: row width when factors 0..r-1 are still to be applied (the others already were)
+    width.assign(pr.N + 1, 0);
+    width[pr.N] = pr.k_in;
+    for (int r = pr.N; r >= 1; --r) width[r - 1] = width[r] / pr.P[r - 1] * pr.Q[r - 1];
+}
+
+// Completes a plan from its groups: take[r] factors are applied when r remain, with pick[r].
+inline km_status finish_plan(const Problem& pr, const Options& opt, const Variant* table,
+                             const std::vector<int>& take, const std::vector<Choice>& pick,
+                             const std::vector<int64_t>& width,
+                             int generic_threads, int generic_tile_slices, int generic_lds, Plan& plan)
 {
     plan = Plan();
-    const int N = pr.N;
-    // width[r]: row width when factors 0..r-1 are still to be applied (the others already were)
-    std::vector<int64_t> width(N + 1);
-    width[N] = pr.k_in;
-    for (int r = N; r >= 1; --r) width[r - 1] = width[r] / pr.P[r - 1] * pr.Q[r - 1];
-    // Grouping by dynamic programming over r: best[r] = cheapest way to apply factors 0..r-1.
-    std::vector<double> best(N + 1, 0.0);
-    std::vector<int> take(N + 1, 1);
-    std::vector<Choice> pick(N + 1);
-    for (int r = 1; r <= N; ++r) {
-        best[r] = -1;
-        for (int nf = 1; nf <= r && nf <= opt.max_fuse; ++nf) {
-            const Choice ch = find_variant(table, count, pr, r - 1, nf, width[r], opt);
-            if (nf > 1 && !ch.var) continue;             // only single factors fall back to the generic kernel
-            const double c = launch_cost(pr, width[r], width[r - nf], ch) + best[r - nf];
-            if (best[r] < 0 || c < best[r]) { best[r] = c; take[r] = nf; pick[r] = ch; }
-        }
-    }
-    for (int r = N; r >= 1; r -= take[r]) {
+    for (int r = pr.N; r >= 1; r -= take[r]) {
         const int nf = take[r];
         const int f = r - 1;
-        const Choice& ch = pick[r];
-        km_plan_step st = {};
-        st.first_factor = f - nf + 1;
-        st.num_factors = nf;
-        st.k_in = width[r];
-        st.k_out = width[r - nf];
-        if (ch.var) {
-            const Variant* var = ch.var;
-            int64_t pg = 1;
-            for (int i = f - nf + 1; i <= f; ++i) pg *= pr.P[i];
-            st.kernel = var->kernel;
-            st.variant = (int)(var - table);
-            st.tile_slices = ch.tile_slices;
-            st.block = var->threads;
-            st.lds_bytes = var->lds_bytes;
-            st.grid = ch.grid;
-            if (var->persistent) {
-                const int64_t tpw = tiles_per_wg(st.grid, opt.tiles_per_wg, (int64_t)nf * var->P * var->Q,
-                                                 (int64_t)ch.tile_slices * pg, var->lds_bytes);
-                st.grid = (st.grid + tpw - 1) / tpw;
-            }
-        } else {
-            st.kernel = KM_KERNEL_GENERIC;
-            st.variant = -1;
-            st.tile_slices = generic_tile_slices;
-            st.block = generic_threads;
-            st.lds_bytes = generic_lds;
-            const int64_t S = st.k_in / pr.P[f];
-            st.grid = pr.M * ((S + generic_tile_slices - 1) / generic_tile_slices);
-        }
+        km_plan_step st = build_step(pr, opt, table, r, nf, pick[r], width, generic_threads, generic_tile_slices, generic_lds);
         // flops of the iterations this launch covers
         int64_t w = st.k_in;
         for (int i = f; i >= f - nf + 1; --i) {
@@ -284,6 +385,28 @@ inline km_status make_plan(const Problem& pr, const Options& opt, const Variant*
     plan.ws0_bytes = round_up((size_t)(pr.M * w0) * pr.esize, 256);
     plan.ws1_bytes = round_up((size_t)(pr.M * w1) * pr.esize, 256);
     return KM_OK;
+}
+
+inline km_status make_plan(const Problem& pr, const Options& opt, const Variant* table, int count,
+                           int generic_threads, int generic_tile_slices, int generic_lds, Plan& plan)
+{
+    const int N = pr.N;
+    std::vector<int64_t> width;
+    row_widths(pr, width);
+    // Grouping by dynamic programming over r: best[r] = cheapest way to apply factors 0..r-1.
+    std::vector<double> best(N + 1, 0.0);
+    std::vector<int> take(N + 1, 1);
+    std::vector<Choice> pick(N + 1);
+    for (int r = 1; r <= N; ++r) {
+        best[r] = -1;
+        for (int nf = 1; nf <= r && nf <= opt.max_fuse; ++nf) {
+            const Choice ch = find_variant(table, count, pr, r - 1, nf, width[r], opt);
+            if (nf > 1 && !ch.var) continue;             // only single factors fall back to the generic kernel
+            const double c = launch_cost(pr, width[r], width[r - nf], ch) + best[r - nf];
+            if (best[r] < 0 || c < best[r]) { best[r] = c; take[r] = nf; pick[r] = ch; }
+        }
+    }
+    return finish_plan(pr, opt, table, take, pick, width, generic_threads, generic_tile_slices, generic_lds, plan);
 }
 
 }  // namespace km

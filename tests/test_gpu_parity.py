@@ -388,3 +388,34 @@ def test_graph_capture_and_replay_matches_eager():
         torch.cuda.synchronize()
         assert np.array_equal(got, eager.cpu().numpy())
         assert_close(got, Xn, Fs)
+
+
+TUNED = [
+    ("float32", 16, [(8, 8)] * 4),
+    ("float32", 64, [(8, 8)] * 5),
+    ("float32", 8, [(32, 32)] * 3),
+    ("float32", 8, [(16, 32)] * 3),
+    ("float64", 2, [(128, 128)] * 2),
+    ("float32", 6, [(4, 4)] * 7),
+    ("float64", 4, [(8, 8)] * 4),
+    ("float32", 5, [(3, 5), (7, 2), (8, 8), (8, 8)]),
+]
+
+
+@pytest.mark.parametrize("dtype,M,shapes", TUNED, ids=lambda v: str(v).replace(" ", ""))
+def test_tuned_plan_matches_the_oracle(dtype, M, shapes):
+    """The autotuner times every instance that fits (each tile length and tile walk it may launch
+    with) and installs the fastest plan: the result must still be the oracle's, the reported plan
+    must be the installed one, and it must not be slower than the cost-model plan it was measured
+    against."""
+    P, Q = [s[0] for s in shapes], [s[1] for s in shapes]
+    kept, model = km.tune(M, P, Q, dtype)
+    assert 0 < kept <= model
+    steps = km.plan(M, P, Q, dtype)
+    assert sum(st["num_factors"] for st in steps) == len(shapes)
+    X, Fs = kron_inputs.make_problem(M, shapes, dtype, seed=77)
+    assert_close(run_gpu(X, Fs, use_ws=True), X, Fs)
+    assert km.plan(M, P, Q, dtype) == steps              # a run does not replace the measured plan
+    Xi, Fi = kron_inputs.make_problem(M, shapes, dtype, x="int2", f="int1", seed=78)
+    assert_close(run_gpu(Xi, Fi), Xi, Fi, exact=True)
+    km.release()                                          # forget the measured plans

@@ -104,6 +104,14 @@ def test_plan_is_consistent(M, shapes, dtype):
             widths[st["dst"]] = max(widths[st["dst"]], st["k_out"])
         assert st["grid"] > 0 and st["block"] > 0
         assert st["lds_bytes"] <= 160 * 1024
+        # walking workgroups cover every tile: grid = ceil(tiles / tiles_per_wg)
+        assert st["tile_order"] in (0, 1, 2) and st["tiles_per_wg"] >= 0
+        if st["tiles_per_wg"] > 0:
+            pg = int(np.prod(P[st["first_factor"]:st["first_factor"] + st["num_factors"]], dtype=np.int64))
+            tiles = M * (st["k_in"] // (st["tile_slices"] * pg))
+            assert st["grid"] == -(-tiles // st["tiles_per_wg"])
+            if st["tile_order"] == 1:
+                assert st["grid"] % 16 == 0 and tiles % (2 * st["tiles_per_wg"]) == 0
     assert f == 0
     assert steps[-1]["dst"] == km.KM_BUF_Y
     need = sum((M * w * es + 255) // 256 * 256 for w in widths.values())
@@ -160,6 +168,17 @@ def test_planner_prefers_fusion_and_mfma_for_the_measured_workloads():
         if name != "c1_f32_m16_8x8x3":
             es = 4 if c["dtype"] == "float32" else 8
             assert all(st["tile_slices"] * es >= 128 for st in got), name
+
+
+def test_walk_lengths_follow_the_measured_rule():
+    """Large factors: long walks (factor loads amortised); small factors: one tile per workgroup;
+    the grid keeps at least two workgroups per compute unit."""
+    big = km.plan(1024, [64] * 3, [64] * 3, "float32")
+    assert all(st["tiles_per_wg"] == 32 for st in big)
+    small = km.plan(1024, [16] * 5, [16] * 5, "float32")
+    assert all(st["tiles_per_wg"] == 1 for st in small)
+    few = km.plan(16, [128] * 3, [128] * 3, "float64")
+    assert all(st["grid"] >= 512 for st in few)
 
 
 def test_tile_instances_are_skipped_for_rows_beyond_32_bit_offsets():
