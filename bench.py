@@ -74,6 +74,12 @@ def main():
         cfg = dict(dtype={"f32": "float32", "f64": "float64"}[d_s], M=int(m_s), shapes=shapes)
         args.workload = "shape_" + args.shape
         X, Fs = kron_inputs.make_problem(cfg["M"], shapes, cfg["dtype"], "uniform", "uniform", args.seed)
+    elif args.workload.startswith("table4_id"):
+        # table4_id<k>[_f64]: problem size k of the paper's Table 4 with synthetic values
+        parts = args.workload.split("_")
+        case = {c[0]: c for c in kron_inputs.TABLE4}[int(parts[1][2:])]
+        cfg = dict(dtype="float64" if parts[-1] == "f64" else "float32", M=case[1], shapes=case[2])
+        X, Fs = kron_inputs.make_problem(cfg["M"], cfg["shapes"], cfg["dtype"], "uniform", "uniform", args.seed)
     else:
         cfg = kron_inputs.CONFIGS[args.workload]
         X, Fs = kron_inputs.make_config(args.workload, seed=args.seed)

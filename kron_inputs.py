@@ -19,6 +19,21 @@ CONFIGS = {
     "c5_f32_m256_16x32x4": dict(dtype="float32", M=256, shapes=[(16, 32)] * 4, x="uniform", f="normal0.25"),
 }
 
+# The problem sizes of the paper's Table 4 (section 6.2.3), as (id, M, list of (P, Q)); only the shapes are
+# the paper's, values are drawn here.  Id 27 is printed there as 32^6 (64 GiB per fp32 matrix at M = 16,
+# more than the paper's 32 GB GPU holds); it is taken as 32^5 here.
+TABLE4 = (
+    [(1, 20, [(2, 2)] * 7), (2, 20, [(2, 2)] * 9), (3, 50, [(2, 2)] * 9), (4, 20, [(2, 2)] * 10),
+     (5, 1, [(2, 2)] * 11),
+     (6, 10, [(52, 50), (65, 20)]), (7, 50, [(32, 8), (64, 128)]), (8, 10, [(52, 65), (50, 20)])]
+    + [(9 + i, m, [(2, 2)] * 9) for i, m in enumerate((4, 8, 16, 20))]
+    + [(13 + i, m, [(8, 8)] * 3) for i, m in enumerate((4, 8, 16, 20))]
+    + [(17, 1024, [(3, 3)] * 7), (18, 1024, [(4, 4)] * 7), (19, 1024, [(6, 6)] * 7),
+       (20, 1, [(5, 5)] * 3 + [(2, 2)]), (21, 1, [(5, 5)] * 2 + [(2, 2), (25, 25)]),
+       (22, 1526, [(4, 4)] * 6), (23, 156, [(8, 8)] * 3), (24, 2967, [(4, 4)] * 7),
+       (25, 16, [(8, 8)] * 8), (26, 16, [(16, 16)] * 6), (27, 16, [(32, 32)] * 5), (28, 16, [(64, 64)] * 3)]
+)
+
 
 def _rng(seed, tag):
     return np.random.Generator(np.random.Philox(key=[int(seed) & (2**64 - 1), int(tag)]))

@@ -209,7 +209,17 @@ static hipError_t launch_shuffle(const LaunchArgs& a)
     W(double, KM_F64, 4, 4, 1, 0, 0, 2048, 256)         \
     W(double, KM_F64, 8, 8, 1, 1, 1, 16, 256)           \
     W(double, KM_F64, 8, 8, 1, 1, 0, 128, 256)          \
-    W(double, KM_F64, 8, 8, 1, 0, 0, 1024, 256)
+    W(double, KM_F64, 8, 8, 1, 0, 0, 1024, 256)         \
+    W(double, KM_F64, 3, 3, 2, 2, 0, 81, 256)           \
+    W(double, KM_F64, 3, 3, 2, 1, 0, 243, 256)          \
+    W(double, KM_F64, 3, 3, 2, 0, 0, 729, 256)          \
+    W(double, KM_F64, 3, 3, 1, 0, 0, 2187, 256)         \
+    W(double, KM_F64, 5, 5, 2, 1, 0, 25, 256)           \
+    W(double, KM_F64, 5, 5, 2, 0, 0, 125, 256)          \
+    W(double, KM_F64, 5, 5, 1, 0, 0, 625, 256)          \
+    W(double, KM_F64, 6, 6, 1, 1, 1, 36, 256)           \
+    W(double, KM_F64, 6, 6, 1, 1, 0, 216, 256)          \
+    W(double, KM_F64, 6, 6, 1, 0, 0, 1296, 256)
 
 #define KM_FUSED_ROW(T, DT, P, Q, NF, ST, NT) \
     {KM_KERNEL_FUSED, DT, P, Q, NF, ST, NT, FusedShape<T, P, Q, NF, ST, NT>::LDS_BYTES, 1, 0, 0, 1.0f, "fused"},

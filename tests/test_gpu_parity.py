@@ -117,6 +117,10 @@ SMALL_CASES = [
     ("float64", 3, [(4, 4)] * 5),
     ("float64", 2, [(8, 8)] * 4),
     ("float32", 7, [(4, 4), (4, 4), (2, 2), (2, 2), (2, 2), (3, 3)]),
+    ("float64", 3, [(3, 3)] * 8),
+    ("float64", 2, [(5, 5)] * 5),
+    ("float64", 2, [(6, 6)] * 5),
+    ("float64", 1, [(6, 6)] * 3 + [(3, 3)] * 2),
 ]
 
 
@@ -268,6 +272,34 @@ def test_full_size_sampled_rows(name):
     torch.cuda.synchronize()
     assert torch.equal(Y, Y2)
     del Y, Y2, Xd
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("case", kron_inputs.TABLE4, ids=lambda c: "id%d_m%d_%s" % (c[0], c[1], "_".join(
+    "%dx%d" % s for s in dict.fromkeys(c[2]))))
+@pytest.mark.parametrize("dtype", ["float32", "float64"])
+def test_table4_shapes_at_full_size(case, dtype):
+    """Every problem size of the paper's Table 4 (odd M, M = 1, distinct and rectangular factors, N up
+    to 11), with synthetic values, in both precisions: all rows where the oracle needs under about
+    2e9 multiply-adds, sampled rows otherwise; then the integer variant bit for bit."""
+    _, M, shapes = case
+    X, Fs = kron_inputs.make_problem(M, shapes, dtype, seed=100 + case[0])
+    width, macs = X.shape[1], 0
+    for p, q in reversed(shapes):
+        macs += width * q
+        width = width // p * q
+    rows = list(range(M)) if M * macs <= 2e9 else _sample_rows(M)
+    Xd = torch.from_numpy(X).cuda()
+    Y = km.kronmatmul(Xd, [torch.from_numpy(F).cuda() for F in Fs])
+    torch.cuda.synchronize()
+    assert_close(Y[rows].cpu().numpy(), X[rows], Fs)
+    Xi, Fi = kron_inputs.make_problem(M, shapes, dtype, x="int2", f="int1", seed=200 + case[0])
+    bound = 2.0 * np.prod([s[0] for s in shapes], dtype=np.float64)
+    if bound < (2 ** 24 if dtype == "float32" else 2 ** 53):      # every partial sum exactly representable
+        Yi = km.kronmatmul(torch.from_numpy(Xi).cuda(), [torch.from_numpy(F).cuda() for F in Fi])
+        torch.cuda.synchronize()
+        assert_close(Yi[rows].cpu().numpy(), Xi[rows], Fi, exact=True)
+    del Y, Xd
     torch.cuda.empty_cache()
 
 
