@@ -71,7 +71,8 @@ typedef struct {
     int lds_bytes;         /* LDS per workgroup                                                    */
     int variant;           /* index of the compiled kernel instance, for reports                   */
     int tiles_per_wg;      /* tiles one workgroup walks over (0: one tile per workgroup)           */
-    int tile_order;        /* walk: 0 contiguous range, 1 interleaved pairs, 2 strided by the grid */
+    int tile_order;        /* walk: 0 contiguous range, 1 interleaved pairs, 2 strided by the grid,
+                              3 strided inside the XCD's eighth of the tiles                       */
 } km_plan_step;
 
 /* Bytes of device workspace kronmatmul_ws needs for this problem (0 when one launch suffices).
@@ -134,7 +135,8 @@ km_status kronmatmul_cost(int M, int N, const int* P, const int* Q, km_dtype dty
  * KM_OPT_PAIR_INTERLEAVE: tuning aid (default 1); MFMA kernels whose output runs are shorter than a
  * cache line give alternate tiles to pairs of workgroups that share an XCD.
  * KM_OPT_TILE_ORDER: tuning aid (default 2); persistent MFMA kernels walk over a contiguous range of
- * tiles (0) or over tiles strided by the grid size (2). */
+ * tiles (0), over tiles strided by the grid size (2), or strided inside a contiguous eighth of the
+ * tiles per XCD (3; taken as 2 when tiles or grid do not split by 8). */
 typedef enum { KM_OPT_KERNELS = 0, KM_OPT_MAX_FUSE = 1, KM_OPT_PROFILE = 2, KM_OPT_PREFER_TILE = 3,
                KM_OPT_PREFER_THREADS = 4, KM_OPT_TILES_PER_WG = 5, KM_OPT_PAIR_INTERLEAVE = 6, KM_OPT_TILE_ORDER = 7 } km_option;
 km_status kronmatmul_set_option(km_option option, int value);

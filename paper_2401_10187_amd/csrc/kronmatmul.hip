@@ -98,20 +98,21 @@ static hipError_t launch_mfma(const LaunchArgs& a)
     const int64_t num_tiles = a.pr->M * tiles_per_row;
     const int64_t tpw = st.tiles_per_wg;
     if (tpw < 1 || (num_tiles + tpw - 1) / tpw != st.grid) return hipErrorInvalidValue;
-    if (st.tile_order < 0 || st.tile_order > 2) return hipErrorInvalidValue;
+    if (st.tile_order < 0 || st.tile_order > 3) return hipErrorInvalidValue;
     if (st.tile_order == 1 && !pair_order_fits(num_tiles, tpw)) return hipErrorInvalidValue;
+    if (st.tile_order == 3 && !xcd_order_fits(num_tiles, st.grid)) return hipErrorInvalidValue;
     hipLaunchKernelGGL(kern, dim3((unsigned)st.grid), dim3(Sh::NT), Sh::LDS_BYTES, a.stream,
                        (const T*)a.src, (T*)a.dst, f[0], f[1], st.k_in, st.k_out, tiles_per_row, num_tiles, tpw,
                        st.tile_order);
     return hipGetLastError();
 }
 
-template <int P, int ST, int NW>
+template <int P, int ST, int NW, int PD>
 static hipError_t launch_mfma_pair(const LaunchArgs& a)
 {
-    typedef MfmaPairShape<P, ST, NW> Sh;
+    typedef MfmaPairShape<P, ST, NW, PD> Sh;
     const km_plan_step& st = *a.st;
-    auto kern = mfma_pair_sliced_multiply<P, ST, NW>;
+    auto kern = mfma_pair_sliced_multiply<P, ST, NW, PD>;
     static unsigned char lds_ok[64];
     hipError_t e = allow_lds((const void*)kern, Sh::LDS_BYTES, lds_ok);
     if (e != hipSuccess) return e;
@@ -121,7 +122,8 @@ static hipError_t launch_mfma_pair(const LaunchArgs& a)
     const int64_t num_tiles = a.pr->M * tiles_per_row;
     const int64_t tpw = st.tiles_per_wg;
     if (tpw < 1 || (num_tiles + tpw - 1) / tpw != st.grid) return hipErrorInvalidValue;
-    if (st.tile_order != 0 && st.tile_order != 2) return hipErrorInvalidValue;
+    if (st.tile_order != 0 && st.tile_order != 2 && st.tile_order != 3) return hipErrorInvalidValue;
+    if (st.tile_order == 3 && !xcd_order_fits(num_tiles, st.grid)) return hipErrorInvalidValue;
     hipLaunchKernelGGL(kern, dim3((unsigned)st.grid), dim3(Sh::NT), Sh::LDS_BYTES, a.stream,
                        (const float*)a.src, (float*)a.dst, f0, f1, st.k_in, st.k_out, tiles_per_row, num_tiles, tpw,
                        st.tile_order);
@@ -139,7 +141,7 @@ static hipError_t launch_shuffle(const LaunchArgs& a)
 }
 
 // Fused FMA instances: X(type, dtype code, P, Q, factors per launch, tile_slices, threads).
-// Register-resident MFMA pairs: Z(P, tile_slices, wavefronts) (fp32, Q = 32, two factors).
+// Register-resident MFMA pairs: Z(P, tile_slices, wavefronts, units fetched ahead) (fp32, Q = 32, two factors).
 // Small-factor instances with several factors per LDS pass and a run-time tile length:
 // W(type, dtype code, P, Q, G0, G1, G2, largest tile_slices, threads).
 // MFMA instances: Y(op, dtype code, P, Q, factors per launch, tile_slices, wavefronts, q split).
@@ -158,18 +160,20 @@ static hipError_t launch_shuffle(const LaunchArgs& a)
     X(float, KM_F32, 8, 8, 1, 64, 64)                   \
     X(float, KM_F32, 8, 8, 1, 8, 64)                    \
     X(float, KM_F32, 8, 8, 1, 1, 64)                    \
-    Z(32, 32, 4)                                        \
+    Z(32, 32, 4, 1)                                     \
     Y(MfmaF32x32, KM_F32, 32, 32, 2, 32, 8, 1)          \
     Y(MfmaF32x32, KM_F32, 32, 32, 2, 32, 16, 1)         \
     Y(MfmaF32x32, KM_F32, 32, 32, 2, 16, 4, 1)          \
     Y(MfmaF32x32, KM_F32, 32, 32, 1, 256, 4, 1)         \
     Y(MfmaF32x32, KM_F32, 32, 32, 1, 128, 4, 1)         \
-    Z(16, 32, 4)                                        \
+    Z(16, 32, 4, 1)                                     \
     Y(MfmaF32x32, KM_F32, 16, 32, 2, 32, 4, 1)          \
     Y(MfmaF32x32, KM_F32, 16, 32, 2, 16, 4, 1)          \
     Y(MfmaF32x32, KM_F32, 16, 32, 1, 256, 4, 1)         \
     Y(MfmaF32x32, KM_F32, 16, 32, 1, 128, 4, 1)         \
     Y(MfmaF64x16, KM_F64, 128, 128, 1, 16, 4, 4)         \
+    Y(MfmaF64x16, KM_F64, 128, 128, 1, 32, 4, 4)         \
+    Y(MfmaF64x16, KM_F64, 128, 128, 1, 32, 8, 8)         \
     Y(MfmaF32x16, KM_F32, 16, 16, 2, 32, 4, 1)          \
     Y(MfmaF32x16, KM_F32, 16, 16, 1, 256, 4, 1)         \
     Y(MfmaF32x16, KM_F32, 16, 16, 1, 64, 4, 1)          \
@@ -225,13 +229,13 @@ static hipError_t launch_shuffle(const LaunchArgs& a)
     {KM_KERNEL_FUSED, DT, P, Q, NF, ST, NT, FusedShape<T, P, Q, NF, ST, NT>::LDS_BYTES, 1, 0, 0, 1.0f, "fused"},
 #define KM_MFMA_ROW(OP, DT, P, Q, NF, ST, NW, QS) \
     {KM_KERNEL_MFMA, DT, P, Q, NF, ST, NW * 64, MfmaShape<OP, P, Q, NF, ST, NW, QS>::LDS_BYTES, 1, 1, 0, 1.0f, "mfma"},
-#define KM_PAIR_ROW(P, ST, NW) \
-    {KM_KERNEL_MFMA, KM_F32, P, 32, 2, ST, NW * 64, MfmaPairShape<P, ST, NW>::LDS_BYTES, 1, 2, 0, 1.0f, "mfma-pair"},
+#define KM_PAIR_ROW(P, ST, NW, PD) \
+    {KM_KERNEL_MFMA, KM_F32, P, 32, 2, ST, NW * 64, MfmaPairShape<P, ST, NW, PD>::LDS_BYTES, 1, 2, 0, 1.0f, "mfma-pair"},
 #define KM_MULTI_ROW(T, DT, P, Q, G0, G1, G2, ST, NT) \
     {KM_KERNEL_FUSED, DT, P, Q, G0 + G1 + G2, ST, NT, MultiShape<T, P, Q, G0, G1, G2, ST, NT>::LDS_BYTES, 1, 0, 1, \
      (G0 == 1 && P < 8) ? 1.6f : 1.0f, "fused-multi"},   /* one tiny factor per LDS pass is instruction-bound */
 #define KM_MULTI_FN(T, DT, P, Q, G0, G1, G2, ST, NT) launch_multi<T, P, Q, G0, G1, G2, ST, NT>,
-#define KM_PAIR_FN(P, ST, NW) launch_mfma_pair<P, ST, NW>,
+#define KM_PAIR_FN(P, ST, NW, PD) launch_mfma_pair<P, ST, NW, PD>,
 #define KM_FUSED_FN(T, DT, P, Q, NF, ST, NT) launch_fused<T, P, Q, NF, ST, NT>,
 #define KM_MFMA_FN(OP, DT, P, Q, NF, ST, NW, QS) launch_mfma<OP, P, Q, NF, ST, NW, QS>,
 
@@ -731,7 +735,7 @@ km_status kronmatmul_set_option(km_option option, int value)
             g_options.pair_interleave = value;
             return KM_OK;
         case KM_OPT_TILE_ORDER:
-            if (value != 0 && value != 2) return KM_EINVAL;
+            if (value != 0 && value != 2 && value != 3) return KM_EINVAL;
             g_options.tile_order = value;
             return KM_OK;
         case KM_OPT_PROFILE:

@@ -275,6 +275,11 @@ void mfma_sliced_multiply(const typename OP::T* __restrict__ Xg, typename OP::T*
         t_begin = blockIdx.x;
         t_step = gridDim.x;
         t_end = num_tiles;
+    } else if (tile_order == 3) {
+        const int64_t per = num_tiles / 8, x = blockIdx.x % 8;
+        t_begin = x * per + blockIdx.x / 8;
+        t_step = gridDim.x / 8;
+        t_end = (x + 1) * per;
     }
     if (t_end > num_tiles) t_end = num_tiles;
 

@@ -27,7 +27,7 @@
 
 namespace km {
 
-template <int P, int ST, int NW>
+template <int P, int ST, int NW, int PD = 1>
 struct MfmaPairShape {
     static constexpr int Q = 32;
     static constexpr int NT = NW * 64;
@@ -44,27 +44,29 @@ struct MfmaPairShape {
     static_assert(P == 16 || P == 32, "P must be 16 or 32");
     static_assert(ST % (AP * NW) == 0 && ST % 4 == 0, "tile must split evenly over the wavefronts");
     static_assert((PASS_ROWS * (ST / 4)) % NT == 0, "output pass must split evenly over the threads");
-    static_assert(UPW % 2 == 0, "the operand double buffer alternates per unit and must wrap per tile");
+    static constexpr int RING = PD + 1;               // operand buffers: PD units in flight + the one in use
+    static_assert(PD >= 1 && PD < UPW && UPW % RING == 0, "the operand ring must wrap once per tile");
     static_assert(RD % 4 == 0, "output reads are issued four at a time");
 };
 
 typedef float pair_f32x16 __attribute__((ext_vector_type(16)));
 typedef float pair_f32x4 __attribute__((ext_vector_type(4)));
 
-template <int P, int ST, int NW>
+template <int P, int ST, int NW, int PD>
 __global__ __launch_bounds__(NW * 64, 2)
 void mfma_pair_sliced_multiply(const float* __restrict__ Xg, float* __restrict__ Yg,
                                const float* __restrict__ F0, const float* __restrict__ F1,   // in order of application
                                int64_t k_in, int64_t k_out, int64_t tiles_per_row, int64_t num_tiles,
                                int64_t tiles_per_wg, int tile_order)
 {
-    typedef MfmaPairShape<P, ST, NW> Sh;
-    constexpr int Q = Sh::Q, KS = Sh::KS, AP = Sh::AP, UPW = Sh::UPW, STP = Sh::STP, NT = Sh::NT;
+    typedef MfmaPairShape<P, ST, NW, PD> Sh;
+    constexpr int Q = Sh::Q, KS = Sh::KS, AP = Sh::AP, UPW = Sh::UPW, STP = Sh::STP, NT = Sh::NT, RING = Sh::RING;
     extern __shared__ __attribute__((aligned(16))) unsigned char pair_lds[];
     float* stage = reinterpret_cast<float*>(pair_lds);
 
     const int tid = threadIdx.x;
-    const int lane = tid % 64, wave = tid / 64;
+    const int lane = tid % 64;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / 64);    // wave-uniform: lets addresses be scalar base + lane offset
     const int col = lane % 32;        // stage 0: row (a_loc, p1) of A, column q2 of B; stage 1: row q1 of A
     const int g = lane / 32;          // which of the two k values of an MFMA step this lane holds
 
@@ -78,25 +80,46 @@ void mfma_pair_sliced_multiply(const float* __restrict__ Xg, float* __restrict__
     }
 
     const int64_t s_row = tiles_per_row * ST;
-    // tile_order 0: a contiguous range of tiles per workgroup; 2: tiles b, b + grid, b + 2*grid, ...
+    // tile_order 0: a contiguous range of tiles per workgroup; 2: tiles b, b + grid, b + 2*grid, ...;
+    // 3: the same stride inside the XCD's own eighth of the tiles
     int64_t t_begin = (int64_t)blockIdx.x * tiles_per_wg, t_step = 1;
     int64_t t_end = t_begin + tiles_per_wg;
     if (tile_order == 2) {
         t_begin = blockIdx.x;
         t_step = gridDim.x;
         t_end = num_tiles;
+    } else if (tile_order == 3) {
+        // each XCD (workgroup b runs on XCD b % 8) owns a contiguous eighth of the tiles and its
+        // workgroups stride through it: neighbouring output runs meet in one L2
+        const int64_t per = num_tiles / 8, x = blockIdx.x % 8;
+        t_begin = x * per + blockIdx.x / 8;
+        t_step = gridDim.x / 8;
+        t_end = (x + 1) * per;
     }
     if (t_end > num_tiles) t_end = num_tiles;
 
     // element offset, inside a tile, of this lane's piece of unit u of this wavefront
-    const int lane_off = col * P + g * KS;
-    auto tile_src = [&](int64_t t) { return Xg + (t / tiles_per_row) * k_in + (t % tiles_per_row) * Sh::TK; };
+    const unsigned lane_off = col * P + g * KS;
+    // tile indices are wave-uniform; saying so keeps tile addresses in scalar registers
+    auto uniform = [](int64_t v) {
+        const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+        const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)((uint64_t)v >> 32));
+        return (int64_t)(((uint64_t)hi << 32) | lo);
+    };
+    auto tile_src = [&](int64_t t) {
+        return Xg + uniform(t / tiles_per_row) * k_in + uniform(t % tiles_per_row) * Sh::TK;
+    };
 
-    pair_f32x4 xa[2][KS / 4];         // double-buffered A operand of stage 0
+    // A operand of stage 0: a ring of PD + 1 units, PD of them in flight while one is multiplied.
+    // Unit v of every tile uses slot v % RING (UPW is a multiple of RING).
+    pair_f32x4 xa[RING][KS / 4];
     if (t_begin < t_end) {
-        const pair_f32x4* src = reinterpret_cast<const pair_f32x4*>(tile_src(t_begin) + (wave * AP) * P * P + lane_off);
 #pragma unroll
-        for (int c = 0; c < KS / 4; ++c) xa[0][c] = src[c];
+        for (int v = 0; v < PD; ++v) {
+            const float* src = tile_src(t_begin) + ((wave + v * NW) * AP) * P * P;
+#pragma unroll
+            for (int c = 0; c < KS / 4; ++c) xa[v][c] = *reinterpret_cast<const pair_f32x4*>(src + (lane_off + 4 * c));
+        }
     }
 
     for (int64_t t = t_begin; t < t_end; t += t_step) {
@@ -107,22 +130,27 @@ void mfma_pair_sliced_multiply(const float* __restrict__ Xg, float* __restrict__
         float keep[Sh::APW][8];
 #pragma unroll
         for (int u = 0; u < UPW; ++u) {
-            // fetch the next unit (of this tile, or the first one of the next tile)
-            if (u + 1 < UPW) {
-                const pair_f32x4* src = reinterpret_cast<const pair_f32x4*>(Xt + ((wave + (u + 1) * NW) * AP) * P * P + lane_off);
+            // fetch unit u + PD (of this tile, or of the next one)
+            {
+                const int v = u + PD;
+                if (v < UPW) {
+                    const float* src = Xt + ((wave + v * NW) * AP) * P * P;
 #pragma unroll
-                for (int c = 0; c < KS / 4; ++c) xa[(u + 1) % 2][c] = src[c];
-            } else if (t + t_step < t_end) {
-                const pair_f32x4* src = reinterpret_cast<const pair_f32x4*>(tile_src(t + t_step) + (wave * AP) * P * P + lane_off);
+                    for (int c = 0; c < KS / 4; ++c)
+                        xa[v % RING][c] = *reinterpret_cast<const pair_f32x4*>(src + (lane_off + 4 * c));
+                } else if (t + t_step < t_end) {
+                    const float* src = tile_src(t + t_step) + ((wave + (v - UPW) * NW) * AP) * P * P;
 #pragma unroll
-                for (int c = 0; c < KS / 4; ++c) xa[(u + 1) % 2][c] = src[c];
+                    for (int c = 0; c < KS / 4; ++c)
+                        xa[v % RING][c] = *reinterpret_cast<const pair_f32x4*>(src + (lane_off + 4 * c));
+                }
             }
             pair_f32x16 d0;
 #pragma unroll
             for (int v = 0; v < 16; ++v) d0[v] = 0.f;
 #pragma unroll
             for (int s = 0; s < KS; ++s)
-                d0 = __builtin_amdgcn_mfma_f32_32x32x2f32(xa[u % 2][s / 4][s % 4], b0[s], d0, 0, 0, 0);
+                d0 = __builtin_amdgcn_mfma_f32_32x32x2f32(xa[u % RING][s / 4][s % 4], b0[s], d0, 0, 0, 0);
 #pragma unroll
             for (int al = 0; al < AP; ++al) {
                 pair_f32x16 acc;
@@ -141,7 +169,7 @@ void mfma_pair_sliced_multiply(const float* __restrict__ Xg, float* __restrict__
             }
         }
 
-        const int64_t row = t / tiles_per_row, h = t % tiles_per_row;
+        const int64_t row = uniform(t / tiles_per_row), h = uniform(t % tiles_per_row);
         float* Yrow = Yg + row * k_out + h * ST;
 #pragma unroll
         for (int pass = 0; pass < 2; ++pass) {

@@ -72,7 +72,8 @@ struct Options {
     int prefer_threads = 0;   // tuning: ... with this workgroup size
     int tiles_per_wg = 0;     // tuning: tiles per workgroup of persistent instances (0 = automatic)
     int pair_interleave = 1;  // neighbouring tiles with short output runs go to workgroup pairs
-    int tile_order = 2;       // persistent kernels: 0 = contiguous tile ranges, 2 = tiles strided by the grid
+    int tile_order = 2;       // persistent kernels: 0 = contiguous tile ranges, 2 = tiles strided by the grid,
+                              // 3 = strided inside the XCD's own eighth of the tiles
 };
 
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -128,6 +129,12 @@ struct Choice {
     int tiles_per_wg = 0;    // persistent instances: 0 = take the rule of tiles_per_wg()
     int tile_order = -1;     // persistent instances: -1 = take the option
 };
+
+// Tile order 3 gives each of the 8 XCDs a contiguous eighth of the tiles, walked by grid / 8 workgroups.
+inline bool xcd_order_fits(int64_t num_tiles, int64_t grid)
+{
+    return num_tiles % 8 == 0 && grid % 8 == 0 && grid >= 8;
+}
 
 // Workgroups of an instance that one compute unit holds at once (160 KB of LDS, 2048 threads).
 inline int64_t resident_per_cu(const Variant& c)
@@ -205,6 +212,10 @@ inline void enumerate_choices(const Variant* table, int count, const Problem& pr
                 ch.tiles_per_wg = (int)w;
                 ch.tile_order = 2;
                 out.push_back(ch);
+                if (w > 1 && xcd_order_fits(ch.grid, (ch.grid + w - 1) / w)) {
+                    ch.tile_order = 3;
+                    out.push_back(ch);
+                }
             }
         }
     }
@@ -323,6 +334,7 @@ inline km_plan_step build_step(const Problem& pr, const Options& opt, const Vari
                 (int64_t)ch.tile_slices * (int64_t)pr.esize < 128 && pair_order_fits(num_tiles, tpw))
                 st.tile_order = 1;
             if (st.tile_order == 1 && (var->persistent != 1 || !pair_order_fits(num_tiles, tpw))) st.tile_order = 0;
+            if (st.tile_order == 3 && !xcd_order_fits(num_tiles, st.grid)) st.tile_order = 2;
         }
     } else {
         st.kernel = KM_KERNEL_GENERIC;

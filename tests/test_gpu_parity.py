@@ -162,6 +162,12 @@ FORCED = [
     ("float32", 16, [(32, 32)] * 3, dict(tile=32, threads=256, tiles_per_wg=3, order=2)),
     ("float32", 4, [(16, 32)] * 4, dict(tile=32, tiles_per_wg=5, order=0)),
     ("float64", 8, [(128, 128)] * 2, dict(tiles_per_wg=1)),
+    ("float64", 8, [(128, 128)] * 2, dict(tiles_per_wg=5, order=3)),
+    ("float64", 8, [(128, 128)] * 2, dict(tile=32, threads=256)),
+    ("float64", 8, [(128, 128)] * 2, dict(tile=32, threads=512, tiles_per_wg=3)),
+    ("float32", 16, [(32, 32)] * 3, dict(tile=32, threads=256, tiles_per_wg=4, order=3)),
+    ("float32", 16, [(32, 32)] * 3, dict(tile=32, threads=256, tiles_per_wg=3, order=3)),   # grid not a multiple of 8: falls back to 2
+    ("float32", 8, [(16, 32)] * 4, dict(tile=32, tiles_per_wg=2, order=3)),
     ("float32", 8, [(8, 8)] * 6, dict(tile=32, threads=256)),
     ("float32", 8, [(8, 8)] * 6, dict(tile=32, threads=1024)),
     ("float32", 8, [(8, 8)] * 6, dict(tile=16, threads=256)),

@@ -105,7 +105,7 @@ def test_plan_is_consistent(M, shapes, dtype):
         assert st["grid"] > 0 and st["block"] > 0
         assert st["lds_bytes"] <= 160 * 1024
         # walking workgroups cover every tile: grid = ceil(tiles / tiles_per_wg)
-        assert st["tile_order"] in (0, 1, 2) and st["tiles_per_wg"] >= 0
+        assert st["tile_order"] in (0, 1, 2, 3) and st["tiles_per_wg"] >= 0
         if st["tiles_per_wg"] > 0:
             pg = int(np.prod(P[st["first_factor"]:st["first_factor"] + st["num_factors"]], dtype=np.int64))
             tiles = M * (st["k_in"] // (st["tile_slices"] * pg))
