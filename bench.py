@@ -28,11 +28,11 @@ PAPER_GFLOPS = {"c2_f32_m1024_8x8x6": 25769803776 / 5.76e-3 / 1e9,
 # (summaries under profiles/); None until measured.
 MEASURED_TRAFFIC = {
     # scaled FETCH_SIZE + WRITE_SIZE of the dominant kernel, from the summaries under profiles/
-    "c1_f32_m16_8x8x3": 85180,             # fused_f32_8x8_nf3_c1_m16_8x8x3.md
-    "c2_f32_m1024_8x8x6": 2147972708,      # fused_f32_8x8_nf3_c2_m1024_8x8x6.md
-    "c3_f32_m1024_32x32x4": 9099635651,    # mfma_f32_32x32_nf2_c3_m1024_32x32x4.md
-    "c4_f64_m16_128x128x3": 537968468,     # mfma_f64_128x128_nf1_c4_m16_128x128x3.md
-    "c5_f32_m256_16x32x4": 1342492607,     # mfma_f32_16x32_nf2_c5_m256_16x32x4.md
+    "c1_f32_m16_8x8x3": 88691,             # fused_f32_8x8_nf3_c1_m16_8x8x3.md
+    "c2_f32_m1024_8x8x6": 2147874395,      # fused_f32_8x8_nf3_c2_m1024_8x8x6.md
+    "c3_f32_m1024_32x32x4": 8593683373,    # mfma_f32_32x32_nf2_c3_m1024_32x32x4.md
+    "c4_f64_m16_128x128x3": 537981406,     # mfma_f64_128x128_nf1_c4_m16_128x128x3.md
+    "c5_f32_m256_16x32x4": 1342527421,     # mfma_f32_16x32_nf2_c5_m256_16x32x4.md
 }
 
 
@@ -181,9 +181,10 @@ def main():
 
     if not args.no_cpu_baseline:
         import oracle
-        # bounded sample: enough rows of the same workload for roughly 10-30 s of CPU work
+        # bounded sample: rows of the same workload worth at most 1e12 multiply-adds (10-30 s of CPU work;
+        # the five measured workloads are smaller than that and are run whole)
         macs_per_row = flops / 2 / M
-        rows = int(max(1, min(M, 4e10 // macs_per_row)))
+        rows = int(max(1, min(M, 1e12 // macs_per_row)))
         c0 = time.perf_counter()
         ref = oracle.kron_matmul(X[:rows], Fs)
         cpu_s = time.perf_counter() - c0
