@@ -194,10 +194,34 @@ def release():
     _check(lib().kronmatmul_release(), "kronmatmul_release")
 
 
-def kronmatmul(X, Fs, Y=None, workspace=None, stream=None):
-    """Y = X (Fs[0] (x) ... (x) Fs[-1]) on the GPU.  X, Fs, Y and workspace are torch CUDA tensors
-    (contiguous, same dtype).  With workspace=None the library's own cached workspace is used.
-    Returns Y.  The call is asynchronous on `stream` (default: torch's current stream)."""
+class Prepared:
+    """A Kron-Matmul call with its arguments already checked and marshalled: calling it only crosses
+    the C-ABI (for iterative callers that repeat one small problem, where marshalling would cost
+    more than the kernels).  Keeps references to the tensors it was built from."""
+
+    def __init__(self, X, Fs, Y=None, workspace=None):
+        import torch
+        self._torch = torch
+        self.Y, self._args, self._ws_call, fptr = _marshal(X, Fs, Y, workspace)
+        self._keep = (X, list(Fs), workspace, fptr)
+        self._device = X.device
+        self._fn = lib().kronmatmul_ws if self._ws_call else lib().kronmatmul
+        self._what = "kronmatmul_ws" if self._ws_call else "kronmatmul"
+
+    def __call__(self, stream=None):
+        """Enqueue on `stream` (a raw hipStream_t value; default: torch's current stream).  The
+        tensors' device must be the current device."""
+        if stream is None:
+            stream = self._torch.cuda.current_stream(self._device).cuda_stream
+        st = self._fn(*self._args, ctypes.c_void_p(stream))
+        if st != KM_OK:
+            raise KronMatmulError(st, self._what)
+        return self.Y
+
+
+def _marshal(X, Fs, Y, workspace):
+    """Checks the tensors and returns (Y, C argument tuple without the stream, uses_workspace, the
+    pointer array the tuple refers to)."""
     import torch
     if not X.is_cuda or X.dim() != 2 or not X.is_contiguous():
         raise ValueError("X must be a contiguous 2-D CUDA tensor")
@@ -222,19 +246,26 @@ def kronmatmul(X, Fs, Y=None, workspace=None, stream=None):
         raise ValueError("Y must be a contiguous CUDA tensor of shape (%d, %d)" % (M, kout))
     code = _dtype_code(X.dtype)
     fptr = (ctypes.c_void_p * max(n, 1))(*[F.data_ptr() for F in Fs])
+    head = (M, n, p, q, X.data_ptr(), ctypes.cast(fptr, ctypes.c_void_p), Y.data_ptr(), code)
+    if workspace is None:
+        return Y, head, False, fptr
+    if not workspace.is_cuda or not workspace.is_contiguous() or workspace.device != X.device:
+        raise ValueError("workspace must be a contiguous CUDA tensor on X's device")
+    nbytes = workspace.numel() * workspace.element_size()
+    return Y, head + (workspace.data_ptr(), nbytes), True, fptr
+
+
+def kronmatmul(X, Fs, Y=None, workspace=None, stream=None):
+    """Y = X (Fs[0] (x) ... (x) Fs[-1]) on the GPU.  X, Fs, Y and workspace are torch CUDA tensors
+    (contiguous, same dtype).  With workspace=None the library's own cached workspace is used.
+    Returns Y.  The call is asynchronous on `stream` (default: torch's current stream)."""
+    import torch
+    Y, args, with_ws, _fptr = _marshal(X, Fs, Y, workspace)
     if stream is None:
         stream = torch.cuda.current_stream(X.device).cuda_stream
     with torch.cuda.device(X.device):
-        if workspace is None:
-            st = lib().kronmatmul(M, n, p, q, X.data_ptr(), ctypes.cast(fptr, ctypes.c_void_p), Y.data_ptr(),
-                                  code, ctypes.c_void_p(stream))
-            _check(st, "kronmatmul")
+        if with_ws:
+            _check(lib().kronmatmul_ws(*args, ctypes.c_void_p(stream)), "kronmatmul_ws")
         else:
-            if not workspace.is_cuda or not workspace.is_contiguous():
-                raise ValueError("workspace must be a contiguous CUDA tensor")
-            nbytes = workspace.numel() * workspace.element_size()
-            st = lib().kronmatmul_ws(M, n, p, q, X.data_ptr(), ctypes.cast(fptr, ctypes.c_void_p),
-                                     Y.data_ptr(), code, workspace.data_ptr(), nbytes,
-                                     ctypes.c_void_p(stream))
-            _check(st, "kronmatmul_ws")
+            _check(lib().kronmatmul(*args, ctypes.c_void_p(stream)), "kronmatmul")
     return Y

@@ -224,6 +224,25 @@ def test_empty_rows_and_library_workspace_reuse():
         assert_close(run_gpu(X, Fs), X, Fs)
 
 
+def test_prepared_call_repeats_without_marshalling():
+    """A prepared call only crosses the C-ABI; repeated with new contents of X it gives what a fresh
+    call gives, with and without a caller workspace."""
+    shapes = [(8, 8)] * 4
+    X, Fs = kron_inputs.make_problem(16, shapes, "float32", seed=41)
+    Xd = torch.from_numpy(X).cuda()
+    Fd = [torch.from_numpy(F).cuda() for F in Fs]
+    ws = torch.empty(max(km.workspace_size(16, [8] * 4, [8] * 4, "float32"), 1), dtype=torch.uint8, device="cuda")
+    for workspace in (None, ws):
+        call = km.Prepared(Xd, Fd, workspace=workspace)
+        for seed in (41, 42, 43):
+            Xn, _ = kron_inputs.make_problem(16, shapes, "float32", seed=seed)
+            Xd.copy_(torch.from_numpy(Xn).cuda())
+            Y = call()
+            torch.cuda.synchronize()
+            assert_close(Y.cpu().numpy(), Xn, Fs)
+            assert torch.equal(Y, km.kronmatmul(Xd, Fd))
+
+
 def test_profiled_call_reports_each_launch():
     X, Fs = kron_inputs.make_problem(8, [(8, 8)] * 4, "float32", seed=5)
     steps = km.plan(8, [8] * 4, [8] * 4, "float32")
