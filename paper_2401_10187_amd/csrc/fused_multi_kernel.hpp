@@ -63,6 +63,8 @@ struct MultiShape {
         return m;
     }
     static constexpr int LDS_BYTES = (lds_elems() * (int)sizeof(T) + 15) / 16 * 16;
+    // the tile only occupies what its st slices need, so short tiles leave LDS to more workgroups
+    static constexpr int LDS_PER_SLICE = lds_elems() / STMAX * (int)sizeof(T);
     static constexpr bool VEC_ROWS = pg(0) % VN == 0;
     static_assert(G0 > 0 && (G1 > 0 || G2 == 0), "super-stages are filled from the first");
 };

@@ -76,7 +76,8 @@ static hipError_t launch_multi(const LaunchArgs& a)
     const int64_t tk = (int64_t)st.tile_slices * Sh::per_slice(0);
     if (st.k_in % tk) return hipErrorInvalidValue;
     const int64_t tiles_per_row = st.k_in / tk;
-    hipLaunchKernelGGL(kern, dim3((unsigned)st.grid), dim3(NT), Sh::LDS_BYTES, a.stream,
+    if (st.lds_bytes < Sh::LDS_PER_SLICE * st.tile_slices || st.lds_bytes > Sh::LDS_BYTES) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(kern, dim3((unsigned)st.grid), dim3(NT), (size_t)st.lds_bytes, a.stream,
                        (const T*)a.src, (T*)a.dst, fp, st.k_in, st.k_out, tiles_per_row, (int64_t)st.grid,
                        st.tile_slices);
     return hipGetLastError();
@@ -233,7 +234,8 @@ static hipError_t launch_shuffle(const LaunchArgs& a)
     {KM_KERNEL_MFMA, KM_F32, P, 32, 2, ST, NW * 64, MfmaPairShape<P, ST, NW, PD>::LDS_BYTES, 1, 2, 0, 1.0f, "mfma-pair"},
 #define KM_MULTI_ROW(T, DT, P, Q, G0, G1, G2, ST, NT) \
     {KM_KERNEL_FUSED, DT, P, Q, G0 + G1 + G2, ST, NT, MultiShape<T, P, Q, G0, G1, G2, ST, NT>::LDS_BYTES, 1, 0, 1, \
-     (G0 == 1 && P < 8) ? 1.6f : 1.0f, "fused-multi"},   /* one tiny factor per LDS pass is instruction-bound */
+     (G0 == 1 && P < 8) ? 1.6f : 1.0f,                   /* one tiny factor per LDS pass is instruction-bound */ \
+     "fused-multi", MultiShape<T, P, Q, G0, G1, G2, ST, NT>::LDS_PER_SLICE},
 #define KM_MULTI_FN(T, DT, P, Q, G0, G1, G2, ST, NT) launch_multi<T, P, Q, G0, G1, G2, ST, NT>,
 #define KM_PAIR_FN(P, ST, NW, PD) launch_mfma_pair<P, ST, NW, PD>,
 #define KM_FUSED_FN(T, DT, P, Q, NF, ST, NT) launch_fused<T, P, Q, NF, ST, NT>,

@@ -25,7 +25,16 @@ struct Variant {
     int flexible;      // 1: tile_slices is an upper limit; the launch picks a divisor of K/prod(P)
     float slowdown;    // measured cost relative to an HBM-bound launch of the same bytes (planner weight)
     const char* name;
+    int lds_per_slice; // flexible instances: LDS bytes per slice of the tile (lds_bytes is the maximum)
 };
+
+// LDS a launch of the instance asks for when its tiles hold `tile_slices` slices.
+inline int launch_lds_bytes(const Variant& c, int tile_slices)
+{
+    if (!c.flexible || c.lds_per_slice <= 0) return c.lds_bytes;
+    const int64_t b = ((int64_t)c.lds_per_slice * tile_slices + 15) / 16 * 16;
+    return b < c.lds_bytes ? (int)b : c.lds_bytes;
+}
 
 // Tiles handled by one workgroup of a persistent instance; `hint` > 0 forces the value.
 // Measured with the autotuner on this chip: a workgroup loads its factors once, so with large
@@ -191,7 +200,7 @@ inline void enumerate_choices(const Variant* table, int count, const Problem& pr
         if (c.dtype != pr.dtype || c.num_factors != nf) continue;
         if (c.P != pr.P[f] || c.Q != pr.Q[f]) continue;
         if (pr.M % c.rows_per_tile) continue;
-        tile_lengths(c, s_row, lens, 3);
+        tile_lengths(c, s_row, lens, 5);
         for (int st : lens) {
             Choice ch;
             ch.var = &c;
@@ -248,13 +257,29 @@ inline Choice find_variant(const Variant* table, int count, const Problem& pr, i
             if (s_row % c.tile_slices) continue;
             cand[0] = c.tile_slices;
         } else {
-            // largest divisor; largest divisor that still leaves enough workgroups; the tuning wish
+            // Best tile length; best one that still leaves enough workgroups; the tuning wish.
+            // "Best" (measured with the autotuner on factors of 3 to 6): output runs that are whole
+            // 128-byte lines before anything else (6x6: runs of 1152 bytes are 50 % faster than runs of
+            // 1296), then tiles of at most 48 KB of LDS (three and more workgroups per compute unit are
+            // 10-30 % faster than two) unless that would cut runs that are not whole lines below 256
+            // bytes (6^6: 288-byte runs in 62 KB tiles are 50 % faster than 96-byte runs in 21 KB
+            // tiles), then the longest tile.
             const int64_t lim = s_row < c.tile_slices ? s_row : c.tile_slices;
-            for (int64_t d = lim; d >= 1 && !cand[0]; --d)
-                if (s_row % d == 0) cand[0] = (int)d;
-            for (int64_t d = lim; d >= 1 && !cand[1]; --d)
-                if (s_row % d == 0 && (pr.M / c.rows_per_tile) * (s_row / d) >= enough) cand[1] = (int)d;
-            if (opt.prefer_tile > 0 && opt.prefer_tile <= lim && s_row % opt.prefer_tile == 0) cand[2] = opt.prefer_tile;
+            const int64_t fit = c.lds_per_slice > 0 ? (48 * 1024) / c.lds_per_slice : lim;
+            const int64_t row_bytes = s_row * (int64_t)pr.esize;
+            const bool alignable = (row_bytes & -row_bytes) >= 32;      // some tile length gives 32-byte aligned runs
+            int64_t best_key[2] = {-1, -1};
+            for (int64_t d = lim; d >= 1; --d) {
+                if (s_row % d) continue;
+                const int64_t run = d * (int64_t)pr.esize;
+                int64_t align = run & -run;                          // largest power of two dividing the run
+                if (align > 128) align = 128;
+                const bool small_enough = d <= fit && (align >= 128 || run >= 256 || !alignable);
+                const int64_t key = (align * 2 + (small_enough ? 1 : 0)) * (lim + 1) + d;
+                if (key > best_key[0]) { best_key[0] = key; cand[0] = (int)d; }
+                if ((pr.M / c.rows_per_tile) * (s_row / d) >= enough && key > best_key[1]) { best_key[1] = key; cand[1] = (int)d; }
+            }
+            if (opt.prefer_tile > 0 && opt.prefer_tile <= c.tile_slices && s_row % opt.prefer_tile == 0) cand[2] = opt.prefer_tile;
         }
         for (int k = 0; k < 3; ++k) {
             if (!cand[k]) continue;
@@ -318,7 +343,7 @@ inline km_plan_step build_step(const Problem& pr, const Options& opt, const Vari
         st.variant = (int)(var - table);
         st.tile_slices = ch.tile_slices;
         st.block = var->threads;
-        st.lds_bytes = var->lds_bytes;
+        st.lds_bytes = launch_lds_bytes(*var, ch.tile_slices);
         st.grid = ch.grid;
         if (var->persistent) {
             const int hint = ch.tiles_per_wg > 0 ? ch.tiles_per_wg : opt.tiles_per_wg;
