@@ -145,6 +145,38 @@ def test_small_integer_bit_exact(dtype, M, shapes):
 
 
 # every compiled instance and launch mode, forced through the tuning options, on mid-size inputs
+def _random_problems(count, seed):
+    """Seeded random problems: any mix of factor shapes (runs of equal shapes are likely, so fused
+    groups, single launches and the generic kernel all occur), rows of at most 2^17 elements."""
+    rng = np.random.default_rng(seed)
+    pool = [1, 2, 2, 3, 4, 4, 5, 6, 7, 8, 8, 9, 12, 16, 16, 17, 32, 32, 33, 64]
+    out = []
+    while len(out) < count:
+        n = int(rng.integers(1, 7))
+        shapes = []
+        while len(shapes) < n:
+            p, q = int(rng.choice(pool)), int(rng.choice(pool))
+            if rng.random() < 0.6:
+                q = p
+            shapes += [(p, q)] * int(min(n - len(shapes), rng.integers(1, 4)))
+        widths = [int(np.prod([s[0] for s in shapes], dtype=np.int64))]
+        for p, q in reversed(shapes):
+            widths.append(widths[-1] // p * q)
+        if max(widths) > 2 ** 17:
+            continue
+        out.append(("float32" if rng.random() < 0.6 else "float64", int(rng.integers(1, 41)), shapes))
+    return out
+
+
+@pytest.mark.parametrize("dtype,M,shapes", _random_problems(48, 2024), ids=lambda v: str(v).replace(" ", ""))
+def test_random_shapes(dtype, M, shapes):
+    X, Fs = kron_inputs.make_problem(M, shapes, dtype, seed=300 + M + len(shapes))
+    assert_close(run_gpu(X, Fs), X, Fs)
+    Xi, Fi = kron_inputs.make_problem(M, shapes, dtype, x="int2", f="int1", seed=400 + M)
+    if 2.0 * np.prod([s[0] for s in shapes], dtype=np.float64) < (2 ** 24 if dtype == "float32" else 2 ** 53):
+        assert_close(run_gpu(Xi, Fi, use_ws=True), Xi, Fi, exact=True)
+
+
 FORCED = [
     ("float32", 64, [(32, 32)] * 3, dict(tile=16, threads=256, tiles_per_wg=1, pair=1)),
     ("float32", 64, [(32, 32)] * 3, dict(tile=16, threads=256, tiles_per_wg=4, pair=1)),

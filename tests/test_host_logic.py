@@ -181,6 +181,36 @@ def test_walk_lengths_follow_the_measured_rule():
     assert all(st["grid"] >= 512 for st in few)
 
 
+def test_host_entry_points_are_thread_safe():
+    """Planning from several threads at once (the plan cache and the options are shared state) gives
+    what planning serially gives."""
+    import threading
+    rng = np.random.default_rng(5)
+    problems = []
+    for _ in range(40):
+        n = int(rng.integers(1, 7))
+        p = int(rng.choice([2, 3, 4, 5, 6, 8, 16, 32, 64, 7]))
+        problems.append((int(rng.integers(1, 2000)), [p] * n, [p] * n, "float32" if rng.random() < 0.5 else "float64"))
+    serial = [(km.plan(*pr), km.workspace_size(*pr), km.cost(*pr)) for pr in problems]
+    results, errors = {}, []
+
+    def work(t):
+        try:
+            for rep in range(5):
+                for i in range(t, len(problems), 4):
+                    results[(t, rep, i)] = (km.plan(*problems[i]), km.workspace_size(*problems[i]), km.cost(*problems[i]))
+        except Exception as e:          # noqa: BLE001 - reported below
+            errors.append(e)
+
+    threads = [threading.Thread(target=work, args=(t,)) for t in range(4)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    assert not errors
+    assert all(v == serial[i] for (_, _, i), v in results.items())
+
+
 def test_tile_instances_are_skipped_for_rows_beyond_32_bit_offsets():
     # 2^31 bytes per row and more: only the generic kernel addresses such rows
     steps = km.plan(1, [8] * 10, [8] * 10, "float32")
