@@ -224,7 +224,29 @@ static hipError_t launch_shuffle(const LaunchArgs& a)
     W(double, KM_F64, 5, 5, 1, 0, 0, 625, 256)          \
     W(double, KM_F64, 6, 6, 1, 1, 1, 36, 256)           \
     W(double, KM_F64, 6, 6, 1, 1, 0, 216, 256)          \
-    W(double, KM_F64, 6, 6, 1, 0, 0, 1296, 256)
+    W(double, KM_F64, 6, 6, 1, 0, 0, 1296, 256)         \
+    W(float, KM_F32, 7, 7, 2, 1, 0, 32, 256)            \
+    W(float, KM_F32, 7, 7, 2, 0, 0, 256, 256)           \
+    W(float, KM_F32, 7, 7, 1, 0, 0, 2048, 256)          \
+    W(float, KM_F32, 9, 9, 1, 1, 1, 16, 256)            \
+    W(float, KM_F32, 9, 9, 1, 1, 0, 128, 256)           \
+    W(float, KM_F32, 9, 9, 1, 0, 0, 1024, 256)          \
+    W(float, KM_F32, 10, 10, 1, 1, 1, 12, 256)          \
+    W(float, KM_F32, 10, 10, 1, 1, 0, 100, 256)         \
+    W(float, KM_F32, 10, 10, 1, 0, 0, 1000, 256)        \
+    W(float, KM_F32, 12, 12, 1, 1, 0, 72, 256)          \
+    W(float, KM_F32, 12, 12, 1, 0, 0, 864, 256)         \
+    W(double, KM_F64, 7, 7, 2, 1, 0, 16, 256)           \
+    W(double, KM_F64, 7, 7, 2, 0, 0, 128, 256)          \
+    W(double, KM_F64, 7, 7, 1, 0, 0, 1024, 256)         \
+    W(double, KM_F64, 9, 9, 1, 1, 1, 8, 256)            \
+    W(double, KM_F64, 9, 9, 1, 1, 0, 64, 256)           \
+    W(double, KM_F64, 9, 9, 1, 0, 0, 512, 256)          \
+    W(double, KM_F64, 10, 10, 1, 1, 1, 6, 256)          \
+    W(double, KM_F64, 10, 10, 1, 1, 0, 50, 256)         \
+    W(double, KM_F64, 10, 10, 1, 0, 0, 500, 256)        \
+    W(double, KM_F64, 12, 12, 1, 1, 0, 36, 256)         \
+    W(double, KM_F64, 12, 12, 1, 0, 0, 432, 256)
 
 #define KM_FUSED_ROW(T, DT, P, Q, NF, ST, NT) \
     {KM_KERNEL_FUSED, DT, P, Q, NF, ST, NT, FusedShape<T, P, Q, NF, ST, NT>::LDS_BYTES, 1, 0, 0, 1.0f, "fused"},

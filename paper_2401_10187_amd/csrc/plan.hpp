@@ -310,7 +310,7 @@ inline double launch_cost(const Problem& pr, int64_t k_in, int64_t k_out, const 
     double slow = 3.0;                                   // generic kernel
     if (ch.var) {
         const int64_t run = (int64_t)ch.tile_slices * (int64_t)pr.esize;
-        slow = run >= 128 ? 1.0 : (run >= 64 ? 1.25 : (run >= 32 ? 1.6 : 2.5));
+        slow = run >= 128 ? 1.0 : (run >= 64 ? 1.25 : (run >= 32 ? 2.5 : 4.0));
         slow *= ch.var->slowdown;
     }
     return bytes * slow + 2.5e7;                         // ~5 us of launch latency at 5 TB/s

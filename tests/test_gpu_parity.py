@@ -121,6 +121,14 @@ SMALL_CASES = [
     ("float64", 2, [(5, 5)] * 5),
     ("float64", 2, [(6, 6)] * 5),
     ("float64", 1, [(6, 6)] * 3 + [(3, 3)] * 2),
+    ("float32", 3, [(7, 7)] * 5),
+    ("float64", 2, [(7, 7)] * 5),
+    ("float32", 2, [(9, 9)] * 4),
+    ("float64", 3, [(9, 9)] * 4),
+    ("float32", 5, [(10, 10)] * 4),
+    ("float64", 1, [(10, 10)] * 4),
+    ("float32", 2, [(12, 12)] * 4),
+    ("float64", 3, [(12, 12)] * 3),
 ]
 
 
