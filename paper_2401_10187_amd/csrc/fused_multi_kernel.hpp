@@ -255,7 +255,21 @@ void fused_multi_sliced_multiply(const T* __restrict__ Xg, T* __restrict__ Yg,
             if (v < nv) *reinterpret_cast<V*>(tile + multi_lds_index<PG0, PAD0>(v * VN)) = tmp[i];
         }
     } else {
-        for (int e = tid; e < tk; e += NT) tile[multi_lds_index<PG0, PAD0>(e)] = src[e];
+        // rows that are not 16-byte aligned: 4- or 8-byte loads, eight in flight per thread
+        constexpr int UN = 8;
+        for (int base = 0; base < tk; base += UN * NT) {
+            T tmp[UN];
+#pragma unroll
+            for (int i = 0; i < UN; ++i) {
+                const int e = base + tid + i * NT;
+                if (e < tk) tmp[i] = stream_load(&src[e]);
+            }
+#pragma unroll
+            for (int i = 0; i < UN; ++i) {
+                const int e = base + tid + i * NT;
+                if (e < tk) tile[multi_lds_index<PG0, PAD0>(e)] = tmp[i];
+            }
+        }
     }
     __syncthreads();
 
