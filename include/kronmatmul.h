@@ -94,6 +94,23 @@ km_status kronmatmul_ws(int M, int N, const int* P, const int* Q,
                         const void* X, const void* const* F, void* Y,
                         km_dtype dtype, void* workspace, size_t workspace_bytes, void* stream);
 
+/* The same product with every factor given transposed: Ft[i] is the Q[i] x P[i] row-major array
+ * whose transpose is the factor applied, Y = X * (Ft[0]^T (x) ... (x) Ft[N-1]^T); X is M x prod(P),
+ * Y is M x prod(Q) as before.  (The operation is the paper's, section 2; this form serves callers
+ * that hold the transposes, e.g. the gradient dX = dY * (F[0]^T (x) ...) of a Kron-Matmul.)  The
+ * factors, which are small, are first copied in P x Q layout behind the plan's workspace by one
+ * extra launch on `stream`; everything after that is the path of kronmatmul.  The workspace is
+ * larger by those copies: kronmatmul_transposed_workspace_size.  kronmatmul_transposed uses the
+ * library's cached workspace, kronmatmul_transposed_ws the caller's and never allocates. */
+km_status kronmatmul_transposed_workspace_size(int M, int N, const int* P, const int* Q, km_dtype dtype,
+                                               size_t* bytes);
+km_status kronmatmul_transposed(int M, int N, const int* P, const int* Q,
+                                const void* X, const void* const* Ft, void* Y,
+                                km_dtype dtype, void* stream);
+km_status kronmatmul_transposed_ws(int M, int N, const int* P, const int* Q,
+                                   const void* X, const void* const* Ft, void* Y,
+                                   km_dtype dtype, void* workspace, size_t workspace_bytes, void* stream);
+
 /* The launches kronmatmul would issue for this problem, in order.  Writes at most `cap` steps and
  * the total count to *nsteps.  Pure host computation (no device needed). */
 km_status kronmatmul_plan(int M, int N, const int* P, const int* Q, km_dtype dtype,

@@ -17,6 +17,7 @@ EXPORTS = [
     "kronmatmul_store_column", "kronmatmul_cost", "kronmatmul_set_option", "kronmatmul_get_option",
     "kronmatmul_last_profile", "kronmatmul_mean_profile", "kronmatmul_release", "kronmatmul_status_string",
     "kronmatmul_kernel_name", "kronmatmul_tune",
+    "kronmatmul_transposed_workspace_size", "kronmatmul_transposed", "kronmatmul_transposed_ws",
 ]
 
 
@@ -56,6 +57,12 @@ def lib():
         L.kronmatmul.argtypes = [ci, ci, ip, ip, vp, vp, vp, ci, vp]
         L.kronmatmul_ws.restype = ci
         L.kronmatmul_ws.argtypes = [ci, ci, ip, ip, vp, vp, vp, ci, vp, ctypes.c_size_t, vp]
+        L.kronmatmul_transposed_workspace_size.restype = ci
+        L.kronmatmul_transposed_workspace_size.argtypes = [ci, ci, ip, ip, ci, ctypes.POINTER(ctypes.c_size_t)]
+        L.kronmatmul_transposed.restype = ci
+        L.kronmatmul_transposed.argtypes = [ci, ci, ip, ip, vp, vp, vp, ci, vp]
+        L.kronmatmul_transposed_ws.restype = ci
+        L.kronmatmul_transposed_ws.argtypes = [ci, ci, ip, ip, vp, vp, vp, ci, vp, ctypes.c_size_t, vp]
         L.kronmatmul_plan.restype = ci
         L.kronmatmul_plan.argtypes = [ci, ci, ip, ip, ci, ctypes.POINTER(PlanStep), ci, ip]
         L.kronmatmul_tune.restype = ci
@@ -115,11 +122,12 @@ def _dtype_code(dtype):
     raise TypeError("unsupported dtype %r (float32 and float64 only)" % (dtype,))
 
 
-def workspace_size(M, P, Q, dtype):
+def workspace_size(M, P, Q, dtype, transposed=False):
+    """Bytes of workspace kronmatmul_ws (or, with transposed=True, kronmatmul_transposed_ws) needs."""
     n, p, q = _shapes(P, Q)
     out = ctypes.c_size_t(0)
-    _check(lib().kronmatmul_workspace_size(int(M), n, p, q, _dtype_code(dtype), ctypes.byref(out)),
-           "kronmatmul_workspace_size")
+    fn = lib().kronmatmul_transposed_workspace_size if transposed else lib().kronmatmul_workspace_size
+    _check(fn(int(M), n, p, q, _dtype_code(dtype), ctypes.byref(out)), "kronmatmul_workspace_size")
     return int(out.value)
 
 
@@ -199,14 +207,14 @@ class Prepared:
     the C-ABI (for iterative callers that repeat one small problem, where marshalling would cost
     more than the kernels).  Keeps references to the tensors it was built from."""
 
-    def __init__(self, X, Fs, Y=None, workspace=None):
+    def __init__(self, X, Fs, Y=None, workspace=None, transposed=False):
         import torch
         self._torch = torch
-        self.Y, self._args, self._ws_call, fptr = _marshal(X, Fs, Y, workspace)
+        self.Y, self._args, self._ws_call, fptr = _marshal(X, Fs, Y, workspace, transposed)
         self._keep = (X, list(Fs), workspace, fptr)
         self._device = X.device
-        self._fn = lib().kronmatmul_ws if self._ws_call else lib().kronmatmul
-        self._what = "kronmatmul_ws" if self._ws_call else "kronmatmul"
+        self._what = _entry_name(self._ws_call, transposed)
+        self._fn = getattr(lib(), self._what)
 
     def __call__(self, stream=None):
         """Enqueue on `stream` (a raw hipStream_t value; default: torch's current stream).  The
@@ -219,7 +227,11 @@ class Prepared:
         return self.Y
 
 
-def _marshal(X, Fs, Y, workspace):
+def _entry_name(with_ws, transposed):
+    return "kronmatmul" + ("_transposed" if transposed else "") + ("_ws" if with_ws else "")
+
+
+def _marshal(X, Fs, Y, workspace, transposed=False):
     """Checks the tensors and returns (Y, C argument tuple without the stream, uses_workspace, the
     pointer array the tuple refers to)."""
     import torch
@@ -229,8 +241,8 @@ def _marshal(X, Fs, Y, workspace):
     for F in Fs:
         if not F.is_cuda or F.dim() != 2 or not F.is_contiguous() or F.dtype != X.dtype or F.device != X.device:
             raise ValueError("factors must be contiguous 2-D CUDA tensors of X's dtype and device")
-        P.append(F.shape[0])
-        Q.append(F.shape[1])
+        P.append(F.shape[1] if transposed else F.shape[0])
+        Q.append(F.shape[0] if transposed else F.shape[1])
     n, p, q = _shapes(P, Q)
     kin = kout = 1
     for a, b in zip(P, Q):
@@ -255,17 +267,16 @@ def _marshal(X, Fs, Y, workspace):
     return Y, head + (workspace.data_ptr(), nbytes), True, fptr
 
 
-def kronmatmul(X, Fs, Y=None, workspace=None, stream=None):
+def kronmatmul(X, Fs, Y=None, workspace=None, stream=None, transposed=False):
     """Y = X (Fs[0] (x) ... (x) Fs[-1]) on the GPU.  X, Fs, Y and workspace are torch CUDA tensors
     (contiguous, same dtype).  With workspace=None the library's own cached workspace is used.
+    With transposed=True every Fs[i] holds the transpose of the factor applied (shape Q_i x P_i).
     Returns Y.  The call is asynchronous on `stream` (default: torch's current stream)."""
     import torch
-    Y, args, with_ws, _fptr = _marshal(X, Fs, Y, workspace)
+    Y, args, with_ws, _fptr = _marshal(X, Fs, Y, workspace, transposed)
     if stream is None:
         stream = torch.cuda.current_stream(X.device).cuda_stream
+    name = _entry_name(with_ws, transposed)
     with torch.cuda.device(X.device):
-        if with_ws:
-            _check(lib().kronmatmul_ws(*args, ctypes.c_void_p(stream)), "kronmatmul_ws")
-        else:
-            _check(lib().kronmatmul(*args, ctypes.c_void_p(stream)), "kronmatmul")
+        _check(getattr(lib(), name)(*args, ctypes.c_void_p(stream)), name)
     return Y

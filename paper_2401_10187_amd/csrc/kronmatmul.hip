@@ -594,6 +594,106 @@ static km_status tune(const Problem& pr, const Options& opt, hipStream_t stream,
     return KM_OK;
 }
 
+// ---------------------------------------------------------------------------------------------
+// factors given transposed
+// ---------------------------------------------------------------------------------------------
+// Copies of the factors in the layout the kernels read (P x Q row-major) sit behind the plan's own
+// workspace, each on a 256-byte boundary.
+static size_t factor_copy_bytes(const Problem& pr)
+{
+    size_t b = 0;
+    for (int i = 0; i < pr.N; ++i) b += round_up((size_t)pr.P[i] * pr.Q[i] * pr.esize, 256);
+    return b;
+}
+
+struct TransposeArgs {
+    const void* src[64];      // stored Q x P, row-major
+    void* dst[64];            // P x Q, row-major
+    int p[64], q[64];
+};
+
+// one workgroup per factor
+template <typename T>
+__global__ __launch_bounds__(256) void transpose_factors(TransposeArgs a)
+{
+    const int f = blockIdx.x;
+    const T* src = static_cast<const T*>(a.src[f]);
+    T* dst = static_cast<T*>(a.dst[f]);
+    const int P = a.p[f], Q = a.q[f];
+    for (int e = threadIdx.x; e < P * Q; e += blockDim.x) {
+        const int pp = e / Q, qq = e % Q;             // element (pp, qq) of the P x Q result
+        dst[e] = src[(int64_t)qq * P + pp];
+    }
+}
+
+// Library-managed workspace of at least `need` bytes on the current device (grown on demand).
+static km_status library_workspace(size_t need, void** ws)
+{
+    *ws = nullptr;
+    if (need == 0) return KM_OK;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return KM_ELAUNCH;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    DeviceState& ds = g_dev[dev];
+    if (ds.ws_bytes < need) {
+        if (ds.ws) {
+            // work already enqueued may still read the old buffer
+            if (hipDeviceSynchronize() != hipSuccess) return KM_ELAUNCH;
+            (void)hipFree(ds.ws);
+            ds.ws = nullptr; ds.ws_bytes = 0;
+        }
+        if (hipMalloc(&ds.ws, need) != hipSuccess) { (void)hipGetLastError(); ds.ws = nullptr; return KM_ENOMEM; }
+        ds.ws_bytes = need;
+    }
+    *ws = ds.ws;
+    return KM_OK;
+}
+
+// The body of every compute entry point.  own_ws: the caller passed a workspace (else the library's).
+static km_status execute(int M, int N, const int* P, const int* Q, const void* X, const void* const* F, void* Y,
+                         km_dtype dtype, bool own_ws, void* workspace, size_t workspace_bytes, void* stream,
+                         bool transposed)
+{
+    Problem pr;
+    km_status s = make_problem(M, N, P, Q, (int)dtype, pr);
+    if (s != KM_OK) return s;
+    s = check_pointers(pr, X, F, Y);
+    if (s != KM_OK) return s;
+    if (pr.M == 0) return KM_OK;
+    Plan plan;
+    s = plan_for(pr, plan);
+    if (s != KM_OK) return s;
+    const size_t plan_need = round_up(plan.ws0_bytes + plan.ws1_bytes, 256);
+    const size_t need = transposed ? plan_need + factor_copy_bytes(pr) : plan.ws0_bytes + plan.ws1_bytes;
+    void* ws = workspace;
+    if (own_ws) {
+        if (need > 0 && (!workspace || workspace_bytes < need)) return KM_ENOMEM;
+        if (need > 0 && !aligned(workspace, 16)) return KM_EINVAL;
+    } else {
+        s = library_workspace(need, &ws);
+        if (s != KM_OK) return s;
+    }
+    if (!transposed) return run(pr, plan, X, F, Y, ws, (hipStream_t)stream);
+
+    TransposeArgs ta;
+    const void* fcopy[64];
+    char* at = (char*)ws + plan_need;
+    for (int i = 0; i < pr.N; ++i) {
+        ta.src[i] = F[i];
+        ta.dst[i] = at;
+        ta.p[i] = pr.P[i];
+        ta.q[i] = pr.Q[i];
+        fcopy[i] = at;
+        at += round_up((size_t)pr.P[i] * pr.Q[i] * pr.esize, 256);
+    }
+    if (pr.dtype == KM_F32)
+        hipLaunchKernelGGL(transpose_factors<float>, dim3(pr.N), dim3(256), 0, (hipStream_t)stream, ta);
+    else
+        hipLaunchKernelGGL(transpose_factors<double>, dim3(pr.N), dim3(256), 0, (hipStream_t)stream, ta);
+    if (hipGetLastError() != hipSuccess) return KM_ELAUNCH;
+    return run(pr, plan, X, fcopy, Y, ws, (hipStream_t)stream);
+}
+
 }  // namespace km
 
 using namespace km;
@@ -618,53 +718,42 @@ km_status kronmatmul_workspace_size(int M, int N, const int* P, const int* Q, km
 km_status kronmatmul_ws(int M, int N, const int* P, const int* Q, const void* X, const void* const* F,
                         void* Y, km_dtype dtype, void* workspace, size_t workspace_bytes, void* stream)
 {
-    Problem pr;
-    km_status s = make_problem(M, N, P, Q, (int)dtype, pr);
-    if (s != KM_OK) return s;
-    s = check_pointers(pr, X, F, Y);
-    if (s != KM_OK) return s;
-    if (pr.M == 0) return KM_OK;
-    Plan plan;
-    s = plan_for(pr, plan);
-    if (s != KM_OK) return s;
-    const size_t need = plan.ws0_bytes + plan.ws1_bytes;
-    if (need > 0 && (!workspace || workspace_bytes < need)) return KM_ENOMEM;
-    if (need > 0 && !aligned(workspace, 16)) return KM_EINVAL;
-    return run(pr, plan, X, F, Y, workspace, (hipStream_t)stream);
+    return execute(M, N, P, Q, X, F, Y, dtype, true, workspace, workspace_bytes, stream, false);
 }
 
 km_status kronmatmul(int M, int N, const int* P, const int* Q, const void* X, const void* const* F,
                      void* Y, km_dtype dtype, void* stream)
 {
+    return execute(M, N, P, Q, X, F, Y, dtype, false, nullptr, 0, stream, false);
+}
+
+km_status kronmatmul_transposed_workspace_size(int M, int N, const int* P, const int* Q, km_dtype dtype,
+                                               size_t* bytes)
+{
+    if (!bytes) return KM_EINVAL;
     Problem pr;
     km_status s = make_problem(M, N, P, Q, (int)dtype, pr);
     if (s != KM_OK) return s;
-    s = check_pointers(pr, X, F, Y);
-    if (s != KM_OK) return s;
+    *bytes = 0;
     if (pr.M == 0) return KM_OK;
     Plan plan;
     s = plan_for(pr, plan);
     if (s != KM_OK) return s;
-    const size_t need = plan.ws0_bytes + plan.ws1_bytes;
-    void* ws = nullptr;
-    if (need > 0) {
-        int dev = 0;
-        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return KM_ELAUNCH;
-        std::lock_guard<std::mutex> lock(g_mutex);
-        DeviceState& ds = g_dev[dev];
-        if (ds.ws_bytes < need) {
-            if (ds.ws) {
-                // work already enqueued may still read the old buffer
-                if (hipDeviceSynchronize() != hipSuccess) return KM_ELAUNCH;
-                (void)hipFree(ds.ws);
-                ds.ws = nullptr; ds.ws_bytes = 0;
-            }
-            if (hipMalloc(&ds.ws, need) != hipSuccess) { (void)hipGetLastError(); ds.ws = nullptr; return KM_ENOMEM; }
-            ds.ws_bytes = need;
-        }
-        ws = ds.ws;
-    }
-    return run(pr, plan, X, F, Y, ws, (hipStream_t)stream);
+    *bytes = round_up(plan.ws0_bytes + plan.ws1_bytes, 256) + factor_copy_bytes(pr);
+    return KM_OK;
+}
+
+km_status kronmatmul_transposed_ws(int M, int N, const int* P, const int* Q, const void* X,
+                                   const void* const* Ft, void* Y, km_dtype dtype, void* workspace,
+                                   size_t workspace_bytes, void* stream)
+{
+    return execute(M, N, P, Q, X, Ft, Y, dtype, true, workspace, workspace_bytes, stream, true);
+}
+
+km_status kronmatmul_transposed(int M, int N, const int* P, const int* Q, const void* X,
+                                const void* const* Ft, void* Y, km_dtype dtype, void* stream)
+{
+    return execute(M, N, P, Q, X, Ft, Y, dtype, false, nullptr, 0, stream, true);
 }
 
 km_status kronmatmul_tune(int M, int N, const int* P, const int* Q, km_dtype dtype, void* stream,

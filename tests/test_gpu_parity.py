@@ -283,6 +283,49 @@ def test_prepared_call_repeats_without_marshalling():
             assert torch.equal(Y, km.kronmatmul(Xd, Fd))
 
 
+@pytest.mark.parametrize("dtype,M,shapes", [
+    ("float32", 16, [(8, 8)] * 3),
+    ("float32", 7, [(3, 5), (4, 2), (6, 6), (2, 3)]),
+    ("float32", 9, [(16, 32)] * 3),
+    ("float64", 2, [(128, 128)] * 2),
+    ("float32", 5, [(8, 8), (8, 8), (32, 32), (32, 32)]),
+    ("float64", 3, [(33, 17), (2, 65)]),
+], ids=lambda v: str(v).replace(" ", ""))
+def test_transposed_factors(dtype, M, shapes):
+    """Factors handed over transposed (Q x P arrays) give the result of the plain form; the oracle is
+    fed the untransposed factors.  Library and caller workspace, and a prepared call."""
+    X, Fs = kron_inputs.make_problem(M, shapes, dtype, seed=51)
+    Xd = torch.from_numpy(X).cuda()
+    Ft = [torch.from_numpy(np.ascontiguousarray(F.T)).cuda() for F in Fs]
+    Y = km.kronmatmul(Xd, Ft, transposed=True)
+    torch.cuda.synchronize()
+    assert_close(Y.cpu().numpy(), X, Fs)
+    P, Q = [s[0] for s in shapes], [s[1] for s in shapes]
+    ws = torch.empty(max(km.workspace_size(M, P, Q, dtype, transposed=True), 1), dtype=torch.uint8, device="cuda")
+    Y2 = km.kronmatmul(Xd, Ft, workspace=ws, transposed=True)
+    Y3 = km.Prepared(Xd, Ft, workspace=ws, transposed=True)()
+    torch.cuda.synchronize()
+    assert torch.equal(Y, Y2) and torch.equal(Y, Y3)
+    assert torch.equal(Y, km.kronmatmul(Xd, [torch.from_numpy(F).cuda() for F in Fs]))
+    small = torch.empty(max(ws.numel() - 256, 1), dtype=torch.uint8, device="cuda")
+    with pytest.raises(km.KronMatmulError):
+        km.kronmatmul(Xd, Ft, workspace=small, transposed=True)
+
+
+def test_transposed_form_is_the_gradient_of_the_plain_form():
+    """d/dX of sum(Y * G) with Y = X (F1 (x) F2 (x) F3) is G (F1^T (x) F2^T (x) F3^T): handing the
+    factors of the forward pass to the transposed entry point as they are gives that product (its
+    shapes are then Q x P).  Checked against the oracle applied to the transposes."""
+    shapes = [(4, 6), (8, 8), (5, 3)]
+    _, Fs = kron_inputs.make_problem(1, shapes, "float64", seed=61)
+    G = kron_inputs.draw((6, 6 * 8 * 3), "float64", "normal", 62, 0)
+    Fd = [torch.from_numpy(F).cuda() for F in Fs]
+    dX = km.kronmatmul(torch.from_numpy(G).cuda(), Fd, transposed=True)      # stored P x Q = transpose of Q x P
+    torch.cuda.synchronize()
+    assert dX.shape == (6, 4 * 8 * 5)
+    assert_close(dX.cpu().numpy(), G, [np.ascontiguousarray(F.T) for F in Fs])
+
+
 def test_profiled_call_reports_each_launch():
     X, Fs = kron_inputs.make_problem(8, [(8, 8)] * 4, "float32", seed=5)
     steps = km.plan(8, [8] * 4, [8] * 4, "float32")

@@ -275,6 +275,25 @@ def test_argument_errors_are_status_codes():
     assert _raw(4, [7, 11], [3, 5], bad, [bad, bad], bad, with_ws=True) == km.KM_ENOMEM
 
 
+def test_transposed_form_needs_room_for_the_factor_copies():
+    """The transposed-factor entry points copy the factors behind the plan's workspace: each copy on a
+    256-byte boundary.  Their argument checks are those of the plain form."""
+    for M, P, Q, dtype, es in [(4, [7, 11], [3, 5], "float32", 4), (16, [8] * 3, [8] * 3, "float32", 4),
+                               (2, [128] * 2, [128] * 2, "float64", 8)]:
+        plain = km.workspace_size(M, P, Q, dtype)
+        copies = sum((p * q * es + 255) // 256 * 256 for p, q in zip(P, Q))
+        assert km.workspace_size(M, P, Q, dtype, transposed=True) == (plain + 255) // 256 * 256 + copies
+    assert km.workspace_size(0, [8], [8], "float32", transposed=True) == 0
+    L = km.lib()
+    bad = 0x1000
+    p, q = (ctypes.c_int * 1)(2), (ctypes.c_int * 1)(2)
+    f = ctypes.cast((ctypes.c_void_p * 1)(bad), ctypes.c_void_p)
+    assert L.kronmatmul_transposed(4, 1, p, q, None, f, bad, 0, None) == km.KM_EINVAL
+    assert L.kronmatmul_transposed(-1, 1, p, q, bad, f, bad, 0, None) == km.KM_EINVAL
+    assert L.kronmatmul_transposed_ws(4, 1, p, q, bad, f, bad, 0, None, 0, None) == km.KM_ENOMEM   # copies need room
+    assert L.kronmatmul_transposed_ws(0, 1, p, q, None, f, None, 0, None, 0, None) == km.KM_OK
+
+
 def test_workspace_size_errors():
     L = km.lib()
     p = (ctypes.c_int * 1)(2)
