@@ -31,7 +31,7 @@ constexpr int gen_lds_bytes()
 template <typename T>
 __global__ __launch_bounds__(GEN_THREADS)
 void sliced_multiply_generic(const T* __restrict__ Xg, const T* __restrict__ Fg, T* __restrict__ Yg,
-                             int64_t K, int P, int Q, int64_t tiles_per_row)
+                             int64_t K, int P, int Q, int64_t tiles_per_row, int64_t num_tiles)
 {
     typedef typename Vec16<T>::type V;
     constexpr int VN = Vec16<T>::N;
@@ -40,75 +40,78 @@ void sliced_multiply_generic(const T* __restrict__ Xg, const T* __restrict__ Fg,
     __shared__ __attribute__((aligned(16))) T Fs[GEN_TP][GEN_TQ];
 
     const int64_t S = K / P;
-    const int64_t row = blockIdx.x / tiles_per_row;
-    const int64_t s0 = (blockIdx.x % tiles_per_row) * GEN_TS;
     const int tid = threadIdx.x;
     const int lane = tid % 64, wave = tid / 64;
-    const T* Xrow = Xg + row * K;
-    T* Yrow = Yg + row * (S * Q);
     // 16-byte global loads are possible when every slice chunk starts on a 16-byte boundary
     const bool vec_ok = (P % VN == 0) && (K % VN == 0);
 
-    for (int q0 = 0; q0 < Q; q0 += GEN_TQ) {
-        T acc[GEN_RS][GEN_QR];
+    // the grid may be smaller than the number of tiles (launches are limited to 2^32 work-items)
+    for (int64_t tile = blockIdx.x; tile < num_tiles; tile += gridDim.x) {
+        const int64_t row = tile / tiles_per_row;
+        const int64_t s0 = (tile % tiles_per_row) * GEN_TS;
+        const T* Xrow = Xg + row * K;
+        T* Yrow = Yg + row * (S * Q);
+        for (int q0 = 0; q0 < Q; q0 += GEN_TQ) {
+            T acc[GEN_RS][GEN_QR];
 #pragma unroll
-        for (int r = 0; r < GEN_RS; ++r)
+            for (int r = 0; r < GEN_RS; ++r)
 #pragma unroll
-            for (int j = 0; j < GEN_QR; ++j) acc[r][j] = T(0);
+                for (int j = 0; j < GEN_QR; ++j) acc[r][j] = T(0);
 
-        for (int p0 = 0; p0 < P; p0 += GEN_TP) {
-            // stage GEN_TS x GEN_TP elements of X: thread t takes half a chunk row (8 elements) of slice t/2
-            {
-                const int s = tid / 2;
-                const int pp = (tid % 2) * (GEN_TP / 2);
-                const bool live = s0 + s < S;
-                const T* src = Xrow + (s0 + s) * P + p0 + pp;
-                if (live && vec_ok && p0 + pp + GEN_TP / 2 <= P) {
+            for (int p0 = 0; p0 < P; p0 += GEN_TP) {
+                // stage GEN_TS x GEN_TP elements of X: thread t takes half a chunk row (8 elements) of slice t/2
+                {
+                    const int s = tid / 2;
+                    const int pp = (tid % 2) * (GEN_TP / 2);
+                    const bool live = s0 + s < S;
+                    const T* src = Xrow + (s0 + s) * P + p0 + pp;
+                    if (live && vec_ok && p0 + pp + GEN_TP / 2 <= P) {
 #pragma unroll
-                    for (int c = 0; c < GEN_TP / 2 / VN; ++c)
-                        *reinterpret_cast<V*>(&Xs[s][pp + c * VN]) = reinterpret_cast<const V*>(src)[c];
-                } else {
+                        for (int c = 0; c < GEN_TP / 2 / VN; ++c)
+                            *reinterpret_cast<V*>(&Xs[s][pp + c * VN]) = reinterpret_cast<const V*>(src)[c];
+                    } else {
 #pragma unroll
-                    for (int e = 0; e < GEN_TP / 2; ++e)
-                        Xs[s][pp + e] = (live && p0 + pp + e < P) ? src[e] : T(0);
-                }
-            }
-            // stage GEN_TP x GEN_TQ elements of F
-            for (int e = tid; e < GEN_TP * GEN_TQ; e += GEN_THREADS) {
-                const int p = e / GEN_TQ, q = e % GEN_TQ;
-                Fs[p][q] = (p0 + p < P && q0 + q < Q) ? Fg[(int64_t)(p0 + p) * Q + q0 + q] : T(0);
-            }
-            __syncthreads();
-#pragma unroll
-            for (int pv = 0; pv < GEN_TP; pv += VN) {
-                V x[GEN_RS];
-#pragma unroll
-                for (int r = 0; r < GEN_RS; ++r) x[r] = *reinterpret_cast<const V*>(&Xs[lane + 64 * r][pv]);
-#pragma unroll
-                for (int e = 0; e < VN; ++e) {
-                    T f[GEN_QR];
-#pragma unroll
-                    for (int c = 0; c < GEN_QR / VN; ++c) {
-                        const V fv = *reinterpret_cast<const V*>(&Fs[pv + e][wave * GEN_QR + c * VN]);
-#pragma unroll
-                        for (int k = 0; k < VN; ++k) f[c * VN + k] = fv[k];
+                        for (int e = 0; e < GEN_TP / 2; ++e)
+                            Xs[s][pp + e] = (live && p0 + pp + e < P) ? src[e] : T(0);
                     }
-#pragma unroll
-                    for (int r = 0; r < GEN_RS; ++r)
-#pragma unroll
-                        for (int j = 0; j < GEN_QR; ++j) acc[r][j] += x[r][e] * f[j];
                 }
+                // stage GEN_TP x GEN_TQ elements of F
+                for (int e = tid; e < GEN_TP * GEN_TQ; e += GEN_THREADS) {
+                    const int p = e / GEN_TQ, q = e % GEN_TQ;
+                    Fs[p][q] = (p0 + p < P && q0 + q < Q) ? Fg[(int64_t)(p0 + p) * Q + q0 + q] : T(0);
+                }
+                __syncthreads();
+#pragma unroll
+                for (int pv = 0; pv < GEN_TP; pv += VN) {
+                    V x[GEN_RS];
+#pragma unroll
+                    for (int r = 0; r < GEN_RS; ++r) x[r] = *reinterpret_cast<const V*>(&Xs[lane + 64 * r][pv]);
+#pragma unroll
+                    for (int e = 0; e < VN; ++e) {
+                        T f[GEN_QR];
+#pragma unroll
+                        for (int c = 0; c < GEN_QR / VN; ++c) {
+                            const V fv = *reinterpret_cast<const V*>(&Fs[pv + e][wave * GEN_QR + c * VN]);
+#pragma unroll
+                            for (int k = 0; k < VN; ++k) f[c * VN + k] = fv[k];
+                        }
+#pragma unroll
+                        for (int r = 0; r < GEN_RS; ++r)
+#pragma unroll
+                            for (int j = 0; j < GEN_QR; ++j) acc[r][j] += x[r][e] * f[j];
+                    }
+                }
+                __syncthreads();
             }
-            __syncthreads();
-        }
 #pragma unroll
-        for (int r = 0; r < GEN_RS; ++r) {
-            const int64_t s = s0 + lane + 64 * r;
-            if (s < S) {
+            for (int r = 0; r < GEN_RS; ++r) {
+                const int64_t s = s0 + lane + 64 * r;
+                if (s < S) {
 #pragma unroll
-                for (int j = 0; j < GEN_QR; ++j) {
-                    const int q = q0 + wave * GEN_QR + j;
-                    if (q < Q) Yrow[(int64_t)q * S + s] = acc[r][j];
+                    for (int j = 0; j < GEN_QR; ++j) {
+                        const int q = q0 + wave * GEN_QR + j;
+                        if (q < Q) Yrow[(int64_t)q * S + s] = acc[r][j];
+                    }
                 }
             }
         }

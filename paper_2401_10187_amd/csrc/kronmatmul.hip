@@ -280,7 +280,7 @@ static hipError_t launch_generic(const LaunchArgs& a)
     const int64_t S = st.k_in / P;
     const int64_t tiles = (S + GEN_TS - 1) / GEN_TS;
     hipLaunchKernelGGL((sliced_multiply_generic<T>), dim3((unsigned)st.grid), dim3(GEN_THREADS), 0, a.stream,
-                       (const T*)a.src, (const T*)a.factors[f], (T*)a.dst, st.k_in, P, Q, tiles);
+                       (const T*)a.src, (const T*)a.factors[f], (T*)a.dst, st.k_in, P, Q, tiles, a.pr->M * tiles);
     return hipGetLastError();
 }
 
@@ -331,6 +331,12 @@ static bool same_options(const Options& a, const Options& b)
            a.pair_interleave == b.pair_interleave && a.tile_order == b.tile_order;
 }
 
+// HIP takes a launch only if its work-items, grid x block, number fewer than 2^32.
+static bool launchable(const km_plan_step& st)
+{
+    return st.grid > 0 && st.block > 0 && (double)st.grid * (double)st.block < 4294967296.0;
+}
+
 static km_status plan_for(const Problem& pr, Plan& plan)
 {
     Options opt;
@@ -349,7 +355,7 @@ static km_status plan_for(const Problem& pr, Plan& plan)
     km_status s = make_plan(pr, opt, g_variants, g_num_variants, GEN_THREADS, GEN_TS, generic_lds(pr.dtype), plan);
     if (s != KM_OK) return s;
     for (const km_plan_step& st : plan.steps)
-        if (st.grid <= 0 || st.grid > 0x7fffffffLL) return KM_EUNSUPPORTED;
+        if (!launchable(st)) return KM_EUNSUPPORTED;
     {
         std::lock_guard<std::mutex> lock(g_mutex);
         cache_plan(pr, opt, plan, false);
@@ -552,7 +558,7 @@ static km_status tune(const Problem& pr, const Options& opt, hipStream_t stream,
             for (const Choice& ch : cands) {
                 const km_plan_step st = build_step(pr, opt, g_variants, r, nf, ch, width, GEN_THREADS, GEN_TS,
                                                    generic_lds(pr.dtype));
-                if (st.grid <= 0 || st.grid > 0x7fffffffLL) continue;
+                if (!launchable(st)) continue;
                 auto body = [&]() { return launch_step(pr, st, sc.a, sc.b, F.data(), stream) == hipSuccess; };
                 const float once = time_body(sc, stream, 1, body);       // also the warm-up
                 if (once < 0.f) return KM_ELAUNCH;
@@ -774,7 +780,7 @@ km_status kronmatmul_tune(int M, int N, const int* P, const int* Q, km_dtype dty
     s = tune(pr, opt, (hipStream_t)stream, plan, tuned_ms, default_ms);
     if (s != KM_OK) return s;
     for (const km_plan_step& st : plan.steps)
-        if (st.grid <= 0 || st.grid > 0x7fffffffLL) return KM_EUNSUPPORTED;
+        if (!launchable(st)) return KM_EUNSUPPORTED;
     std::lock_guard<std::mutex> lock(g_mutex);
     cache_plan(pr, opt, plan, true);
     return KM_OK;

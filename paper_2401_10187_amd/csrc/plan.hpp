@@ -287,6 +287,8 @@ inline Choice find_variant(const Variant* table, int count, const Problem& pr, i
             ch.var = &c;
             ch.tile_slices = cand[k];
             ch.grid = (pr.M / c.rows_per_tile) * (s_row / cand[k]);
+            // a launch may hold at most 2^32 - 1 work-items (walking instances shrink their grid later)
+            if (!c.persistent && (double)ch.grid * (double)c.threads >= 4294967296.0) continue;
             if (!first_big.var && ch.grid >= enough) first_big = ch;
             // among small launches prefer output runs of at least 32 bytes over more workgroups
             const bool long_run = (int64_t)ch.tile_slices * (int64_t)pr.esize >= 32;
@@ -309,7 +311,10 @@ inline double launch_cost(const Problem& pr, int64_t k_in, int64_t k_out, const 
     const double bytes = (double)pr.M * ((double)k_in + (double)k_out) * (double)pr.esize;
     double slow = 3.0;                                   // generic kernel
     if (ch.var) {
-        const int64_t run = (int64_t)ch.tile_slices * (int64_t)pr.esize;
+        int64_t run = (int64_t)ch.tile_slices * (int64_t)pr.esize;
+        // a tile that holds a whole row writes the whole output row: its runs join up
+        const int64_t rows = pr.M / ch.var->rows_per_tile;
+        if (rows > 0 && ch.grid == rows) run = k_out * (int64_t)pr.esize;
         slow = run >= 128 ? 1.0 : (run >= 64 ? 1.25 : (run >= 32 ? 2.5 : 4.0));
         slow *= ch.var->slowdown;
     }
@@ -369,6 +374,9 @@ inline km_plan_step build_step(const Problem& pr, const Options& opt, const Vari
         st.lds_bytes = generic_lds;
         const int64_t S = st.k_in / pr.P[f];
         st.grid = pr.M * ((S + generic_tile_slices - 1) / generic_tile_slices);
+        // the generic kernel strides over its tiles, so its grid can stay below the launch limit
+        const int64_t most = ((int64_t)1 << 32) / generic_threads - 1;
+        if (st.grid > most) st.grid = most;
     }
     return st;
 }

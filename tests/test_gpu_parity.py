@@ -498,6 +498,20 @@ def test_rows_beyond_32_bit_offsets_use_the_generic_kernel_and_stay_exact():
     km.release()
 
 
+def test_more_rows_than_a_launch_has_workgroups():
+    """Maximum sizes along M: 2^24 + 5 rows of 4 elements.  One row per workgroup would need more
+    work-items than a launch may hold, so the planner takes the generic kernel with a capped grid that
+    strides over its tiles; every row must still be right, the last ones included."""
+    M, shapes = (1 << 24) + 5, [(2, 2), (2, 2)]
+    steps = km.plan(M, [2, 2], [2, 2], "float32")
+    assert all(st["grid"] * st["block"] < 2 ** 32 for st in steps)
+    assert any(st["kernel"] == km.KM_KERNEL_GENERIC and st["grid"] < M for st in steps)
+    X, Fs = kron_inputs.make_problem(M, shapes, "float32", x="int2", f="int2", seed=71)
+    Y = km.kronmatmul(torch.from_numpy(X).cuda(), [torch.from_numpy(F).cuda() for F in Fs])
+    torch.cuda.synchronize()
+    assert np.array_equal(Y.cpu().numpy(), oracle.kron_matmul(X, Fs))
+
+
 def test_graph_capture_and_replay_matches_eager():
     """Iterative callers (the small-M, many-calls pattern of the paper's Gaussian-process case study)
     can capture kronmatmul_ws in a HIP graph: it allocates nothing and synchronises nothing.  Replays

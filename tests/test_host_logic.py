@@ -188,8 +188,10 @@ def test_host_entry_points_are_thread_safe():
     rng = np.random.default_rng(5)
     problems = []
     for _ in range(40):
-        n = int(rng.integers(1, 7))
         p = int(rng.choice([2, 3, 4, 5, 6, 8, 16, 32, 64, 7]))
+        n = int(rng.integers(1, 7))
+        while p ** n > 2 ** 24:                      # keep to sizes a device could hold
+            n -= 1
         problems.append((int(rng.integers(1, 2000)), [p] * n, [p] * n, "float32" if rng.random() < 0.5 else "float64"))
     serial = [(km.plan(*pr), km.workspace_size(*pr), km.cost(*pr)) for pr in problems]
     results, errors = {}, []
@@ -209,6 +211,15 @@ def test_host_entry_points_are_thread_safe():
         th.join()
     assert not errors
     assert all(v == serial[i] for (_, _, i), v in results.items())
+
+
+def test_launches_stay_below_the_work_item_limit():
+    """A launch may hold fewer than 2^32 work-items: instances whose grid would exceed that are not
+    chosen; the generic kernel strides over its tiles with a capped grid, so size alone never makes a
+    problem unsupported."""
+    for M, P, n in [(1 << 20, 4, 4), (1 << 24, 8, 3), (1 << 22, 2, 6), (1 << 24, 2, 8), (1 << 26, 7, 2)]:
+        for st in km.plan(M, [P] * n, [P] * n, "float32"):
+            assert 0 < st["grid"] * st["block"] < 2 ** 32
 
 
 def test_tile_instances_are_skipped_for_rows_beyond_32_bit_offsets():
