@@ -73,6 +73,8 @@ typedef struct {
     int tiles_per_wg;      /* tiles one workgroup walks over (0: one tile per workgroup)           */
     int tile_order;        /* walk: 0 contiguous range, 1 interleaved pairs, 2 strided by the grid,
                               3 strided inside the XCD's eighth of the tiles                       */
+    int tile_rows;         /* rows per tile (the T_M of section 4); above 1 only when a tile holds
+                              whole rows, tile_slices then being the slices of one row            */
 } km_plan_step;
 
 /* Bytes of device workspace kronmatmul_ws needs for this problem (0 when one launch suffices).

@@ -26,7 +26,7 @@ class PlanStep(ctypes.Structure):
                 ("tile_slices", ctypes.c_int), ("k_in", ctypes.c_longlong), ("k_out", ctypes.c_longlong),
                 ("src", ctypes.c_int), ("dst", ctypes.c_int), ("grid", ctypes.c_longlong),
                 ("block", ctypes.c_int), ("lds_bytes", ctypes.c_int), ("variant", ctypes.c_int),
-                ("tiles_per_wg", ctypes.c_int), ("tile_order", ctypes.c_int)]
+                ("tiles_per_wg", ctypes.c_int), ("tile_order", ctypes.c_int), ("tile_rows", ctypes.c_int)]
 
     def as_dict(self):
         return {k: getattr(self, k) for k, _ in self._fields_}

@@ -69,13 +69,48 @@ struct MultiShape {
     static_assert(G0 > 0 && (G1 > 0 || G2 == 0), "super-stages are filled from the first");
 };
 
+// Tiles of whole rows: the final stage leaves the tile's output rows in LDS, unpadded and in
+// memory order (they are contiguous in Y), and this writes them out with contiguous stores.
+template <typename T, int NT>
+__device__ __forceinline__ void multi_store_rows(const T* __restrict__ tile, T* __restrict__ dst, int n, bool vec_ok)
+{
+    typedef typename Vec16<T>::type V;
+    constexpr int VN = Vec16<T>::N, UN = 4;
+    const int tid = threadIdx.x;
+    if (vec_ok) {
+        const int nv = n / VN;
+        for (int base = 0; base < nv; base += UN * NT) {
+            V tmp[UN];
+#pragma unroll
+            for (int i = 0; i < UN; ++i) {
+                const int v = base + tid + i * NT;
+                if (v < nv) tmp[i] = reinterpret_cast<const V*>(tile)[v];
+            }
+#pragma unroll
+            for (int i = 0; i < UN; ++i) {
+                const int v = base + tid + i * NT;
+                if (v < nv) stream_store(tmp[i], &reinterpret_cast<V*>(dst)[v]);
+            }
+        }
+    } else {
+        for (int base = 0; base < n; base += UN * NT) {
+#pragma unroll
+            for (int i = 0; i < UN; ++i) {
+                const int e = base + tid + i * NT;
+                if (e < n) stream_store(tile[e], &dst[e]);
+            }
+        }
+    }
+}
+
 // position in LDS of flat tile index c when rows of `PGN` elements are padded by `PADN`
 template <int PGN, int PADN>
 __device__ __forceinline__ int multi_lds_index(int c) { return PADN == 0 ? c : c + (c / PGN) * PADN; }
 
 template <typename T, int P, int Q, int G0, int G1, int G2, int STMAX, int NT, int J>
 __device__ __forceinline__ void multi_stage(T* __restrict__ tile, const FactorPtrs<G0 + G1 + G2>& fp,
-                                            T* __restrict__ Yrow, int64_t s_row, int64_t h, int st)
+                                            T* __restrict__ Yrow, int64_t s_row, int64_t h, int st,
+                                            int sr_tile, int64_t k_out, int rows_here, int tile_rows)
 {
     typedef MultiShape<T, P, Q, G0, G1, G2, STMAX, NT> Sh;
     typedef typename Vec16<T>::type V;
@@ -117,7 +152,7 @@ __device__ __forceinline__ void multi_stage(T* __restrict__ tile, const FactorPt
         // Results go straight to their destination, one chunk of columns per trip of a loop that is
         // deliberately not unrolled (unrolled, all of the factor would be fetched up front again).
         const auto Fc = as_constant(static_cast<const T*>(fp.f[Sh::done(J)]));
-        if constexpr (!LAST) __syncthreads();            // every slice has been read
+        if (!LAST || tile_rows > 1) __syncthreads();     // every slice has been read
         constexpr int QREST1 = (int)ipow(Q, Sh::done(J));
 #pragma unroll 1
         for (int q0 = 0; q0 < Q; q0 += QCH) {
@@ -135,14 +170,19 @@ __device__ __forceinline__ void multi_stage(T* __restrict__ tile, const FactorPt
                             constexpr int PGN1 = Sh::pg(J + 1 < Sh::NS ? J + 1 : J), PADN1 = Sh::pad(J + 1 < Sh::NS ? J + 1 : J);
                             tile[multi_lds_index<PGN1, PADN1>(q * SJ + s)] = acc;
                         } else {
-                            T* dst = Yrow + (int64_t)(s / st) * s_row + h * st + (s % st);
-                            stream_store(acc, &dst[(int64_t)(q * QREST1) * s_row]);
+                            const int m = (s % st) / sr_tile;        // row of the tile (0 unless it holds whole rows)
+                            const int64_t at = m * k_out + (int64_t)(s / st + q * QREST1) * s_row + h * sr_tile + (s % st) % sr_tile;
+                            if (tile_rows > 1) tile[at] = acc;       // whole rows: collected in LDS, stored below
+                            else stream_store(acc, &Yrow[at]);
                         }
                     }
                 }
             }
         }
-        if constexpr (!LAST) __syncthreads();
+        if (!LAST || tile_rows > 1) __syncthreads();
+        if constexpr (LAST) {
+            if (tile_rows > 1) multi_store_rows<T, NT>(tile, Yrow, (int)(rows_here * k_out), k_out % VN == 0);
+        }
         return;
     } else {
 #pragma unroll
@@ -201,16 +241,28 @@ __device__ __forceinline__ void multi_stage(T* __restrict__ tile, const FactorPt
         }
         __syncthreads();
     } else {
-        // local (qq, s) with s = qrest*st + r  ->  column (qq*Q^done + qrest)*s_row + h*st + r
+        if (tile_rows > 1) __syncthreads();              // every group has been read; LDS is reused for the rows
+        // local (qq, s) with s = qrest*st + r  ->  column (qq*Q^done + qrest)*s_row + h*st + r; when the
+        // tile holds several whole rows, r = m*s_row + r' and the element belongs to row m of the tile
         constexpr int QREST = (int)ipow(Q, Sh::done(J));
 #pragma unroll
         for (int i = 0; i < R; ++i) {
             const int s = tid + i * NT;
             if (s < SJ) {
-                T* dst = Yrow + (int64_t)(s / st) * s_row + h * st + (s % st);
+                const int m = (s % st) / sr_tile;            // row of the tile (0 unless it holds whole rows)
+                const int64_t at = m * k_out + (int64_t)(s / st) * s_row + h * sr_tile + (s % st) % sr_tile;
+                if (tile_rows > 1) {                         // whole rows: collected in LDS, stored below
 #pragma unroll
-                for (int qq = 0; qq < QGJ; ++qq) stream_store(out[i][qq], &dst[(int64_t)(qq * QREST) * s_row]);
+                    for (int qq = 0; qq < QGJ; ++qq) tile[at + (int64_t)(qq * QREST) * s_row] = out[i][qq];
+                } else {
+#pragma unroll
+                    for (int qq = 0; qq < QGJ; ++qq) stream_store(out[i][qq], &Yrow[at + (int64_t)(qq * QREST) * s_row]);
+                }
             }
+        }
+        if (tile_rows > 1) {
+            __syncthreads();
+            multi_store_rows<T, NT>(tile, Yrow, (int)(rows_here * k_out), k_out % VN == 0);
         }
     }
 }
@@ -219,7 +271,8 @@ template <typename T, int P, int Q, int G0, int G1, int G2, int STMAX, int NT>
 __global__ __launch_bounds__(NT)
 void fused_multi_sliced_multiply(const T* __restrict__ Xg, T* __restrict__ Yg,
                                  const FactorPtrs<G0 + G1 + G2> fp,     // in order of application
-                                 int64_t k_in, int64_t k_out, int64_t tiles_per_row, int64_t num_tiles, int st)
+                                 int64_t k_in, int64_t k_out, int64_t tiles_per_row, int64_t num_tiles, int st,
+                                 int tile_rows, int64_t M)
 {
     typedef MultiShape<T, P, Q, G0, G1, G2, STMAX, NT> Sh;
     typedef typename Vec16<T>::type V;
@@ -230,18 +283,24 @@ void fused_multi_sliced_multiply(const T* __restrict__ Xg, T* __restrict__ Yg,
     // XCD-aware order: workgroup b runs on XCD b % 8; give each XCD a contiguous range of tiles
     int64_t t = blockIdx.x;
     if (num_tiles % 8 == 0) t = (t % 8) * (num_tiles / 8) + t / 8;
-    const int64_t row = t / tiles_per_row;
+    // A tile is `st` slices: a stretch of one row (tile_rows == 1), or tile_rows whole rows, which are
+    // contiguous in memory and go through the stages as one long tile; only the final store tells
+    // the rows apart.
+    const int64_t row = (t / tiles_per_row) * tile_rows;
     const int64_t h = t % tiles_per_row;
-    const int tk = st * Sh::per_slice(0);                // elements in this tile
+    const int sr_tile = st / tile_rows;                  // slices of one row inside the tile
+    const int rows_here = (int)(M - row < tile_rows ? M - row : tile_rows);
+    const int tk = st * Sh::per_slice(0);                // elements in a full tile
+    const int valid = tile_rows > 1 ? (int)(rows_here * k_in) : tk;     // ... that exist (last tile of whole rows)
     const T* src = Xg + row * k_in + h * tk;
     T* Yrow = Yg + row * k_out;
-    const int64_t s_row = tiles_per_row * st;
+    const int64_t s_row = tiles_per_row * sr_tile;
     const int tid = threadIdx.x;
     constexpr int PG0 = Sh::pg(0), PAD0 = Sh::pad(0);
 
     // 16-byte loads need every tile to start on a 16-byte boundary and rows of whole vectors
     if (Sh::VEC_ROWS && tk % VN == 0 && k_in % VN == 0) {
-        const int nv = tk / VN;
+        const int nv = valid / VN;
         constexpr int RV = (STMAX * Sh::per_slice(0) / VN + NT - 1) / NT;
         V tmp[RV];
 #pragma unroll
@@ -257,25 +316,25 @@ void fused_multi_sliced_multiply(const T* __restrict__ Xg, T* __restrict__ Yg,
     } else {
         // rows that are not 16-byte aligned: 4- or 8-byte loads, eight in flight per thread
         constexpr int UN = 8;
-        for (int base = 0; base < tk; base += UN * NT) {
+        for (int base = 0; base < valid; base += UN * NT) {
             T tmp[UN];
 #pragma unroll
             for (int i = 0; i < UN; ++i) {
                 const int e = base + tid + i * NT;
-                if (e < tk) tmp[i] = stream_load(&src[e]);
+                if (e < valid) tmp[i] = stream_load(&src[e]);
             }
 #pragma unroll
             for (int i = 0; i < UN; ++i) {
                 const int e = base + tid + i * NT;
-                if (e < tk) tile[multi_lds_index<PG0, PAD0>(e)] = tmp[i];
+                if (e < valid) tile[multi_lds_index<PG0, PAD0>(e)] = tmp[i];
             }
         }
     }
     __syncthreads();
 
-    multi_stage<T, P, Q, G0, G1, G2, STMAX, NT, 0>(tile, fp, Yrow, s_row, h, st);
-    if constexpr (Sh::NS > 1) multi_stage<T, P, Q, G0, G1, G2, STMAX, NT, 1>(tile, fp, Yrow, s_row, h, st);
-    if constexpr (Sh::NS > 2) multi_stage<T, P, Q, G0, G1, G2, STMAX, NT, 2>(tile, fp, Yrow, s_row, h, st);
+    multi_stage<T, P, Q, G0, G1, G2, STMAX, NT, 0>(tile, fp, Yrow, s_row, h, st, sr_tile, k_out, rows_here, tile_rows);
+    if constexpr (Sh::NS > 1) multi_stage<T, P, Q, G0, G1, G2, STMAX, NT, 1>(tile, fp, Yrow, s_row, h, st, sr_tile, k_out, rows_here, tile_rows);
+    if constexpr (Sh::NS > 2) multi_stage<T, P, Q, G0, G1, G2, STMAX, NT, 2>(tile, fp, Yrow, s_row, h, st, sr_tile, k_out, rows_here, tile_rows);
 }
 
 }  // namespace km

@@ -137,7 +137,26 @@ struct Choice {
     int64_t grid = 0;        // tiles (before the persistent-walk division)
     int tiles_per_wg = 0;    // persistent instances: 0 = take the rule of tiles_per_wg()
     int tile_order = -1;     // persistent instances: -1 = take the option
+    int tile_rows = 1;       // rows per tile; above 1 the tile holds whole rows (tile_slices = K/prod(P))
 };
+
+// Rows a flexible instance puts into one tile when a whole row is shorter than its tile (rows are
+// contiguous in memory, so several of them pass through the stages as one long tile): as many as
+// fit 48 KB of LDS (three and more workgroups per compute unit, see find_variant), within the
+// instance's limit, leaving at least 512 tiles when there are that many rows.
+inline int whole_rows_per_tile(const Variant& c, int64_t s_row, int64_t M)
+{
+    if (!c.flexible || s_row > c.tile_slices / 2 || M < 1024) return 1;   // few rows: one workgroup each
+    if (c.P != c.Q) return 1;       // the output rows are collected in the tile's own LDS: same size needed
+    int64_t most = c.tile_slices / s_row;
+    if (c.lds_per_slice > 0) {
+        const int64_t fit = (48 * 1024) / c.lds_per_slice / s_row;
+        if (fit >= 1 && fit < most) most = fit;
+    }
+    if (most > M) most = M;
+    while (most > 1 && (M + most - 1) / most < 512) --most;
+    return most < 1 ? 1 : (int)most;
+}
 
 // Tile order 3 gives each of the 8 XCDs a contiguous eighth of the tiles, walked by grid / 8 workgroups.
 inline bool xcd_order_fits(int64_t num_tiles, int64_t grid)
@@ -201,6 +220,17 @@ inline void enumerate_choices(const Variant* table, int count, const Problem& pr
         if (c.P != pr.P[f] || c.Q != pr.Q[f]) continue;
         if (pr.M % c.rows_per_tile) continue;
         tile_lengths(c, s_row, lens, 5);
+        const int rows = whole_rows_per_tile(c, s_row, pr.M);
+        if (rows > 1) {                                   // whole rows, several per tile, and half as many
+            for (int r = rows; r >= 2 && r >= rows / 2; r = (r == rows && rows / 2 >= 2) ? rows / 2 : 1) {
+                Choice ch;
+                ch.var = &c;
+                ch.tile_slices = (int)s_row;
+                ch.tile_rows = r;
+                ch.grid = (pr.M + r - 1) / r;
+                out.push_back(ch);
+            }
+        }
         for (int st : lens) {
             Choice ch;
             ch.var = &c;
@@ -253,6 +283,7 @@ inline Choice find_variant(const Variant* table, int count, const Problem& pr, i
         if (pr.M % c.rows_per_tile) continue;
         // slices per tile: fixed, or the best divisor of s_row up to the instance's limit
         int cand[3] = {0, 0, 0};
+        int rows = 1;
         if (!c.flexible) {
             if (s_row % c.tile_slices) continue;
             cand[0] = c.tile_slices;
@@ -280,6 +311,9 @@ inline Choice find_variant(const Variant* table, int count, const Problem& pr, i
                 if ((pr.M / c.rows_per_tile) * (s_row / d) >= enough && key > best_key[1]) { best_key[1] = key; cand[1] = (int)d; }
             }
             if (opt.prefer_tile > 0 && opt.prefer_tile <= c.tile_slices && s_row % opt.prefer_tile == 0) cand[2] = opt.prefer_tile;
+            // rows much shorter than the tile: whole rows, several per tile
+            rows = whole_rows_per_tile(c, s_row, pr.M);
+            if (rows > 1) { cand[0] = (int)s_row; cand[1] = cand[2] = 0; }
         }
         for (int k = 0; k < 3; ++k) {
             if (!cand[k]) continue;
@@ -287,6 +321,10 @@ inline Choice find_variant(const Variant* table, int count, const Problem& pr, i
             ch.var = &c;
             ch.tile_slices = cand[k];
             ch.grid = (pr.M / c.rows_per_tile) * (s_row / cand[k]);
+            if (rows > 1) {
+                ch.tile_rows = rows;
+                ch.grid = (pr.M + rows - 1) / rows;
+            }
             // a launch may hold at most 2^32 - 1 work-items (walking instances shrink their grid later)
             if (!c.persistent && (double)ch.grid * (double)c.threads >= 4294967296.0) continue;
             if (!first_big.var && ch.grid >= enough) first_big = ch;
@@ -314,7 +352,7 @@ inline double launch_cost(const Problem& pr, int64_t k_in, int64_t k_out, const 
         int64_t run = (int64_t)ch.tile_slices * (int64_t)pr.esize;
         // a tile that holds a whole row writes the whole output row: its runs join up
         const int64_t rows = pr.M / ch.var->rows_per_tile;
-        if (rows > 0 && ch.grid == rows) run = k_out * (int64_t)pr.esize;
+        if (ch.tile_rows > 1 || (rows > 0 && ch.grid == rows)) run = k_out * (int64_t)pr.esize;
         slow = run >= 128 ? 1.0 : (run >= 64 ? 1.25 : (run >= 32 ? 2.5 : 4.0));
         slow *= ch.var->slowdown;
     }
@@ -348,7 +386,8 @@ inline km_plan_step build_step(const Problem& pr, const Options& opt, const Vari
         st.variant = (int)(var - table);
         st.tile_slices = ch.tile_slices;
         st.block = var->threads;
-        st.lds_bytes = launch_lds_bytes(*var, ch.tile_slices);
+        st.tile_rows = ch.tile_rows;
+        st.lds_bytes = launch_lds_bytes(*var, ch.tile_slices * ch.tile_rows);
         st.grid = ch.grid;
         if (var->persistent) {
             const int hint = ch.tiles_per_wg > 0 ? ch.tiles_per_wg : opt.tiles_per_wg;
@@ -369,6 +408,7 @@ inline km_plan_step build_step(const Problem& pr, const Options& opt, const Vari
     } else {
         st.kernel = KM_KERNEL_GENERIC;
         st.variant = -1;
+        st.tile_rows = 1;
         st.tile_slices = generic_tile_slices;
         st.block = generic_threads;
         st.lds_bytes = generic_lds;

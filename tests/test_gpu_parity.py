@@ -498,18 +498,51 @@ def test_rows_beyond_32_bit_offsets_use_the_generic_kernel_and_stay_exact():
     km.release()
 
 
+@pytest.mark.parametrize("dtype,M,shapes", [
+    ("float32", 4099, [(4, 4)] * 4),          # ragged last tile
+    ("float32", 2048, [(2, 2)] * 8),
+    ("float64", 1500, [(6, 6)] * 3),
+    ("float32", 3001, [(3, 3)] * 4),          # rows that are not 16-byte aligned
+    ("float64", 1024, [(8, 8)] * 3),
+    ("float32", 1025, [(5, 5)] * 2 + [(7, 7)] * 2),
+    ("float32", 1030, [(12, 12)] * 2),
+], ids=lambda v: str(v).replace(" ", ""))
+def test_many_short_rows_share_a_tile(dtype, M, shapes):
+    """Rows much shorter than a tile: several whole rows per tile (the T_M of section 4), the last
+    tile ragged.  All rows are compared."""
+    P, Q = [s[0] for s in shapes], [s[1] for s in shapes]
+    assert any(st["tile_rows"] > 1 for st in km.plan(M, P, Q, dtype))
+    X, Fs = kron_inputs.make_problem(M, shapes, dtype, seed=81)
+    assert_close(run_gpu(X, Fs), X, Fs)
+    Xi, Fi = kron_inputs.make_problem(M, shapes, dtype, x="int2", f="int1", seed=82)
+    assert_close(run_gpu(Xi, Fi, use_ws=True), Xi, Fi, exact=True)
+
+
 def test_more_rows_than_a_launch_has_workgroups():
     """Maximum sizes along M: 2^24 + 5 rows of 4 elements.  One row per workgroup would need more
-    work-items than a launch may hold, so the planner takes the generic kernel with a capped grid that
-    strides over its tiles; every row must still be right, the last ones included."""
+    work-items than a launch may hold.  The planner puts many rows into each tile; restricted to the
+    generic kernel it caps the grid and the kernel strides over its tiles.  Every row must be right
+    either way, the last ones included."""
     M, shapes = (1 << 24) + 5, [(2, 2), (2, 2)]
-    steps = km.plan(M, [2, 2], [2, 2], "float32")
-    assert all(st["grid"] * st["block"] < 2 ** 32 for st in steps)
-    assert any(st["kernel"] == km.KM_KERNEL_GENERIC and st["grid"] < M for st in steps)
     X, Fs = kron_inputs.make_problem(M, shapes, "float32", x="int2", f="int2", seed=71)
-    Y = km.kronmatmul(torch.from_numpy(X).cuda(), [torch.from_numpy(F).cuda() for F in Fs])
+    want = oracle.kron_matmul(X, Fs)
+    Xd = torch.from_numpy(X).cuda()
+    Fd = [torch.from_numpy(F).cuda() for F in Fs]
+    steps = km.plan(M, [2, 2], [2, 2], "float32")
+    assert all(st["grid"] * st["block"] < 2 ** 32 for st in steps) and any(st["tile_rows"] > 1 for st in steps)
+    Y = km.kronmatmul(Xd, Fd)
     torch.cuda.synchronize()
-    assert np.array_equal(Y.cpu().numpy(), oracle.kron_matmul(X, Fs))
+    assert np.array_equal(Y.cpu().numpy(), want)
+    with options(kernels=1):
+        steps = km.plan(M, [2, 2], [2, 2], "float32")
+        assert all(st["kernel"] == km.KM_KERNEL_GENERIC and st["grid"] < M and st["grid"] * st["block"] < 2 ** 32
+                   for st in steps)
+        Y = km.kronmatmul(Xd, Fd)
+        torch.cuda.synchronize()
+    assert np.array_equal(Y.cpu().numpy(), want)
+    del Y, Xd
+    torch.cuda.empty_cache()
+    km.release()
 
 
 def test_graph_capture_and_replay_matches_eager():
