@@ -1,8 +1,10 @@
 // One sliced-multiply iteration for any factor shape (Algorithm 1, inner loops; the four steps of
 // the kernel in section 4: global->LDS, LDS->registers, multiply-accumulate, permuted store).
 //
-// A workgroup owns GEN_TS consecutive slices of one row and walks the factor columns in groups of
-// GEN_TQ and the slice elements in chunks of GEN_TP.  Lanes run along the slice index, so for a
+// A workgroup owns GEN_TS consecutive slices and walks the factor columns in groups of GEN_TQ and
+// the slice elements in chunks of GEN_TP.  Slices are numbered through all rows (row r, slice s is
+// slice r*S + s and starts at element (r*S + s)*P of X, rows being contiguous), so a tile may span
+// rows and short rows (S small, down to one slice per row when N = 1) still fill the workgroup.  Lanes run along the slice index, so for a
 // fixed factor column a wavefront stores one contiguous run of the output row: the output column of
 // (slice s, column q) is q*(K/P)+s.  A thread keeps GEN_RS slices x GEN_QR consecutive columns in
 // registers; per 16-byte read of its slices' elements it reads the matching factor rows, which are
@@ -31,7 +33,7 @@ constexpr int gen_lds_bytes()
 template <typename T>
 __global__ __launch_bounds__(GEN_THREADS)
 void sliced_multiply_generic(const T* __restrict__ Xg, const T* __restrict__ Fg, T* __restrict__ Yg,
-                             int64_t K, int P, int Q, int64_t tiles_per_row, int64_t num_tiles)
+                             int64_t K, int P, int Q, int64_t num_slices, int64_t num_tiles)
 {
     typedef typename Vec16<T>::type V;
     constexpr int VN = Vec16<T>::N;
@@ -47,10 +49,7 @@ void sliced_multiply_generic(const T* __restrict__ Xg, const T* __restrict__ Fg,
 
     // the grid may be smaller than the number of tiles (launches are limited to 2^32 work-items)
     for (int64_t tile = blockIdx.x; tile < num_tiles; tile += gridDim.x) {
-        const int64_t row = tile / tiles_per_row;
-        const int64_t s0 = (tile % tiles_per_row) * GEN_TS;
-        const T* Xrow = Xg + row * K;
-        T* Yrow = Yg + row * (S * Q);
+        const int64_t g0 = tile * GEN_TS;                // first slice of the tile, counted through all rows
         for (int q0 = 0; q0 < Q; q0 += GEN_TQ) {
             T acc[GEN_RS][GEN_QR];
 #pragma unroll
@@ -63,8 +62,8 @@ void sliced_multiply_generic(const T* __restrict__ Xg, const T* __restrict__ Fg,
                 {
                     const int s = tid / 2;
                     const int pp = (tid % 2) * (GEN_TP / 2);
-                    const bool live = s0 + s < S;
-                    const T* src = Xrow + (s0 + s) * P + p0 + pp;
+                    const bool live = g0 + s < num_slices;
+                    const T* src = Xg + (g0 + s) * P + p0 + pp;
                     if (live && vec_ok && p0 + pp + GEN_TP / 2 <= P) {
 #pragma unroll
                         for (int c = 0; c < GEN_TP / 2 / VN; ++c)
@@ -105,12 +104,13 @@ void sliced_multiply_generic(const T* __restrict__ Xg, const T* __restrict__ Fg,
             }
 #pragma unroll
             for (int r = 0; r < GEN_RS; ++r) {
-                const int64_t s = s0 + lane + 64 * r;
-                if (s < S) {
+                const int64_t g = g0 + lane + 64 * r;
+                if (g < num_slices) {
+                    T* Yrow = Yg + (g / S) * (S * Q) + g % S;        // row of the slice, and the slice within it
 #pragma unroll
                     for (int j = 0; j < GEN_QR; ++j) {
                         const int q = q0 + wave * GEN_QR + j;
-                        if (q < Q) Yrow[(int64_t)q * S + s] = acc[r][j];
+                        if (q < Q) Yrow[(int64_t)q * S] = acc[r][j];
                     }
                 }
             }

@@ -231,6 +231,9 @@ static hipError_t launch_shuffle(const LaunchArgs& a)
     W(double, KM_F64, 6, 6, 1, 1, 1, 36, 256)           \
     W(double, KM_F64, 6, 6, 1, 1, 0, 216, 256)          \
     W(double, KM_F64, 6, 6, 1, 0, 0, 1296, 256)         \
+    W(float, KM_F32, 8, 8, 1, 1, 1, 16, 256)            \
+    W(float, KM_F32, 8, 8, 1, 1, 0, 128, 256)           \
+    W(float, KM_F32, 8, 8, 1, 0, 0, 1024, 256)          \
     W(float, KM_F32, 7, 7, 2, 1, 0, 32, 256)            \
     W(float, KM_F32, 7, 7, 2, 0, 0, 256, 256)           \
     W(float, KM_F32, 7, 7, 1, 0, 0, 2048, 256)          \
@@ -284,9 +287,11 @@ static hipError_t launch_generic(const LaunchArgs& a)
     const int f = st.first_factor;
     const int P = a.pr->P[f], Q = a.pr->Q[f];
     const int64_t S = st.k_in / P;
-    const int64_t tiles = (S + GEN_TS - 1) / GEN_TS;
+    const int64_t slices = a.pr->M * S;                  // counted through all rows
+    const int64_t tiles = (slices + GEN_TS - 1) / GEN_TS;
+    if (st.grid < 1 || st.grid > tiles) return hipErrorInvalidValue;
     hipLaunchKernelGGL((sliced_multiply_generic<T>), dim3((unsigned)st.grid), dim3(GEN_THREADS), 0, a.stream,
-                       (const T*)a.src, (const T*)a.factors[f], (T*)a.dst, st.k_in, P, Q, tiles, a.pr->M * tiles);
+                       (const T*)a.src, (const T*)a.factors[f], (T*)a.dst, st.k_in, P, Q, slices, tiles);
     return hipGetLastError();
 }
 

@@ -273,7 +273,7 @@ inline Choice find_variant(const Variant* table, int count, const Problem& pr, i
     if (!group_shape(pr, f, nf, k_cur, pg, s_row)) return none;
 
     const int64_t enough = 2 * 256;
-    Choice first_big, most, wanted;
+    Choice first_big, first_tiny, most, wanted;
     int64_t wanted_score = 0;
     for (int v = 0; v < count; ++v) {
         const Variant& c = table[v];
@@ -327,7 +327,12 @@ inline Choice find_variant(const Variant* table, int count, const Problem& pr, i
             }
             // a launch may hold at most 2^32 - 1 work-items (walking instances shrink their grid later)
             if (!c.persistent && (double)ch.grid * (double)c.threads >= 4294967296.0) continue;
-            if (!first_big.var && ch.grid >= enough) first_big = ch;
+            // Tiles under 1 KB leave a workgroup with next to nothing to do (one 8x8 factor on rows of
+            // 8 elements: a tile of several whole rows is 10 times faster): they only count when no
+            // instance with a decent tile gives the chip enough workgroups.
+            const int64_t tile_bytes = (int64_t)ch.tile_slices * ch.tile_rows * pg * (int64_t)pr.esize;
+            if (!first_big.var && ch.grid >= enough && tile_bytes >= 1024) first_big = ch;
+            if (!first_tiny.var && ch.grid >= enough) first_tiny = ch;
             // among small launches prefer output runs of at least 32 bytes over more workgroups
             const bool long_run = (int64_t)ch.tile_slices * (int64_t)pr.esize >= 32;
             const bool most_long = most.var && (int64_t)most.tile_slices * (int64_t)pr.esize >= 32;
@@ -339,7 +344,8 @@ inline Choice find_variant(const Variant* table, int count, const Problem& pr, i
         }
     }
     if (wanted.var) return wanted;
-    return first_big.var ? first_big : most;
+    if (first_big.var) return first_big;
+    return first_tiny.var ? first_tiny : most;
 }
 
 // Estimated cost of one launch in "bytes moved at full speed": rows read and written, scaled up for
@@ -413,7 +419,7 @@ inline km_plan_step build_step(const Problem& pr, const Options& opt, const Vari
         st.block = generic_threads;
         st.lds_bytes = generic_lds;
         const int64_t S = st.k_in / pr.P[f];
-        st.grid = pr.M * ((S + generic_tile_slices - 1) / generic_tile_slices);
+        st.grid = (pr.M * S + generic_tile_slices - 1) / generic_tile_slices;   // tiles may span rows
         // the generic kernel strides over its tiles, so its grid can stay below the launch limit
         const int64_t most = ((int64_t)1 << 32) / generic_threads - 1;
         if (st.grid > most) st.grid = most;
