@@ -1,4 +1,4 @@
-// Fused sliced multiplies for very small factors (P, Q <= 8): several factors per LDS pass.
+// Fused sliced multiplies for small factors (P, Q <= 12): several factors per LDS pass.
 //
 // Same tile and same final scatter as fused_kernel.hpp (section 4.2 of the paper), but a thread
 // now owns a group of P^G contiguous elements and applies G factors to it entirely in registers
@@ -12,6 +12,9 @@
 // with scalar loads, as in fused_kernel.hpp.  LDS rows (one group each) are padded when their
 // length is an even number of 16-byte units above two, which would otherwise put the 16-byte reads
 // of eight consecutive lanes into the same banks.
+//
+// A tile is a stretch of one row, or, for problems with many short rows, several whole rows (the
+// T_M of section 4): rows are contiguous in memory and pass through the stages as one long tile.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
