@@ -173,6 +173,7 @@ static hipError_t launch_shuffle(const LaunchArgs& a)
     Y(MfmaF32x32, KM_F32, 32, 32, 2, 16, 4, 1)          \
     Y(MfmaF32x32, KM_F32, 32, 32, 1, 256, 4, 1)         \
     Y(MfmaF32x32, KM_F32, 32, 32, 1, 128, 4, 1)         \
+    Y(MfmaF32x32, KM_F32, 32, 32, 1, 32, 1, 1)          \
     Z(16, 32, 4, 1)                                     \
     Y(MfmaF32x32, KM_F32, 16, 32, 2, 32, 4, 1)          \
     Y(MfmaF32x32, KM_F32, 16, 32, 2, 16, 4, 1)          \
@@ -184,12 +185,16 @@ static hipError_t launch_shuffle(const LaunchArgs& a)
     Y(MfmaF32x16, KM_F32, 16, 16, 2, 32, 4, 1)          \
     Y(MfmaF32x16, KM_F32, 16, 16, 1, 256, 4, 1)         \
     Y(MfmaF32x16, KM_F32, 16, 16, 1, 64, 4, 1)          \
+    Y(MfmaF32x16, KM_F32, 16, 16, 1, 16, 1, 1)          \
     Y(MfmaF32x32, KM_F32, 64, 64, 1, 128, 4, 1)         \
+    Y(MfmaF32x32, KM_F32, 64, 64, 1, 64, 2, 1)          \
     Y(MfmaF32x32, KM_F32, 128, 128, 1, 32, 4, 4)        \
     Y(MfmaF64x16, KM_F64, 16, 16, 2, 16, 4, 1)          \
     Y(MfmaF64x16, KM_F64, 16, 16, 1, 256, 4, 1)         \
     Y(MfmaF64x16, KM_F64, 16, 16, 1, 64, 4, 1)          \
+    Y(MfmaF64x16, KM_F64, 16, 16, 1, 16, 1, 1)          \
     Y(MfmaF64x16, KM_F64, 32, 32, 1, 128, 4, 1)         \
+    Y(MfmaF64x16, KM_F64, 32, 32, 1, 32, 2, 1)          \
     Y(MfmaF64x16, KM_F64, 64, 64, 1, 64, 4, 1)          \
     W(float, KM_F32, 2, 2, 3, 3, 3, 32, 256)            \
     W(float, KM_F32, 2, 2, 3, 3, 0, 256, 256)           \

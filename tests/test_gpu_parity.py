@@ -121,6 +121,13 @@ SMALL_CASES = [
     ("float64", 2, [(5, 5)] * 5),
     ("float64", 2, [(6, 6)] * 5),
     ("float64", 1, [(6, 6)] * 3 + [(3, 3)] * 2),
+    # rows of K = P^2: one whole row per tile of the single-factor MFMA instances
+    ("float32", 70, [(16, 16)] * 2),
+    ("float32", 33, [(32, 32)] * 2),
+    ("float32", 9, [(64, 64)] * 2),
+    ("float64", 21, [(16, 16)] * 2),
+    ("float64", 10, [(32, 32)] * 2),
+    ("float64", 5, [(64, 64)] * 2),
     ("float32", 3, [(7, 7)] * 5),
     ("float64", 2, [(7, 7)] * 5),
     ("float32", 2, [(9, 9)] * 4),
