@@ -155,9 +155,13 @@ km_status kronmatmul_cost(int M, int N, const int* P, const int* Q, km_dtype dty
  * cache line give alternate tiles to pairs of workgroups that share an XCD.
  * KM_OPT_TILE_ORDER: tuning aid (default 2); persistent MFMA kernels walk over a contiguous range of
  * tiles (0), over tiles strided by the grid size (2), or strided inside a contiguous eighth of the
- * tiles per XCD (3; taken as 2 when tiles or grid do not split by 8). */
+ * tiles per XCD (3; taken as 2 when tiles or grid do not split by 8).
+ * KM_OPT_PREFER_INSTANCE: tuning aid; k > 0 makes the planner take compiled instance k - 1 (the
+ * `variant` of a plan step) wherever it fits the shape (0 = automatic).
+ * KM_OPT_INSTANCE_COUNT: read-only; the number of compiled instances. */
 typedef enum { KM_OPT_KERNELS = 0, KM_OPT_MAX_FUSE = 1, KM_OPT_PROFILE = 2, KM_OPT_PREFER_TILE = 3,
-               KM_OPT_PREFER_THREADS = 4, KM_OPT_TILES_PER_WG = 5, KM_OPT_PAIR_INTERLEAVE = 6, KM_OPT_TILE_ORDER = 7 } km_option;
+               KM_OPT_PREFER_THREADS = 4, KM_OPT_TILES_PER_WG = 5, KM_OPT_PAIR_INTERLEAVE = 6, KM_OPT_TILE_ORDER = 7,
+               KM_OPT_PREFER_INSTANCE = 8, KM_OPT_INSTANCE_COUNT = 9 } km_option;
 km_status kronmatmul_set_option(km_option option, int value);
 km_status kronmatmul_get_option(km_option option, int* value);
 

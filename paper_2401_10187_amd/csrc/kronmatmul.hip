@@ -12,6 +12,7 @@
 #include "fused_multi_kernel.hpp"
 #include "mfma_kernel.hpp"
 #include "mfma_pair_kernel.hpp"
+#include "mfma_pair_split_kernel.hpp"
 #include "shuffle_kernel.hpp"
 
 namespace km {
@@ -137,6 +138,29 @@ static hipError_t launch_mfma_pair(const LaunchArgs& a)
     return hipGetLastError();
 }
 
+template <int P, int ST, int PD>
+static hipError_t launch_mfma_pair_split(const LaunchArgs& a)
+{
+    typedef MfmaPairSplitShape<P, ST, PD> Sh;
+    const km_plan_step& st = *a.st;
+    auto kern = mfma_pair_split_sliced_multiply<P, ST, PD>;
+    static unsigned char lds_ok[64];
+    hipError_t e = allow_lds((const void*)kern, Sh::LDS_BYTES, lds_ok);
+    if (e != hipSuccess) return e;
+    const float* f0 = (const float*)a.factors[st.first_factor + 1];    // applied first
+    const float* f1 = (const float*)a.factors[st.first_factor];
+    const int64_t tiles_per_row = st.k_in / Sh::TK;
+    const int64_t num_tiles = a.pr->M * tiles_per_row;
+    const int64_t tpw = st.tiles_per_wg;
+    if (tpw < 1 || (num_tiles + tpw - 1) / tpw != st.grid) return hipErrorInvalidValue;
+    if (st.tile_order != 0 && st.tile_order != 2 && st.tile_order != 3) return hipErrorInvalidValue;
+    if (st.tile_order == 3 && !xcd_order_fits(num_tiles, st.grid)) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(kern, dim3((unsigned)st.grid), dim3(Sh::NT), Sh::LDS_BYTES, a.stream,
+                       (const float*)a.src, (float*)a.dst, f0, f1, st.k_in, st.k_out, tiles_per_row, num_tiles, tpw,
+                       st.tile_order);
+    return hipGetLastError();
+}
+
 static hipError_t launch_shuffle(const LaunchArgs& a)
 {
     const km_plan_step& st = *a.st;
@@ -151,9 +175,10 @@ static hipError_t launch_shuffle(const LaunchArgs& a)
 // Register-resident MFMA pairs: Z(P, tile_slices, wavefronts, units fetched ahead) (fp32, Q = 32, two factors).
 // Small-factor instances with several factors per LDS pass and a run-time tile length:
 // W(type, dtype code, P, Q, G0, G1, G2, largest tile_slices, threads).
+// The same with compute and store wavefronts: S(P, tile_slices, units fetched ahead).
 // MFMA instances: Y(op, dtype code, P, Q, factors per launch, tile_slices, wavefronts, q split).
 // Order = preference among instances that fit a shape.
-#define KM_INSTANCES(X, Y, Z, W)                            \
+#define KM_INSTANCES(X, Y, Z, W, S)                          \
     X(float, KM_F32, 8, 8, 3, 32, 1024)                 \
     X(float, KM_F32, 8, 8, 3, 32, 256)                  \
     X(float, KM_F32, 8, 8, 3, 16, 256)                  \
@@ -168,6 +193,8 @@ static hipError_t launch_shuffle(const LaunchArgs& a)
     X(float, KM_F32, 8, 8, 1, 8, 64)                    \
     X(float, KM_F32, 8, 8, 1, 1, 64)                    \
     Z(32, 32, 4, 1)                                     \
+    S(32, 32, 1)                                        \
+    S(32, 32, 3)                                        \
     Y(MfmaF32x32, KM_F32, 32, 32, 2, 32, 8, 1)          \
     Y(MfmaF32x32, KM_F32, 32, 32, 2, 32, 16, 1)         \
     Y(MfmaF32x32, KM_F32, 32, 32, 2, 16, 4, 1)          \
@@ -175,6 +202,7 @@ static hipError_t launch_shuffle(const LaunchArgs& a)
     Y(MfmaF32x32, KM_F32, 32, 32, 1, 128, 4, 1)         \
     Y(MfmaF32x32, KM_F32, 32, 32, 1, 32, 1, 1)          \
     Z(16, 32, 4, 1)                                     \
+    S(16, 32, 1)                                        \
     Y(MfmaF32x32, KM_F32, 16, 32, 2, 32, 4, 1)          \
     Y(MfmaF32x32, KM_F32, 16, 32, 2, 16, 4, 1)          \
     Y(MfmaF32x32, KM_F32, 16, 32, 1, 256, 4, 1)         \
@@ -272,6 +300,9 @@ static hipError_t launch_shuffle(const LaunchArgs& a)
     {KM_KERNEL_FUSED, DT, P, Q, G0 + G1 + G2, ST, NT, MultiShape<T, P, Q, G0, G1, G2, ST, NT>::LDS_BYTES, 1, 0, 1, \
      (G0 == 1 && P < 8) ? 1.6f : 1.0f,                   /* one tiny factor per LDS pass is instruction-bound */ \
      "fused-multi", MultiShape<T, P, Q, G0, G1, G2, ST, NT>::LDS_PER_SLICE},
+#define KM_SPLIT_ROW(P, ST, PD) \
+    {KM_KERNEL_MFMA, KM_F32, P, 32, 2, ST, 512, MfmaPairSplitShape<P, ST, PD>::LDS_BYTES, 1, 2, 0, 1.0f, "mfma-pair-split"},
+#define KM_SPLIT_FN(P, ST, PD) launch_mfma_pair_split<P, ST, PD>,
 #define KM_MULTI_FN(T, DT, P, Q, G0, G1, G2, ST, NT) launch_multi<T, P, Q, G0, G1, G2, ST, NT>,
 #define KM_PAIR_FN(P, ST, NW, PD) launch_mfma_pair<P, ST, NW, PD>,
 #define KM_FUSED_FN(T, DT, P, Q, NF, ST, NT) launch_fused<T, P, Q, NF, ST, NT>,
@@ -279,10 +310,10 @@ static hipError_t launch_shuffle(const LaunchArgs& a)
 
 static const Variant g_variants[] = {
     {KM_KERNEL_SHUFFLE, KM_F32, SHF_P, SHF_Q, 1, SHF_ST, SHF_NT, 0, 1, 0, 0, 1.0f, "shuffle"},
-    KM_INSTANCES(KM_FUSED_ROW, KM_MFMA_ROW, KM_PAIR_ROW, KM_MULTI_ROW) };
+    KM_INSTANCES(KM_FUSED_ROW, KM_MFMA_ROW, KM_PAIR_ROW, KM_MULTI_ROW, KM_SPLIT_ROW) };
 static const LaunchFn g_launchers[] = {
     launch_shuffle,
-    KM_INSTANCES(KM_FUSED_FN, KM_MFMA_FN, KM_PAIR_FN, KM_MULTI_FN) };
+    KM_INSTANCES(KM_FUSED_FN, KM_MFMA_FN, KM_PAIR_FN, KM_MULTI_FN, KM_SPLIT_FN) };
 static const int g_num_variants = (int)(sizeof(g_variants) / sizeof(g_variants[0]));
 
 template <typename T>
@@ -344,7 +375,8 @@ static bool same_options(const Options& a, const Options& b)
 {
     return a.kernels == b.kernels && a.max_fuse == b.max_fuse && a.prefer_tile == b.prefer_tile &&
            a.prefer_threads == b.prefer_threads && a.tiles_per_wg == b.tiles_per_wg &&
-           a.pair_interleave == b.pair_interleave && a.tile_order == b.tile_order;
+           a.pair_interleave == b.pair_interleave && a.tile_order == b.tile_order &&
+           a.prefer_instance == b.prefer_instance;
 }
 
 // HIP takes a launch only if its work-items, grid x block, number fewer than 2^32.
@@ -873,6 +905,12 @@ km_status kronmatmul_set_option(km_option option, int value)
             if (value != 0 && value != 2 && value != 3) return KM_EINVAL;
             g_options.tile_order = value;
             return KM_OK;
+        case KM_OPT_PREFER_INSTANCE:
+            if (value < 0 || value > g_num_variants) return KM_EINVAL;
+            g_options.prefer_instance = value;
+            return KM_OK;
+        case KM_OPT_INSTANCE_COUNT:
+            return KM_EINVAL;                      // read-only
         case KM_OPT_PROFILE:
             if (value != 0 && value != 1) return KM_EINVAL;
             if (value == 1 && g_profile == 0)      // a fresh history on every device
@@ -896,6 +934,8 @@ km_status kronmatmul_get_option(km_option option, int* value)
         case KM_OPT_TILES_PER_WG: *value = g_options.tiles_per_wg; return KM_OK;
         case KM_OPT_PAIR_INTERLEAVE: *value = g_options.pair_interleave; return KM_OK;
         case KM_OPT_TILE_ORDER: *value = g_options.tile_order; return KM_OK;
+        case KM_OPT_PREFER_INSTANCE: *value = g_options.prefer_instance; return KM_OK;
+        case KM_OPT_INSTANCE_COUNT: *value = g_num_variants; return KM_OK;
     }
     return KM_EINVAL;
 }

@@ -81,6 +81,7 @@ struct Options {
     int prefer_threads = 0;   // tuning: ... with this workgroup size
     int tiles_per_wg = 0;     // tuning: tiles per workgroup of persistent instances (0 = automatic)
     int pair_interleave = 1;  // neighbouring tiles with short output runs go to workgroup pairs
+    int prefer_instance = 0;  // tuning: k > 0 = take compiled instance k - 1 wherever it fits
     int tile_order = 2;       // persistent kernels: 0 = contiguous tile ranges, 2 = tiles strided by the grid,
                               // 3 = strided inside the XCD's own eighth of the tiles
 };
@@ -340,6 +341,7 @@ inline Choice find_variant(const Variant* table, int count, const Problem& pr, i
             int64_t sc = 0;
             if (opt.prefer_tile && ch.tile_slices == opt.prefer_tile) sc += 2;
             if (opt.prefer_threads && c.threads == opt.prefer_threads) sc += 1;
+            if (opt.prefer_instance && v == opt.prefer_instance - 1) sc += 4;
             if (sc > wanted_score) { wanted = ch; wanted_score = sc; }
         }
     }

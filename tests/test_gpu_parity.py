@@ -34,10 +34,11 @@ class options:
     """Temporarily restrict the planner (kernel families bit mask, fusion depth)."""
 
     def __init__(self, kernels=None, max_fuse=None, tile=None, threads=None, tiles_per_wg=None, pair=None,
-                 order=None):
+                 order=None, instance=None):
         self.new = {km.KM_OPT_KERNELS: kernels, km.KM_OPT_MAX_FUSE: max_fuse, km.KM_OPT_PREFER_TILE: tile,
                     km.KM_OPT_PREFER_THREADS: threads, km.KM_OPT_TILES_PER_WG: tiles_per_wg,
-                    km.KM_OPT_PAIR_INTERLEAVE: pair, km.KM_OPT_TILE_ORDER: order}
+                    km.KM_OPT_PAIR_INTERLEAVE: pair, km.KM_OPT_TILE_ORDER: order,
+                    km.KM_OPT_PREFER_INSTANCE: instance}
 
     def __enter__(self):
         self.old = {k: km.get_option(k) for k in self.new}
@@ -244,6 +245,68 @@ def test_forced_instances(dtype, M, shapes, opts):
         assert_close(got, X, Fs)
         Xi, Fi = kron_inputs.make_problem(M, shapes, dtype, "int2", "int1", seed=18)
         assert_close(run_gpu(Xi, Fi), Xi, Fi, exact=True)
+
+
+EVERY_INSTANCE = [
+    ("float32", 8, [(8, 8)] * 6), ("float64", 4, [(8, 8)] * 5),
+    ("float32", 16, [(32, 32)] * 3), ("float32", 32, [(32, 32)] * 4), ("float64", 4, [(32, 32)] * 3),
+    ("float32", 4, [(16, 32)] * 4),
+    ("float32", 8, [(16, 16)] * 4), ("float64", 8, [(16, 16)] * 4),
+    ("float32", 8, [(64, 64)] * 3), ("float64", 8, [(64, 64)] * 3),
+    ("float32", 4, [(128, 128)] * 2), ("float64", 8, [(128, 128)] * 2),
+    ("float32", 2, [(2, 2)] * 14), ("float64", 2, [(2, 2)] * 13),
+    ("float32", 3, [(3, 3)] * 9), ("float64", 3, [(3, 3)] * 9),
+    ("float32", 4, [(4, 4)] * 8), ("float64", 4, [(4, 4)] * 7),
+    ("float32", 2, [(5, 5)] * 6), ("float64", 2, [(5, 5)] * 6),
+    ("float32", 2, [(6, 6)] * 6), ("float64", 2, [(6, 6)] * 6),
+    ("float32", 2, [(7, 7)] * 5), ("float64", 2, [(7, 7)] * 5),
+    ("float32", 2, [(9, 9)] * 5), ("float64", 2, [(9, 9)] * 4),
+    ("float32", 2, [(10, 10)] * 5), ("float64", 2, [(10, 10)] * 4),
+    ("float32", 2, [(12, 12)] * 4), ("float64", 2, [(12, 12)] * 4),
+    # short rows, for the instances with short tiles
+    ("float32", 16, [(8, 8)] * 3), ("float32", 5, [(8, 8)] * 4), ("float32", 3, [(8, 8)] * 2), ("float32", 2, [(8, 8)]),
+    ("float32", 6, [(32, 32)] * 2), ("float32", 8, [(16, 32)] * 3), ("float32", 5, [(16, 16)] * 2),
+    ("float64", 5, [(16, 16)] * 3), ("float64", 3, [(32, 32)] * 2), ("float32", 3, [(64, 64)] * 2),
+    ("float32", 1100, [(8, 8)] * 2), ("float32", 1100, [(8, 8)]), ("float64", 3, [(8, 8)] * 3),
+    ("float32", 2, [(2, 2)] * 9), ("float64", 2, [(4, 4)] * 4), ("float32", 2, [(4, 4)] * 5),
+    ("float64", 2, [(2, 2)] * 9), ("float64", 2, [(9, 9)] * 3), ("float64", 2, [(10, 10)] * 3),
+]
+
+
+def test_every_instance_is_reached_by_some_shape_of_the_list():
+    """The list above reaches every compiled instance (planning only)."""
+    n = km.get_option(km.KM_OPT_INSTANCE_COUNT)
+    reached = set()
+    for dtype, M, shapes in EVERY_INSTANCE:
+        P, Q = [s[0] for s in shapes], [s[1] for s in shapes]
+        for k in range(n):
+            for fuse in (9, 4, 3, 2, 1):
+                with options(instance=k + 1, max_fuse=fuse, kernels=15):
+                    if any(st["variant"] == k for st in km.plan(M, P, Q, dtype)):
+                        reached.add(k)
+    assert reached == set(range(n))
+
+
+@pytest.mark.parametrize("dtype,M,shapes", EVERY_INSTANCE, ids=lambda v: str(v).replace(" ", ""))
+def test_every_compiled_instance_that_fits(dtype, M, shapes):
+    """Each compiled kernel instance in turn is made the planner's first choice; wherever it fits the
+    shape (the plan then names it) the result is checked, integer inputs bit for bit.  Every family's
+    instances fit at least one of the shapes."""
+    P, Q = [s[0] for s in shapes], [s[1] for s in shapes]
+    X, Fs = kron_inputs.make_problem(M, shapes, dtype, seed=91)
+    exact = 2.0 * np.prod(P, dtype=np.float64) < (2 ** 24 if dtype == "float32" else 2 ** 53)
+    Xi, Fi = kron_inputs.make_problem(M, shapes, dtype, x="int2", f="int1", seed=92)
+    used = set()
+    for k in range(km.get_option(km.KM_OPT_INSTANCE_COUNT)):
+        for fuse in (9, 4, 3, 2, 1):                     # the grouping must also ask for its number of factors
+            with options(instance=k + 1, max_fuse=fuse, kernels=15):
+                if k in used or not any(st["variant"] == k for st in km.plan(M, P, Q, dtype)):
+                    continue
+                used.add(k)
+                assert_close(run_gpu(X, Fs), X, Fs)
+                if exact:
+                    assert_close(run_gpu(Xi, Fi, use_ws=True), Xi, Fi, exact=True)
+    assert used
 
 
 def test_config1_integer_and_float():
