@@ -193,6 +193,32 @@ def test_random_shapes(dtype, M, shapes):
         assert_close(run_gpu(Xi, Fi, use_ws=True), Xi, Fi, exact=True)
 
 
+def _random_short_row_problems(count, seed):
+    """Seeded random problems with many short rows (M of 1024 to 6000, rows of at most 4096 elements)."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        p = int(rng.choice([2, 3, 4, 5, 6, 7, 8, 9, 10, 12, 16, 32]))
+        n = int(rng.integers(1, 7))
+        if p ** n > 4096:
+            continue
+        shapes = [(p, p)] * n
+        if rng.random() < 0.3:                      # a second family in front
+            p2 = int(rng.choice([2, 3, 4, 5]))
+            if p2 * p ** n <= 4096:
+                shapes = [(p2, p2)] + shapes
+        out.append(("float32" if rng.random() < 0.6 else "float64", int(rng.integers(1024, 6001)), shapes))
+    return out
+
+
+@pytest.mark.parametrize("dtype,M,shapes", _random_short_row_problems(24, 7), ids=lambda v: str(v).replace(" ", ""))
+def test_random_short_row_shapes(dtype, M, shapes):
+    X, Fs = kron_inputs.make_problem(M, shapes, dtype, x="int2", f="int1", seed=500 + M)
+    assert_close(run_gpu(X, Fs), X, Fs, exact=True)
+    X, Fs = kron_inputs.make_problem(M, shapes, dtype, seed=600 + M)
+    assert_close(run_gpu(X, Fs, use_ws=True), X, Fs)
+
+
 FORCED = [
     ("float32", 64, [(32, 32)] * 3, dict(tile=16, threads=256, tiles_per_wg=1, pair=1)),
     ("float32", 64, [(32, 32)] * 3, dict(tile=16, threads=256, tiles_per_wg=4, pair=1)),
