@@ -127,7 +127,7 @@ def test_plan_is_consistent(M, shapes, dtype):
 
 
 def test_workspace_follows_algorithm_1_buffers():
-    """Two swapped intermediates of M x max-width (Algorithm 1, line 3) are an upper bound."""
+    """Two swapped intermediates of M x max-width (the pair Algorithm 1 declares) are an upper bound."""
     M, P, Q = 5, [4, 2, 3, 2], [2, 6, 3, 5]
     ws = km.workspace_size(M, P, Q, "float64")
     k, widest = int(np.prod(P)), 0
