@@ -221,6 +221,7 @@ static hipError_t launch_shuffle(const LaunchArgs& a)
     Y(MfmaF64x16, KM_F64, 16, 16, 1, 256, 4, 1)         \
     Y(MfmaF64x16, KM_F64, 16, 16, 1, 64, 4, 1)          \
     Y(MfmaF64x16, KM_F64, 16, 16, 1, 16, 1, 1)          \
+    Y(MfmaF64x16, KM_F64, 32, 32, 2, 16, 8, 1)          \
     Y(MfmaF64x16, KM_F64, 32, 32, 1, 128, 4, 1)         \
     Y(MfmaF64x16, KM_F64, 32, 32, 1, 32, 2, 1)          \
     Y(MfmaF64x16, KM_F64, 64, 64, 1, 64, 4, 1)          \
