@@ -207,9 +207,9 @@ static hipError_t launch_shuffle(const LaunchArgs& a)
     Y(MfmaF32x32, KM_F32, 16, 32, 2, 16, 4, 1)          \
     Y(MfmaF32x32, KM_F32, 16, 32, 1, 256, 4, 1)         \
     Y(MfmaF32x32, KM_F32, 16, 32, 1, 128, 4, 1)         \
+    Y(MfmaF64x16, KM_F64, 128, 128, 1, 32, 8, 8)         \
     Y(MfmaF64x16, KM_F64, 128, 128, 1, 16, 4, 4)         \
     Y(MfmaF64x16, KM_F64, 128, 128, 1, 32, 4, 4)         \
-    Y(MfmaF64x16, KM_F64, 128, 128, 1, 32, 8, 8)         \
     Y(MfmaF32x16, KM_F32, 16, 16, 2, 32, 4, 1)          \
     Y(MfmaF32x16, KM_F32, 16, 16, 1, 256, 4, 1)         \
     Y(MfmaF32x16, KM_F32, 16, 16, 1, 64, 4, 1)          \
