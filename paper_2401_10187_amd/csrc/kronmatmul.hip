@@ -214,6 +214,7 @@ static hipError_t launch_shuffle(const LaunchArgs& a)
     Y(MfmaF32x16, KM_F32, 16, 16, 1, 256, 4, 1)         \
     Y(MfmaF32x16, KM_F32, 16, 16, 1, 64, 4, 1)          \
     Y(MfmaF32x16, KM_F32, 16, 16, 1, 16, 1, 1)          \
+    Y(MfmaF32x32, KM_F32, 64, 64, 1, 128, 8, 2)         \
     Y(MfmaF32x32, KM_F32, 64, 64, 1, 128, 4, 1)         \
     Y(MfmaF32x32, KM_F32, 64, 64, 1, 64, 2, 1)          \
     Y(MfmaF32x32, KM_F32, 128, 128, 1, 32, 4, 4)        \
@@ -224,6 +225,7 @@ static hipError_t launch_shuffle(const LaunchArgs& a)
     Y(MfmaF64x16, KM_F64, 32, 32, 2, 16, 8, 1)          \
     Y(MfmaF64x16, KM_F64, 32, 32, 1, 128, 4, 1)         \
     Y(MfmaF64x16, KM_F64, 32, 32, 1, 32, 2, 1)          \
+    Y(MfmaF64x16, KM_F64, 64, 64, 1, 64, 8, 2)          \
     Y(MfmaF64x16, KM_F64, 64, 64, 1, 64, 4, 1)          \
     W(float, KM_F32, 2, 2, 3, 3, 3, 32, 256)            \
     W(float, KM_F32, 2, 2, 3, 3, 0, 256, 256)           \
