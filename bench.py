@@ -31,7 +31,7 @@ MEASURED_TRAFFIC = {
     "c1_f32_m16_8x8x3": 88691,             # fused_f32_8x8_nf3_c1_m16_8x8x3.md
     "c2_f32_m1024_8x8x6": 2147874395,      # fused_f32_8x8_nf3_c2_m1024_8x8x6.md
     "c3_f32_m1024_32x32x4": 8593683373,    # mfma_f32_32x32_nf2_c3_m1024_32x32x4.md
-    "c4_f64_m16_128x128x3": 537981406,     # mfma_f64_128x128_nf1_c4_m16_128x128x3.md
+    "c4_f64_m16_128x128x3": 537962152,     # mfma_f64_128x128_nf1_c4_m16_128x128x3.md
     "c5_f32_m256_16x32x4": 1342527421,     # mfma_f32_16x32_nf2_c5_m256_16x32x4.md
 }
 
