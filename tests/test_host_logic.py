@@ -21,6 +21,38 @@ def test_library_exports_every_declared_symbol():
         assert getattr(L, name) is not None
 
 
+def test_header_is_plain_c_and_links_against_the_library(tmp_path):
+    """The boundary is a C ABI: the header compiles as C99 and a C program that calls a host-only entry
+    point links against the shared library and runs."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    src = tmp_path / "use.c"
+    src.write_text('''
+#include <stdio.h>
+#include "kronmatmul.h"
+int main(void)
+{
+    int P[3] = {8, 8, 8}, Q[3] = {8, 8, 8}, n = 0;
+    km_plan_step steps[8];
+    km_status s = kronmatmul_plan(16, 3, P, Q, KM_F32, steps, 8, &n);
+    if (s != KM_OK || n != 1 || steps[0].num_factors != 3) return 1;
+    if (kronmatmul_store_column(64, 2, 8, 3, 5) != 45) return 2;
+    printf("%s\\n", kronmatmul_status_string(KM_EUNSUPPORTED));
+    return 0;
+}
+''')
+    exe = tmp_path / "use"
+    lib_dir = os.path.dirname(km.LIB_PATH)
+    subprocess.run([gcc, "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"), str(src),
+                    "-o", str(exe), "-L", lib_dir, "-lkronmatmul", "-Wl,-rpath," + lib_dir], check=True)
+    out = subprocess.run([str(exe)], capture_output=True, text=True, timeout=120)
+    assert out.returncode == 0, out.stderr
+    assert "not supported" in out.stdout
+
+
 def test_status_and_kernel_names():
     assert km.status_string(km.KM_OK) == "ok"
     assert "invalid" in km.status_string(km.KM_EINVAL)
