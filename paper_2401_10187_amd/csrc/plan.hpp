@@ -44,7 +44,6 @@ inline int launch_lds_bytes(const Variant& c, int tile_slices)
 // powers of two so that the usual power-of-two tile counts split evenly over the grid.
 // Instances that fill most of a compute unit's LDS run one or two workgroups per unit and need the
 // walk to overlap their loads with their stores: at least 4 tiles above 64 KB, 32 above 80 KB.
-// The launch must keep two workgroups for each of the 256 compute units.
 inline int64_t tiles_per_wg(int64_t num_tiles, int hint, int64_t factor_elems, int64_t tile_elems,
                             int lds_bytes, size_t esize)
 {
@@ -55,7 +54,10 @@ inline int64_t tiles_per_wg(int64_t num_tiles, int hint, int64_t factor_elems, i
     if ((size_t)factor_elems * esize >= 16 * 1024) t = 32;
     if (lds_bytes > 64 * 1024 && t < 4) t = 4;
     if (lds_bytes > 80 * 1024) t = 32;
-    while (t > 1 && num_tiles / t < 512) t /= 2;
+    // two workgroups per compute unit at least; four when the instance is light (small factor, at most
+    // 64 KB of LDS): 1024 x 64x64^2 is 28 % faster with 1024 workgroups than with 512
+    const int64_t fewest = ((size_t)factor_elems * esize >= 64 * 1024 || lds_bytes > 64 * 1024) ? 512 : 1024;
+    while (t > 1 && num_tiles / t < fewest) t /= 2;
     return t;
 }
 
