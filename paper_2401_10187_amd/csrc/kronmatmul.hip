@@ -138,6 +138,25 @@ static hipError_t launch_mfma_pair(const LaunchArgs& a)
     return hipGetLastError();
 }
 
+template <int P, int ST, int NW>
+static hipError_t launch_mfma_pair_rows(const LaunchArgs& a)
+{
+    const km_plan_step& st = *a.st;
+    auto kern = mfma_pair_rows_sliced_multiply<P, ST, NW>;
+    if (st.k_in != (int64_t)P * P || st.k_out != 32 * 32 || st.tile_rows != ST || st.tile_slices != 1)
+        return hipErrorInvalidValue;
+    const float* f0 = (const float*)a.factors[st.first_factor + 1];    // applied first
+    const float* f1 = (const float*)a.factors[st.first_factor];
+    const int64_t num_tiles = (a.pr->M + ST - 1) / ST;
+    const int64_t tpw = st.tiles_per_wg;
+    if (tpw < 1 || (num_tiles + tpw - 1) / tpw != st.grid) return hipErrorInvalidValue;
+    if (st.tile_order != 0 && st.tile_order != 2 && st.tile_order != 3) return hipErrorInvalidValue;
+    if (st.tile_order == 3 && !xcd_order_fits(num_tiles, st.grid)) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(kern, dim3((unsigned)st.grid), dim3(NW * 64), 0, a.stream,
+                       (const float*)a.src, (float*)a.dst, f0, f1, a.pr->M, num_tiles, tpw, st.tile_order);
+    return hipGetLastError();
+}
+
 template <int P, int ST, int PD>
 static hipError_t launch_mfma_pair_split(const LaunchArgs& a)
 {
@@ -176,9 +195,10 @@ static hipError_t launch_shuffle(const LaunchArgs& a)
 // Small-factor instances with several factors per LDS pass and a run-time tile length:
 // W(type, dtype code, P, Q, G0, G1, G2, largest tile_slices, threads).
 // The same with compute and store wavefronts: S(P, tile_slices, units fetched ahead).
+// The same for rows of exactly P*P elements, ST rows per tile: R(P, rows per tile, wavefronts).
 // MFMA instances: Y(op, dtype code, P, Q, factors per launch, tile_slices, wavefronts, q split).
 // Order = preference among instances that fit a shape.
-#define KM_INSTANCES(X, Y, Z, W, S)                          \
+#define KM_INSTANCES(X, Y, Z, W, S, R)                          \
     X(float, KM_F32, 8, 8, 3, 32, 1024)                 \
     X(float, KM_F32, 8, 8, 3, 32, 256)                  \
     X(float, KM_F32, 8, 8, 3, 16, 256)                  \
@@ -192,6 +212,7 @@ static hipError_t launch_shuffle(const LaunchArgs& a)
     X(float, KM_F32, 8, 8, 1, 64, 64)                   \
     X(float, KM_F32, 8, 8, 1, 8, 64)                    \
     X(float, KM_F32, 8, 8, 1, 1, 64)                    \
+    R(32, 32, 4)                                        \
     Z(32, 32, 4, 1)                                     \
     S(32, 32, 1)                                        \
     S(32, 32, 3)                                        \
@@ -201,6 +222,7 @@ static hipError_t launch_shuffle(const LaunchArgs& a)
     Y(MfmaF32x32, KM_F32, 32, 32, 1, 256, 4, 1)         \
     Y(MfmaF32x32, KM_F32, 32, 32, 1, 128, 4, 1)         \
     Y(MfmaF32x32, KM_F32, 32, 32, 1, 32, 1, 1)          \
+    R(16, 32, 4)                                        \
     Z(16, 32, 4, 1)                                     \
     S(16, 32, 1)                                        \
     Y(MfmaF32x32, KM_F32, 16, 32, 2, 32, 4, 1)          \
@@ -303,6 +325,9 @@ static hipError_t launch_shuffle(const LaunchArgs& a)
     {KM_KERNEL_FUSED, DT, P, Q, G0 + G1 + G2, ST, NT, MultiShape<T, P, Q, G0, G1, G2, ST, NT>::LDS_BYTES, 1, 0, 1, \
      (G0 == 1 && P < 8) ? 1.6f : 1.0f,                   /* one tiny factor per LDS pass is instruction-bound */ \
      "fused-multi", MultiShape<T, P, Q, G0, G1, G2, ST, NT>::LDS_PER_SLICE},
+#define KM_ROWS_ROW(P, ST, NW) \
+    {KM_KERNEL_MFMA, KM_F32, P, 32, 2, 1, NW * 64, 0, ST, 2, 0, 1.0f, "mfma-pair-rows"},
+#define KM_ROWS_FN(P, ST, NW) launch_mfma_pair_rows<P, ST, NW>,
 #define KM_SPLIT_ROW(P, ST, PD) \
     {KM_KERNEL_MFMA, KM_F32, P, 32, 2, ST, 512, MfmaPairSplitShape<P, ST, PD>::LDS_BYTES, 1, 2, 0, 1.0f, "mfma-pair-split"},
 #define KM_SPLIT_FN(P, ST, PD) launch_mfma_pair_split<P, ST, PD>,
@@ -313,10 +338,10 @@ static hipError_t launch_shuffle(const LaunchArgs& a)
 
 static const Variant g_variants[] = {
     {KM_KERNEL_SHUFFLE, KM_F32, SHF_P, SHF_Q, 1, SHF_ST, SHF_NT, 0, 1, 0, 0, 1.0f, "shuffle"},
-    KM_INSTANCES(KM_FUSED_ROW, KM_MFMA_ROW, KM_PAIR_ROW, KM_MULTI_ROW, KM_SPLIT_ROW) };
+    KM_INSTANCES(KM_FUSED_ROW, KM_MFMA_ROW, KM_PAIR_ROW, KM_MULTI_ROW, KM_SPLIT_ROW, KM_ROWS_ROW) };
 static const LaunchFn g_launchers[] = {
     launch_shuffle,
-    KM_INSTANCES(KM_FUSED_FN, KM_MFMA_FN, KM_PAIR_FN, KM_MULTI_FN, KM_SPLIT_FN) };
+    KM_INSTANCES(KM_FUSED_FN, KM_MFMA_FN, KM_PAIR_FN, KM_MULTI_FN, KM_SPLIT_FN, KM_ROWS_FN) };
 static const int g_num_variants = (int)(sizeof(g_variants) / sizeof(g_variants[0]));
 
 template <typename T>

@@ -209,3 +209,99 @@ void mfma_pair_sliced_multiply(const float* __restrict__ Xg, float* __restrict__
 }
 
 }  // namespace km
+
+namespace km {
+
+// The same register-chained pair for rows that hold exactly one slice of the pair (K_in = P*P, the
+// whole Kron-Matmul of two factors on a matrix with many rows): the slow index `a` of the tile is the
+// row itself.  X rows are contiguous, so a tile of ST rows is read exactly as above; on the output
+// side row a is (q1, q2) in memory order, which is how the stage-1 accumulator already lies (column
+// q2 on lane % 32, one q1 per register), so every accumulator register is stored as full 128-byte
+// lines straight from the registers: no LDS, no barrier.  The last tile may hold fewer than ST rows.
+template <int P, int ST, int NW>
+__global__ __launch_bounds__(NW * 64, 2)
+void mfma_pair_rows_sliced_multiply(const float* __restrict__ Xg, float* __restrict__ Yg,
+                                    const float* __restrict__ F0, const float* __restrict__ F1,   // in order of application
+                                    int64_t M, int64_t num_tiles, int64_t tiles_per_wg, int tile_order)
+{
+    typedef MfmaPairShape<P, ST, NW, 1> Sh;
+    constexpr int Q = Sh::Q, KS = Sh::KS, AP = Sh::AP, UPW = Sh::UPW;
+    constexpr int KIN = P * P, KOUT = Q * Q;
+
+    const int tid = threadIdx.x;
+    const int lane = tid % 64;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
+    const int col = lane % 32;
+    const int g = lane / 32;
+
+    float b0[KS], a1[KS];
+#pragma unroll
+    for (int t = 0; t < KS; ++t) {
+        b0[t] = F0[(g * KS + t) * Q + col];
+        a1[t] = F1[(8 * (t / 4) + 4 * g + (t % 4)) * Q + col];
+    }
+
+    int64_t t_begin = (int64_t)blockIdx.x * tiles_per_wg, t_step = 1;
+    int64_t t_end = t_begin + tiles_per_wg;
+    if (tile_order == 2) {
+        t_begin = blockIdx.x;
+        t_step = gridDim.x;
+        t_end = num_tiles;
+    } else if (tile_order == 3) {
+        const int64_t per = num_tiles / 8, x = blockIdx.x % 8;
+        t_begin = x * per + blockIdx.x / 8;
+        t_step = gridDim.x / 8;
+        t_end = (x + 1) * per;
+    }
+    if (t_end > num_tiles) t_end = num_tiles;
+
+    // this lane's piece of unit u: row (of the tile) a_loc + first row of the unit, elements from lane_off
+    const int a_loc = (col * P) / KIN;                    // 0, or 0/1 when a unit holds two rows (P = 16)
+    const unsigned lane_off = col * P + g * KS;           // = a_loc * KIN + p1 * P + g * KS
+    auto load_unit = [&](int64_t t, int u, pair_f32x4 (&dst)[KS / 4]) {
+        const int64_t row0 = t * ST + (wave + u * NW) * AP;                 // first row of the unit
+        const float* src = Xg + row0 * KIN;
+        const bool live = row0 + a_loc < M;
+#pragma unroll
+        for (int c = 0; c < KS / 4; ++c) {
+            if (live) dst[c] = *reinterpret_cast<const pair_f32x4*>(src + (lane_off + 4 * c));
+            else dst[c] = pair_f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+    };
+
+    pair_f32x4 xa[2][KS / 4];
+    if (t_begin < t_end) load_unit(t_begin, 0, xa[0]);
+    for (int64_t t = t_begin; t < t_end; t += t_step) {
+#pragma unroll
+        for (int u = 0; u < UPW; ++u) {
+            if (u + 1 < UPW) load_unit(t, u + 1, xa[(u + 1) % 2]);
+            else if (t + t_step < t_end) load_unit(t + t_step, 0, xa[(u + 1) % 2]);
+            pair_f32x16 d0;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) d0[v] = 0.f;
+#pragma unroll
+            for (int s = 0; s < KS; ++s)
+                d0 = __builtin_amdgcn_mfma_f32_32x32x2f32(xa[u % 2][s / 4][s % 4], b0[s], d0, 0, 0, 0);
+#pragma unroll
+            for (int al = 0; al < AP; ++al) {
+                pair_f32x16 acc;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+#pragma unroll
+                for (int s = 0; s < KS; ++s)
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[s], d0[al * KS + s], acc, 0, 0, 0);
+                const int64_t row = t * ST + (wave + u * NW) * AP + al;
+                if (row < M) {
+                    float* dst = Yg + row * KOUT + col;
+#pragma unroll
+                    for (int w = 0; w < 16; ++w) {
+                        const int q1 = 8 * (w / 4) + 4 * g + (w % 4);
+                        stream_store(acc[w], &dst[q1 * Q]);
+                    }
+                }
+            }
+        }
+    }
+}
+
+}  // namespace km

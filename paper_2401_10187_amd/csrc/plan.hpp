@@ -221,7 +221,7 @@ inline void enumerate_choices(const Variant* table, int count, const Problem& pr
         if (!(opt.kernels >> c.kernel & 1)) continue;
         if (c.dtype != pr.dtype || c.num_factors != nf) continue;
         if (c.P != pr.P[f] || c.Q != pr.Q[f]) continue;
-        if (pr.M % c.rows_per_tile) continue;
+        if (c.rows_per_tile > 1 && s_row != c.tile_slices) continue;      // tiles of several rows hold whole rows
         tile_lengths(c, s_row, lens, 5);
         const int rows = whole_rows_per_tile(c, s_row, pr.M);
         if (rows > 1) {                                   // whole rows, several per tile, and half as many
@@ -238,7 +238,8 @@ inline void enumerate_choices(const Variant* table, int count, const Problem& pr
             Choice ch;
             ch.var = &c;
             ch.tile_slices = st;
-            ch.grid = (pr.M / c.rows_per_tile) * (s_row / st);
+            ch.tile_rows = c.rows_per_tile;
+            ch.grid = ((pr.M + c.rows_per_tile - 1) / c.rows_per_tile) * (s_row / st);
             if (!c.persistent) { out.push_back(ch); continue; }
             // walks: fixed lengths, and the lengths that make the grid exactly one or two rounds of
             // the workgroups the chip holds at once (every workgroup then gets the same share)
@@ -283,10 +284,10 @@ inline Choice find_variant(const Variant* table, int count, const Problem& pr, i
         if (!(opt.kernels >> c.kernel & 1)) continue;
         if (c.dtype != pr.dtype || c.num_factors != nf) continue;
         if (c.P != pr.P[f] || c.Q != pr.Q[f]) continue;
-        if (pr.M % c.rows_per_tile) continue;
+        if (c.rows_per_tile > 1 && s_row != c.tile_slices) continue;      // tiles of several rows hold whole rows
         // slices per tile: fixed, or the best divisor of s_row up to the instance's limit
         int cand[3] = {0, 0, 0};
-        int rows = 1;
+        int rows = c.rows_per_tile;
         if (!c.flexible) {
             if (s_row % c.tile_slices) continue;
             cand[0] = c.tile_slices;
@@ -311,7 +312,7 @@ inline Choice find_variant(const Variant* table, int count, const Problem& pr, i
                 const bool small_enough = d <= fit && (align >= 128 || run >= 256 || !alignable);
                 const int64_t key = (align * 2 + (small_enough ? 1 : 0)) * (lim + 1) + d;
                 if (key > best_key[0]) { best_key[0] = key; cand[0] = (int)d; }
-                if ((pr.M / c.rows_per_tile) * (s_row / d) >= enough && key > best_key[1]) { best_key[1] = key; cand[1] = (int)d; }
+                if (pr.M * (s_row / d) >= enough && key > best_key[1]) { best_key[1] = key; cand[1] = (int)d; }
             }
             if (opt.prefer_tile > 0 && opt.prefer_tile <= c.tile_slices && s_row % opt.prefer_tile == 0) cand[2] = opt.prefer_tile;
             // rows much shorter than the tile: whole rows, several per tile
@@ -323,7 +324,7 @@ inline Choice find_variant(const Variant* table, int count, const Problem& pr, i
             Choice ch;
             ch.var = &c;
             ch.tile_slices = cand[k];
-            ch.grid = (pr.M / c.rows_per_tile) * (s_row / cand[k]);
+            ch.grid = pr.M * (s_row / cand[k]);
             if (rows > 1) {
                 ch.tile_rows = rows;
                 ch.grid = (pr.M + rows - 1) / rows;
@@ -361,8 +362,7 @@ inline double launch_cost(const Problem& pr, int64_t k_in, int64_t k_out, const 
     if (ch.var) {
         int64_t run = (int64_t)ch.tile_slices * (int64_t)pr.esize;
         // a tile that holds a whole row writes the whole output row: its runs join up
-        const int64_t rows = pr.M / ch.var->rows_per_tile;
-        if (ch.tile_rows > 1 || (rows > 0 && ch.grid == rows)) run = k_out * (int64_t)pr.esize;
+        if (ch.tile_rows > 1 || ch.grid == pr.M) run = k_out * (int64_t)pr.esize;
         slow = run >= 128 ? 1.0 : (run >= 64 ? 1.25 : (run >= 32 ? 2.5 : 4.0));
         slow *= ch.var->slowdown;
     }
@@ -402,7 +402,7 @@ inline km_plan_step build_step(const Problem& pr, const Options& opt, const Vari
         if (var->persistent) {
             const int hint = ch.tiles_per_wg > 0 ? ch.tiles_per_wg : opt.tiles_per_wg;
             const int64_t tpw = tiles_per_wg(st.grid, hint, (int64_t)nf * var->P * var->Q,
-                                             (int64_t)ch.tile_slices * pg, var->lds_bytes, pr.esize);
+                                             (int64_t)ch.tile_slices * ch.tile_rows * pg, var->lds_bytes, pr.esize);
             const int64_t num_tiles = st.grid;
             st.tiles_per_wg = (int)tpw;
             st.grid = (num_tiles + tpw - 1) / tpw;

@@ -129,6 +129,10 @@ SMALL_CASES = [
     ("float64", 21, [(16, 16)] * 2),
     ("float64", 10, [(32, 32)] * 2),
     ("float64", 5, [(64, 64)] * 2),
+    # rows of exactly P*P elements: the pair kernel that takes rows as its slow index, ragged last tile
+    ("float32", 1000, [(32, 32)] * 2),
+    ("float32", 77, [(16, 32)] * 2),
+    ("float32", 1, [(32, 32)] * 2),
     ("float32", 3, [(7, 7)] * 5),
     ("float64", 2, [(7, 7)] * 5),
     ("float32", 2, [(9, 9)] * 4),
@@ -296,6 +300,7 @@ EVERY_INSTANCE = [
     ("float32", 1100, [(8, 8)] * 2), ("float32", 1100, [(8, 8)]), ("float64", 3, [(8, 8)] * 3),
     ("float32", 2, [(2, 2)] * 9), ("float64", 2, [(4, 4)] * 4), ("float32", 2, [(4, 4)] * 5),
     ("float64", 2, [(2, 2)] * 9), ("float64", 2, [(9, 9)] * 3), ("float64", 2, [(10, 10)] * 3),
+    ("float32", 9, [(16, 32)] * 2),
 ]
 
 
