@@ -498,7 +498,7 @@ inline km_status make_plan(const Problem& pr, const Options& opt, const Variant*
             const Choice ch = find_variant(table, count, pr, r - 1, nf, width[r], opt);
             if (nf > 1 && !ch.var) continue;             // only single factors fall back to the generic kernel
             const double c = launch_cost(pr, width[r], width[r - nf], ch) + best[r - nf];
-            if (best[r] < 0 || c < best[r]) { best[r] = c; take[r] = nf; pick[r] = ch; }
+            if (best[r] < 0 || c <= best[r] * (1 + 1e-9)) { best[r] = c; take[r] = nf; pick[r] = ch; }
         }
     }
     return finish_plan(pr, opt, table, take, pick, width, generic_threads, generic_tile_slices, generic_lds, plan);
