@@ -50,6 +50,9 @@ def main():
                     help="time the steps without per-launch events and take the per-launch durations from a "
                          "second, untimed pass (for launch-bound problems, where the events cost as much as "
                          "the kernels); default: events inside the timed region")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture the timed steps in one HIP graph and time its replay (the repeated small-M "
+                         "calls of an iterative solver; implies --separate-profile)")
     ap.add_argument("--tune", action="store_true",
                     help="run the library's autotuner for the workload before the warm-up (set-up, not timed)")
     ap.add_argument("--seed", type=int, default=1)
@@ -113,15 +116,33 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.graph:
+        args.separate_profile = True
     if not args.separate_profile:
         km.set_option(km.KM_OPT_PROFILE, 1)     # HIP events around every launch, on the launch stream
     t0 = torch.cuda.Event(enable_timing=True)
     t1 = torch.cuda.Event(enable_timing=True)
+    graph = None
+    if args.graph:
+        # the steps become one graph (kronmatmul_ws allocates nothing and synchronises nothing); one
+        # replay warms it up, the next is timed
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(stream)
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                for _ in range(args.steps):
+                    step()
+        stream.wait_stream(side)
+        graph.replay()
     torch.cuda.synchronize()
     wall0 = time.perf_counter()
     t0.record(stream)
-    for _ in range(args.steps):
-        step()
+    if graph is not None:
+        graph.replay()
+    else:
+        for _ in range(args.steps):
+            step()
     t1.record(stream)
     torch.cuda.synchronize()
     wall = time.perf_counter() - wall0
@@ -186,6 +207,7 @@ def main():
                    "end_to_end_gbs": round(planned_bytes / (ms_per_step * 1e-3) / 1e9, 1),
                    "wall_ms_per_step": round(wall * 1e3 / args.steps, 4),
                    "launch_events_in_timed_region": not args.separate_profile,
+                   "steps_replayed_from_one_graph": bool(args.graph),
                    "autotuned": ({"kept_ms": round(tuned[0], 4), "cost_model_ms": round(tuned[1], 4)}
                                  if tuned else False),
                    "paper_baseline": "one V100, Table 1" if args.workload in PAPER_GFLOPS else None},

@@ -20,9 +20,10 @@ def test_more_than_one_gpu_is_refused_with_a_message():
 
 
 @pytest.mark.gpu
-@pytest.mark.parametrize("workload", ["c1_f32_m16_8x8x3", "table4_id21_f64"])
-def test_one_json_line_with_the_agreed_keys(workload):
-    proc = subprocess.run([sys.executable, BENCH, "--workload", workload, "--steps", "7", "--warmup", "3"],
+@pytest.mark.parametrize("workload,extra", [("c1_f32_m16_8x8x3", []), ("table4_id21_f64", []),
+                                            ("c1_f32_m16_8x8x3", ["--graph"])])
+def test_one_json_line_with_the_agreed_keys(workload, extra):
+    proc = subprocess.run([sys.executable, BENCH, "--workload", workload, "--steps", "7", "--warmup", "3"] + extra,
                           capture_output=True, text=True, timeout=600)
     assert proc.returncode == 0, proc.stderr[-2000:]
     lines = [line for line in proc.stdout.splitlines() if line.strip()]
