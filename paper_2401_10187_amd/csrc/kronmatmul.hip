@@ -313,7 +313,27 @@ static hipError_t launch_shuffle(const LaunchArgs& a)
     W(double, KM_F64, 10, 10, 1, 1, 0, 50, 256)         \
     W(double, KM_F64, 10, 10, 1, 0, 0, 500, 256)        \
     W(double, KM_F64, 12, 12, 1, 1, 0, 36, 256)         \
-    W(double, KM_F64, 12, 12, 1, 0, 0, 432, 256)
+    W(double, KM_F64, 12, 12, 1, 0, 0, 432, 256)        \
+    W(float, KM_F32, 2, 4, 2, 2, 0, 16, 256)            \
+    W(float, KM_F32, 2, 4, 2, 0, 0, 512, 256)           \
+    W(float, KM_F32, 2, 4, 1, 0, 0, 2048, 256)          \
+    W(float, KM_F32, 4, 2, 2, 2, 0, 32, 256)            \
+    W(float, KM_F32, 4, 2, 2, 0, 0, 512, 256)           \
+    W(float, KM_F32, 4, 2, 1, 0, 0, 2048, 256)          \
+    W(float, KM_F32, 4, 8, 2, 1, 0, 16, 256)            \
+    W(float, KM_F32, 4, 8, 2, 0, 0, 128, 256)           \
+    W(float, KM_F32, 4, 8, 1, 0, 0, 1024, 256)          \
+    W(float, KM_F32, 8, 4, 1, 1, 1, 16, 256)            \
+    W(float, KM_F32, 8, 4, 1, 1, 0, 128, 256)           \
+    W(float, KM_F32, 8, 4, 1, 0, 0, 1024, 256)          \
+    W(double, KM_F64, 2, 4, 2, 2, 0, 8, 256)            \
+    W(double, KM_F64, 2, 4, 2, 0, 0, 256, 256)          \
+    W(double, KM_F64, 4, 2, 2, 2, 0, 16, 256)           \
+    W(double, KM_F64, 4, 2, 2, 0, 0, 256, 256)          \
+    W(double, KM_F64, 4, 8, 2, 0, 0, 64, 256)           \
+    W(double, KM_F64, 4, 8, 1, 0, 0, 512, 256)          \
+    W(double, KM_F64, 8, 4, 1, 1, 0, 64, 256)           \
+    W(double, KM_F64, 8, 4, 1, 0, 0, 512, 256)
 
 #define KM_FUSED_ROW(T, DT, P, Q, NF, ST, NT) \
     {KM_KERNEL_FUSED, DT, P, Q, NF, ST, NT, FusedShape<T, P, Q, NF, ST, NT>::LDS_BYTES, 1, 0, 0, 1.0f, "fused"},

@@ -129,6 +129,13 @@ SMALL_CASES = [
     ("float64", 21, [(16, 16)] * 2),
     ("float64", 10, [(32, 32)] * 2),
     ("float64", 5, [(64, 64)] * 2),
+    # rectangular small factors, growing and shrinking rows
+    ("float32", 5, [(2, 4)] * 7),
+    ("float32", 5, [(4, 2)] * 7),
+    ("float64", 3, [(4, 8)] * 4),
+    ("float64", 3, [(8, 4)] * 5),
+    ("float32", 1100, [(2, 4)] * 4),
+    ("float32", 4, [(4, 8), (4, 8), (8, 4), (8, 4), (2, 4)]),
     # rows of exactly P*P elements: the pair kernel that takes rows as its slow index, ragged last tile
     ("float32", 1000, [(32, 32)] * 2),
     ("float32", 77, [(16, 32)] * 2),
@@ -301,6 +308,10 @@ EVERY_INSTANCE = [
     ("float32", 2, [(2, 2)] * 9), ("float64", 2, [(4, 4)] * 4), ("float32", 2, [(4, 4)] * 5),
     ("float64", 2, [(2, 2)] * 9), ("float64", 2, [(9, 9)] * 3), ("float64", 2, [(10, 10)] * 3),
     ("float32", 9, [(16, 32)] * 2),
+    # rectangular small factors
+    ("float32", 3, [(2, 4)] * 6), ("float32", 3, [(4, 2)] * 6), ("float32", 3, [(4, 8)] * 4), ("float32", 3, [(8, 4)] * 5),
+    ("float64", 3, [(2, 4)] * 6), ("float64", 3, [(4, 2)] * 6), ("float64", 3, [(4, 8)] * 4), ("float64", 3, [(8, 4)] * 4),
+    ("float32", 2, [(2, 4)] * 2), ("float32", 2, [(4, 2)]), ("float64", 2, [(4, 8)]), ("float32", 2, [(8, 4)] * 2),
 ]
 
 
