@@ -240,6 +240,19 @@ static hipError_t launch_shuffle(const LaunchArgs& a)
     Y(MfmaF32x32, KM_F32, 64, 64, 1, 128, 4, 1)         \
     Y(MfmaF32x32, KM_F32, 64, 64, 1, 64, 2, 1)          \
     Y(MfmaF32x32, KM_F32, 128, 128, 1, 32, 4, 4)        \
+    Y(MfmaF32x16, KM_F32, 32, 16, 1, 256, 4, 1)         \
+    Y(MfmaF32x16, KM_F32, 64, 16, 1, 128, 4, 1)         \
+    Y(MfmaF32x32, KM_F32, 64, 32, 1, 128, 4, 1)         \
+    Y(MfmaF32x32, KM_F32, 32, 64, 1, 256, 4, 1)         \
+    Y(MfmaF32x32, KM_F32, 16, 64, 1, 256, 4, 1)         \
+    Y(MfmaF32x32, KM_F32, 128, 64, 1, 64, 4, 2)         \
+    Y(MfmaF32x32, KM_F32, 64, 128, 1, 128, 8, 2)        \
+    Y(MfmaF32x32, KM_F32, 128, 32, 1, 64, 2, 1)         \
+    Y(MfmaF32x32, KM_F32, 32, 128, 1, 256, 4, 2)        \
+    Y(MfmaF64x16, KM_F64, 32, 16, 1, 128, 4, 1)         \
+    Y(MfmaF64x16, KM_F64, 16, 32, 1, 128, 4, 1)         \
+    Y(MfmaF64x16, KM_F64, 64, 32, 1, 64, 4, 1)          \
+    Y(MfmaF64x16, KM_F64, 32, 64, 1, 128, 4, 1)         \
     Y(MfmaF64x16, KM_F64, 16, 16, 2, 16, 4, 1)          \
     Y(MfmaF64x16, KM_F64, 16, 16, 1, 256, 4, 1)         \
     Y(MfmaF64x16, KM_F64, 16, 16, 1, 64, 4, 1)          \

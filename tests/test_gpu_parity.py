@@ -308,6 +308,12 @@ EVERY_INSTANCE = [
     ("float32", 2, [(2, 2)] * 9), ("float64", 2, [(4, 4)] * 4), ("float32", 2, [(4, 4)] * 5),
     ("float64", 2, [(2, 2)] * 9), ("float64", 2, [(9, 9)] * 3), ("float64", 2, [(10, 10)] * 3),
     ("float32", 9, [(16, 32)] * 2),
+    # rectangular factors on the matrix cores
+    ("float32", 4, [(32, 16)] * 3), ("float32", 4, [(64, 16)] * 3), ("float32", 4, [(64, 32)] * 3),
+    ("float32", 8, [(32, 64)] * 3), ("float32", 8, [(16, 64)] * 4), ("float32", 4, [(128, 64)] * 2),
+    ("float32", 8, [(64, 128)] * 3), ("float32", 4, [(128, 32)] * 2), ("float32", 16, [(32, 128)] * 3),
+    ("float64", 4, [(32, 16)] * 3), ("float64", 4, [(16, 32)] * 4), ("float64", 4, [(64, 32)] * 3),
+    ("float64", 4, [(32, 64)] * 3),
     # rectangular small factors
     ("float32", 3, [(2, 4)] * 6), ("float32", 3, [(4, 2)] * 6), ("float32", 3, [(4, 8)] * 4), ("float32", 3, [(8, 4)] * 5),
     ("float64", 3, [(2, 4)] * 6), ("float64", 3, [(4, 2)] * 6), ("float64", 3, [(4, 8)] * 4), ("float64", 3, [(8, 4)] * 4),
