@@ -33,15 +33,19 @@ struct MfmaF32x32 {
     typedef float T;
     typedef mfma_f32x16 Acc;
     static constexpr int MB = 32, NB = 32, KG = 2, NACC = 16;
+    static constexpr bool JOIN_BLOCKS = false;         // a register is already a 128-byte run of the output row
     static __device__ __forceinline__ int row_lane(int lane) { return 4 * (lane / 32); }
     static constexpr int row_reg(int v) { return 8 * (v / 4) + (v % 4); }
     static __device__ __forceinline__ Acc mma(float a, float b, Acc c) { return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0); }
 };
 // v_mfma_f32_16x16x4_f32: lane l holds A[l%16][l/16], B[l/16][l%16]; register v is D[4*(l/16) + v][l%16].
+// A register holds four 64-byte runs of the output row.  Two neighbouring slice blocks are joined
+// into 128-byte runs before the store (join_blocks below) where the tile allows it.
 struct MfmaF32x16 {
     typedef float T;
     typedef mfma_f32x4 Acc;
     static constexpr int MB = 16, NB = 16, KG = 4, NACC = 4;
+    static constexpr bool JOIN_BLOCKS = true;
     static __device__ __forceinline__ int row_lane(int lane) { return 4 * (lane / 16); }
     static constexpr int row_reg(int v) { return v; }
     static __device__ __forceinline__ Acc mma(float a, float b, Acc c) { return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0); }
@@ -51,10 +55,24 @@ struct MfmaF64x16 {
     typedef double T;
     typedef mfma_f64x4 Acc;
     static constexpr int MB = 16, NB = 16, KG = 4, NACC = 4;
+    static constexpr bool JOIN_BLOCKS = false;         // 16 doubles are a 128-byte run
     static __device__ __forceinline__ int row_lane(int lane) { return lane / 16; }
     static constexpr int row_reg(int v) { return 4 * v; }
     static __device__ __forceinline__ Acc mma(double a, double b, Acc c) { return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0); }
 };
+
+// Registers x and y of the 16x16 fp32 accumulators of slice blocks 2k and 2k+1 (same register
+// index v): afterwards lane l of x holds row 8*(l/32) + v, slice 32k + l%32, and lane l of y holds
+// row 8*(l/32) + 4 + v of the same slice, so each half of a wavefront stores one 128-byte run.
+// (v_permlane16_swap exchanges the odd 16-lane groups of x with the even ones of y.)
+template <class Acc>
+__device__ __forceinline__ void join_blocks(Acc& x, Acc& y, int v)
+{
+    const float xv = x[v], yv = y[v];
+    const auto r = __builtin_amdgcn_permlane16_swap(__builtin_bit_cast(unsigned, xv), __builtin_bit_cast(unsigned, yv), false, false);
+    x[v] = __builtin_bit_cast(float, (unsigned)r[0]);
+    y[v] = __builtin_bit_cast(float, (unsigned)r[1]);
+}
 
 // NW wavefronts per workgroup; the factor's column blocks are dealt to QSPLIT wave groups and the
 // slice blocks of a stage to the NW/QSPLIT wave groups along the other axis.
@@ -84,6 +102,13 @@ struct MfmaShape {
     static constexpr int NBUF = (NF == 1 && QSPLIT == 1) ? 2 : 1;
     static constexpr int LDS_BYTES = NBUF * BUF_ELEMS * (int)sizeof(T);
     static constexpr int RV = TK / VN / NT;            // 16-byte vectors of a tile per thread
+    // Slice block number `bi` of wave group `ws` out of `bpw` per group.  Joined stores need a
+    // wavefront to own blocks 2k and 2k+1; otherwise the blocks are dealt round-robin.
+    static constexpr bool joined(int bpw) { return OP::JOIN_BLOCKS && ST % (2 * OP::NB) == 0 && bpw % 2 == 0; }
+    static __device__ __forceinline__ int block_of(int ws, int bi, int bpw)
+    {
+        return joined(bpw) ? 2 * (ws + (bi / 2) * SG) + bi % 2 : ws + bi * SG;
+    }
     static_assert(P % OP::KG == 0 && Q % OP::MB == 0 && QT % QSPLIT == 0 && NW % QSPLIT == 0, "shape");
     static_assert((PL * sizeof(T)) % 16 == 0, "a lane's piece of a slice must be whole 16-byte vectors");
     static_assert(TK % (VN * NT) == 0, "tile must be a whole number of vectors per thread");
@@ -107,10 +132,11 @@ __device__ __forceinline__ void mfma_stage(typename OP::T* __restrict__ tile,
     const int j = lane % OP::NB, g = lane / OP::NB;
     const int wq = wave % QSPLIT, ws = wave / QSPLIT;
 
-    typename OP::Acc acc[LAST ? 1 : BPW][QTW];
+    constexpr bool JOIN = LAST && Sh::joined(BPW);
+    typename OP::Acc acc[LAST ? (JOIN ? 2 : 1) : BPW][QTW];
 #pragma unroll
     for (int bi = 0; bi < BPW; ++bi) {
-        const int s0 = (ws + bi * SG) * OP::NB;
+        const int s0 = (LAST ? Sh::block_of(ws, bi, BPW) : ws + bi * SG) * OP::NB;
         T b[PL];
         const V* src = reinterpret_cast<const V*>(tile + (s0 + j) * RS + g * PL);
 #pragma unroll
@@ -119,7 +145,7 @@ __device__ __forceinline__ void mfma_stage(typename OP::T* __restrict__ tile,
 #pragma unroll
             for (int e = 0; e < VN; ++e) b[VN * c + e] = v[e];
         }
-        const int ai = LAST ? 0 : bi;
+        const int ai = LAST ? (JOIN ? bi % 2 : 0) : bi;
 #pragma unroll
         for (int qt = 0; qt < QTW; ++qt) {
 #pragma unroll
@@ -130,15 +156,31 @@ __device__ __forceinline__ void mfma_stage(typename OP::T* __restrict__ tile,
         if constexpr (LAST) {
             // local (q, s), s = qrest*ST + r  ->  column (q*Q^(NF-1) + qrest)*s_row + h*ST + r
             constexpr int QREST = (int)ipow(Q, NF - 1);
-            const int s = s0 + j;
             // (in-row offsets fit 32 bits: the planner only picks this kernel for rows below 2^31 bytes)
             const int sr = (int)s_row;
-            const int off = (s / ST) * sr + (int)h * ST + (s % ST) + (wq * QTW * OP::MB + OP::row_lane(lane)) * QREST * sr;
+            if constexpr (JOIN) {
+                if (bi % 2 == 1) {
+                    // blocks s0 - NB and s0 together: 2*NB consecutive slices per half wavefront
+                    const int s = s0 - OP::NB + lane % 32;
+                    const int off = (s / ST) * sr + (int)h * ST + (s % ST) + (wq * QTW * OP::MB + 8 * (lane / 32)) * QREST * sr;
 #pragma unroll
-            for (int qt = 0; qt < QTW; ++qt)
+                    for (int qt = 0; qt < QTW; ++qt)
 #pragma unroll
-                for (int v = 0; v < OP::NACC; ++v)
-                    stream_store(acc[0][qt][v], &Yrow[off + (qt * OP::MB + OP::row_reg(v)) * QREST * sr]);
+                        for (int v = 0; v < OP::NACC; ++v) {
+                            join_blocks(acc[0][qt], acc[1][qt], v);
+                            stream_store(acc[0][qt][v], &Yrow[off + (qt * OP::MB + v) * QREST * sr]);
+                            stream_store(acc[1][qt][v], &Yrow[off + (qt * OP::MB + 4 + v) * QREST * sr]);
+                        }
+                }
+            } else {
+                const int s = s0 + j;
+                const int off = (s / ST) * sr + (int)h * ST + (s % ST) + (wq * QTW * OP::MB + OP::row_lane(lane)) * QREST * sr;
+#pragma unroll
+                for (int qt = 0; qt < QTW; ++qt)
+#pragma unroll
+                    for (int v = 0; v < OP::NACC; ++v)
+                        stream_store(acc[0][qt][v], &Yrow[off + (qt * OP::MB + OP::row_reg(v)) * QREST * sr]);
+            }
         }
     }
     if constexpr (!LAST) {
@@ -178,7 +220,7 @@ __device__ __forceinline__ void mfma_single_compute(
     const int ws = wave / QSPLIT;
 #pragma unroll
     for (int bi = 0; bi < BPW; ++bi) {
-        const int s0 = (ws + bi * SG) * OP::NB;
+        const int s0 = Sh::block_of(ws, bi, BPW) * OP::NB;
         T b[PL];
         const V* src = reinterpret_cast<const V*>(tile + (s0 + j) * RS + g * PL);
 #pragma unroll
@@ -200,8 +242,8 @@ __device__ __forceinline__ void mfma_single_compute(
 // ... then the permuted store: (q, s) -> column q*s_row + h*ST + s.
 template <class OP, int P, int Q, int ST, int NW, int QSPLIT>
 __device__ __forceinline__ void mfma_single_store(
-    const typename OP::Acc (&acc)[ST / OP::NB / MfmaShape<OP, P, Q, 1, ST, NW, QSPLIT>::SG][MfmaShape<OP, P, Q, 1, ST, NW, QSPLIT>::QTW],
-    typename OP::T* __restrict__ Yrow, int64_t s_row, int64_t h)
+    typename OP::T* __restrict__ Yrow, int64_t s_row, int64_t h,
+    typename OP::Acc (&acc)[ST / OP::NB / MfmaShape<OP, P, Q, 1, ST, NW, QSPLIT>::SG][MfmaShape<OP, P, Q, 1, ST, NW, QSPLIT>::QTW])
 {
     typedef MfmaShape<OP, P, Q, 1, ST, NW, QSPLIT> Sh;
     constexpr int QTW = Sh::QTW, SG = Sh::SG;
@@ -211,15 +253,31 @@ __device__ __forceinline__ void mfma_single_store(
     const int wq = wave % QSPLIT, ws = wave / QSPLIT;
     // (in-row offsets fit 32 bits: the planner only picks this kernel for rows below 2^31 bytes)
     const int sr = (int)s_row;
+    if constexpr (Sh::joined(BPW)) {
 #pragma unroll
-    for (int bi = 0; bi < BPW; ++bi) {
-        const int s = (ws + bi * SG) * OP::NB + j;
-        const int off = (int)h * ST + s + (wq * QTW * OP::MB + OP::row_lane(lane)) * sr;
+        for (int bi = 0; bi < BPW; bi += 2) {
+            const int s = Sh::block_of(ws, bi, BPW) * OP::NB + lane % 32;
+            const int off = (int)h * ST + s + (wq * QTW * OP::MB + 8 * (lane / 32)) * sr;
 #pragma unroll
-        for (int qt = 0; qt < QTW; ++qt)
+            for (int qt = 0; qt < QTW; ++qt)
 #pragma unroll
-            for (int v = 0; v < OP::NACC; ++v)
-                stream_store(acc[bi][qt][v], &Yrow[off + (qt * OP::MB + OP::row_reg(v)) * sr]);
+                for (int v = 0; v < OP::NACC; ++v) {
+                    join_blocks(acc[bi][qt], acc[bi + 1][qt], v);
+                    stream_store(acc[bi][qt][v], &Yrow[off + (qt * OP::MB + v) * sr]);
+                    stream_store(acc[bi + 1][qt][v], &Yrow[off + (qt * OP::MB + 4 + v) * sr]);
+                }
+        }
+    } else {
+#pragma unroll
+        for (int bi = 0; bi < BPW; ++bi) {
+            const int s = (ws + bi * SG) * OP::NB + j;
+            const int off = (int)h * ST + s + (wq * QTW * OP::MB + OP::row_lane(lane)) * sr;
+#pragma unroll
+            for (int qt = 0; qt < QTW; ++qt)
+#pragma unroll
+                for (int v = 0; v < OP::NACC; ++v)
+                    stream_store(acc[bi][qt][v], &Yrow[off + (qt * OP::MB + OP::row_reg(v)) * sr]);
+        }
     }
 }
 
@@ -331,7 +389,7 @@ void mfma_sliced_multiply(const typename OP::T* __restrict__ Xg, typename OP::T*
                 }
             }
             const int64_t row = t / tiles_per_row, h = t % tiles_per_row;
-            mfma_single_store<OP, P, Q, ST, NW, QSPLIT>(acc, Yg + row * k_out, s_row, h);
+            mfma_single_store<OP, P, Q, ST, NW, QSPLIT>(Yg + row * k_out, s_row, h, acc);
             __syncthreads();      // the other buffer is complete; this one has been read by everybody
             cur ^= 1;
         }
