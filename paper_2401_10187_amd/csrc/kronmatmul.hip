@@ -385,10 +385,10 @@ static hipError_t launch_generic(const LaunchArgs& a)
     const int P = a.pr->P[f], Q = a.pr->Q[f];
     const int64_t S = st.k_in / P;
     const int64_t slices = a.pr->M * S;                  // counted through all rows
-    const int64_t tiles = (slices + GEN_TS - 1) / GEN_TS;
-    if (st.grid < 1 || st.grid > tiles) return hipErrorInvalidValue;
+    const int64_t units = ((slices + GEN_TS - 1) / GEN_TS) * ((Q + GEN_TQ - 1) / GEN_TQ);
+    if (st.grid < 1 || st.grid > units) return hipErrorInvalidValue;
     hipLaunchKernelGGL((sliced_multiply_generic<T>), dim3((unsigned)st.grid), dim3(GEN_THREADS), 0, a.stream,
-                       (const T*)a.src, (const T*)a.factors[f], (T*)a.dst, st.k_in, P, Q, slices, tiles);
+                       (const T*)a.src, (const T*)a.factors[f], (T*)a.dst, st.k_in, P, Q, slices, units);
     return hipGetLastError();
 }
 
@@ -411,9 +411,9 @@ static Options g_options;
 static int g_profile = 0;
 static DeviceState g_dev[64];
 
-static int generic_lds(int dtype)
+static GenericKernel generic_kernel(int dtype)
 {
-    return dtype == KM_F32 ? gen_lds_bytes<float>() : gen_lds_bytes<double>();
+    return GenericKernel{GEN_THREADS, GEN_TS, GEN_TQ, dtype == KM_F32 ? gen_lds_bytes<float>() : gen_lds_bytes<double>()};
 }
 
 // Plans are memoised: iterative callers repeat the same small problem thousands of times and the
@@ -461,7 +461,7 @@ static km_status plan_for(const Problem& pr, Plan& plan)
             }
         }
     }
-    km_status s = make_plan(pr, opt, g_variants, g_num_variants, GEN_THREADS, GEN_TS, generic_lds(pr.dtype), plan);
+    km_status s = make_plan(pr, opt, g_variants, g_num_variants, generic_kernel(pr.dtype), plan);
     if (s != KM_OK) return s;
     for (const km_plan_step& st : plan.steps)
         if (!launchable(st)) return KM_EUNSUPPORTED;
@@ -631,7 +631,7 @@ static km_status tune(const Problem& pr, const Options& opt, hipStream_t stream,
     for (int i = 0; i < N; ++i) fmax = (int64_t)pr.P[i] * pr.Q[i] > fmax ? (int64_t)pr.P[i] * pr.Q[i] : fmax;
 
     Plan deflt;
-    km_status s = make_plan(pr, opt, g_variants, g_num_variants, GEN_THREADS, GEN_TS, generic_lds(pr.dtype), deflt);
+    km_status s = make_plan(pr, opt, g_variants, g_num_variants, generic_kernel(pr.dtype), deflt);
     if (s != KM_OK) return s;
 
     TuneScratch sc;
@@ -665,8 +665,7 @@ static km_status tune(const Problem& pr, const Options& opt, hipStream_t stream,
             float group_best = -1.f;
             Choice group_pick;
             for (const Choice& ch : cands) {
-                const km_plan_step st = build_step(pr, opt, g_variants, r, nf, ch, width, GEN_THREADS, GEN_TS,
-                                                   generic_lds(pr.dtype));
+                const km_plan_step st = build_step(pr, opt, g_variants, r, nf, ch, width, generic_kernel(pr.dtype));
                 if (!launchable(st)) continue;
                 auto body = [&]() { return launch_step(pr, st, sc.a, sc.b, F.data(), stream) == hipSuccess; };
                 const float once = time_body(sc, stream, 1, body);       // also the warm-up
@@ -683,7 +682,7 @@ static km_status tune(const Problem& pr, const Options& opt, hipStream_t stream,
         if (best[r] < 0) return KM_EUNSUPPORTED;
     }
     Plan tuned;
-    s = finish_plan(pr, opt, g_variants, take, pick, width, GEN_THREADS, GEN_TS, generic_lds(pr.dtype), tuned);
+    s = finish_plan(pr, opt, g_variants, take, pick, width, generic_kernel(pr.dtype), tuned);
     if (s != KM_OK) return s;
 
     // Launches timed alone can rank differently than in sequence: keep the measured plan only if the

@@ -134,6 +134,12 @@ inline int64_t store_column(int64_t k_in, int64_t p_group, int64_t tile_k, int64
 }
 
 // A compiled instance chosen for one group of factors, with the slices per tile it will run with.
+// What the planner needs to know of the generic kernel: a workgroup of `threads` work-items takes
+// `tile_slices` slices and `tile_cols` factor columns at a time.
+struct GenericKernel {
+    int threads, tile_slices, tile_cols, lds_bytes;
+};
+
 struct Choice {
     const Variant* var = nullptr;
     int tile_slices = 0;
@@ -380,7 +386,7 @@ inline bool pair_order_fits(int64_t num_tiles, int64_t tpw)
 // One launch of the plan for factors [r - nf, r - 1] with the given choice (var == nullptr: generic).
 inline km_plan_step build_step(const Problem& pr, const Options& opt, const Variant* table, int r, int nf,
                                const Choice& ch, const std::vector<int64_t>& width,
-                               int generic_threads, int generic_tile_slices, int generic_lds)
+                               const GenericKernel& gen)
 {
     const int f = r - 1;
     km_plan_step st = {};
@@ -419,13 +425,14 @@ inline km_plan_step build_step(const Problem& pr, const Options& opt, const Vari
         st.kernel = KM_KERNEL_GENERIC;
         st.variant = -1;
         st.tile_rows = 1;
-        st.tile_slices = generic_tile_slices;
-        st.block = generic_threads;
-        st.lds_bytes = generic_lds;
+        st.tile_slices = gen.tile_slices;
+        st.block = gen.threads;
+        st.lds_bytes = gen.lds_bytes;
         const int64_t S = st.k_in / pr.P[f];
-        st.grid = (pr.M * S + generic_tile_slices - 1) / generic_tile_slices;   // tiles may span rows
-        // the generic kernel strides over its tiles, so its grid can stay below the launch limit
-        const int64_t most = ((int64_t)1 << 32) / generic_threads - 1;
+        // one workgroup per (tile of slices, group of factor columns); tiles may span rows
+        st.grid = ((pr.M * S + gen.tile_slices - 1) / gen.tile_slices) * ((pr.Q[f] + gen.tile_cols - 1) / gen.tile_cols);
+        // the generic kernel strides over its work, so its grid can stay below the launch limit
+        const int64_t most = ((int64_t)1 << 32) / gen.threads - 1;
         if (st.grid > most) st.grid = most;
     }
     return st;
@@ -443,13 +450,13 @@ inline void row_widths(const Problem& pr, std::vector<int64_t>& width)
 inline km_status finish_plan(const Problem& pr, const Options& opt, const Variant* table,
                              const std::vector<int>& take, const std::vector<Choice>& pick,
                              const std::vector<int64_t>& width,
-                             int generic_threads, int generic_tile_slices, int generic_lds, Plan& plan)
+                             const GenericKernel& gen, Plan& plan)
 {
     plan = Plan();
     for (int r = pr.N; r >= 1; r -= take[r]) {
         const int nf = take[r];
         const int f = r - 1;
-        km_plan_step st = build_step(pr, opt, table, r, nf, pick[r], width, generic_threads, generic_tile_slices, generic_lds);
+        km_plan_step st = build_step(pr, opt, table, r, nf, pick[r], width, gen);
         // flops of the iterations this launch covers
         int64_t w = st.k_in;
         for (int i = f; i >= f - nf + 1; --i) {
@@ -483,7 +490,7 @@ inline km_status finish_plan(const Problem& pr, const Options& opt, const Varian
 }
 
 inline km_status make_plan(const Problem& pr, const Options& opt, const Variant* table, int count,
-                           int generic_threads, int generic_tile_slices, int generic_lds, Plan& plan)
+                           const GenericKernel& gen, Plan& plan)
 {
     const int N = pr.N;
     std::vector<int64_t> width;
@@ -501,7 +508,7 @@ inline km_status make_plan(const Problem& pr, const Options& opt, const Variant*
             if (best[r] < 0 || c <= best[r] * (1 + 1e-9)) { best[r] = c; take[r] = nf; pick[r] = ch; }
         }
     }
-    return finish_plan(pr, opt, table, take, pick, width, generic_threads, generic_tile_slices, generic_lds, plan);
+    return finish_plan(pr, opt, table, take, pick, width, gen, plan);
 }
 
 }  // namespace km
