@@ -253,6 +253,7 @@ static hipError_t launch_shuffle(const LaunchArgs& a)
     Y(MfmaF64x16, KM_F64, 16, 32, 1, 128, 4, 1)         \
     Y(MfmaF64x16, KM_F64, 64, 32, 1, 64, 4, 1)          \
     Y(MfmaF64x16, KM_F64, 32, 64, 1, 128, 4, 1)         \
+    Y(MfmaF64x16, KM_F64, 16, 16, 2, 32, 8, 1)          \
     Y(MfmaF64x16, KM_F64, 16, 16, 2, 16, 4, 1)          \
     Y(MfmaF64x16, KM_F64, 16, 16, 1, 256, 4, 1)         \
     Y(MfmaF64x16, KM_F64, 16, 16, 1, 64, 4, 1)          \
