@@ -317,19 +317,31 @@ void fused_multi_sliced_multiply(const T* __restrict__ Xg, T* __restrict__ Yg,
             if (v < nv) *reinterpret_cast<V*>(tile + multi_lds_index<PG0, PAD0>(v * VN)) = tmp[i];
         }
     } else {
-        // rows that are not 16-byte aligned: 4- or 8-byte loads, eight in flight per thread
-        constexpr int UN = 8;
-        for (int base = 0; base < valid; base += UN * NT) {
-            T tmp[UN];
+        // Tiles that do not start on a 16-byte boundary (rows of odd length): 16-byte loads from the
+        // boundary below the tile, so the first and the last vector may hold up to VN - 1 elements of
+        // the neighbouring tiles, which are dropped.  Such a vector never leaves X: X itself starts on
+        // a 16-byte boundary, and a 16-byte unit that holds one element of X lies in the same page.
+        const int mis = (int)((reinterpret_cast<uintptr_t>(src) / sizeof(T)) % VN);
+        const V* vsrc = reinterpret_cast<const V*>(src - mis);
+        const int nv = (valid + mis + VN - 1) / VN;
+        constexpr int UN = 4;
+        for (int base = 0; base < nv; base += UN * NT) {
+            V tmp[UN];
 #pragma unroll
             for (int i = 0; i < UN; ++i) {
-                const int e = base + tid + i * NT;
-                if (e < valid) tmp[i] = stream_load(&src[e]);
+                const int v = base + tid + i * NT;
+                if (v < nv) tmp[i] = stream_load(&vsrc[v]);
             }
 #pragma unroll
             for (int i = 0; i < UN; ++i) {
-                const int e = base + tid + i * NT;
-                if (e < valid) tile[multi_lds_index<PG0, PAD0>(e)] = tmp[i];
+                const int v = base + tid + i * NT;
+                if (v < nv) {
+#pragma unroll
+                    for (int k = 0; k < VN; ++k) {
+                        const int e = v * VN + k - mis;
+                        if (e >= 0 && e < valid) tile[multi_lds_index<PG0, PAD0>(e)] = tmp[i][k];
+                    }
+                }
             }
         }
     }

@@ -26,6 +26,7 @@ struct Variant {
     float slowdown;    // measured cost relative to an HBM-bound launch of the same bytes (planner weight)
     const char* name;
     int lds_per_slice; // flexible instances: LDS bytes per slice of the tile (lds_bytes is the maximum)
+    int thread_elems;  // flexible instances: contiguous elements of a tile that one thread multiplies first
 };
 
 // LDS a launch of the instance asks for when its tiles hold `tile_slices` slices.
@@ -153,10 +154,13 @@ struct Choice {
 // contiguous in memory, so several of them pass through the stages as one long tile): as many as
 // fit 48 KB of LDS (three and more workgroups per compute unit, see find_variant), within the
 // instance's limit, leaving at least 512 tiles when there are that many rows.
-inline int whole_rows_per_tile(const Variant& c, int64_t s_row, int64_t M)
+inline int whole_rows_per_tile(const Variant& c, int64_t s_row, int64_t M, int64_t row_bytes)
 {
     if (!c.flexible || s_row > c.tile_slices / 2 || M < 1024) return 1;   // few rows: one workgroup each
     if (c.P != c.Q) return 1;       // the output rows are collected in the tile's own LDS: same size needed
+    // rows of 8 KB that do not start on 16-byte boundaries are tiles of their own: the joined rows
+    // would be stored element by element (1024 rows of 3^7: one row per tile 0.014 ms, two 0.018 ms)
+    if (row_bytes >= 8192 && row_bytes % 16 != 0) return 1;
     int64_t most = c.tile_slices / s_row;
     if (c.lds_per_slice > 0) {
         const int64_t fit = (48 * 1024) / c.lds_per_slice / s_row;
@@ -229,7 +233,7 @@ inline void enumerate_choices(const Variant* table, int count, const Problem& pr
         if (c.P != pr.P[f] || c.Q != pr.Q[f]) continue;
         if (c.rows_per_tile > 1 && s_row != c.tile_slices) continue;      // tiles of several rows hold whole rows
         tile_lengths(c, s_row, lens, 5);
-        const int rows = whole_rows_per_tile(c, s_row, pr.M);
+        const int rows = whole_rows_per_tile(c, s_row, pr.M, s_row * pg * (int64_t)pr.esize);
         if (rows > 1) {                                   // whole rows, several per tile, and half as many
             for (int r = rows; r >= 2 && r >= rows / 2; r = (r == rows && rows / 2 >= 2) ? rows / 2 : 1) {
                 Choice ch;
@@ -304,25 +308,37 @@ inline Choice find_variant(const Variant* table, int count, const Problem& pr, i
             // 1296), then tiles of at most 48 KB of LDS (three and more workgroups per compute unit are
             // 10-30 % faster than two) unless that would cut runs that are not whole lines below 256
             // bytes (6^6: 288-byte runs in 62 KB tiles are 50 % faster than 96-byte runs in 21 KB
-            // tiles), then the longest tile.
+            // tiles; rows of odd length, where no run is ever aligned, from 128 bytes: 5^8 with 500-byte
+            // runs in 62 KB tiles is 34 % faster than with 100-byte runs in 12 KB tiles), then the
+            // longest tile.
             const int64_t lim = s_row < c.tile_slices ? s_row : c.tile_slices;
             const int64_t fit = c.lds_per_slice > 0 ? (48 * 1024) / c.lds_per_slice : lim;
             const int64_t row_bytes = s_row * (int64_t)pr.esize;
             const bool alignable = (row_bytes & -row_bytes) >= 32;      // some tile length gives 32-byte aligned runs
             int64_t best_key[2] = {-1, -1};
+            int best_tier = 0;
             for (int64_t d = lim; d >= 1; --d) {
                 if (s_row % d) continue;
                 const int64_t run = d * (int64_t)pr.esize;
                 int64_t align = run & -run;                          // largest power of two dividing the run
                 if (align > 128) align = 128;
-                const bool small_enough = d <= fit && (align >= 128 || run >= 256 || !alignable);
+                const bool small_enough = d <= fit && (align >= 128 || run >= 256 || (!alignable && run >= 128));
                 const int64_t key = (align * 2 + (small_enough ? 1 : 0)) * (lim + 1) + d;
                 if (key > best_key[0]) { best_key[0] = key; cand[0] = (int)d; }
-                if (pr.M * (s_row / d) >= enough && key > best_key[1]) { best_key[1] = key; cand[1] = (int)d; }
+                // ... that leaves enough workgroups: 512 with at least 16 busy threads, else 96 with at
+                // least 4.  A thread takes thread_elems contiguous elements, so short tiles only
+                // multiply the wavefronts that run the same instructions for a few lanes (20 rows of
+                // 5^6, 125 elements per thread: one-slice tiles 0.037 ms, 5 or 25 slices 0.018 ms).
+                const int64_t wgs = pr.M * (s_row / d);
+                const int64_t busy = c.thread_elems > 0 ? d * pg / c.thread_elems : d;     // threads with work
+                const int tier = (wgs >= enough && (busy >= 16 || d == lim)) ? 2 : (wgs >= 96 && (busy >= 4 || d == lim)) ? 1 : 0;
+                if (tier > 0 && (tier > best_tier || (tier == best_tier && key > best_key[1]))) {
+                    best_tier = tier; best_key[1] = key; cand[1] = (int)d;
+                }
             }
             if (opt.prefer_tile > 0 && opt.prefer_tile <= c.tile_slices && s_row % opt.prefer_tile == 0) cand[2] = opt.prefer_tile;
             // rows much shorter than the tile: whole rows, several per tile
-            rows = whole_rows_per_tile(c, s_row, pr.M);
+            rows = whole_rows_per_tile(c, s_row, pr.M, s_row * pg * (int64_t)pr.esize);
             if (rows > 1) { cand[0] = (int)s_row; cand[1] = cand[2] = 0; }
         }
         for (int k = 0; k < 3; ++k) {
@@ -343,10 +359,13 @@ inline Choice find_variant(const Variant* table, int count, const Problem& pr, i
             const int64_t tile_bytes = (int64_t)ch.tile_slices * ch.tile_rows * pg * (int64_t)pr.esize;
             if (!first_big.var && ch.grid >= enough && tile_bytes >= 1024) first_big = ch;
             if (!first_tiny.var && ch.grid >= enough) first_tiny = ch;
-            // among small launches prefer output runs of at least 32 bytes over more workgroups
-            const bool long_run = (int64_t)ch.tile_slices * (int64_t)pr.esize >= 32;
-            const bool most_long = most.var && (int64_t)most.tile_slices * (int64_t)pr.esize >= 32;
-            if (!most.var || (long_run && !most_long) || (long_run == most_long && ch.grid > most.grid)) most = ch;
+            // among small launches: at least 96 workgroups first (16 rows of 10^4 in 16 tiles of 100
+            // slices are twice as slow as in 400 tiles of 4), then output runs of at least 32 bytes,
+            // then more workgroups
+            auto rank = [&](const Choice& x) {
+                return (x.grid >= 96 ? 2 : 0) + ((int64_t)x.tile_slices * (int64_t)pr.esize >= 32 ? 1 : 0);
+            };
+            if (!most.var || rank(ch) > rank(most) || (rank(ch) == rank(most) && ch.grid > most.grid)) most = ch;
             int64_t sc = 0;
             if (opt.prefer_tile && ch.tile_slices == opt.prefer_tile) sc += 2;
             if (opt.prefer_threads && c.threads == opt.prefer_threads) sc += 1;

@@ -318,6 +318,8 @@ EVERY_INSTANCE = [
     ("float32", 3, [(2, 4)] * 6), ("float32", 3, [(4, 2)] * 6), ("float32", 3, [(4, 8)] * 4), ("float32", 3, [(8, 4)] * 5),
     ("float64", 3, [(2, 4)] * 6), ("float64", 3, [(4, 2)] * 6), ("float64", 3, [(4, 8)] * 4), ("float64", 3, [(8, 4)] * 4),
     ("float32", 2, [(2, 4)] * 2), ("float32", 2, [(4, 2)]), ("float64", 2, [(4, 8)]), ("float32", 2, [(8, 4)] * 2),
+    # six 2x2 factors in one launch
+    ("float32", 2, [(2, 2)] * 6), ("float64", 2, [(2, 2)] * 6),
 ]
 
 
