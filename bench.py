@@ -154,6 +154,18 @@ def main():
         torch.cuda.synchronize()
     per_launch_ms, ncalls = km.mean_profile()
     km.set_option(km.KM_OPT_PROFILE, 0)
+    # a further, untimed pass with the clock probe on a second stream: the shader clock the chip
+    # sustains under this load (the matrix cores' published peak is quoted at the maximum clock)
+    ticks = torch.zeros(2, dtype=torch.int64, device=dev)
+    probe_stream = torch.cuda.Stream()
+    probe_us = int(min(max(0.8 * ms_total * 1e3, 50.0), 1e6))
+    torch.cuda.synchronize()
+    km.clock_probe(ticks, probe_us, probe_stream)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    tk = ticks.tolist()
+    shader_mhz = round(100.0 * tk[0] / tk[1], 1) if tk[1] > 0 else None
     ms_per_step = ms_total / args.steps
     gflops = flops / (ms_per_step * 1e-3) / 1e9
 
@@ -206,6 +218,7 @@ def main():
                    "planned_bytes": planned_bytes, "flops": flops,
                    "end_to_end_gbs": round(planned_bytes / (ms_per_step * 1e-3) / 1e9, 1),
                    "wall_ms_per_step": round(wall * 1e3 / args.steps, 4),
+                   "shader_clock_mhz_under_load": shader_mhz,
                    "launch_events_in_timed_region": not args.separate_profile,
                    "steps_replayed_from_one_graph": bool(args.graph),
                    "autotuned": ({"kept_ms": round(tuned[0], 4), "cost_model_ms": round(tuned[1], 4)}

@@ -174,6 +174,16 @@ km_status kronmatmul_last_profile(float* ms, int cap, int* nsteps);
  * calls must have had the same number of launches, else KM_EINVAL.  *ncalls receives their count. */
 km_status kronmatmul_mean_profile(float* ms, int cap, int* nsteps, int* ncalls);
 
+/* Measurement aid: enqueues on `stream` a one-wavefront kernel that sleeps for about `micros`
+ * microseconds (1 to 1,000,000) and writes to `ticks` (device memory, two 64-bit unsigned integers,
+ * 8-byte aligned) how far the shader clock and the constant 100 MHz clock advanced meanwhile:
+ * shader MHz = 100 * ticks[0] / ticks[1].  Launched on a second stream next to Kron-Matmul calls
+ * it shows the clock the chip sustains under their load, which is what the matrix cores' peak
+ * (quoted at the maximum clock) has to be scaled by.  The kernel ends by itself after `micros`, or
+ * after a fixed number of sleep steps (a few seconds) whatever the clocks read.  Does not
+ * synchronise.  KM_EINVAL for a null or misaligned pointer or micros out of range. */
+km_status kronmatmul_clock_probe(unsigned long long* ticks, int micros, void* stream);
+
 /* Frees the library-managed workspaces and profiling events (synchronises the device). */
 km_status kronmatmul_release(void);
 

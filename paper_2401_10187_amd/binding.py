@@ -19,6 +19,7 @@ EXPORTS = [
     "kronmatmul_last_profile", "kronmatmul_mean_profile", "kronmatmul_release", "kronmatmul_status_string",
     "kronmatmul_kernel_name", "kronmatmul_tune",
     "kronmatmul_transposed_workspace_size", "kronmatmul_transposed", "kronmatmul_transposed_ws",
+    "kronmatmul_clock_probe",
 ]
 
 
@@ -82,6 +83,8 @@ def lib():
         L.kronmatmul_last_profile.argtypes = [ctypes.POINTER(ctypes.c_float), ci, ip]
         L.kronmatmul_mean_profile.restype = ci
         L.kronmatmul_mean_profile.argtypes = [ctypes.POINTER(ctypes.c_float), ci, ip, ip]
+        L.kronmatmul_clock_probe.restype = ci
+        L.kronmatmul_clock_probe.argtypes = [vp, ci, vp]
         L.kronmatmul_release.restype = ci
         L.kronmatmul_release.argtypes = []
         L.kronmatmul_status_string.restype = ctypes.c_char_p
@@ -197,6 +200,16 @@ def mean_profile():
     _check(lib().kronmatmul_mean_profile(ms, cap, ctypes.byref(cnt), ctypes.byref(calls)),
            "kronmatmul_mean_profile")
     return [float(ms[i]) for i in range(min(cnt.value, cap))], calls.value
+
+
+def clock_probe(ticks, micros, stream):
+    """Enqueue the clock probe on `stream` (a torch stream): `ticks` is a CUDA int64 tensor of two
+    elements that receives the shader-clock and 100 MHz-clock advances over about `micros` us."""
+    import torch
+    if ticks.dtype != torch.int64 or ticks.numel() < 2 or not ticks.is_cuda or not ticks.is_contiguous():
+        raise ValueError("ticks must be a contiguous CUDA int64 tensor of two elements")
+    _check(lib().kronmatmul_clock_probe(ctypes.c_void_p(ticks.data_ptr()), int(micros),
+                                        ctypes.c_void_p(stream.cuda_stream)), "kronmatmul_clock_probe")
 
 
 def release():

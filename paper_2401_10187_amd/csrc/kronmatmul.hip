@@ -553,6 +553,21 @@ static km_status run(const Problem& pr, const Plan& plan, const void* X, const v
 
 static bool aligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
 
+// Sleeps until the constant 100 MHz clock has advanced by `wall_ticks`, in steps of a few
+// microseconds and at most 2^21 of them, then reports how far both clocks moved.
+__global__ void clock_probe_kernel(unsigned long long* ticks, unsigned long long wall_ticks)
+{
+    const unsigned long long c0 = clock64(), w0 = wall_clock64();
+    for (int i = 0; i < (1 << 21); ++i) {
+        __builtin_amdgcn_s_sleep(127);
+        if (wall_clock64() - w0 >= wall_ticks) break;
+    }
+    if (threadIdx.x == 0) {
+        ticks[0] = clock64() - c0;
+        ticks[1] = wall_clock64() - w0;
+    }
+}
+
 static km_status check_pointers(const Problem& pr, const void* X, const void* const* F, void* Y)
 {
     if (!F) return KM_EINVAL;
@@ -1038,6 +1053,14 @@ km_status kronmatmul_last_profile(float* ms, int cap, int* nsteps)
 km_status kronmatmul_mean_profile(float* ms, int cap, int* nsteps, int* ncalls)
 {
     return profile_query(true, ms, cap, nsteps, ncalls);
+}
+
+km_status kronmatmul_clock_probe(unsigned long long* ticks, int micros, void* stream)
+{
+    if (!ticks || !aligned(ticks, 8) || micros < 1 || micros > 1000000) return KM_EINVAL;
+    hipLaunchKernelGGL(clock_probe_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream, ticks,
+                       (unsigned long long)micros * 100ull);
+    return hipGetLastError() == hipSuccess ? KM_OK : KM_ELAUNCH;
 }
 
 km_status kronmatmul_release(void)

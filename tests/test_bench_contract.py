@@ -40,6 +40,7 @@ def test_one_json_line_with_the_agreed_keys(workload, extra):
     for key in ("bound", "achieved", "peak", "unit", "frac", "traffic"):
         assert key in roof, key
     assert roof["bound"] in ("hbm", "mfma", "alu") and abs(roof["frac"] - roof["achieved"] / roof["peak"]) < 1e-3
+    assert 300.0 < out["config"]["shader_clock_mhz_under_load"] < 3000.0
     cpu = out["cpu_baseline"]
     for key in ("value", "unit", "cores", "kind", "sample"):
         assert key in cpu, key

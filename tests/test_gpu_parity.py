@@ -726,3 +726,20 @@ def test_tuned_plan_matches_the_oracle(dtype, M, shapes):
     Xi, Fi = kron_inputs.make_problem(M, shapes, dtype, x="int2", f="int1", seed=78)
     assert_close(run_gpu(Xi, Fi), Xi, Fi, exact=True)
     km.release()                                          # forget the measured plans
+
+
+def test_clock_probe_reports_both_clocks():
+    """The probe sleeps for the asked time and reports how far the shader clock and the constant
+    100 MHz clock advanced; next to a Kron-Matmul on another stream it neither disturbs the result
+    nor fails to end."""
+    ticks = torch.zeros(2, dtype=torch.int64, device="cuda")
+    side = torch.cuda.Stream()
+    X, Fs = kron_inputs.make_problem(64, [(8, 8)] * 4, "float32", seed=5)
+    torch.cuda.synchronize()
+    km.clock_probe(ticks, 300, side)
+    Y = run_gpu(X, Fs)
+    torch.cuda.synchronize()
+    shader, wall = ticks.tolist()
+    assert 300 * 100 <= wall < 3 * 300 * 100             # at least the asked time, and not much more
+    assert 300.0 < 100.0 * shader / wall < 3000.0        # MHz
+    assert_close(Y, X, Fs)

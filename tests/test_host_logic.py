@@ -318,6 +318,16 @@ def test_argument_errors_are_status_codes():
     assert _raw(4, [7, 11], [3, 5], bad, [bad, bad], bad, with_ws=True) == km.KM_ENOMEM
 
 
+def test_clock_probe_argument_errors():
+    """The probe checks its arguments before launching anything."""
+    probe = km.lib().kronmatmul_clock_probe
+    bad = 0x1000
+    assert probe(None, 100, None) == km.KM_EINVAL
+    assert probe(ctypes.c_void_p(bad + 4), 100, None) == km.KM_EINVAL        # not 8-byte aligned
+    assert probe(ctypes.c_void_p(bad), 0, None) == km.KM_EINVAL
+    assert probe(ctypes.c_void_p(bad), 1000001, None) == km.KM_EINVAL
+
+
 def test_transposed_form_needs_room_for_the_factor_copies():
     """The transposed-factor entry points copy the factors behind the plan's workspace: each copy on a
     256-byte boundary.  Their argument checks are those of the plain form."""
