@@ -213,6 +213,35 @@ def test_walk_lengths_follow_the_measured_rule():
     assert all(st["grid"] >= 512 for st in few)
 
 
+def test_tile_lengths_for_small_problems_and_odd_rows():
+    """Small problems keep several threads of a workgroup busy instead of cutting one-slice tiles to
+    reach more workgroups; rows of odd length take tiles whose output runs reach 128 bytes; long
+    rows that do not start on 16-byte boundaries are not joined into tiles of several rows."""
+    for M, P, n, dtype in ((20, 5, 6, "float32"), (100, 5, 5, "float64")):      # 125 or 25 elements per thread
+        steps = km.plan(M, [P] * n, [P] * n, dtype)
+        assert all(st["tile_slices"] * st["tile_rows"] >= 4 for st in steps if st["num_factors"] >= 2), (M, P, n, steps)
+        assert all(st["grid"] >= 96 for st in steps), (M, P, n, steps)
+    first = km.plan(1024, [5] * 8, [5] * 8, "float32")[0]
+    assert first["num_factors"] == 3 and first["tile_slices"] == 125
+    assert all(st["tile_rows"] == 1 for st in km.plan(1024, [3] * 7, [3] * 7, "float32"))
+    assert all(st["tile_rows"] == 2 for st in km.plan(1526, [4] * 6, [4] * 6, "float32"))
+    assert km.plan(1 << 20, [4] * 4, [4] * 4, "float32")[0]["tile_rows"] > 8
+
+
+def test_generic_launches_cover_slices_times_column_groups():
+    """The generic kernel's units of work are 128 slices by 32 factor columns."""
+    st = km.plan(10, [65], [20], "float32")[0]
+    assert st["kernel"] == km.KM_KERNEL_GENERIC
+    assert st["grid"] == -(-10 // 128) * -(-20 // 32)
+    old = km.get_option(km.KM_OPT_KERNELS)
+    try:
+        km.set_option(km.KM_OPT_KERNELS, 1)              # generic kernel only
+        st = km.plan(50, [64], [128], "float32")[0]
+    finally:
+        km.set_option(km.KM_OPT_KERNELS, old)
+    assert st["kernel"] == km.KM_KERNEL_GENERIC and st["grid"] == -(-50 // 128) * (128 // 32)
+
+
 def test_host_entry_points_are_thread_safe():
     """Planning from several threads at once (the plan cache and the options are shared state) gives
     what planning serially gives."""
