@@ -263,15 +263,28 @@ static hipError_t launch_shuffle(const LaunchArgs& a)
     Y(MfmaF64x16, KM_F64, 32, 32, 1, 32, 2, 1)          \
     Y(MfmaF64x16, KM_F64, 64, 64, 1, 64, 8, 2)          \
     Y(MfmaF64x16, KM_F64, 64, 64, 1, 64, 4, 1)          \
+    W(float, KM_F32, 2, 2, 4, 4, 4, 4, 256)             \
+    W(float, KM_F32, 2, 2, 4, 4, 3, 8, 256)             \
+    W(float, KM_F32, 2, 2, 4, 3, 3, 16, 256)            \
     W(float, KM_F32, 2, 2, 3, 3, 3, 32, 256)            \
+    W(float, KM_F32, 2, 2, 4, 4, 0, 64, 256)            \
+    W(float, KM_F32, 2, 2, 4, 3, 0, 128, 256)           \
     W(float, KM_F32, 2, 2, 3, 3, 0, 256, 256)           \
+    W(float, KM_F32, 2, 2, 3, 2, 0, 512, 256)           \
+    W(float, KM_F32, 2, 2, 4, 0, 0, 1024, 256)          \
     W(float, KM_F32, 2, 2, 3, 0, 0, 2048, 256)          \
     W(float, KM_F32, 2, 2, 2, 0, 0, 4096, 256)          \
     W(float, KM_F32, 2, 2, 1, 0, 0, 8192, 256)          \
+    W(float, KM_F32, 4, 4, 3, 2, 2, 1, 256)             \
+    W(float, KM_F32, 4, 4, 2, 2, 2, 4, 256)             \
+    W(float, KM_F32, 4, 4, 2, 2, 1, 16, 256)            \
     W(float, KM_F32, 4, 4, 2, 2, 0, 64, 256)            \
     W(float, KM_F32, 4, 4, 2, 1, 0, 256, 256)           \
     W(float, KM_F32, 4, 4, 2, 0, 0, 1024, 256)          \
     W(float, KM_F32, 4, 4, 1, 0, 0, 4096, 256)          \
+    W(float, KM_F32, 3, 3, 3, 2, 2, 9, 256)             \
+    W(float, KM_F32, 3, 3, 2, 2, 2, 27, 256)            \
+    W(float, KM_F32, 3, 3, 2, 2, 1, 81, 256)            \
     W(float, KM_F32, 3, 3, 2, 2, 0, 81, 256)            \
     W(float, KM_F32, 3, 3, 2, 1, 0, 243, 256)           \
     W(float, KM_F32, 3, 3, 2, 0, 0, 729, 256)           \
@@ -283,16 +296,28 @@ static hipError_t launch_shuffle(const LaunchArgs& a)
     W(float, KM_F32, 6, 6, 1, 1, 1, 72, 256)            \
     W(float, KM_F32, 6, 6, 2, 0, 0, 432, 256)           \
     W(float, KM_F32, 6, 6, 1, 0, 0, 2592, 256)          \
+    W(double, KM_F64, 2, 2, 4, 4, 4, 2, 256)            \
+    W(double, KM_F64, 2, 2, 4, 4, 3, 4, 256)            \
+    W(double, KM_F64, 2, 2, 4, 3, 3, 8, 256)            \
     W(double, KM_F64, 2, 2, 3, 3, 3, 16, 256)           \
+    W(double, KM_F64, 2, 2, 4, 4, 0, 32, 256)           \
+    W(double, KM_F64, 2, 2, 4, 3, 0, 64, 256)           \
     W(double, KM_F64, 2, 2, 3, 3, 0, 128, 256)          \
+    W(double, KM_F64, 2, 2, 3, 2, 0, 256, 256)          \
+    W(double, KM_F64, 2, 2, 4, 0, 0, 512, 256)          \
     W(double, KM_F64, 2, 2, 3, 0, 0, 1024, 256)         \
     W(double, KM_F64, 2, 2, 1, 0, 0, 4096, 256)         \
+    W(double, KM_F64, 4, 4, 2, 2, 2, 2, 256)            \
+    W(double, KM_F64, 4, 4, 2, 2, 1, 8, 256)            \
     W(double, KM_F64, 4, 4, 2, 2, 0, 32, 256)           \
     W(double, KM_F64, 4, 4, 2, 0, 0, 512, 256)          \
     W(double, KM_F64, 4, 4, 1, 0, 0, 2048, 256)         \
     W(double, KM_F64, 8, 8, 1, 1, 1, 16, 256)           \
     W(double, KM_F64, 8, 8, 1, 1, 0, 128, 256)          \
     W(double, KM_F64, 8, 8, 1, 0, 0, 1024, 256)         \
+    W(double, KM_F64, 3, 3, 3, 2, 2, 3, 256)            \
+    W(double, KM_F64, 3, 3, 2, 2, 2, 9, 256)            \
+    W(double, KM_F64, 3, 3, 2, 2, 1, 27, 256)           \
     W(double, KM_F64, 3, 3, 2, 2, 0, 81, 256)           \
     W(double, KM_F64, 3, 3, 2, 1, 0, 243, 256)          \
     W(double, KM_F64, 3, 3, 2, 0, 0, 729, 256)          \
@@ -357,7 +382,8 @@ static hipError_t launch_shuffle(const LaunchArgs& a)
     {KM_KERNEL_MFMA, KM_F32, P, 32, 2, ST, NW * 64, MfmaPairShape<P, ST, NW, PD>::LDS_BYTES, 1, 2, 0, 1.0f, "mfma-pair"},
 #define KM_MULTI_ROW(T, DT, P, Q, G0, G1, G2, ST, NT) \
     {KM_KERNEL_FUSED, DT, P, Q, G0 + G1 + G2, ST, NT, MultiShape<T, P, Q, G0, G1, G2, ST, NT>::LDS_BYTES, 1, 0, 1, \
-     (G0 == 1 && P < 8) ? 1.6f : 1.0f,                   /* one tiny factor per LDS pass is instruction-bound */ \
+     (G0 == 1 && P < 8) ? 1.6f                           /* one tiny factor per LDS pass is instruction-bound */ \
+     : (P == 3 && G0 + G1 + G2 >= 5) ? 1.6f : 1.0f,      /* 3^5 and more elements per slice: long runs need tiles that leave two workgroups per compute unit (3^11: 1.85x slower per byte) */ \
      "fused-multi", MultiShape<T, P, Q, G0, G1, G2, ST, NT>::LDS_PER_SLICE, (int)ipow(P, G0)},
 #define KM_ROWS_ROW(P, ST, NW) \
     {KM_KERNEL_MFMA, KM_F32, P, 32, 2, 1, NW * 64, 0, ST, 2, 0, 1.0f, "mfma-pair-rows"},

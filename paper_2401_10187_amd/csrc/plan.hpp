@@ -79,7 +79,7 @@ struct Plan {
 
 struct Options {
     int kernels = 0x7;    // bit mask of km_kernel families
-    int max_fuse = 9;
+    int max_fuse = 12;
     int prefer_tile = 0;      // tuning: choose instances with this tile_slices when one fits
     int prefer_threads = 0;   // tuning: ... with this workgroup size
     int tiles_per_wg = 0;     // tuning: tiles per workgroup of persistent instances (0 = automatic)
@@ -391,6 +391,9 @@ inline double launch_cost(const Problem& pr, int64_t k_in, int64_t k_out, const 
         slow = run >= 128 ? 1.0 : (run >= 64 ? 1.25 : (run >= 32 ? 2.5 : 4.0));
         slow *= ch.var->slowdown;
     }
+    // fewer workgroups than compute units: the launch streams at a matching fraction of the chip's
+    // rate (one row of 4^9: seven factors in 16 workgroups take 0.017 ms, four in 256 take 0.005)
+    if (ch.var && ch.grid < 256) slow *= 256.0 / (double)(ch.grid < 1 ? 1 : ch.grid);
     return bytes * slow + 2.5e7;                         // ~5 us of launch latency at 5 TB/s
 }
 

@@ -320,7 +320,20 @@ EVERY_INSTANCE = [
     ("float32", 2, [(2, 4)] * 2), ("float32", 2, [(4, 2)]), ("float64", 2, [(4, 8)]), ("float32", 2, [(8, 4)] * 2),
     # six 2x2 factors in one launch
     ("float32", 2, [(2, 2)] * 6), ("float64", 2, [(2, 2)] * 6),
+    # whole short rows in one launch: up to twelve 2x2, seven 3x3 or 4x4 factors
+    ("float32", 3, [(2, 2)] * 12), ("float32", 3, [(2, 2)] * 11), ("float32", 3, [(2, 2)] * 10), ("float32", 3, [(2, 2)] * 8),
+    ("float32", 3, [(2, 2)] * 7), ("float32", 3, [(2, 2)] * 5), ("float32", 3, [(2, 2)] * 4),
+    ("float64", 3, [(2, 2)] * 12), ("float64", 3, [(2, 2)] * 11), ("float64", 3, [(2, 2)] * 10), ("float64", 3, [(2, 2)] * 8),
+    ("float64", 3, [(2, 2)] * 7), ("float64", 3, [(2, 2)] * 5), ("float64", 3, [(2, 2)] * 4),
+    ("float32", 3, [(4, 4)] * 7), ("float32", 3, [(4, 4)] * 6), ("float32", 3, [(4, 4)] * 5),
+    ("float64", 3, [(4, 4)] * 6), ("float64", 3, [(4, 4)] * 5),
+    ("float32", 3, [(3, 3)] * 7), ("float32", 3, [(3, 3)] * 6), ("float32", 3, [(3, 3)] * 5),
+    ("float64", 3, [(3, 3)] * 7), ("float64", 3, [(3, 3)] * 6), ("float64", 3, [(3, 3)] * 5),
+    # one launch for a single short row, and two shapes whose groupings name the remaining instances
+    ("float32", 1, [(4, 4)] * 7), ("float32", 1, [(5, 5)] * 3), ("float32", 1, [(6, 6)] * 3), ("float64", 1, [(6, 6)] * 3),
+    ("float64", 1, [(6, 6)] * 2), ("float32", 1, [(9, 9)] * 3), ("float32", 64, [(8, 8)] * 4), ("float64", 64, [(32, 32)] * 3),
 ]
+FUSE_LIMITS = (12, 11, 10, 9, 8, 7, 6, 5, 4, 3, 2, 1)
 
 
 def test_every_instance_is_reached_by_some_shape_of_the_list():
@@ -330,7 +343,7 @@ def test_every_instance_is_reached_by_some_shape_of_the_list():
     for dtype, M, shapes in EVERY_INSTANCE:
         P, Q = [s[0] for s in shapes], [s[1] for s in shapes]
         for k in range(n):
-            for fuse in (9, 4, 3, 2, 1):
+            for fuse in FUSE_LIMITS:
                 with options(instance=k + 1, max_fuse=fuse, kernels=15):
                     if any(st["variant"] == k for st in km.plan(M, P, Q, dtype)):
                         reached.add(k)
@@ -348,7 +361,7 @@ def test_every_compiled_instance_that_fits(dtype, M, shapes):
     Xi, Fi = kron_inputs.make_problem(M, shapes, dtype, x="int2", f="int1", seed=92)
     used = set()
     for k in range(km.get_option(km.KM_OPT_INSTANCE_COUNT)):
-        for fuse in (9, 4, 3, 2, 1):                     # the grouping must also ask for its number of factors
+        for fuse in FUSE_LIMITS:                         # the grouping must also ask for its number of factors
             with options(instance=k + 1, max_fuse=fuse, kernels=15):
                 if k in used or not any(st["variant"] == k for st in km.plan(M, P, Q, dtype)):
                     continue
