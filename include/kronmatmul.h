@@ -49,7 +49,9 @@ typedef enum {
     KM_KERNEL_GENERIC = 0,  /* one factor, any P and Q: LDS-tiled FMA kernel                       */
     KM_KERNEL_FUSED = 1,    /* up to 9 consecutive small factors, tile resident in LDS (section 4.2) */
     KM_KERNEL_MFMA = 2,     /* factors with P and Q multiples of 16: slice contraction on MFMA     */
-    KM_KERNEL_SHUFFLE = 3   /* one 8x8 fp32 factor, no LDS: P-reduction by wavefront lane exchanges */
+    KM_KERNEL_SHUFFLE = 3,  /* one 8x8 fp32 factor, no LDS: P-reduction by wavefront lane exchanges */
+    KM_KERNEL_ROWS = 4      /* every factor of a short row in one launch, any shapes: the row and its
+                               intermediates stay in LDS (section 4.2's fusion with the row as tile) */
 } km_kernel;
 
 /* Buffers a plan step reads or writes. */
@@ -145,7 +147,7 @@ km_status kronmatmul_cost(int M, int N, const int* P, const int* Q, km_dtype dty
                           double* flops, double* planned_bytes);
 
 /* Options.  KM_OPT_KERNELS: bit mask of km_kernel families the planner may use (bit k = family k;
- * the generic family is always allowed; default 7: the shuffle family is off because the LDS-tiled
+ * the generic family is always allowed; default 23: the shuffle family is off because the LDS-tiled
  * kernels measured faster).  KM_OPT_MAX_FUSE: upper limit on factors per launch (default 12).
  * KM_OPT_PROFILE: when 1, every launch is bracketed by HIP events on the caller's stream.
  * KM_OPT_PREFER_TILE / KM_OPT_PREFER_THREADS: tuning aids; when non-zero the planner prefers compiled
@@ -157,7 +159,8 @@ km_status kronmatmul_cost(int M, int N, const int* P, const int* Q, km_dtype dty
  * tiles (0), over tiles strided by the grid size (2), or strided inside a contiguous eighth of the
  * tiles per XCD (3; taken as 2 when tiles or grid do not split by 8).
  * KM_OPT_PREFER_INSTANCE: tuning aid; k > 0 makes the planner take compiled instance k - 1 (the
- * `variant` of a plan step) wherever it fits the shape (0 = automatic).
+ * `variant` of a plan step) wherever it fits the shape (0 = automatic); k = instance count + 1
+ * makes it take the whole-row kernel (KM_KERNEL_ROWS) whenever the rows fit LDS.
  * KM_OPT_INSTANCE_COUNT: read-only; the number of compiled instances. */
 typedef enum { KM_OPT_KERNELS = 0, KM_OPT_MAX_FUSE = 1, KM_OPT_PROFILE = 2, KM_OPT_PREFER_TILE = 3,
                KM_OPT_PREFER_THREADS = 4, KM_OPT_TILES_PER_WG = 5, KM_OPT_PAIR_INTERLEAVE = 6, KM_OPT_TILE_ORDER = 7,

@@ -8,6 +8,7 @@
 #include "../../include/kronmatmul.h"
 #include "plan.hpp"
 #include "generic_kernel.hpp"
+#include "row_kernel.hpp"
 #include "fused_kernel.hpp"
 #include "fused_multi_kernel.hpp"
 #include "mfma_kernel.hpp"
@@ -419,6 +420,36 @@ static hipError_t launch_generic(const LaunchArgs& a)
     return hipGetLastError();
 }
 
+template <typename T>
+static hipError_t launch_rows(const LaunchArgs& a)
+{
+    const km_plan_step& st = *a.st;
+    const Problem& pr = *a.pr;
+    const int n = st.num_factors;
+    if (st.first_factor != 0 || n != pr.N || n > ROW_MAXF) return hipErrorInvalidValue;
+    RowFactors fa{};
+    fa.n = n;
+    int64_t w = st.k_in, maxw = st.k_in, fel = 0;
+    for (int i = 0; i < n; ++i) {                        // order of application: last factor first
+        const int f = n - 1 - i;
+        fa.f[i] = a.factors[f];
+        fa.P[i] = pr.P[f];
+        fa.Q[i] = pr.Q[f];
+        if (w % pr.P[f]) return hipErrorInvalidValue;
+        const int64_t s_blocks = (w / pr.P[f] + ROW_SB - 1) / ROW_SB;
+        fa.magic[i] = ((1ull << 40) + (unsigned long long)s_blocks - 1) / (unsigned long long)s_blocks;
+        w = w / pr.P[f] * pr.Q[f];
+        if (w > maxw) maxw = w;
+        fel += (int64_t)pr.P[f] * pr.Q[f];
+    }
+    const int64_t need = row_lds_bytes(maxw, fel, (int)sizeof(T));
+    if (w != st.k_out || need > ROW_LDS_LIMIT || st.lds_bytes < need) return hipErrorInvalidValue;
+    if (st.grid < 1 || st.grid > pr.M) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((row_sliced_multiply<T>), dim3((unsigned)st.grid), dim3(ROW_THREADS), (size_t)st.lds_bytes, a.stream,
+                       (const T*)a.src, (T*)a.dst, fa, (int)st.k_in, (int)st.k_out, (int)maxw, pr.M);
+    return hipGetLastError();
+}
+
 // ---------------------------------------------------------------------------------------------
 // library state
 // ---------------------------------------------------------------------------------------------
@@ -440,7 +471,8 @@ static DeviceState g_dev[64];
 
 static GenericKernel generic_kernel(int dtype)
 {
-    return GenericKernel{GEN_THREADS, GEN_TS, GEN_TQ, dtype == KM_F32 ? gen_lds_bytes<float>() : gen_lds_bytes<double>()};
+    return GenericKernel{GEN_THREADS, GEN_TS, GEN_TQ, dtype == KM_F32 ? gen_lds_bytes<float>() : gen_lds_bytes<double>(),
+                         ROW_THREADS, ROW_LDS_LIMIT, ROW_MAXF};
 }
 
 // Plans are memoised: iterative callers repeat the same small problem thousands of times and the
@@ -527,6 +559,8 @@ static hipError_t launch_step(const Problem& pr, const km_plan_step& st, const v
     LaunchArgs a{src, dst, F, &pr, &st, stream};
     if (st.kernel == KM_KERNEL_GENERIC)
         return pr.dtype == KM_F32 ? launch_generic<float>(a) : launch_generic<double>(a);
+    if (st.kernel == KM_KERNEL_ROWS)
+        return pr.dtype == KM_F32 ? launch_rows<float>(a) : launch_rows<double>(a);
     if (st.variant < 0 || st.variant >= g_num_variants) return hipErrorInvalidValue;
     return g_launchers[st.variant](a);
 }
@@ -980,7 +1014,7 @@ km_status kronmatmul_set_option(km_option option, int value)
     std::lock_guard<std::mutex> lock(g_mutex);
     switch (option) {
         case KM_OPT_KERNELS:
-            if (value < 0 || value > 15) return KM_EINVAL;
+            if (value < 0 || value > 31) return KM_EINVAL;
             g_options.kernels = value | 1;
             return KM_OK;
         case KM_OPT_MAX_FUSE:
@@ -1008,7 +1042,7 @@ km_status kronmatmul_set_option(km_option option, int value)
             g_options.tile_order = value;
             return KM_OK;
         case KM_OPT_PREFER_INSTANCE:
-            if (value < 0 || value > g_num_variants) return KM_EINVAL;
+            if (value < 0 || value > g_num_variants + 1) return KM_EINVAL;
             g_options.prefer_instance = value;
             return KM_OK;
         case KM_OPT_INSTANCE_COUNT:
@@ -1124,6 +1158,7 @@ const char* kronmatmul_kernel_name(int kernel)
         case KM_KERNEL_FUSED: return "fused";
         case KM_KERNEL_MFMA: return "mfma";
         case KM_KERNEL_SHUFFLE: return "shuffle";
+        case KM_KERNEL_ROWS: return "rows";
     }
     return "unknown";
 }

@@ -78,7 +78,7 @@ struct Plan {
 };
 
 struct Options {
-    int kernels = 0x7;    // bit mask of km_kernel families
+    int kernels = 0x17;   // bit mask of km_kernel families
     int max_fuse = 12;
     int prefer_tile = 0;      // tuning: choose instances with this tile_slices when one fits
     int prefer_threads = 0;   // tuning: ... with this workgroup size
@@ -139,6 +139,9 @@ inline int64_t store_column(int64_t k_in, int64_t p_group, int64_t tile_k, int64
 // `tile_slices` slices and `tile_cols` factor columns at a time.
 struct GenericKernel {
     int threads, tile_slices, tile_cols, lds_bytes;
+    // the whole-row kernel: a workgroup of row_threads work-items applies up to row_max_factors
+    // factors to one row held in two LDS buffers of at most row_lds_limit bytes together
+    int row_threads, row_lds_limit, row_max_factors;
 };
 
 struct Choice {
@@ -530,7 +533,58 @@ inline km_status make_plan(const Problem& pr, const Options& opt, const Variant*
             if (best[r] < 0 || c <= best[r] * (1 + 1e-9)) { best[r] = c; take[r] = nf; pick[r] = ch; }
         }
     }
-    return finish_plan(pr, opt, table, take, pick, width, gen, plan);
+    km_status st = finish_plan(pr, opt, table, take, pick, width, gen, plan);
+    if (st != KM_OK) return st;
+
+    // Every factor in one launch with the row resident in LDS, whatever the factor shapes, when
+    // that is cheaper: plain FMA code run by one workgroup per row, so only where the launches saved
+    // outweigh it.  Measured time per row of one workgroup: about 2 us plus 0.4 us per factor of
+    // fixed cost, plus 35 ns (fp64: 55 ns) per multiply-add of each of its threads (with few rows a
+    // compute unit holds one wavefront per SIMD, so every latency is exposed); rows run side by
+    // side as far as LDS and 8 workgroups per compute unit allow.
+    const bool force_rows = opt.prefer_instance == count + 1;      // tuning aid: whenever it fits
+    if ((opt.kernels >> KM_KERNEL_ROWS & 1) && N >= 2 && N <= gen.row_max_factors && N <= opt.max_fuse &&
+        (plan.steps.size() > 1 || force_rows)) {
+        int64_t maxw = 0;
+        double macs = 0;
+        for (int r = 0; r <= N; ++r) maxw = width[r] > maxw ? width[r] : maxw;
+        for (int r = 1; r <= N; ++r) macs += (double)width[r] * (double)pr.Q[r - 1];
+        int64_t fel = 0;
+        for (int i = 0; i < N; ++i) fel += (int64_t)pr.P[i] * pr.Q[i];
+        // two row buffers (one word in 33 skipped, see row_kernel.hpp) and every factor
+        const int64_t lds = (2 * (maxw + (maxw >> 5) + 1) + fel) * (int64_t)pr.esize;
+        if (lds <= gen.row_lds_limit) {
+            const int64_t per_cu = 160 * 1024 / (lds < 20 * 1024 ? 20 * 1024 : lds);
+            const int64_t side_by_side = 256 * per_cu;
+            const double rounds = (double)((pr.M + side_by_side - 1) / side_by_side);
+            const double seconds = rounds * (2.0e-6 + 0.4e-6 * N + macs / gen.row_threads * (pr.esize == 4 ? 35e-9 : 55e-9));
+            const double bytes = (double)pr.M * ((double)width[N] + (double)width[0]) * (double)pr.esize;
+            double c = seconds * 5e12;
+            if (c < 2 * bytes) c = 2 * bytes;
+            c += 2.5e7;
+            if (c < best[N] || force_rows) {
+                km_plan_step one{};
+                one.kernel = KM_KERNEL_ROWS;
+                one.variant = -1;
+                one.first_factor = 0;
+                one.num_factors = N;
+                one.tile_slices = 1;
+                one.tile_rows = 1;
+                one.k_in = width[N];
+                one.k_out = width[0];
+                one.src = KM_BUF_X;
+                one.dst = KM_BUF_Y;
+                one.grid = pr.M < 65536 ? pr.M : 65536;     // the kernel strides over the rows
+                one.block = gen.row_threads;
+                one.lds_bytes = (int)lds;
+                plan.steps.assign(1, one);
+                plan.ws0_bytes = plan.ws1_bytes = 0;
+                plan.bytes = bytes;
+                for (int i = 0; i < N; ++i) plan.bytes += (double)pr.P[i] * pr.Q[i] * pr.esize;
+            }
+        }
+    }
+    return KM_OK;
 }
 
 }  // namespace km

@@ -644,11 +644,12 @@ def test_many_short_rows_share_a_tile(dtype, M, shapes):
     """Rows much shorter than a tile: several whole rows per tile (the T_M of section 4), the last
     tile ragged.  All rows are compared."""
     P, Q = [s[0] for s in shapes], [s[1] for s in shapes]
-    assert any(st["tile_rows"] > 1 for st in km.plan(M, P, Q, dtype))
-    X, Fs = kron_inputs.make_problem(M, shapes, dtype, seed=81)
-    assert_close(run_gpu(X, Fs), X, Fs)
-    Xi, Fi = kron_inputs.make_problem(M, shapes, dtype, x="int2", f="int1", seed=82)
-    assert_close(run_gpu(Xi, Fi, use_ws=True), Xi, Fi, exact=True)
+    with options(kernels=7):                             # the tiled families (not the whole-row kernel)
+        assert any(st["tile_rows"] > 1 for st in km.plan(M, P, Q, dtype))
+        X, Fs = kron_inputs.make_problem(M, shapes, dtype, seed=81)
+        assert_close(run_gpu(X, Fs), X, Fs)
+        Xi, Fi = kron_inputs.make_problem(M, shapes, dtype, x="int2", f="int1", seed=82)
+        assert_close(run_gpu(Xi, Fi, use_ws=True), Xi, Fi, exact=True)
 
 
 def test_more_rows_than_a_launch_has_workgroups():
@@ -756,3 +757,44 @@ def test_clock_probe_reports_both_clocks():
     assert 300 * 100 <= wall < 3 * 300 * 100             # at least the asked time, and not much more
     assert 300.0 < 100.0 * shader / wall < 3000.0        # MHz
     assert_close(Y, X, Fs)
+
+
+ROWS_CASES = [
+    ("float32", 5, [(3, 5), (5, 3), (7, 2), (2, 7)]),
+    ("float64", 5, [(3, 5), (5, 3), (7, 2), (2, 7)]),
+    ("float32", 1, [(5, 5), (5, 5), (5, 5), (2, 2)]),                 # Table 4, id 20
+    ("float64", 1, [(5, 5), (5, 5), (2, 2), (25, 25)]),               # Table 4, id 21
+    ("float32", 10, [(52, 50), (65, 20)]),                            # Table 4, id 6
+    ("float32", 7, [(2, 3)] * 8),                                     # eight factors, rows growing 256 -> 6561
+    ("float64", 3, [(9, 1), (4, 6), (1, 5)]),                         # one-column and one-row factors
+    ("float32", 70001, [(3, 2), (2, 3)]),                             # more rows than workgroups
+    ("float32", 33, [(32, 32), (64, 3)]),                             # slices a multiple of 32 words apart
+    ("float32", 4, [(1, 1), (6, 6), (6, 6)]),
+]
+
+
+@pytest.mark.parametrize("dtype,M,shapes", ROWS_CASES, ids=lambda v: str(v).replace(" ", ""))
+def test_whole_row_kernel_matches_the_oracle(dtype, M, shapes):
+    """Every factor in one launch with the row resident in LDS (any factor shapes): forced wherever
+    the row fits, against the oracle, integer inputs bit for bit."""
+    P, Q = [s[0] for s in shapes], [s[1] for s in shapes]
+    with options(instance=km.get_option(km.KM_OPT_INSTANCE_COUNT) + 1):
+        steps = km.plan(M, P, Q, dtype)
+        assert len(steps) == 1 and steps[0]["kernel"] == km.KM_KERNEL_ROWS and steps[0]["num_factors"] == len(shapes)
+        assert km.workspace_size(M, P, Q, dtype) == 0
+        X, Fs = kron_inputs.make_problem(M, shapes, dtype, seed=41)
+        assert_close(run_gpu(X, Fs), X, Fs)
+        Xi, Fi = kron_inputs.make_problem(M, shapes, dtype, x="int2", f="int1", seed=42)
+        assert_close(run_gpu(Xi, Fi, use_ws=True), Xi, Fi, exact=True)
+
+
+def test_whole_row_kernel_is_planned_for_small_mixed_shapes_only():
+    """Distinct small factors on a few rows take the one-launch kernel; rows that do not fit LDS,
+    more than eight factors and work-heavy rows do not."""
+    assert [st["kernel"] for st in km.plan(5, [3, 5, 7, 2], [5, 3, 2, 7], "float32")] == [km.KM_KERNEL_ROWS]
+    assert [st["kernel"] for st in km.plan(1, [5, 5, 5, 2], [5, 5, 5, 2], "float32")] == [km.KM_KERNEL_ROWS]
+    assert all(st["kernel"] != km.KM_KERNEL_ROWS for st in km.plan(16, [6] * 5, [6] * 5, "float32"))
+    assert all(st["kernel"] != km.KM_KERNEL_ROWS for st in km.plan(4, [30, 31, 32], [30, 31, 32], "float32"))
+    with options(instance=km.get_option(km.KM_OPT_INSTANCE_COUNT) + 1):
+        assert all(st["kernel"] != km.KM_KERNEL_ROWS for st in km.plan(4, [30, 31, 32], [30, 31, 32], "float32"))
+        assert all(st["kernel"] != km.KM_KERNEL_ROWS for st in km.plan(4, [2] * 9, [2] * 9, "float32"))

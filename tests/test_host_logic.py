@@ -342,9 +342,9 @@ def test_argument_errors_are_status_codes():
     assert _raw(0, [2, 3], [2, 3], None, [bad, bad], None) == km.KM_OK
     assert _raw(0, [2, 3], [2, 3], None, [bad, bad], None, with_ws=True) == km.KM_OK
     # a workspace that is too small is refused before any launch
-    # (two factors of different shapes always take two launches, hence an intermediate)
-    assert km.workspace_size(4, [7, 11], [3, 5], "float32") > 0
-    assert _raw(4, [7, 11], [3, 5], bad, [bad, bad], bad, with_ws=True) == km.KM_ENOMEM
+    # (two factors of different shapes, rows too long for the one-launch kernel: two launches, hence an intermediate)
+    assert km.workspace_size(4, [70, 110], [30, 50], "float32") > 0
+    assert _raw(4, [70, 110], [30, 50], bad, [bad, bad], bad, with_ws=True) == km.KM_ENOMEM
 
 
 def test_clock_probe_argument_errors():
