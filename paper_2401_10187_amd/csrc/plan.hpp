@@ -56,8 +56,11 @@ inline int64_t tiles_per_wg(int64_t num_tiles, int hint, int64_t factor_elems, i
     if (lds_bytes > 64 * 1024 && t < 4) t = 4;
     if (lds_bytes > 80 * 1024) t = 32;
     // two workgroups per compute unit at least; four when the instance is light (small factor, at most
-    // 64 KB of LDS): 1024 x 64x64^2 is 28 % faster with 1024 workgroups than with 512
-    const int64_t fewest = ((size_t)factor_elems * esize >= 64 * 1024 || lds_bytes > 64 * 1024) ? 512 : 1024;
+    // 64 KB of LDS): 1024 x 64x64^2 is 28 % faster with 1024 workgroups than with 512; but one per unit
+    // is enough when loading the factor costs a workgroup as much as a tile does (16 x 64x64^3 fp64:
+    // 256 workgroups walking 4 tiles each are 28 % faster than 1024 with one tile)
+    const bool heavy = (size_t)factor_elems * esize >= 64 * 1024 || lds_bytes > 64 * 1024;
+    const int64_t fewest = heavy ? 512 : (factor_elems >= tile_elems ? 256 : 1024);
     while (t > 1 && num_tiles / t < fewest) t /= 2;
     return t;
 }
