@@ -185,7 +185,10 @@ def main():
             k = k // P[i] * Q[i]
         key = (st["kernel"], st["variant"], st["k_in"], st["k_out"])
         launches.append(dict(key=key, ms=ms, bytes=nb, flops=fl,
-                             name="%s[%dx(%dx%d)]" % (km.kernel_name(st["kernel"]), nf, P[f0], Q[f0])))
+                             name=("%s[%dx(%dx%d)]" % (km.kernel_name(st["kernel"]), nf, P[f0], Q[f0])
+                                   if len(set(zip(P[f0:f0 + nf], Q[f0:f0 + nf]))) == 1 else
+                                   "%s[%s]" % (km.kernel_name(st["kernel"]),
+                                               ",".join("%dx%d" % pq for pq in zip(P[f0:f0 + nf], Q[f0:f0 + nf]))))))
     groups = {}
     for l in launches:
         g = groups.setdefault(l["key"], dict(ms=0.0, n=0, bytes=l["bytes"], flops=l["flops"], name=l["name"]))

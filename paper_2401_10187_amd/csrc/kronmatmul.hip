@@ -445,7 +445,12 @@ static hipError_t launch_rows(const LaunchArgs& a)
     const int64_t need = row_lds_bytes(maxw, fel, (int)sizeof(T));
     if (w != st.k_out || need > ROW_LDS_LIMIT || st.lds_bytes < need) return hipErrorInvalidValue;
     if (st.grid < 1 || st.grid > pr.M) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((row_sliced_multiply<T>), dim3((unsigned)st.grid), dim3(ROW_THREADS), (size_t)st.lds_bytes, a.stream,
+    if (st.block != ROW_THREADS_MANY && st.block != ROW_THREADS_FEW) return hipErrorInvalidValue;
+    auto kern = st.block == ROW_THREADS_FEW ? row_sliced_multiply<T, ROW_THREADS_FEW> : row_sliced_multiply<T, ROW_THREADS_MANY>;
+    static unsigned char lds_ok[2][64];
+    hipError_t e = allow_lds((const void*)kern, ROW_LDS_LIMIT, lds_ok[st.block == ROW_THREADS_FEW]);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, dim3((unsigned)st.grid), dim3((unsigned)st.block), (size_t)st.lds_bytes, a.stream,
                        (const T*)a.src, (T*)a.dst, fa, (int)st.k_in, (int)st.k_out, (int)maxw, pr.M);
     return hipGetLastError();
 }
@@ -472,7 +477,7 @@ static DeviceState g_dev[64];
 static GenericKernel generic_kernel(int dtype)
 {
     return GenericKernel{GEN_THREADS, GEN_TS, GEN_TQ, dtype == KM_F32 ? gen_lds_bytes<float>() : gen_lds_bytes<double>(),
-                         ROW_THREADS, ROW_LDS_LIMIT, ROW_MAXF};
+                         ROW_THREADS_MANY, ROW_THREADS_FEW, ROW_FEW_ROWS, ROW_LDS_LIMIT, ROW_MAXF};
 }
 
 // Plans are memoised: iterative callers repeat the same small problem thousands of times and the

@@ -142,9 +142,10 @@ inline int64_t store_column(int64_t k_in, int64_t p_group, int64_t tile_k, int64
 // `tile_slices` slices and `tile_cols` factor columns at a time.
 struct GenericKernel {
     int threads, tile_slices, tile_cols, lds_bytes;
-    // the whole-row kernel: a workgroup of row_threads work-items applies up to row_max_factors
-    // factors to one row held in two LDS buffers of at most row_lds_limit bytes together
-    int row_threads, row_lds_limit, row_max_factors;
+    // the whole-row kernel: a workgroup of row_threads_many work-items (row_threads_few when there
+    // are at most row_few_rows rows) applies up to row_max_factors factors to one row held, with the
+    // factors, in at most row_lds_limit bytes of LDS
+    int row_threads_many, row_threads_few, row_few_rows, row_lds_limit, row_max_factors;
 };
 
 struct Choice {
@@ -386,7 +387,7 @@ inline Choice find_variant(const Variant* table, int count, const Problem& pr, i
 
 // Estimated cost of one launch in "bytes moved at full speed": rows read and written, scaled up for
 // short output runs and for the generic kernel, plus a constant per launch.
-inline double launch_cost(const Problem& pr, int64_t k_in, int64_t k_out, const Choice& ch)
+inline double launch_cost(const Problem& pr, int64_t k_in, int64_t k_out, const Choice& ch, int generic_P = 0)
 {
     const double bytes = (double)pr.M * ((double)k_in + (double)k_out) * (double)pr.esize;
     double slow = 3.0;                                   // generic kernel
@@ -400,7 +401,12 @@ inline double launch_cost(const Problem& pr, int64_t k_in, int64_t k_out, const 
     // fewer workgroups than compute units: the launch streams at a matching fraction of the chip's
     // rate (one row of 4^9: seven factors in 16 workgroups take 0.017 ms, four in 256 take 0.005)
     if (ch.var && ch.grid < 256) slow *= 256.0 / (double)(ch.grid < 1 ? 1 : ch.grid);
-    return bytes * slow + 2.5e7;                         // ~5 us of launch latency at 5 TB/s
+    double fixed = 2.5e7;                                // ~5 us of launch latency at 5 TB/s
+    // the generic kernel walks the slice elements in chunks of 16, a barrier apart: a launch of it
+    // takes about 2 us + 0.7 us per chunk even when it moves next to nothing (measured: 5.5 us for
+    // P = 65, 4.8 us for P = 52 on ten rows)
+    if (!ch.var) fixed += 1.0e7 + 3.5e6 * (double)((generic_P + 15) / 16);
+    return bytes * slow + fixed;
 }
 
 // Tile order 1 hands tiles out in groups of 16 workgroups (8 XCDs x 2) that each take every other
@@ -532,7 +538,7 @@ inline km_status make_plan(const Problem& pr, const Options& opt, const Variant*
         for (int nf = 1; nf <= r && nf <= opt.max_fuse; ++nf) {
             const Choice ch = find_variant(table, count, pr, r - 1, nf, width[r], opt);
             if (nf > 1 && !ch.var) continue;             // only single factors fall back to the generic kernel
-            const double c = launch_cost(pr, width[r], width[r - nf], ch) + best[r - nf];
+            const double c = launch_cost(pr, width[r], width[r - nf], ch, pr.P[r - 1]) + best[r - nf];
             if (best[r] < 0 || c <= best[r] * (1 + 1e-9)) { best[r] = c; take[r] = nf; pick[r] = ch; }
         }
     }
@@ -542,9 +548,9 @@ inline km_status make_plan(const Problem& pr, const Options& opt, const Variant*
     // Every factor in one launch with the row resident in LDS, whatever the factor shapes, when
     // that is cheaper: plain FMA code run by one workgroup per row, so only where the launches saved
     // outweigh it.  Measured time per row of one workgroup: about 2 us plus 0.4 us per factor of
-    // fixed cost, plus 35 ns (fp64: 55 ns) per multiply-add of each of its threads (with few rows a
-    // compute unit holds one wavefront per SIMD, so every latency is exposed); rows run side by
-    // side as far as LDS and 8 workgroups per compute unit allow.
+    // fixed cost, plus 35 ns per multiply-add of each of its 256 threads, or 50 ns with the 1024
+    // threads taken when rows are few (fp64: 1.5 times that); rows run side by side as far as LDS
+    // and 2048 threads per compute unit allow.
     const bool force_rows = opt.prefer_instance == count + 1;      // tuning aid: whenever it fits
     if ((opt.kernels >> KM_KERNEL_ROWS & 1) && N >= 2 && N <= gen.row_max_factors && N <= opt.max_fuse &&
         (plan.steps.size() > 1 || force_rows)) {
@@ -557,10 +563,14 @@ inline km_status make_plan(const Problem& pr, const Options& opt, const Variant*
         // two row buffers (one word in 33 skipped, see row_kernel.hpp) and every factor
         const int64_t lds = (2 * (maxw + (maxw >> 5) + 1) + fel) * (int64_t)pr.esize;
         if (lds <= gen.row_lds_limit) {
-            const int64_t per_cu = 160 * 1024 / (lds < 20 * 1024 ? 20 * 1024 : lds);
+            const bool few = pr.M <= gen.row_few_rows;
+            const int threads = few ? gen.row_threads_few : gen.row_threads_many;
+            int64_t per_cu = 160 * 1024 / (lds < 20 * 1024 ? 20 * 1024 : lds);
+            if (per_cu > 2048 / threads) per_cu = 2048 / threads;
             const int64_t side_by_side = 256 * per_cu;
             const double rounds = (double)((pr.M + side_by_side - 1) / side_by_side);
-            const double seconds = rounds * (2.0e-6 + 0.4e-6 * N + macs / gen.row_threads * (pr.esize == 4 ? 35e-9 : 55e-9));
+            const double per_mac = (few ? 50e-9 : 35e-9) * (pr.esize == 4 ? 1.0 : 1.5);
+            const double seconds = rounds * (2.0e-6 + 0.4e-6 * N + macs / threads * per_mac);
             const double bytes = (double)pr.M * ((double)width[N] + (double)width[0]) * (double)pr.esize;
             double c = seconds * 5e12;
             if (c < 2 * bytes) c = 2 * bytes;
@@ -578,7 +588,7 @@ inline km_status make_plan(const Problem& pr, const Options& opt, const Variant*
                 one.src = KM_BUF_X;
                 one.dst = KM_BUF_Y;
                 one.grid = pr.M < 65536 ? pr.M : 65536;     // the kernel strides over the rows
-                one.block = gen.row_threads;
+                one.block = threads;
                 one.lds_bytes = (int)lds;
                 plan.steps.assign(1, one);
                 plan.ws0_bytes = plan.ws1_bytes = 0;

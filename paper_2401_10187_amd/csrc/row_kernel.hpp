@@ -18,10 +18,12 @@
 namespace km {
 
 constexpr int ROW_MAXF = 8;                // factors per launch
-constexpr int ROW_THREADS = 256;
+constexpr int ROW_THREADS_MANY = 256;      // threads per row when there are many rows (eight rows per compute unit)
+constexpr int ROW_THREADS_FEW = 1024;      // ... when there are few: sixteen wavefronts hide each other's latencies
+constexpr int ROW_FEW_ROWS = 512;          // "few": at most two rows per compute unit
 constexpr int ROW_SB = 2;                  // slices per thread
 constexpr int ROW_QB = 4;                  // factor columns per thread
-constexpr int ROW_LDS_LIMIT = 64 * 1024;   // row buffers and factor: two workgroups per compute unit still fit
+constexpr int ROW_LDS_LIMIT = 96 * 1024;   // row buffers and factors
 
 // Row buffers skip one word in 33, so that reads P words apart (one slice per lane) spread over the
 // banks also when P is a multiple of 32.
@@ -40,7 +42,7 @@ struct RowFactors {
     int n;
 };
 
-template <typename T>
+template <typename T, int ROW_THREADS>
 __global__ __launch_bounds__(ROW_THREADS)
 void row_sliced_multiply(const T* __restrict__ Xg, T* __restrict__ Yg, const RowFactors fa,
                          int k_in, int k_out, int max_width, int64_t M)

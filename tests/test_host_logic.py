@@ -217,10 +217,15 @@ def test_tile_lengths_for_small_problems_and_odd_rows():
     """Small problems keep several threads of a workgroup busy instead of cutting one-slice tiles to
     reach more workgroups; rows of odd length take tiles whose output runs reach 128 bytes; long
     rows that do not start on 16-byte boundaries are not joined into tiles of several rows."""
-    for M, P, n, dtype in ((20, 5, 6, "float32"), (100, 5, 5, "float64")):      # 125 or 25 elements per thread
-        steps = km.plan(M, [P] * n, [P] * n, dtype)
-        assert all(st["tile_slices"] * st["tile_rows"] >= 4 for st in steps if st["num_factors"] >= 2), (M, P, n, steps)
-        assert all(st["grid"] >= 96 for st in steps), (M, P, n, steps)
+    old = km.get_option(km.KM_OPT_KERNELS)
+    try:
+        km.set_option(km.KM_OPT_KERNELS, 7)              # the tiled families, not the whole-row kernel
+        for M, P, n, dtype in ((20, 5, 6, "float32"), (100, 5, 5, "float64")):      # 125 or 25 elements per thread
+            steps = km.plan(M, [P] * n, [P] * n, dtype)
+            assert all(st["tile_slices"] * st["tile_rows"] >= 4 for st in steps if st["num_factors"] >= 2), (M, P, n, steps)
+            assert all(st["grid"] >= 96 for st in steps), (M, P, n, steps)
+    finally:
+        km.set_option(km.KM_OPT_KERNELS, old)
     first = km.plan(1024, [5] * 8, [5] * 8, "float32")[0]
     assert first["num_factors"] == 3 and first["tile_slices"] == 125
     assert all(st["tile_rows"] == 1 for st in km.plan(1024, [3] * 7, [3] * 7, "float32"))
