@@ -768,23 +768,43 @@ static km_status tune(const Problem& pr, const Options& opt, hipStream_t stream,
 
     // Launches timed alone can rank differently than in sequence: keep the measured plan only if the
     // whole sequence beats the planner's own.
+    // A third candidate: the whole-row kernel wherever it fits, if the planner did not take it itself.
+    Plan rows;
+    bool have_rows = false;
+    if (deflt.steps.size() != 1 || deflt.steps[0].kernel != KM_KERNEL_ROWS) {
+        Options force = opt;
+        force.prefer_instance = g_num_variants + 1;
+        have_rows = make_plan(pr, force, g_variants, g_num_variants, generic_kernel(pr.dtype), rows) == KM_OK &&
+                    rows.steps.size() == 1 && rows.steps[0].kernel == KM_KERNEL_ROWS && launchable(rows.steps[0]);
+    }
     const size_t need_d = deflt.ws0_bytes + deflt.ws1_bytes, need_t = tuned.ws0_bytes + tuned.ws1_bytes;
     const size_t need = need_d > need_t ? need_d : need_t;
     if (need > 0 && hipMalloc(&sc.ws, need) != hipSuccess) { (void)hipGetLastError(); return KM_ENOMEM; }
-    auto run_default = [&]() { return run(pr, deflt, sc.a, F.data(), sc.b, sc.ws, stream, false) == KM_OK; };
-    auto run_tuned = [&]() { return run(pr, tuned, sc.a, F.data(), sc.b, sc.ws, stream, false) == KM_OK; };
-    float td = time_body(sc, stream, 1, run_default), tt = time_body(sc, stream, 1, run_tuned);
-    if (td < 0.f || tt < 0.f) return KM_ELAUNCH;
-    const int reps = reps_for(td < tt ? td : tt);
-    for (int round = 0; round < 2; ++round) {
-        const float d = time_body(sc, stream, reps, run_default), t = time_body(sc, stream, reps, run_tuned);
-        if (d < 0.f || t < 0.f) return KM_ELAUNCH;
-        if (round == 0 || d < td) td = d;
-        if (round == 0 || t < tt) tt = t;
+    const Plan* plans[3] = {&deflt, &tuned, have_rows ? &rows : nullptr};
+    float t[3] = {-1.f, -1.f, -1.f};
+    float quickest = -1.f;
+    for (int k = 0; k < 3; ++k) {
+        if (!plans[k]) continue;
+        auto body = [&]() { return run(pr, *plans[k], sc.a, F.data(), sc.b, sc.ws, stream, false) == KM_OK; };
+        t[k] = time_body(sc, stream, 1, body);
+        if (t[k] < 0.f) return KM_ELAUNCH;
+        if (quickest < 0.f || t[k] < quickest) quickest = t[k];
     }
-    chosen = tt < 0.99f * td ? tuned : deflt;
-    if (tuned_ms) *tuned_ms = tt < 0.99f * td ? tt : td;
-    if (default_ms) *default_ms = td;
+    const int reps = reps_for(quickest);
+    for (int round = 0; round < 2; ++round)
+        for (int k = 0; k < 3; ++k) {
+            if (!plans[k]) continue;
+            auto body = [&]() { return run(pr, *plans[k], sc.a, F.data(), sc.b, sc.ws, stream, false) == KM_OK; };
+            const float ms = time_body(sc, stream, reps, body);
+            if (ms < 0.f) return KM_ELAUNCH;
+            if (round == 0 || ms < t[k]) t[k] = ms;
+        }
+    int keep = 0;                                         // the planner's own unless another is 1 % faster
+    for (int k = 1; k < 3; ++k)
+        if (plans[k] && t[k] < 0.99f * t[0] && t[k] < t[keep]) keep = k;
+    chosen = *plans[keep];
+    if (tuned_ms) *tuned_ms = t[keep];
+    if (default_ms) *default_ms = t[0];
     if (hipStreamSynchronize(stream) != hipSuccess) return KM_ELAUNCH;
     return KM_OK;
 }
