@@ -27,6 +27,7 @@ struct Variant {
     const char* name;
     int lds_per_slice; // flexible instances: LDS bytes per slice of the tile (lds_bytes is the maximum)
     int thread_elems;  // flexible instances: contiguous elements of a tile that one thread multiplies first
+    int max_srow;      // > 0: only for rows of at most this many slices of the group (K / prod P)
 };
 
 // LDS a launch of the instance asks for when its tiles hold `tile_slices` slices.
@@ -238,6 +239,7 @@ inline void enumerate_choices(const Variant* table, int count, const Problem& pr
         if (!(opt.kernels >> c.kernel & 1)) continue;
         if (c.dtype != pr.dtype || c.num_factors != nf) continue;
         if (c.P != pr.P[f] || c.Q != pr.Q[f]) continue;
+        if (c.max_srow > 0 && s_row > c.max_srow) continue;
         if (c.rows_per_tile > 1 && s_row != c.tile_slices) continue;      // tiles of several rows hold whole rows
         tile_lengths(c, s_row, lens, 5);
         const int rows = whole_rows_per_tile(c, s_row, pr.M, s_row * pg * (int64_t)pr.esize);
@@ -301,6 +303,7 @@ inline Choice find_variant(const Variant* table, int count, const Problem& pr, i
         if (!(opt.kernels >> c.kernel & 1)) continue;
         if (c.dtype != pr.dtype || c.num_factors != nf) continue;
         if (c.P != pr.P[f] || c.Q != pr.Q[f]) continue;
+        if (c.max_srow > 0 && s_row > c.max_srow) continue;
         if (c.rows_per_tile > 1 && s_row != c.tile_slices) continue;      // tiles of several rows hold whole rows
         // slices per tile: fixed, or the best divisor of s_row up to the instance's limit
         int cand[3] = {0, 0, 0};

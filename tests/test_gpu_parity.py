@@ -332,6 +332,7 @@ EVERY_INSTANCE = [
     # one launch for a single short row, and two shapes whose groupings name the remaining instances
     ("float32", 1, [(4, 4)] * 7), ("float32", 1, [(5, 5)] * 3), ("float32", 1, [(6, 6)] * 3), ("float64", 1, [(6, 6)] * 3),
     ("float64", 1, [(6, 6)] * 2), ("float32", 1, [(9, 9)] * 3), ("float32", 64, [(8, 8)] * 4), ("float64", 64, [(32, 32)] * 3),
+    ("float64", 64, [(8, 8)] * 6),
 ]
 FUSE_LIMITS = (12, 11, 10, 9, 8, 7, 6, 5, 4, 3, 2, 1)
 
