@@ -47,7 +47,7 @@ typedef enum {
 /* Kernel families a plan step can use. */
 typedef enum {
     KM_KERNEL_GENERIC = 0,  /* one factor, any P and Q: LDS-tiled FMA kernel                       */
-    KM_KERNEL_FUSED = 1,    /* up to 9 consecutive small factors, tile resident in LDS (section 4.2) */
+    KM_KERNEL_FUSED = 1,    /* up to 12 consecutive small factors, tile resident in LDS (section 4.2) */
     KM_KERNEL_MFMA = 2,     /* factors with P and Q multiples of 16: slice contraction on MFMA     */
     KM_KERNEL_SHUFFLE = 3,  /* one 8x8 fp32 factor, no LDS: P-reduction by wavefront lane exchanges */
     KM_KERNEL_ROWS = 4      /* every factor of a short row in one launch, any shapes: the row and its
