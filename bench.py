@@ -33,7 +33,7 @@ MEASURED_TRAFFIC = {
     "c3_f32_m1024_32x32x4": 8593677371,    # mfma_f32_32x32_nf2_c3_m1024_32x32x4.md
     "c4_f64_m16_128x128x3": 537972830,     # mfma_f64_128x128_nf1_c4_m16_128x128x3.md
     "c5_f32_m256_16x32x4": 1342541049,     # mfma_f32_16x32_nf2_c5_m256_16x32x4.md
-    "table4_id19": 2413778570,             # fused_multi_f32_6x6_table4_id19_m1024_6x6x7.md
+    "table4_id19": 2389435788,             # fused_f32_6x6_table4_id19_m1024_6x6x7.md
     "table4_id26": 2147624081,             # mfma_f32_16x16_nf2_table4_id26_m16_16x16x6.md
     "table4_id25_f64": 4295090193,         # fused_multi_f64_8x8_table4_id25_m16_8x8x8.md
     "table4_id28_f64": 67411369,           # mfma_f64_64x64_nf1_table4_id28_m16_64x64x3.md

@@ -213,6 +213,9 @@ static hipError_t launch_shuffle(const LaunchArgs& a)
     X(float, KM_F32, 8, 8, 1, 64, 64)                   \
     X(float, KM_F32, 8, 8, 1, 8, 64)                    \
     X(float, KM_F32, 8, 8, 1, 1, 64)                    \
+    X(float, KM_F32, 6, 6, 3, 48, 256)                  \
+    X(float, KM_F32, 6, 6, 2, 288, 256)                 \
+    X(double, KM_F64, 6, 6, 3, 16, 256)                 \
     R(32, 32, 4)                                        \
     Z(32, 32, 4, 1)                                     \
     S(32, 32, 1)                                        \

@@ -333,6 +333,8 @@ EVERY_INSTANCE = [
     ("float32", 1, [(4, 4)] * 7), ("float32", 1, [(5, 5)] * 3), ("float32", 1, [(6, 6)] * 3), ("float64", 1, [(6, 6)] * 3),
     ("float64", 1, [(6, 6)] * 2), ("float32", 1, [(9, 9)] * 3), ("float32", 64, [(8, 8)] * 4), ("float64", 64, [(32, 32)] * 3),
     ("float64", 64, [(8, 8)] * 6),
+    # rows of 6^7 elements, for the 6x6 instances with fixed tiles of 48, 288 and 16 slices
+    ("float32", 24, [(6, 6)] * 7), ("float64", 12, [(6, 6)] * 7),
 ]
 FUSE_LIMITS = (12, 11, 10, 9, 8, 7, 6, 5, 4, 3, 2, 1)
 
