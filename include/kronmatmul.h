@@ -17,13 +17,21 @@
  *     memory on the current HIP device.  F[0] is the leftmost factor (slowest index digit).
  *   - X, Y and the workspace must be 16-byte aligned (hipMalloc and torch allocations are); factors
  *     need only their element's alignment.  KM_EINVAL otherwise.
- *   - The caller owns every buffer.  X and the factors are only read.  Y may be used as scratch
- *     for intermediates before it receives the result.  X, Y and the workspace must not overlap.
+ *   - The caller owns every buffer.  X and the factors are only read, and nothing outside the
+ *     M x prod(P) elements of X, the P[i] x Q[i] elements of F[i], the M x prod(Q) elements of Y and
+ *     the stated workspace bytes is read or written.  Y may be used as scratch for intermediates
+ *     before it receives the result.  X, Y and the workspace must not overlap: KM_EINVAL if they do.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is enqueued
  *     on it; no entry point synchronises with the device unless stated.
  *   - Errors are returned, never thrown; nothing calls exit().  M == 0 is a successful no-op.
  *   - Entry points are thread-safe with respect to each other; concurrent calls that share the
  *     library-managed workspace (kronmatmul) on different streams are serialised by the caller.
+ *     Options (kronmatmul_set_option) are process-wide, not per thread: a call uses the values in
+ *     force when it starts.
+ *   - Graph capture: kronmatmul_ws and kronmatmul_transposed_ws only enqueue kernels, with one
+ *     exception: the first launch of a kernel instance on a device raises that kernel's LDS limit
+ *     (hipFuncSetAttribute).  Call kronmatmul_prepare for the problem before capturing, or make one
+ *     uncaptured call first.
  */
 #ifndef KRONMATMUL_H
 #define KRONMATMUL_H
@@ -92,6 +100,11 @@ km_status kronmatmul(int M, int N, const int* P, const int* Q,
                      const void* X, const void* const* F, void* Y,
                      km_dtype dtype, void* stream);
 
+/* Set-up for a problem on the current HIP device, outside any timed or captured region: plans it
+ * (the plan is memoised) and sets the attributes of every kernel instance the plan launches, so that
+ * later kronmatmul_ws calls for this problem do nothing but enqueue kernels.  Launches nothing. */
+km_status kronmatmul_prepare(int M, int N, const int* P, const int* Q, km_dtype dtype);
+
 /* Same, with a caller-provided device workspace of at least kronmatmul_workspace_size bytes
  * (may be NULL when that size is 0).  Never allocates.  KM_ENOMEM if workspace_bytes is too small. */
 km_status kronmatmul_ws(int M, int N, const int* P, const int* Q,
@@ -120,12 +133,14 @@ km_status kronmatmul_transposed_ws(int M, int N, const int* P, const int* Q,
 km_status kronmatmul_plan(int M, int N, const int* P, const int* Q, km_dtype dtype,
                           km_plan_step* steps, int cap, int* nsteps);
 
-/* Autotuning (the search over tile sizes of section 5, done at run time on the device that will
+/* Autotuning (the search over tile sizes of section 4.3, done at run time on the device that will
  * run the problem): times every compiled instance, tile length and tile walk that fits each group
  * of consecutive factors on synthetic rows of the problem's size, plans on the measured times, and
  * keeps that plan for later kronmatmul / kronmatmul_ws / kronmatmul_plan calls with this problem and
- * the options in force now, if its launches in sequence beat the cost-model plan (otherwise that one
- * is kept).  The plan stays until kronmatmul_release.  Allocates and frees device memory (two
+ * the options in force now, if its launches in sequence beat the cost-model plan and need no more
+ * workspace than that plan (otherwise that one is kept: a workspace sized with
+ * kronmatmul_workspace_size before tuning stays large enough).  The plan stays until
+ * kronmatmul_release.  Allocates and frees device memory (two
  * buffers of M x the widest intermediate, plus the plan's workspace; KM_ENOMEM if that fails),
  * enqueues on `stream` and waits for it: not for use under graph capture.  Results do not depend on
  * the plan beyond rounding order.  tuned_ms / default_ms (host, may be NULL) receive the time of the
@@ -146,7 +161,9 @@ long long kronmatmul_store_column(long long k_in, long long p_group, long long t
 km_status kronmatmul_cost(int M, int N, const int* P, const int* Q, km_dtype dtype,
                           double* flops, double* planned_bytes);
 
-/* Options.  KM_OPT_KERNELS: bit mask of km_kernel families the planner may use (bit k = family k;
+/* Options (process-wide).  KM_OPT_KERNELS, KM_OPT_MAX_FUSE and KM_OPT_PROFILE are for users; the
+ * options called "tuning aid" force the planner's hand and exist for tests and sweeps only: they are
+ * not meant to be changed while other threads are making calls.  KM_OPT_KERNELS: bit mask of km_kernel families the planner may use (bit k = family k;
  * the generic family is always allowed; default 23: the shuffle family is off because the LDS-tiled
  * kernels measured faster).  KM_OPT_MAX_FUSE: upper limit on factors per launch (default 12).
  * KM_OPT_PROFILE: when 1, every launch is bracketed by HIP events on the caller's stream.

@@ -19,7 +19,7 @@ EXPORTS = [
     "kronmatmul_last_profile", "kronmatmul_mean_profile", "kronmatmul_release", "kronmatmul_status_string",
     "kronmatmul_kernel_name", "kronmatmul_tune",
     "kronmatmul_transposed_workspace_size", "kronmatmul_transposed", "kronmatmul_transposed_ws",
-    "kronmatmul_clock_probe",
+    "kronmatmul_clock_probe", "kronmatmul_prepare",
 ]
 
 
@@ -57,6 +57,8 @@ def lib():
         L.kronmatmul_workspace_size.argtypes = [ci, ci, ip, ip, ci, ctypes.POINTER(ctypes.c_size_t)]
         L.kronmatmul.restype = ci
         L.kronmatmul.argtypes = [ci, ci, ip, ip, vp, vp, vp, ci, vp]
+        L.kronmatmul_prepare.restype = ci
+        L.kronmatmul_prepare.argtypes = [ci, ci, ip, ip, ci]
         L.kronmatmul_ws.restype = ci
         L.kronmatmul_ws.argtypes = [ci, ci, ip, ip, vp, vp, vp, ci, vp, ctypes.c_size_t, vp]
         L.kronmatmul_transposed_workspace_size.restype = ci
@@ -133,6 +135,12 @@ def workspace_size(M, P, Q, dtype, transposed=False):
     fn = lib().kronmatmul_transposed_workspace_size if transposed else lib().kronmatmul_workspace_size
     _check(fn(int(M), n, p, q, _dtype_code(dtype), ctypes.byref(out)), "kronmatmul_workspace_size")
     return int(out.value)
+
+
+def prepare(M, P, Q, dtype):
+    """Set-up on the current device: plan the problem and set its kernels' attributes (before graph capture)."""
+    n, p, q = _shapes(P, Q)
+    _check(lib().kronmatmul_prepare(int(M), n, p, q, _dtype_code(dtype)), "kronmatmul_prepare")
 
 
 def plan(M, P, Q, dtype):

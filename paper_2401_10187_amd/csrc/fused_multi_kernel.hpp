@@ -19,6 +19,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include "fused_kernel.hpp"   // ipow, Vec16, as_constant, stream_load/stream_store
+#include "plan.hpp"           // unaligned_vectors
 
 namespace km {
 
@@ -318,19 +319,28 @@ void fused_multi_sliced_multiply(const T* __restrict__ Xg, T* __restrict__ Yg,
         }
     } else {
         // Tiles that do not start on a 16-byte boundary (rows of odd length): 16-byte loads from the
-        // boundary below the tile, so the first and the last vector may hold up to VN - 1 elements of
-        // the neighbouring tiles, which are dropped.  Such a vector never leaves X: X itself starts on
-        // a 16-byte boundary, and a 16-byte unit that holds one element of X lies in the same page.
+        // boundary below the tile, so the first vector may hold up to VN - 1 elements of the tile
+        // before, which are dropped.  Below the tile there always is one when mis > 0 (X itself starts
+        // on a 16-byte boundary); above it there need not be (the last tile of X), so a last vector
+        // that is only partly the tile's is fetched element by element: nothing outside
+        // [src - mis, src + valid) is read.
         const int mis = (int)((reinterpret_cast<uintptr_t>(src) / sizeof(T)) % VN);
         const V* vsrc = reinterpret_cast<const V*>(src - mis);
-        const int nv = (valid + mis + VN - 1) / VN;
+        const int nv = unaligned_vectors(valid, mis, VN), nfull = unaligned_whole_vectors(valid, mis, VN);
         constexpr int UN = 4;
         for (int base = 0; base < nv; base += UN * NT) {
             V tmp[UN];
 #pragma unroll
             for (int i = 0; i < UN; ++i) {
                 const int v = base + tid + i * NT;
-                if (v < nv) tmp[i] = stream_load(&vsrc[v]);
+                if (v < nfull) tmp[i] = stream_load(&vsrc[v]);
+                else if (v < nv) {
+#pragma unroll
+                    for (int k = 0; k < VN; ++k) {
+                        const int e = v * VN + k - mis;
+                        tmp[i][k] = (e >= 0 && e < valid) ? src[e] : T(0);
+                    }
+                }
             }
 #pragma unroll
             for (int i = 0; i < UN; ++i) {

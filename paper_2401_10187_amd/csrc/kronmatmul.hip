@@ -7,378 +7,21 @@
 
 #include "../../include/kronmatmul.h"
 #include "plan.hpp"
+#include "launch.hpp"
+#include "instances.hpp"
 #include "generic_kernel.hpp"
 #include "row_kernel.hpp"
-#include "fused_kernel.hpp"
+#include "fused_kernel.hpp"          // the kernel headers below are only needed for their shape structs
 #include "fused_multi_kernel.hpp"
 #include "mfma_kernel.hpp"
 #include "mfma_pair_kernel.hpp"
-#include "mfma_pair_split_kernel.hpp"
 #include "shuffle_kernel.hpp"
 
 namespace km {
 
 // ---------------------------------------------------------------------------------------------
-// compiled kernel instances
+// compiled kernel instances (launchers: launch.hpp; the list: instances.hpp)
 // ---------------------------------------------------------------------------------------------
-struct LaunchArgs {
-    const void* src;
-    void* dst;
-    const void* const* factors;   // host array of device pointers, all N of the problem
-    const Problem* pr;
-    const km_plan_step* st;
-    hipStream_t stream;
-};
-typedef hipError_t (*LaunchFn)(const LaunchArgs&);
-
-// Kernels that need more than 48 KB of dynamic LDS must raise their limit once per device.
-static hipError_t allow_lds(const void* kernel, int bytes, unsigned char (&done)[64])
-{
-    if (bytes <= 48 * 1024) return hipSuccess;
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess) return e;
-    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
-    if (done[dev]) return hipSuccess;
-    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-    if (e == hipSuccess) done[dev] = 1;     // racing threads at worst set the same value twice
-    return e;
-}
-
-template <typename T, int P, int Q, int NF, int ST, int NT>
-static hipError_t launch_fused(const LaunchArgs& a)
-{
-    typedef FusedShape<T, P, Q, NF, ST, NT> Sh;
-    const km_plan_step& st = *a.st;
-    auto kern = fused_sliced_multiply<T, P, Q, NF, ST, NT>;
-    static unsigned char lds_ok[64];
-    hipError_t e = allow_lds((const void*)kern, Sh::LDS_BYTES, lds_ok);
-    if (e != hipSuccess) return e;
-    const T* f[3] = {nullptr, nullptr, nullptr};
-    for (int j = 0; j < NF; ++j) f[j] = (const T*)a.factors[st.first_factor + NF - 1 - j];   // order of application
-    const int64_t tiles_per_row = st.k_in / Sh::TK;
-    hipLaunchKernelGGL(kern, dim3((unsigned)st.grid), dim3(NT), Sh::LDS_BYTES, a.stream,
-                       (const T*)a.src, (T*)a.dst, f[0], f[1], f[2], st.k_in, st.k_out, tiles_per_row,
-                       (int64_t)st.grid);
-    return hipGetLastError();
-}
-
-template <typename T, int P, int Q, int G0, int G1, int G2, int STMAX, int NT>
-static hipError_t launch_multi(const LaunchArgs& a)
-{
-    typedef MultiShape<T, P, Q, G0, G1, G2, STMAX, NT> Sh;
-    const km_plan_step& st = *a.st;
-    auto kern = fused_multi_sliced_multiply<T, P, Q, G0, G1, G2, STMAX, NT>;
-    static unsigned char lds_ok[64];
-    hipError_t e = allow_lds((const void*)kern, Sh::LDS_BYTES, lds_ok);
-    if (e != hipSuccess) return e;
-    const int rows = st.tile_rows;
-    if (rows < 1 || st.tile_slices < 1 || (int64_t)st.tile_slices * rows > STMAX) return hipErrorInvalidValue;
-    const int slices = st.tile_slices * rows;            // what the kernel treats as one tile
-    FactorPtrs<Sh::NF> fp;
-    for (int j = 0; j < Sh::NF; ++j) fp.f[j] = a.factors[st.first_factor + Sh::NF - 1 - j];   // order of application
-    const int64_t tk_row = (int64_t)st.tile_slices * Sh::per_slice(0);
-    if (st.k_in % tk_row) return hipErrorInvalidValue;
-    const int64_t tiles_per_row = st.k_in / tk_row;
-    // tiles of several rows hold whole rows
-    if (rows > 1 && tiles_per_row != 1) return hipErrorInvalidValue;
-    const int64_t tiles = rows > 1 ? (a.pr->M + rows - 1) / rows : a.pr->M * tiles_per_row;
-    if (tiles != st.grid) return hipErrorInvalidValue;
-    if (st.lds_bytes < Sh::LDS_PER_SLICE * slices || st.lds_bytes > Sh::LDS_BYTES) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(kern, dim3((unsigned)st.grid), dim3(NT), (size_t)st.lds_bytes, a.stream,
-                       (const T*)a.src, (T*)a.dst, fp, st.k_in, st.k_out, tiles_per_row, (int64_t)st.grid,
-                       slices, rows, a.pr->M);
-    return hipGetLastError();
-}
-
-template <class OP, int P, int Q, int NF, int ST, int NW, int QSPLIT>
-static hipError_t launch_mfma(const LaunchArgs& a)
-{
-    typedef MfmaShape<OP, P, Q, NF, ST, NW, QSPLIT> Sh;
-    typedef typename OP::T T;
-    const km_plan_step& st = *a.st;
-    auto kern = mfma_sliced_multiply<OP, P, Q, NF, ST, NW, QSPLIT>;
-    static unsigned char lds_ok[64];
-    hipError_t e = allow_lds((const void*)kern, Sh::LDS_BYTES, lds_ok);
-    if (e != hipSuccess) return e;
-    const T* f[2] = {nullptr, nullptr};
-    for (int j = 0; j < NF; ++j) f[j] = (const T*)a.factors[st.first_factor + NF - 1 - j];   // order of application
-    const int64_t tiles_per_row = st.k_in / Sh::TK;
-    const int64_t num_tiles = a.pr->M * tiles_per_row;
-    const int64_t tpw = st.tiles_per_wg;
-    if (tpw < 1 || (num_tiles + tpw - 1) / tpw != st.grid) return hipErrorInvalidValue;
-    if (st.tile_order < 0 || st.tile_order > 3) return hipErrorInvalidValue;
-    if (st.tile_order == 1 && !pair_order_fits(num_tiles, tpw)) return hipErrorInvalidValue;
-    if (st.tile_order == 3 && !xcd_order_fits(num_tiles, st.grid)) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(kern, dim3((unsigned)st.grid), dim3(Sh::NT), Sh::LDS_BYTES, a.stream,
-                       (const T*)a.src, (T*)a.dst, f[0], f[1], st.k_in, st.k_out, tiles_per_row, num_tiles, tpw,
-                       st.tile_order);
-    return hipGetLastError();
-}
-
-template <int P, int ST, int NW, int PD>
-static hipError_t launch_mfma_pair(const LaunchArgs& a)
-{
-    typedef MfmaPairShape<P, ST, NW, PD> Sh;
-    const km_plan_step& st = *a.st;
-    auto kern = mfma_pair_sliced_multiply<P, ST, NW, PD>;
-    static unsigned char lds_ok[64];
-    hipError_t e = allow_lds((const void*)kern, Sh::LDS_BYTES, lds_ok);
-    if (e != hipSuccess) return e;
-    const float* f0 = (const float*)a.factors[st.first_factor + 1];    // applied first
-    const float* f1 = (const float*)a.factors[st.first_factor];
-    const int64_t tiles_per_row = st.k_in / Sh::TK;
-    const int64_t num_tiles = a.pr->M * tiles_per_row;
-    const int64_t tpw = st.tiles_per_wg;
-    if (tpw < 1 || (num_tiles + tpw - 1) / tpw != st.grid) return hipErrorInvalidValue;
-    if (st.tile_order != 0 && st.tile_order != 2 && st.tile_order != 3) return hipErrorInvalidValue;
-    if (st.tile_order == 3 && !xcd_order_fits(num_tiles, st.grid)) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(kern, dim3((unsigned)st.grid), dim3(Sh::NT), Sh::LDS_BYTES, a.stream,
-                       (const float*)a.src, (float*)a.dst, f0, f1, st.k_in, st.k_out, tiles_per_row, num_tiles, tpw,
-                       st.tile_order);
-    return hipGetLastError();
-}
-
-template <int P, int ST, int NW>
-static hipError_t launch_mfma_pair_rows(const LaunchArgs& a)
-{
-    const km_plan_step& st = *a.st;
-    auto kern = mfma_pair_rows_sliced_multiply<P, ST, NW>;
-    if (st.k_in != (int64_t)P * P || st.k_out != 32 * 32 || st.tile_rows != ST || st.tile_slices != 1)
-        return hipErrorInvalidValue;
-    const float* f0 = (const float*)a.factors[st.first_factor + 1];    // applied first
-    const float* f1 = (const float*)a.factors[st.first_factor];
-    const int64_t num_tiles = (a.pr->M + ST - 1) / ST;
-    const int64_t tpw = st.tiles_per_wg;
-    if (tpw < 1 || (num_tiles + tpw - 1) / tpw != st.grid) return hipErrorInvalidValue;
-    if (st.tile_order != 0 && st.tile_order != 2 && st.tile_order != 3) return hipErrorInvalidValue;
-    if (st.tile_order == 3 && !xcd_order_fits(num_tiles, st.grid)) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(kern, dim3((unsigned)st.grid), dim3(NW * 64), 0, a.stream,
-                       (const float*)a.src, (float*)a.dst, f0, f1, a.pr->M, num_tiles, tpw, st.tile_order);
-    return hipGetLastError();
-}
-
-template <int P, int ST, int PD>
-static hipError_t launch_mfma_pair_split(const LaunchArgs& a)
-{
-    typedef MfmaPairSplitShape<P, ST, PD> Sh;
-    const km_plan_step& st = *a.st;
-    auto kern = mfma_pair_split_sliced_multiply<P, ST, PD>;
-    static unsigned char lds_ok[64];
-    hipError_t e = allow_lds((const void*)kern, Sh::LDS_BYTES, lds_ok);
-    if (e != hipSuccess) return e;
-    const float* f0 = (const float*)a.factors[st.first_factor + 1];    // applied first
-    const float* f1 = (const float*)a.factors[st.first_factor];
-    const int64_t tiles_per_row = st.k_in / Sh::TK;
-    const int64_t num_tiles = a.pr->M * tiles_per_row;
-    const int64_t tpw = st.tiles_per_wg;
-    if (tpw < 1 || (num_tiles + tpw - 1) / tpw != st.grid) return hipErrorInvalidValue;
-    if (st.tile_order != 0 && st.tile_order != 2 && st.tile_order != 3) return hipErrorInvalidValue;
-    if (st.tile_order == 3 && !xcd_order_fits(num_tiles, st.grid)) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(kern, dim3((unsigned)st.grid), dim3(Sh::NT), Sh::LDS_BYTES, a.stream,
-                       (const float*)a.src, (float*)a.dst, f0, f1, st.k_in, st.k_out, tiles_per_row, num_tiles, tpw,
-                       st.tile_order);
-    return hipGetLastError();
-}
-
-static hipError_t launch_shuffle(const LaunchArgs& a)
-{
-    const km_plan_step& st = *a.st;
-    const int64_t tiles_per_row = st.k_in / ((int64_t)SHF_ST * SHF_P);
-    hipLaunchKernelGGL(shuffle_sliced_multiply_8x8, dim3((unsigned)st.grid), dim3(SHF_NT), 0, a.stream,
-                       (const float*)a.src, (float*)a.dst, (const float*)a.factors[st.first_factor], st.k_in,
-                       tiles_per_row, (int64_t)st.grid);
-    return hipGetLastError();
-}
-
-// Fused FMA instances: X(type, dtype code, P, Q, factors per launch, tile_slices, threads).
-// Register-resident MFMA pairs: Z(P, tile_slices, wavefronts, units fetched ahead) (fp32, Q = 32, two factors).
-// Small-factor instances with several factors per LDS pass and a run-time tile length:
-// W(type, dtype code, P, Q, G0, G1, G2, largest tile_slices, threads).
-// The same with compute and store wavefronts: S(P, tile_slices, units fetched ahead).
-// The same for rows of exactly P*P elements, ST rows per tile: R(P, rows per tile, wavefronts).
-// MFMA instances: Y(op, dtype code, P, Q, factors per launch, tile_slices, wavefronts, q split).
-// Order = preference among instances that fit a shape.
-#define KM_INSTANCES(X, Y, Z, W, S, R)                          \
-    X(float, KM_F32, 8, 8, 3, 32, 1024)                 \
-    X(float, KM_F32, 8, 8, 3, 32, 256)                  \
-    X(float, KM_F32, 8, 8, 3, 16, 256)                  \
-    X(float, KM_F32, 8, 8, 3, 8, 128)                   \
-    X(float, KM_F32, 8, 8, 3, 1, 64)                    \
-    X(float, KM_F32, 8, 8, 2, 256, 256)                 \
-    X(float, KM_F32, 8, 8, 2, 64, 256)                  \
-    X(float, KM_F32, 8, 8, 2, 8, 64)                    \
-    X(float, KM_F32, 8, 8, 2, 1, 64)                    \
-    X(float, KM_F32, 8, 8, 1, 2048, 256)                \
-    X(float, KM_F32, 8, 8, 1, 64, 64)                   \
-    X(float, KM_F32, 8, 8, 1, 8, 64)                    \
-    X(float, KM_F32, 8, 8, 1, 1, 64)                    \
-    X(float, KM_F32, 6, 6, 3, 48, 256)                  \
-    X(float, KM_F32, 6, 6, 2, 288, 256)                 \
-    X(double, KM_F64, 6, 6, 3, 16, 256)                 \
-    R(32, 32, 4)                                        \
-    Z(32, 32, 4, 1)                                     \
-    S(32, 32, 1)                                        \
-    S(32, 32, 3)                                        \
-    Y(MfmaF32x32, KM_F32, 32, 32, 2, 32, 8, 1)          \
-    Y(MfmaF32x32, KM_F32, 32, 32, 2, 32, 16, 1)         \
-    Y(MfmaF32x32, KM_F32, 32, 32, 2, 16, 4, 1)          \
-    Y(MfmaF32x32, KM_F32, 32, 32, 1, 256, 4, 1)         \
-    Y(MfmaF32x32, KM_F32, 32, 32, 1, 128, 4, 1)         \
-    Y(MfmaF32x32, KM_F32, 32, 32, 1, 32, 1, 1)          \
-    R(16, 32, 4)                                        \
-    Z(16, 32, 4, 1)                                     \
-    S(16, 32, 1)                                        \
-    Y(MfmaF32x32, KM_F32, 16, 32, 2, 32, 4, 1)          \
-    Y(MfmaF32x32, KM_F32, 16, 32, 2, 16, 4, 1)          \
-    Y(MfmaF32x32, KM_F32, 16, 32, 1, 256, 4, 1)         \
-    Y(MfmaF32x32, KM_F32, 16, 32, 1, 128, 4, 1)         \
-    Y(MfmaF64x16, KM_F64, 128, 128, 1, 32, 8, 8)         \
-    Y(MfmaF64x16, KM_F64, 128, 128, 1, 16, 4, 4)         \
-    Y(MfmaF64x16, KM_F64, 128, 128, 1, 32, 4, 4)         \
-    Y(MfmaF32x16, KM_F32, 16, 16, 2, 32, 4, 1)          \
-    Y(MfmaF32x16, KM_F32, 16, 16, 1, 256, 4, 1)         \
-    Y(MfmaF32x16, KM_F32, 16, 16, 1, 64, 4, 1)          \
-    Y(MfmaF32x16, KM_F32, 16, 16, 1, 16, 1, 1)          \
-    Y(MfmaF32x32, KM_F32, 64, 64, 1, 128, 8, 2)         \
-    Y(MfmaF32x32, KM_F32, 64, 64, 1, 128, 4, 1)         \
-    Y(MfmaF32x32, KM_F32, 64, 64, 1, 64, 2, 1)          \
-    Y(MfmaF32x32, KM_F32, 128, 128, 1, 32, 4, 4)        \
-    Y(MfmaF32x16, KM_F32, 32, 16, 1, 256, 4, 1)         \
-    Y(MfmaF32x16, KM_F32, 64, 16, 1, 128, 4, 1)         \
-    Y(MfmaF32x32, KM_F32, 64, 32, 1, 128, 4, 1)         \
-    Y(MfmaF32x32, KM_F32, 32, 64, 1, 256, 4, 1)         \
-    Y(MfmaF32x32, KM_F32, 16, 64, 1, 256, 4, 1)         \
-    Y(MfmaF32x32, KM_F32, 128, 64, 1, 64, 4, 2)         \
-    Y(MfmaF32x32, KM_F32, 64, 128, 1, 128, 8, 2)        \
-    Y(MfmaF32x32, KM_F32, 128, 32, 1, 64, 2, 1)         \
-    Y(MfmaF32x32, KM_F32, 32, 128, 1, 256, 4, 2)        \
-    Y(MfmaF64x16, KM_F64, 32, 16, 1, 128, 4, 1)         \
-    Y(MfmaF64x16, KM_F64, 16, 32, 1, 128, 4, 1)         \
-    Y(MfmaF64x16, KM_F64, 64, 32, 1, 64, 4, 1)          \
-    Y(MfmaF64x16, KM_F64, 32, 64, 1, 128, 4, 1)         \
-    Y(MfmaF64x16, KM_F64, 16, 16, 2, 32, 8, 1)          \
-    Y(MfmaF64x16, KM_F64, 16, 16, 2, 16, 4, 1)          \
-    Y(MfmaF64x16, KM_F64, 16, 16, 1, 256, 4, 1)         \
-    Y(MfmaF64x16, KM_F64, 16, 16, 1, 64, 4, 1)          \
-    Y(MfmaF64x16, KM_F64, 16, 16, 1, 16, 1, 1)          \
-    Y(MfmaF64x16, KM_F64, 32, 32, 2, 16, 8, 1)          \
-    Y(MfmaF64x16, KM_F64, 32, 32, 1, 128, 4, 1)         \
-    Y(MfmaF64x16, KM_F64, 32, 32, 1, 32, 2, 1)          \
-    Y(MfmaF64x16, KM_F64, 64, 64, 1, 64, 8, 2)          \
-    Y(MfmaF64x16, KM_F64, 64, 64, 1, 64, 4, 1)          \
-    W(float, KM_F32, 2, 2, 4, 4, 4, 4, 256)             \
-    W(float, KM_F32, 2, 2, 4, 4, 3, 8, 256)             \
-    W(float, KM_F32, 2, 2, 4, 3, 3, 16, 256)            \
-    W(float, KM_F32, 2, 2, 3, 3, 3, 32, 256)            \
-    W(float, KM_F32, 2, 2, 4, 4, 0, 64, 256)            \
-    W(float, KM_F32, 2, 2, 4, 3, 0, 128, 256)           \
-    W(float, KM_F32, 2, 2, 3, 3, 0, 256, 256)           \
-    W(float, KM_F32, 2, 2, 3, 2, 0, 512, 256)           \
-    W(float, KM_F32, 2, 2, 4, 0, 0, 1024, 256)          \
-    W(float, KM_F32, 2, 2, 3, 0, 0, 2048, 256)          \
-    W(float, KM_F32, 2, 2, 2, 0, 0, 4096, 256)          \
-    W(float, KM_F32, 2, 2, 1, 0, 0, 8192, 256)          \
-    W(float, KM_F32, 4, 4, 3, 2, 2, 1, 256)             \
-    W(float, KM_F32, 4, 4, 2, 2, 2, 4, 256)             \
-    W(float, KM_F32, 4, 4, 2, 2, 1, 16, 256)            \
-    W(float, KM_F32, 4, 4, 2, 2, 0, 64, 256)            \
-    W(float, KM_F32, 4, 4, 2, 1, 0, 256, 256)           \
-    W(float, KM_F32, 4, 4, 2, 0, 0, 1024, 256)          \
-    W(float, KM_F32, 4, 4, 1, 0, 0, 4096, 256)          \
-    W(float, KM_F32, 3, 3, 3, 2, 2, 9, 256)             \
-    W(float, KM_F32, 3, 3, 2, 2, 2, 27, 256)            \
-    W(float, KM_F32, 3, 3, 2, 2, 1, 81, 256)            \
-    W(float, KM_F32, 3, 3, 2, 2, 0, 81, 256)            \
-    W(float, KM_F32, 3, 3, 2, 1, 0, 243, 256)           \
-    W(float, KM_F32, 3, 3, 2, 0, 0, 729, 256)           \
-    W(float, KM_F32, 3, 3, 1, 0, 0, 2187, 256)          \
-    W(float, KM_F32, 5, 5, 2, 1, 0, 125, 256)           \
-    W(float, KM_F32, 5, 5, 2, 0, 0, 625, 256)           \
-    W(float, KM_F32, 5, 5, 1, 0, 0, 3125, 256)          \
-    W(float, KM_F32, 6, 6, 2, 1, 0, 72, 256)            \
-    W(float, KM_F32, 6, 6, 1, 1, 1, 72, 256)            \
-    W(float, KM_F32, 6, 6, 2, 0, 0, 432, 256)           \
-    W(float, KM_F32, 6, 6, 1, 0, 0, 2592, 256)          \
-    W(double, KM_F64, 2, 2, 4, 4, 4, 2, 256)            \
-    W(double, KM_F64, 2, 2, 4, 4, 3, 4, 256)            \
-    W(double, KM_F64, 2, 2, 4, 3, 3, 8, 256)            \
-    W(double, KM_F64, 2, 2, 3, 3, 3, 16, 256)           \
-    W(double, KM_F64, 2, 2, 4, 4, 0, 32, 256)           \
-    W(double, KM_F64, 2, 2, 4, 3, 0, 64, 256)           \
-    W(double, KM_F64, 2, 2, 3, 3, 0, 128, 256)          \
-    W(double, KM_F64, 2, 2, 3, 2, 0, 256, 256)          \
-    W(double, KM_F64, 2, 2, 4, 0, 0, 512, 256)          \
-    W(double, KM_F64, 2, 2, 3, 0, 0, 1024, 256)         \
-    W(double, KM_F64, 2, 2, 1, 0, 0, 4096, 256)         \
-    W(double, KM_F64, 4, 4, 2, 2, 2, 2, 256)            \
-    W(double, KM_F64, 4, 4, 2, 2, 1, 8, 256)            \
-    W(double, KM_F64, 4, 4, 2, 2, 0, 32, 256)           \
-    W(double, KM_F64, 4, 4, 2, 0, 0, 512, 256)          \
-    W(double, KM_F64, 4, 4, 1, 0, 0, 2048, 256)         \
-    X(double, KM_F64, 8, 8, 3, 16, 256)                 \
-    W(double, KM_F64, 8, 8, 1, 1, 1, 16, 256)           \
-    W(double, KM_F64, 8, 8, 1, 1, 0, 128, 256)          \
-    W(double, KM_F64, 8, 8, 1, 0, 0, 1024, 256)         \
-    W(double, KM_F64, 3, 3, 3, 2, 2, 3, 256)            \
-    W(double, KM_F64, 3, 3, 2, 2, 2, 9, 256)            \
-    W(double, KM_F64, 3, 3, 2, 2, 1, 27, 256)           \
-    W(double, KM_F64, 3, 3, 2, 2, 0, 81, 256)           \
-    W(double, KM_F64, 3, 3, 2, 1, 0, 243, 256)          \
-    W(double, KM_F64, 3, 3, 2, 0, 0, 729, 256)          \
-    W(double, KM_F64, 3, 3, 1, 0, 0, 2187, 256)         \
-    W(double, KM_F64, 5, 5, 2, 1, 0, 25, 256)           \
-    W(double, KM_F64, 5, 5, 2, 0, 0, 125, 256)          \
-    W(double, KM_F64, 5, 5, 1, 0, 0, 625, 256)          \
-    W(double, KM_F64, 6, 6, 1, 1, 1, 36, 256)           \
-    W(double, KM_F64, 6, 6, 1, 1, 0, 216, 256)          \
-    W(double, KM_F64, 6, 6, 1, 0, 0, 1296, 256)         \
-    W(float, KM_F32, 8, 8, 1, 1, 1, 16, 256)            \
-    W(float, KM_F32, 8, 8, 1, 1, 0, 128, 256)           \
-    W(float, KM_F32, 8, 8, 1, 0, 0, 1024, 256)          \
-    W(float, KM_F32, 7, 7, 2, 1, 0, 32, 256)            \
-    W(float, KM_F32, 7, 7, 2, 0, 0, 256, 256)           \
-    W(float, KM_F32, 7, 7, 1, 0, 0, 2048, 256)          \
-    W(float, KM_F32, 9, 9, 1, 1, 1, 16, 256)            \
-    W(float, KM_F32, 9, 9, 1, 1, 0, 128, 256)           \
-    W(float, KM_F32, 9, 9, 1, 0, 0, 1024, 256)          \
-    W(float, KM_F32, 10, 10, 1, 1, 1, 12, 256)          \
-    W(float, KM_F32, 10, 10, 1, 1, 0, 100, 256)         \
-    W(float, KM_F32, 10, 10, 1, 0, 0, 1000, 256)        \
-    W(float, KM_F32, 12, 12, 1, 1, 0, 72, 256)          \
-    W(float, KM_F32, 12, 12, 1, 0, 0, 864, 256)         \
-    W(double, KM_F64, 7, 7, 2, 1, 0, 16, 256)           \
-    W(double, KM_F64, 7, 7, 2, 0, 0, 128, 256)          \
-    W(double, KM_F64, 7, 7, 1, 0, 0, 1024, 256)         \
-    W(double, KM_F64, 9, 9, 1, 1, 1, 8, 256)            \
-    W(double, KM_F64, 9, 9, 1, 1, 0, 64, 256)           \
-    W(double, KM_F64, 9, 9, 1, 0, 0, 512, 256)          \
-    W(double, KM_F64, 10, 10, 1, 1, 1, 6, 256)          \
-    W(double, KM_F64, 10, 10, 1, 1, 0, 50, 256)         \
-    W(double, KM_F64, 10, 10, 1, 0, 0, 500, 256)        \
-    W(double, KM_F64, 12, 12, 1, 1, 0, 36, 256)         \
-    W(double, KM_F64, 12, 12, 1, 0, 0, 432, 256)        \
-    W(float, KM_F32, 2, 4, 2, 2, 0, 16, 256)            \
-    W(float, KM_F32, 2, 4, 2, 0, 0, 512, 256)           \
-    W(float, KM_F32, 2, 4, 1, 0, 0, 2048, 256)          \
-    W(float, KM_F32, 4, 2, 2, 2, 0, 32, 256)            \
-    W(float, KM_F32, 4, 2, 2, 0, 0, 512, 256)           \
-    W(float, KM_F32, 4, 2, 1, 0, 0, 2048, 256)          \
-    W(float, KM_F32, 4, 8, 2, 1, 0, 16, 256)            \
-    W(float, KM_F32, 4, 8, 2, 0, 0, 128, 256)           \
-    W(float, KM_F32, 4, 8, 1, 0, 0, 1024, 256)          \
-    W(float, KM_F32, 8, 4, 1, 1, 1, 16, 256)            \
-    W(float, KM_F32, 8, 4, 1, 1, 0, 128, 256)           \
-    W(float, KM_F32, 8, 4, 1, 0, 0, 1024, 256)          \
-    W(double, KM_F64, 2, 4, 2, 2, 0, 8, 256)            \
-    W(double, KM_F64, 2, 4, 2, 0, 0, 256, 256)          \
-    W(double, KM_F64, 4, 2, 2, 2, 0, 16, 256)           \
-    W(double, KM_F64, 4, 2, 2, 0, 0, 256, 256)          \
-    W(double, KM_F64, 4, 8, 2, 0, 0, 64, 256)           \
-    W(double, KM_F64, 4, 8, 1, 0, 0, 512, 256)          \
-    W(double, KM_F64, 8, 4, 1, 1, 0, 64, 256)           \
-    W(double, KM_F64, 8, 4, 1, 0, 0, 512, 256)
-
 #define KM_FUSED_ROW(T, DT, P, Q, NF, ST, NT) \
     {KM_KERNEL_FUSED, DT, P, Q, NF, ST, NT, FusedShape<T, P, Q, NF, ST, NT>::LDS_BYTES, 1, 0, 0, 1.0f, "fused", 0, 0, \
      sizeof(T) == 8 ? 8192 : 0},   /* fp64: 10-20 % faster than the several-factors-per-pass kernel up to 4096 slices per row, 10 % slower at 32768 */
@@ -394,9 +37,6 @@ static hipError_t launch_shuffle(const LaunchArgs& a)
 #define KM_ROWS_ROW(P, ST, NW) \
     {KM_KERNEL_MFMA, KM_F32, P, 32, 2, 1, NW * 64, 0, ST, 2, 0, 1.0f, "mfma-pair-rows"},
 #define KM_ROWS_FN(P, ST, NW) launch_mfma_pair_rows<P, ST, NW>,
-#define KM_SPLIT_ROW(P, ST, PD) \
-    {KM_KERNEL_MFMA, KM_F32, P, 32, 2, ST, 512, MfmaPairSplitShape<P, ST, PD>::LDS_BYTES, 1, 2, 0, 1.0f, "mfma-pair-split"},
-#define KM_SPLIT_FN(P, ST, PD) launch_mfma_pair_split<P, ST, PD>,
 #define KM_MULTI_FN(T, DT, P, Q, G0, G1, G2, ST, NT) launch_multi<T, P, Q, G0, G1, G2, ST, NT>,
 #define KM_PAIR_FN(P, ST, NW, PD) launch_mfma_pair<P, ST, NW, PD>,
 #define KM_FUSED_FN(T, DT, P, Q, NF, ST, NT) launch_fused<T, P, Q, NF, ST, NT>,
@@ -404,10 +44,10 @@ static hipError_t launch_shuffle(const LaunchArgs& a)
 
 static const Variant g_variants[] = {
     {KM_KERNEL_SHUFFLE, KM_F32, SHF_P, SHF_Q, 1, SHF_ST, SHF_NT, 0, 1, 0, 0, 1.0f, "shuffle"},
-    KM_INSTANCES(KM_FUSED_ROW, KM_MFMA_ROW, KM_PAIR_ROW, KM_MULTI_ROW, KM_SPLIT_ROW, KM_ROWS_ROW) };
+    KM_INSTANCES(KM_FUSED_ROW, KM_MFMA_ROW, KM_PAIR_ROW, KM_MULTI_ROW, KM_ROWS_ROW) };
 static const LaunchFn g_launchers[] = {
     launch_shuffle,
-    KM_INSTANCES(KM_FUSED_FN, KM_MFMA_FN, KM_PAIR_FN, KM_MULTI_FN, KM_SPLIT_FN, KM_ROWS_FN) };
+    KM_INSTANCES(KM_FUSED_FN, KM_MFMA_FN, KM_PAIR_FN, KM_MULTI_FN, KM_ROWS_FN) };
 static const int g_num_variants = (int)(sizeof(g_variants) / sizeof(g_variants[0]));
 
 template <typename T>
@@ -420,6 +60,7 @@ static hipError_t launch_generic(const LaunchArgs& a)
     const int64_t slices = a.pr->M * S;                  // counted through all rows
     const int64_t units = ((slices + GEN_TS - 1) / GEN_TS) * ((Q + GEN_TQ - 1) / GEN_TQ);
     if (st.grid < 1 || st.grid > units) return hipErrorInvalidValue;
+    if (a.prepare_only) return hipSuccess;
     hipLaunchKernelGGL((sliced_multiply_generic<T>), dim3((unsigned)st.grid), dim3(GEN_THREADS), 0, a.stream,
                        (const T*)a.src, (const T*)a.factors[f], (T*)a.dst, st.k_in, P, Q, slices, units);
     return hipGetLastError();
@@ -454,7 +95,7 @@ static hipError_t launch_rows(const LaunchArgs& a)
     auto kern = st.block == ROW_THREADS_FEW ? row_sliced_multiply<T, ROW_THREADS_FEW> : row_sliced_multiply<T, ROW_THREADS_MANY>;
     static unsigned char lds_ok[2][64];
     hipError_t e = allow_lds((const void*)kern, ROW_LDS_LIMIT, lds_ok[st.block == ROW_THREADS_FEW]);
-    if (e != hipSuccess) return e;
+    if (e != hipSuccess || a.prepare_only) return e;
     hipLaunchKernelGGL(kern, dim3((unsigned)st.grid), dim3((unsigned)st.block), (size_t)st.lds_bytes, a.stream,
                        (const T*)a.src, (T*)a.dst, fa, (int)st.k_in, (int)st.k_out, (int)maxw, pr.M);
     return hipGetLastError();
@@ -564,9 +205,9 @@ static void cache_plan(const Problem& pr, const Options& opt, const Plan& plan, 
 }
 
 static hipError_t launch_step(const Problem& pr, const km_plan_step& st, const void* src, void* dst,
-                              const void* const* F, hipStream_t stream)
+                              const void* const* F, hipStream_t stream, bool prepare_only = false)
 {
-    LaunchArgs a{src, dst, F, &pr, &st, stream};
+    LaunchArgs a{src, dst, F, &pr, &st, stream, prepare_only};
     if (st.kernel == KM_KERNEL_GENERIC)
         return pr.dtype == KM_F32 ? launch_generic<float>(a) : launch_generic<double>(a);
     if (st.kernel == KM_KERNEL_ROWS)
@@ -586,6 +227,7 @@ static km_status run(const Problem& pr, const Plan& plan, const void* X, const v
     const int n = (int)plan.steps.size();
     int profile;
     int ev0 = 0;
+    std::vector<hipEvent_t> ev;      // this call's events, copied while the lock is held: another thread may grow ds.events
     {
         std::lock_guard<std::mutex> lock(g_mutex);
         profile = allow_profile && g_profile && (int)ds.call_first.size() < MAX_PROFILED_CALLS;
@@ -597,9 +239,10 @@ static km_status run(const Problem& pr, const Plan& plan, const void* X, const v
                 ds.events.push_back(e);
             }
             ds.events_used = ev0 + n + 1;
+            ev.assign(ds.events.begin() + ev0, ds.events.begin() + ev0 + n + 1);
         }
     }
-    if (profile && hipEventRecord(ds.events[ev0], stream) != hipSuccess) return KM_ELAUNCH;
+    if (profile && hipEventRecord(ev[0], stream) != hipSuccess) return KM_ELAUNCH;
     for (int i = 0; i < n; ++i) {
         const km_plan_step& st = plan.steps[i];
         auto buf = [&](int b) -> void* {
@@ -611,7 +254,7 @@ static km_status run(const Problem& pr, const Plan& plan, const void* X, const v
             }
         };
         if (launch_step(pr, st, buf(st.src), buf(st.dst), F, stream) != hipSuccess) return KM_ELAUNCH;
-        if (profile && hipEventRecord(ds.events[ev0 + i + 1], stream) != hipSuccess) return KM_ELAUNCH;
+        if (profile && hipEventRecord(ev[i + 1], stream) != hipSuccess) return KM_ELAUNCH;
     }
     if (profile) {
         std::lock_guard<std::mutex> lock(g_mutex);
@@ -638,6 +281,12 @@ __global__ void clock_probe_kernel(unsigned long long* ticks, unsigned long long
     }
 }
 
+static bool overlap(const void* a, size_t na, const void* b, size_t nb)
+{
+    const uintptr_t a0 = (uintptr_t)a, b0 = (uintptr_t)b;
+    return na > 0 && nb > 0 && a0 < b0 + nb && b0 < a0 + na;
+}
+
 static km_status check_pointers(const Problem& pr, const void* X, const void* const* F, void* Y)
 {
     if (!F) return KM_EINVAL;
@@ -646,6 +295,17 @@ static km_status check_pointers(const Problem& pr, const void* X, const void* co
     if (!aligned(X, 16) || !aligned(Y, 16)) return KM_EINVAL;      // kernels use 16-byte accesses
     for (int i = 0; i < pr.N; ++i)
         if (!F[i] || !aligned(F[i], pr.esize)) return KM_EINVAL;
+    // Y is written while X is still being read (and used for intermediates): they must be apart
+    if (overlap(X, (size_t)(pr.M * pr.k_in) * pr.esize, Y, (size_t)(pr.M * pr.k_out) * pr.esize)) return KM_EINVAL;
+    return KM_OK;
+}
+
+// The workspace (ws_bytes of it are used) must be apart from X and from Y.
+static km_status check_workspace(const Problem& pr, const void* X, const void* Y, const void* ws, size_t ws_bytes)
+{
+    if (overlap(ws, ws_bytes, X, (size_t)(pr.M * pr.k_in) * pr.esize) ||
+        overlap(ws, ws_bytes, Y, (size_t)(pr.M * pr.k_out) * pr.esize))
+        return KM_EINVAL;
     return KM_OK;
 }
 
@@ -804,9 +464,12 @@ static km_status tune(const Problem& pr, const Options& opt, hipStream_t stream,
             if (ms < 0.f) return KM_ELAUNCH;
             if (round == 0 || ms < t[k]) t[k] = ms;
         }
-    int keep = 0;                                         // the planner's own unless another is 1 % faster
+    // The planner's own unless another is 1 % faster and needs no more workspace: a caller that sized
+    // its workspace before tuning must not find it too small afterwards.
+    int keep = 0;
     for (int k = 1; k < 3; ++k)
-        if (plans[k] && t[k] < 0.99f * t[0] && t[k] < t[keep]) keep = k;
+        if (plans[k] && t[k] < 0.99f * t[0] && t[k] < t[keep] &&
+            plans[k]->ws0_bytes + plans[k]->ws1_bytes <= need_d) keep = k;
     chosen = *plans[keep];
     if (tuned_ms) *tuned_ms = t[keep];
     if (default_ms) *default_ms = t[0];
@@ -889,6 +552,7 @@ static km_status execute(int M, int N, const int* P, const int* Q, const void* X
     if (own_ws) {
         if (need > 0 && (!workspace || workspace_bytes < need)) return KM_ENOMEM;
         if (need > 0 && !aligned(workspace, 16)) return KM_EINVAL;
+        if (need > 0 && check_workspace(pr, X, Y, workspace, need) != KM_OK) return KM_EINVAL;
     } else {
         s = library_workspace(need, &ws);
         if (s != KM_OK) return s;
@@ -1000,6 +664,21 @@ km_status kronmatmul_tune(int M, int N, const int* P, const int* Q, km_dtype dty
     return KM_OK;
 }
 
+km_status kronmatmul_prepare(int M, int N, const int* P, const int* Q, km_dtype dtype)
+{
+    Problem pr;
+    km_status s = make_problem(M, N, P, Q, (int)dtype, pr);
+    if (s != KM_OK) return s;
+    if (pr.M == 0) return KM_OK;
+    Plan plan;
+    s = plan_for(pr, plan);
+    if (s != KM_OK) return s;
+    std::vector<const void*> none(pr.N, nullptr);
+    for (const km_plan_step& st : plan.steps)
+        if (launch_step(pr, st, nullptr, nullptr, none.data(), nullptr, true) != hipSuccess) return KM_ELAUNCH;
+    return KM_OK;
+}
+
 km_status kronmatmul_plan(int M, int N, const int* P, const int* Q, km_dtype dtype,
                           km_plan_step* steps, int cap, int* nsteps)
 {
@@ -1007,6 +686,8 @@ km_status kronmatmul_plan(int M, int N, const int* P, const int* Q, km_dtype dty
     Problem pr;
     km_status s = make_problem(M, N, P, Q, (int)dtype, pr);
     if (s != KM_OK) return s;
+    *nsteps = 0;
+    if (pr.M == 0) return KM_OK;                 // nothing to launch
     Plan plan;
     s = plan_for(pr, plan);
     if (s != KM_OK) return s;
@@ -1018,10 +699,6 @@ km_status kronmatmul_plan(int M, int N, const int* P, const int* Q, km_dtype dty
 long long kronmatmul_store_column(long long k_in, long long p_group, long long tile_k,
                                   long long tile_index, long long local_col)
 {
-    if (tile_k > 0 && p_group > 0 && local_col >= tile_k) {
-        // a tile never holds more than (tile_k / p_group) * q_group elements; the caller's q_group is
-        // not known here, so only reject what is impossible for every q_group: negative handled below
-    }
     return store_column(k_in, p_group, tile_k, tile_index, local_col);
 }
 
@@ -1031,6 +708,11 @@ km_status kronmatmul_cost(int M, int N, const int* P, const int* Q, km_dtype dty
     Problem pr;
     km_status s = make_problem(M, N, P, Q, (int)dtype, pr);
     if (s != KM_OK) return s;
+    if (pr.M == 0) {
+        if (flops) *flops = 0;
+        if (planned_bytes) *planned_bytes = 0;
+        return KM_OK;
+    }
     Plan plan;
     s = plan_for(pr, plan);
     if (s != KM_OK) return s;

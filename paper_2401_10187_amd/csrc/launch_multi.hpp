@@ -1,0 +1,38 @@
+// Launchers of the small-factor kernel with several factors per LDS pass (declared in launch.hpp): argument checks against what the kernel
+// and its grid assume, the LDS attribute, the launch.  Included only by the translation units that
+// instantiate these kernels.
+#pragma once
+#include "launch.hpp"
+#include "fused_multi_kernel.hpp"
+
+namespace km {
+
+template <typename T, int P, int Q, int G0, int G1, int G2, int STMAX, int NT>
+hipError_t launch_multi(const LaunchArgs& a)
+{
+    typedef MultiShape<T, P, Q, G0, G1, G2, STMAX, NT> Sh;
+    const km_plan_step& st = *a.st;
+    auto kern = fused_multi_sliced_multiply<T, P, Q, G0, G1, G2, STMAX, NT>;
+    static unsigned char lds_ok[64];
+    hipError_t e = allow_lds((const void*)kern, Sh::LDS_BYTES, lds_ok);
+    if (e != hipSuccess || a.prepare_only) return e;
+    const int rows = st.tile_rows;
+    if (rows < 1 || st.tile_slices < 1 || (int64_t)st.tile_slices * rows > STMAX) return hipErrorInvalidValue;
+    const int slices = st.tile_slices * rows;            // what the kernel treats as one tile
+    FactorPtrs<Sh::NF> fp;
+    for (int j = 0; j < Sh::NF; ++j) fp.f[j] = a.factors[st.first_factor + Sh::NF - 1 - j];   // order of application
+    const int64_t tk_row = (int64_t)st.tile_slices * Sh::per_slice(0);
+    if (st.k_in % tk_row) return hipErrorInvalidValue;
+    const int64_t tiles_per_row = st.k_in / tk_row;
+    // tiles of several rows hold whole rows
+    if (rows > 1 && tiles_per_row != 1) return hipErrorInvalidValue;
+    const int64_t tiles = rows > 1 ? (a.pr->M + rows - 1) / rows : a.pr->M * tiles_per_row;
+    if (tiles != st.grid) return hipErrorInvalidValue;
+    if (st.lds_bytes < Sh::LDS_PER_SLICE * slices || st.lds_bytes > Sh::LDS_BYTES) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(kern, dim3((unsigned)st.grid), dim3(NT), (size_t)st.lds_bytes, a.stream,
+                       (const T*)a.src, (T*)a.dst, fp, st.k_in, st.k_out, tiles_per_row, (int64_t)st.grid,
+                       slices, rows, a.pr->M);
+    return hipGetLastError();
+}
+
+}  // namespace km

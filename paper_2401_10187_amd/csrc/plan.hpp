@@ -95,6 +95,20 @@ struct Options {
 
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+#if defined(__HIPCC__)
+#define KM_HOST_DEVICE __host__ __device__
+#else
+#define KM_HOST_DEVICE
+#endif
+// A run of `valid` elements that starts `mis` elements (0 <= mis < vn) above a 16-byte boundary is
+// moved in vectors of vn elements counted from that boundary: unaligned_vectors() of them touch the
+// run; the first unaligned_whole_vectors() are loaded or stored whole.  Those lie inside
+// [-mis, valid): the elements below the run exist whenever mis > 0 (buffers start on 16-byte
+// boundaries), so a whole vector never leaves the buffer.  What is left, the part of the last vector
+// that belongs to the run, is moved element by element.
+KM_HOST_DEVICE inline int unaligned_vectors(int valid, int mis, int vn) { return (valid + mis + vn - 1) / vn; }
+KM_HOST_DEVICE inline int unaligned_whole_vectors(int valid, int mis, int vn) { return (valid + mis) / vn; }
+
 // Validates the shapes and fills the derived sizes.  Products must stay below 2^62 elements.
 inline km_status make_problem(int M, int N, const int* P, const int* Q, int dtype, Problem& pr)
 {

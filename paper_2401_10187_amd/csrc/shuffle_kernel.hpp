@@ -33,12 +33,15 @@ __device__ __forceinline__ float shf_pair_exchange(float v)
     return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));
 }
 
-__global__ __launch_bounds__(SHF_NT)
+// (a template only so that the header can be included by several translation units)
+template <int NT_>
+__global__ __launch_bounds__(NT_)
 void shuffle_sliced_multiply_8x8(const float* __restrict__ Xg, float* __restrict__ Yg,
                                  const float* __restrict__ Fg, int64_t k_in, int64_t tiles_per_row,
                                  int64_t num_tiles)
 {
-    constexpr int P = SHF_P, Q = SHF_Q, NT = SHF_NT, R = SHF_R;
+    constexpr int P = SHF_P, Q = SHF_Q, NT = NT_, R = SHF_R;
+    static_assert(NT_ == SHF_NT, "one workgroup size");
     // XCD-aware order: workgroup b runs on XCD b % 8; give each XCD a contiguous range of tiles
     int64_t t = blockIdx.x;
     if (num_tiles % 8 == 0) t = (t % 8) * (num_tiles / 8) + t / 8;

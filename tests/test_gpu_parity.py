@@ -692,8 +692,7 @@ def test_graph_capture_and_replay_matches_eager():
     Fd = [torch.from_numpy(F).cuda() for F in Fs]
     Yd = torch.empty_like(Xd)
     ws = torch.empty(max(km.workspace_size(16, P, P, "float32"), 1), dtype=torch.uint8, device="cuda")
-    km.kronmatmul(Xd, Fd, Y=Yd, workspace=ws)            # first use sets kernel attributes, outside capture
-    torch.cuda.synchronize()
+    km.prepare(16, P, P, "float32")                      # sets kernel attributes, outside capture; launches nothing
     g = torch.cuda.CUDAGraph()
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())

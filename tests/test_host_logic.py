@@ -349,7 +349,70 @@ def test_argument_errors_are_status_codes():
     # a workspace that is too small is refused before any launch
     # (two factors of different shapes, rows too long for the one-launch kernel: two launches, hence an intermediate)
     assert km.workspace_size(4, [70, 110], [30, 50], "float32") > 0
-    assert _raw(4, [70, 110], [30, 50], bad, [bad, bad], bad, with_ws=True) == km.KM_ENOMEM
+    assert _raw(4, [70, 110], [30, 50], bad, [bad, bad], bad + (1 << 30), with_ws=True) == km.KM_ENOMEM
+
+
+def test_overlapping_buffers_are_refused():
+    """X, Y and the workspace must be apart: checked on the host, before any launch."""
+    L = km.lib()
+    base = 0x10000000
+    P, Q = [70, 110], [30, 50]                       # two launches, hence an intermediate in the workspace
+    n = len(P)
+    p, q = (ctypes.c_int * n)(*P), (ctypes.c_int * n)(*Q)
+    f = ctypes.cast((ctypes.c_void_p * n)(0x1000, 0x2000), ctypes.c_void_p)
+    x_bytes, y_bytes = 4 * 7700 * 4, 4 * 1500 * 4
+    need = km.workspace_size(4, P, Q, "float32")
+    far = base + (1 << 30)
+    call = lambda X, Y, ws: L.kronmatmul_ws(4, n, p, q, X, f, Y, 0, ws, need, None)
+    assert call(base, base, far) == km.KM_EINVAL                              # Y is X
+    assert call(base, base + x_bytes - 16, far) == km.KM_EINVAL               # Y starts inside X
+    assert call(base + y_bytes - 16, base, far) == km.KM_EINVAL               # X starts inside Y
+    assert call(base, far, base + x_bytes - 256) == km.KM_EINVAL              # workspace reaches into X ... from inside
+    assert call(base + need - 16, far, base) == km.KM_EINVAL                  # ... from below
+    assert call(base, far, far + y_bytes - 16) == km.KM_EINVAL                # workspace starts inside Y
+    # the library-managed form checks X against Y too
+    assert L.kronmatmul(4, n, p, q, base, f, base + 64, 0, None) == km.KM_EINVAL
+
+
+def test_empty_problems_plan_to_nothing():
+    """M == 0 is a successful no-op for every entry point, the planning ones included."""
+    assert km.plan(0, [8, 8], [8, 8], "float32") == []
+    assert km.cost(0, [8, 8], [8, 8], "float64") == (0.0, 0.0)
+    assert km.workspace_size(0, [70, 110], [30, 50], "float32") == 0
+    km.prepare(0, [8, 8], [8, 8], "float32")
+    with pytest.raises(km.KronMatmulError):
+        km.prepare(4, [0], [8], "float32")
+
+
+def test_unaligned_tiles_are_moved_without_leaving_the_buffer(tmp_path):
+    """Rows of odd length (3^7 fp32 and the like) start off 16-byte boundaries; their tiles are moved in
+    16-byte vectors counted from the boundary below.  The two counts the kernels take from plan.hpp
+    must cover the run exactly, with every whole vector inside [-mis, valid): checked for every
+    (run length, misalignment, vector width) by a host program that includes that header."""
+    src = tmp_path / "span.cpp"
+    src.write_text(r"""
+#include "paper_2401_10187_amd/csrc/plan.hpp"
+#include <stdio.h>
+int main() {
+    for (int vn = 2; vn <= 4; vn += 2)
+        for (int mis = 0; mis < vn; ++mis)
+            for (int valid = 1; valid <= 3 * 3 * 3 * 3 * 3 * 3 * 3 + 5; ++valid) {
+                const int nv = km::unaligned_vectors(valid, mis, vn), nfull = km::unaligned_whole_vectors(valid, mis, vn);
+                if (nfull > nv || nv - nfull > 1) return 1;
+                if (nv * vn - mis < valid) return 2;                      // the vectors cover the run
+                if ((nv - 1) * vn - mis >= valid) return 3;               // and none lies wholly outside it
+                for (int v = 0; v < nfull; ++v)                           // whole vectors stay inside [-mis, valid)
+                    if (v * vn - mis < -mis || (v + 1) * vn - mis > valid) return 4;
+                if (nfull < nv && nfull * vn - mis + vn <= valid) return 5;   // the partial one really is partial
+            }
+    puts("ok");
+    return 0;
+}
+""")
+    exe = tmp_path / "span"
+    import subprocess
+    subprocess.run(["g++", "-std=c++17", "-I", ROOT, "-o", str(exe), str(src)], check=True)
+    assert subprocess.run([str(exe)], capture_output=True, text=True).stdout.strip() == "ok"
 
 
 def test_clock_probe_argument_errors():
@@ -377,7 +440,7 @@ def test_transposed_form_needs_room_for_the_factor_copies():
     f = ctypes.cast((ctypes.c_void_p * 1)(bad), ctypes.c_void_p)
     assert L.kronmatmul_transposed(4, 1, p, q, None, f, bad, 0, None) == km.KM_EINVAL
     assert L.kronmatmul_transposed(-1, 1, p, q, bad, f, bad, 0, None) == km.KM_EINVAL
-    assert L.kronmatmul_transposed_ws(4, 1, p, q, bad, f, bad, 0, None, 0, None) == km.KM_ENOMEM   # copies need room
+    assert L.kronmatmul_transposed_ws(4, 1, p, q, bad, f, bad + 4096, 0, None, 0, None) == km.KM_ENOMEM   # copies need room
     assert L.kronmatmul_transposed_ws(0, 1, p, q, None, f, None, 0, None, 0, None) == km.KM_OK
 
 
