@@ -1,0 +1,318 @@
+"""rocprofv3 harness for the Kron-Matmul kernels: achieved HBM GB/s, HBM traffic from the memory
+counters, matrix-core (MFMA) utilisation and LDS bank-conflict rate of a workload's kernels, against
+the chip's published peaks.
+
+    python3 -m paper_2401_10187_amd.profile collect   --workload c3_f32_m1024_32x32x4 [--dir gpurun_out/prof]
+    python3 -m paper_2401_10187_amd.profile summarise --workload c3_f32_m1024_32x32x4 [--dir gpurun_out/prof]
+
+`collect` needs the GPU: it runs the benchmark once plainly and then once under rocprofv3 per pass (the
+profiler collects one counter set per run), the program after `--` always being `python3 bench.py ...`
+itself.  Every run has its own time limit; the first failure ends the collection.  `summarise` needs
+only the files `collect` left and writes profiles/<kernel>__<workload>.md: the kernel-trace statistics,
+the counters, what was derived from them and how, and every command that was run.
+
+Passes (one rocprofv3 run each):
+  stats       --kernel-trace --stats of the default benchmark command (kernel durations)
+  fetch       --pmc FETCH_SIZE  with a copy kernel of known size in the same run (HBM bytes read)
+  write       --pmc WRITE_SIZE  the same for bytes written
+  pipes       --pmc matrix-core busy cycles, MFMA operation counts, LDS bank-conflict and active cycles
+  stalls_sq   --pmc wave cycles and what the waves wait for (optional, --passes)
+  stalls_mem  --pmc write-request sizes and stalls in the L2 / texture path (optional, --passes)
+"""
+import argparse
+import collections
+import csv
+import glob
+import json
+import os
+import re
+import subprocess
+import sys
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+BENCH = os.path.join(ROOT, "bench.py")
+
+PIPES = ["SQ_VALU_MFMA_BUSY_CYCLES", "SQ_BUSY_CU_CYCLES", "SQ_INSTS_VALU_MFMA_MOPS_F32", "SQ_INSTS_VALU_MFMA_MOPS_F64",
+         "SQ_LDS_BANK_CONFLICT", "SQ_LDS_IDX_ACTIVE", "SQ_WAVE_CYCLES", "GRBM_GUI_ACTIVE"]
+STALLS_SQ = ["SQ_WAVE_CYCLES", "SQ_BUSY_CYCLES", "SQ_WAIT_ANY", "SQ_WAIT_INST_ANY", "SQ_WAIT_INST_LDS",
+             "SQ_ACTIVE_INST_VMEM", "SQ_ACTIVE_INST_LDS", "SQ_ACTIVE_INST_VALU"]
+STALLS_MEM = ["TCC_EA0_WRREQ_sum", "TCC_EA0_WRREQ_64B_sum", "TCC_EA0_WRREQ_STALL_sum", "TCC_TAG_STALL_sum",
+              "TCP_PENDING_STALL_CYCLES_sum", "TCP_TCR_TCP_STALL_CYCLES_sum", "TCP_TCC_READ_REQ_sum",
+              "TCP_TCC_WRITE_REQ_sum", "TA_BUSY_avr", "TA_ADDR_STALLED_BY_TC_CYCLES_sum"]
+SHORT = ["--steps", "5", "--warmup", "2", "--no-settle", "--no-cpu-baseline", "--only-headline"]
+
+PASSES = {
+    # name: (rocprofv3 options, extra benchmark options, time limit in seconds)
+    "stats": (["--kernel-trace", "--stats"], ["--no-cpu-baseline", "--only-headline"], 240),
+    "fetch": (["--pmc", "FETCH_SIZE"], SHORT + ["--calibrate-copy"], 180),
+    "write": (["--pmc", "WRITE_SIZE"], SHORT + ["--calibrate-copy"], 180),
+    "pipes": (["--pmc"] + PIPES, SHORT, 180),
+    "stalls_sq": (["--pmc"] + STALLS_SQ, SHORT, 180),
+    "stalls_mem": (["--pmc"] + STALLS_MEM, SHORT, 180),
+}
+DEFAULT_PASSES = "stats,fetch,write,pipes"
+
+
+def bench_args(workload):
+    return ["--shape", workload[len("shape_"):]] if workload.startswith("shape_") else ["--workload", workload]
+
+
+def pass_command(workload, name, outdir):
+    opts, extra, limit = PASSES[name]
+    kill = ["timeout", "-s", "KILL", str(limit)]
+    return kill + ["rocprofv3"] + opts + ["--output-format", "csv", "-d", os.path.join(outdir, name), "-o", "p", "--",
+                                          "python3", BENCH] + bench_args(workload) + extra
+
+
+def collect(workload, base, passes):
+    outdir = os.path.join(base, workload)
+    os.makedirs(outdir, exist_ok=True)
+    env = dict(os.environ, TMPDIR="/tmp")
+    plain = ["timeout", "-k", "10", "300", "python3", BENCH] + bench_args(workload) + ["--only-headline"]
+    print("profile: " + " ".join(plain), flush=True)
+    proc = subprocess.run(plain, cwd="/tmp", env=env, stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True)
+    open(os.path.join(outdir, "bench.json"), "w").write(proc.stdout)
+    if proc.returncode != 0:
+        sys.stderr.write(proc.stderr[-3000:])
+        sys.exit("profile: the plain benchmark run failed with status %d; nothing further is run" % proc.returncode)
+    for name in passes:
+        cmd = pass_command(workload, name, outdir)
+        print("profile: " + " ".join(cmd), flush=True)
+        with open(os.path.join(outdir, name + ".log"), "w") as log:
+            rc = subprocess.run(cmd, cwd="/tmp", env=env, stdout=log, stderr=subprocess.STDOUT).returncode
+        if rc != 0:
+            sys.exit("profile: pass %s ended with status %d (log: %s); nothing further is run"
+                     % (name, rc, os.path.join(outdir, name + ".log")))
+    print("profile: collected %s into %s" % (",".join(passes), outdir), flush=True)
+
+
+# ------------------------------------------------------------------------------------------------
+# summary
+# ------------------------------------------------------------------------------------------------
+def short_name(kernel):
+    return kernel.split("(")[0].replace("void ", "").strip()
+
+
+def is_ours(kernel):
+    return "km::" in kernel
+
+
+def find_csv(folder, suffix):
+    hits = glob.glob(os.path.join(folder, "**", "*" + suffix), recursive=True)
+    return hits[0] if hits else None
+
+
+def read_counters(folder):
+    """{(kernel, grid size): {counter: [value per dispatch]}} plus per-kernel register/LDS figures."""
+    path = find_csv(folder, "counter_collection.csv")
+    agg = collections.defaultdict(lambda: collections.defaultdict(list))
+    info = {}
+    if not path:
+        return agg, info
+    for r in csv.DictReader(open(path)):
+        key = (short_name(r["Kernel_Name"]), int(r["Grid_Size"]))
+        agg[key][r["Counter_Name"]].append(float(r["Counter_Value"]))
+        info[key] = dict(vgpr=r.get("VGPR_Count"), agpr=r.get("Accum_VGPR_Count"), sgpr=r.get("SGPR_Count"),
+                         lds=r.get("LDS_Block_Size"), scratch=r.get("Scratch_Size"), wg=r.get("Workgroup_Size"))
+    return agg, info
+
+
+def mean(v):
+    return sum(v) / len(v) if v else float("nan")
+
+
+def problem_of(workload):
+    sys.path.insert(0, ROOT)
+    import bench
+    import kron_inputs
+    if workload.startswith("shape_"):
+        M, shapes, dtype = bench.parse_shape(workload[len("shape_"):])
+    elif workload in kron_inputs.CONFIGS:
+        c = kron_inputs.CONFIGS[workload]
+        M, shapes, dtype = c["M"], c["shapes"], c["dtype"]
+    else:
+        case = {t[0]: t for t in kron_inputs.TABLE4}[int(workload.split("_")[1][2:])]
+        M, shapes, dtype = case[1], case[2], "float64" if workload.endswith("_f64") else "float32"
+    return M, shapes, dtype
+
+
+def summarise(workload, base, out_folder):
+    d = os.path.join(base, workload)
+    bj = json.loads([l for l in open(os.path.join(d, "bench.json")) if l.startswith("{")][-1])
+    rf, cfg = bj["roofline"], bj["config"]
+    M, shapes, dtype = problem_of(workload)
+    es = 4 if dtype == "float32" else 8
+    L = []
+    add = L.append
+
+    # ---- kernel-trace statistics
+    stats_csv, trace_csv = find_csv(os.path.join(d, "stats"), "kernel_stats.csv"), find_csv(os.path.join(d, "stats"), "kernel_trace.csv")
+    add("## Kernel time: `rocprofv3 --kernel-trace --stats`\n")
+    add("    " + " ".join(pass_command(workload, "stats", os.path.join(base, workload))).replace(ROOT + "/", "") + "\n")
+    dom_grid, dom_mean_us = None, None
+    if stats_csv and trace_csv:
+        add("| Name | Calls | TotalDurationNs | AverageNs | Percentage | MinNs | MaxNs | StdDev |\n|---|---|---|---|---|---|---|---|")
+        for r in csv.DictReader(open(stats_csv)):
+            add("| %s | %s | %s | %.1f | %s | %s | %s | %.1f |" % (short_name(r["Name"])[-90:], r["Calls"], r["TotalDurationNs"],
+                                                                 float(r["AverageNs"]), r["Percentage"], r["MinNs"], r["MaxNs"], float(r["StdDev"])))
+        by = collections.defaultdict(list)
+        for r in csv.DictReader(open(trace_csv)):
+            if is_ours(r["Kernel_Name"]):
+                by[(short_name(r["Kernel_Name"]), int(r["Grid_Size_X"]))].append(int(r["End_Timestamp"]) - int(r["Start_Timestamp"]))
+        # the command runs: warm-up steps, settling batches, the timed steps, one more pass next to the clock probe
+        sj = bj
+        log = os.path.join(d, "stats.log")
+        if os.path.exists(log):
+            own = [l for l in open(log, errors="replace") if l.startswith('{"metric"')]
+            if own:
+                sj = json.loads(own[-1])
+        steps, total_steps = sj["steps"], sj["warmup"] + sj["config"]["settle_steps"] + 2 * sj["steps"]
+        add("\nPer launch shape (kernel, grid in work-items), all calls, and the calls of the timed region alone (the %d Kron-Matmuls "
+            "before the last %d, which run next to the clock probe):\n" % (steps, steps))
+        add("| kernel | grid | calls | mean us | min us | timed-region mean us |\n|---|---|---|---|---|---|")
+        for k, v in sorted(by.items()):
+            per_step = len(v) // total_steps if total_steps and len(v) % total_steps == 0 else 0
+            timed = v[-2 * steps * per_step:-steps * per_step] if per_step else []
+            tm = mean(timed) / 1e3 if timed else float("nan")
+            add("| %s | %d | %d | %.1f | %.1f | %.1f |" % (k[0][-90:], k[1], len(v), mean(v) / 1e3, min(v) / 1e3, tm))
+            if timed and (dom_mean_us is None or tm * per_step > dom_mean_us[1]):
+                dom_grid, dom_mean_us = k, (tm, tm * per_step)
+        add("\nThe same command without the profiler (`bench.py`, HIP events around every launch inside the timed region): "
+            "dominant kernel %s %.1f us per launch; %.4f ms per Kron-Matmul = %.0f GFLOP/s; shader clock under load %s MHz."
+            % (rf["kernel"], rf["kernel_ms"] * 1e3, bj["ms_per_step"], bj["value"], cfg["shader_clock_mhz_under_load"]))
+        add("Roofline of that kernel: algorithmic bytes per launch %s B (rows read + rows written + factors), flops per launch %s; "
+            "bound %s: %s %s of %s = %.3f (HBM fraction %.3f of 8000 GB/s, flop fraction %.3f of the published %s peak).\n"
+            % (format(rf["algorithmic_bytes_per_launch"], ","), format(rf["flops_per_launch"], ","), rf["bound"], rf["achieved"],
+               rf["unit"], rf["peak"], rf["frac"], rf["alt_frac_hbm"], rf["alt_frac_flops"], dtype))
+    else:
+        add("(pass not collected)\n")
+
+    # ---- HBM traffic
+    traffic = None
+    fetch, _ = read_counters(os.path.join(d, "fetch"))
+    write, _ = read_counters(os.path.join(d, "write"))
+    add("## HBM traffic: `rocprofv3 --pmc FETCH_SIZE`, `--pmc WRITE_SIZE` (one counter per run)\n")
+    for n in ("fetch", "write"):
+        add("    " + " ".join(pass_command(workload, n, os.path.join(base, workload))).replace(ROOT + "/", ""))
+    if fetch and write:
+        add("\n`--calibrate-copy` adds one plain elementwise kernel (torch `mul(X, 1.0, out=...)`) that reads X once and writes as "
+            "many bytes; its readings give each counter's scale.\n")
+        add("| kernel | grid | dispatches | FETCH_SIZE mean | WRITE_SIZE mean |\n|---|---|---|---|---|")
+        keys = sorted(set(fetch) | set(write))
+        for k in keys:
+            add("| %s | %d | %d | %.2f | %.2f |" % (k[0][-90:], k[1], len(fetch.get(k, {}).get("FETCH_SIZE", [])),
+                                                    mean(fetch.get(k, {}).get("FETCH_SIZE", [])), mean(write.get(k, {}).get("WRITE_SIZE", []))))
+        cal = [k for k in keys if "elementwise" in k[0]]
+        if cal:
+            kin = 1
+            for p, _q in shapes:
+                kin *= p
+            ncal = len(fetch[cal[0]]["FETCH_SIZE"])       # torch splits tensors above 2^31 bytes into several dispatches
+            cal_kib = M * kin * es / 1024.0 / ncal
+            sf = cal_kib / mean(fetch[cal[0]]["FETCH_SIZE"])
+            sw = cal_kib / mean(write[cal[0]]["WRITE_SIZE"])
+            add("\nThe copy kernel moves %s KiB each way per dispatch (%d dispatch(es)): scale FETCH_SIZE x%.5f, WRITE_SIZE x%.5f "
+                "(KiB per counter unit)." % (format(cal_kib, ",.0f"), ncal, sf, sw))
+            best = None
+            for k in keys:
+                if is_ours(k[0]) and k in fetch and k in write:
+                    t = (mean(fetch[k]["FETCH_SIZE"]) * sf + mean(write[k]["WRITE_SIZE"]) * sw) * 1024
+                    add("Scaled HBM traffic of %s (grid %d): %s B per launch." % (k[0][-70:], k[1], format(t, ",.0f")))
+                    if best is None or k == dom_grid:
+                        best = t
+            traffic = int(round(best)) if best is not None else None
+            if traffic:
+                add("Dominant kernel: %s B measured against %s B algorithmic = %.4f x.\n"
+                    % (format(traffic, ","), format(rf["algorithmic_bytes_per_launch"], ","), traffic / rf["algorithmic_bytes_per_launch"]))
+    else:
+        add("\n(pass not collected)\n")
+
+    # ---- pipes
+    pipes, info = read_counters(os.path.join(d, "pipes"))
+    add("## Matrix cores and LDS: `rocprofv3 --pmc` (one run)\n")
+    add("    " + " ".join(pass_command(workload, "pipes", os.path.join(base, workload))).replace(ROOT + "/", "") + "\n")
+    if pipes:
+        add("Counter means per dispatch, summed over the chip by the profiler.  Derived figures:\n"
+            "- MFMA busy = SQ_VALU_MFMA_BUSY_CYCLES / (GRBM_GUI_ACTIVE x 1024 SIMDs): the profiler's own MfmaUtil expression "
+            "(GRBM_GUI_ACTIVE, the cycles the dispatch kept the chip busy, is read per XCD; the mean over the 8 XCDs is used);\n"
+            "- MFMA TFLOP/s = 512 x SQ_INSTS_VALU_MFMA_MOPS_F32 (256 x ..._F64) flops / kernel duration: an independent count of "
+            "the matrix work actually issued (one MOPS unit is 512 fp32 or 256 fp64 flops);\n"
+            "- LDS bank-conflict rate = SQ_LDS_BANK_CONFLICT / SQ_LDS_IDX_ACTIVE: the share of LDS-active cycles lost to conflicts "
+            "(the shared-memory transaction counts of the paper's Table 2 have no direct counterpart on this chip).\n")
+        add("| kernel | grid | VGPR+AGPR | LDS B | " + " | ".join(c.replace("SQ_", "").replace("INSTS_VALU_", "") for c in PIPES) + " |")
+        add("|---|---|---|---|" + "---|" * len(PIPES))
+        for k in sorted(pipes):
+            if not is_ours(k[0]):
+                continue
+            i = info.get(k, {})
+            add("| %s | %d | %s+%s | %s | " % (k[0][-70:], k[1], i.get("vgpr"), i.get("agpr"), i.get("lds"))
+                + " | ".join("%.4g" % mean(pipes[k].get(c, [])) for c in PIPES) + " |")
+        add("")
+        for k in sorted(pipes):
+            if not is_ours(k[0]):
+                continue
+            c = {n: mean(pipes[k].get(n, [])) for n in PIPES}
+            gui = c["GRBM_GUI_ACTIVE"] / 8.0
+            busy = c["SQ_VALU_MFMA_BUSY_CYCLES"] / (gui * 1024.0) if gui > 0 else float("nan")
+            conf = c["SQ_LDS_BANK_CONFLICT"] / c["SQ_LDS_IDX_ACTIVE"] if c["SQ_LDS_IDX_ACTIVE"] > 0 else 0.0
+            flops = 512.0 * c["SQ_INSTS_VALU_MFMA_MOPS_F32"] + 256.0 * c["SQ_INSTS_VALU_MFMA_MOPS_F64"]
+            add("%s (grid %d): MFMA busy %.1f %%; MFMA flops issued %.4g per launch; LDS bank-conflict rate %.2f %% "
+                "(LDS active %.1f %% of the busy cycles of a CU)."
+                % (k[0][-70:], k[1], 100 * busy, flops, 100 * conf,
+                   100 * c["SQ_LDS_IDX_ACTIVE"] / (gui * 256.0) if gui > 0 else float("nan")))
+        add("")
+    else:
+        add("(pass not collected)\n")
+
+    # ---- stalls (optional passes)
+    for pname, names, title in (("stalls_sq", STALLS_SQ, "What the waves wait for"), ("stalls_mem", STALLS_MEM, "L2 and texture path")):
+        st, _ = read_counters(os.path.join(d, pname))
+        if not st:
+            continue
+        add("## %s: `rocprofv3 --pmc` (one run)\n" % title)
+        add("    " + " ".join(pass_command(workload, pname, os.path.join(base, workload))).replace(ROOT + "/", "") + "\n")
+        add("| kernel | grid | " + " | ".join(n.replace("_sum", "") for n in names) + " |")
+        add("|---|---|" + "---|" * len(names))
+        for k in sorted(st):
+            if is_ours(k[0]):
+                add("| %s | %d | " % (k[0][-70:], k[1]) + " | ".join("%.4g" % mean(st[k].get(n, [])) for n in names) + " |")
+        add("")
+
+    head = ["# %s on workload %s" % (rf["kernel"], workload), "",
+            "workload: %s" % workload, "kernel: %s" % rf["kernel"],
+            "hbm_traffic_bytes_per_launch: %s" % (traffic if traffic is not None else "unmeasured"),
+            "algorithmic_bytes_per_launch: %d" % rf["algorithmic_bytes_per_launch"], "",
+            "Launches per Kron-Matmul: %s; per-launch ms from HIP events inside `bench.py`: %s."
+            % (cfg["launches"], cfg["per_launch_ms"]),
+            "Collected with `python3 -m paper_2401_10187_amd.profile collect --workload %s`, written by its `summarise` "
+            "(commands are relative to the repository root; the harness runs them from /tmp with TMPDIR=/tmp).\n" % workload]
+    name = re.sub(r"[^A-Za-z0-9]+", "_", rf["kernel"]).strip("_") + "__" + workload.replace(":", "_").replace("^", "p").replace(",", "_") + ".md"
+    os.makedirs(out_folder, exist_ok=True)
+    path = os.path.join(out_folder, name)
+    open(path, "w").write("\n".join(head + L) + "\n")
+    print("wrote", os.path.relpath(path, ROOT))
+    return path
+
+
+def main():
+    ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
+    ap.add_argument("mode", choices=["collect", "summarise"])
+    ap.add_argument("--workload", action="append", required=True,
+                    help="a workload name of bench.py (c1..c5, table4_id<k>[_f64]) or shape_<M:PxQ^N:f32>; may be repeated")
+    ap.add_argument("--dir", default=os.path.join(ROOT, "gpurun_out", "prof"))
+    ap.add_argument("--passes", default=DEFAULT_PASSES, help="comma-separated; known: " + ",".join(PASSES))
+    ap.add_argument("--out", default=os.path.join(ROOT, "profiles"))
+    args = ap.parse_args()
+    passes = [p for p in args.passes.split(",") if p]
+    for p in passes:
+        if p not in PASSES:
+            sys.exit("profile: unknown pass %r" % p)
+    for w in args.workload:
+        if args.mode == "collect":
+            collect(w, args.dir, passes)
+        else:
+            summarise(w, args.dir, args.out)
+
+
+if __name__ == "__main__":
+    main()
