@@ -102,7 +102,8 @@ km_status kronmatmul(int M, int N, const int* P, const int* Q,
 
 /* Set-up for a problem on the current HIP device, outside any timed or captured region: plans it
  * (the plan is memoised) and sets the attributes of every kernel instance the plan launches, so that
- * later kronmatmul_ws calls for this problem do nothing but enqueue kernels.  Launches nothing. */
+ * later kronmatmul_ws calls for this problem do nothing but enqueue kernels.  Also looks up the
+ * address of kronmatmul_static's array on this device.  Launches nothing. */
 km_status kronmatmul_prepare(int M, int N, const int* P, const int* Q, km_dtype dtype);
 
 /* Same, with a caller-provided device workspace of at least kronmatmul_workspace_size bytes
@@ -110,6 +111,22 @@ km_status kronmatmul_prepare(int M, int N, const int* P, const int* Q, km_dtype 
 km_status kronmatmul_ws(int M, int N, const int* P, const int* Q,
                         const void* X, const void* const* F, void* Y,
                         km_dtype dtype, void* workspace, size_t workspace_bytes, void* stream);
+
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid it): kronmatmul_ws with the workspace taken from an array that is part of the
+ * library's device code, KM_STATIC_SCRATCH_BYTES per GPU, held from the moment the library's code is
+ * loaded on a GPU until the process ends.  Calls no hipMalloc / hipFree and creates no events; the
+ * caller still passes X, F and Y.  KM_ENOMEM, before anything is enqueued, if the problem's
+ * intermediates (kronmatmul_workspace_size) exceed KM_STATIC_SCRATCH_BYTES.  The array's address on
+ * a device is looked up on the first call there, or by kronmatmul_prepare.  Every call on a GPU uses
+ * that GPU's one array: calls that overlap in time on one GPU (different streams or threads) race
+ * and must be serialised by the caller.  Nothing in it needs clearing between calls: every
+ * intermediate element is written by one launch before the next launch reads it.  Calls made while
+ * KM_OPT_PROFILE is 1 are not profiled. */
+#define KM_STATIC_SCRATCH_BYTES (16u << 20)
+km_status kronmatmul_static(int M, int N, const int* P, const int* Q,
+                            const void* X, const void* const* F, void* Y,
+                            km_dtype dtype, void* stream);
 
 /* The same product with every factor given transposed: Ft[i] is the Q[i] x P[i] row-major array
  * whose transpose is the factor applied, Y = X * (Ft[0]^T (x) ... (x) Ft[N-1]^T); X is M x prod(P),

@@ -9,4 +9,5 @@ from .binding import (  # noqa: F401
     KM_OPT_KERNELS, KM_OPT_MAX_FUSE, KM_OPT_PROFILE, KM_OPT_PREFER_TILE, KM_OPT_PREFER_THREADS, KM_OPT_TILES_PER_WG, KM_OPT_PAIR_INTERLEAVE, KM_OPT_TILE_ORDER, KM_OPT_PREFER_INSTANCE, KM_OPT_INSTANCE_COUNT,
     KronMatmulError, kronmatmul, Prepared, workspace_size, prepare, plan, tune, cost, store_column, set_option, get_option,
     last_profile, mean_profile, clock_probe, release, status_string, kernel_name, lib, EXPORTS, LIB_PATH,
+    KM_STATIC_SCRATCH_BYTES,
 )

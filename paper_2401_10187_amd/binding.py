@@ -19,8 +19,9 @@ EXPORTS = [
     "kronmatmul_last_profile", "kronmatmul_mean_profile", "kronmatmul_release", "kronmatmul_status_string",
     "kronmatmul_kernel_name", "kronmatmul_tune",
     "kronmatmul_transposed_workspace_size", "kronmatmul_transposed", "kronmatmul_transposed_ws",
-    "kronmatmul_clock_probe", "kronmatmul_prepare",
+    "kronmatmul_clock_probe", "kronmatmul_prepare", "kronmatmul_static",
 ]
+KM_STATIC_SCRATCH_BYTES = 16 << 20
 
 
 class PlanStep(ctypes.Structure):
@@ -57,6 +58,8 @@ def lib():
         L.kronmatmul_workspace_size.argtypes = [ci, ci, ip, ip, ci, ctypes.POINTER(ctypes.c_size_t)]
         L.kronmatmul.restype = ci
         L.kronmatmul.argtypes = [ci, ci, ip, ip, vp, vp, vp, ci, vp]
+        L.kronmatmul_static.restype = ci
+        L.kronmatmul_static.argtypes = [ci, ci, ip, ip, vp, vp, vp, ci, vp]
         L.kronmatmul_prepare.restype = ci
         L.kronmatmul_prepare.argtypes = [ci, ci, ip, ip, ci]
         L.kronmatmul_ws.restype = ci
@@ -249,7 +252,9 @@ class Prepared:
         return self.Y
 
 
-def _entry_name(with_ws, transposed):
+def _entry_name(with_ws, transposed, static=False):
+    if static:
+        return "kronmatmul_static"
     return "kronmatmul" + ("_transposed" if transposed else "") + ("_ws" if with_ws else "")
 
 
@@ -289,16 +294,20 @@ def _marshal(X, Fs, Y, workspace, transposed=False):
     return Y, head + (workspace.data_ptr(), nbytes), True, fptr
 
 
-def kronmatmul(X, Fs, Y=None, workspace=None, stream=None, transposed=False):
+def kronmatmul(X, Fs, Y=None, workspace=None, stream=None, transposed=False, static=False):
     """Y = X (Fs[0] (x) ... (x) Fs[-1]) on the GPU.  X, Fs, Y and workspace are torch CUDA tensors
     (contiguous, same dtype).  With workspace=None the library's own cached workspace is used.
     With transposed=True every Fs[i] holds the transpose of the factor applied (shape Q_i x P_i).
+    With static=True the call goes to kronmatmul_static (no allocation; Y must then be given, or the
+    binding's own torch.empty allocates it).
     Returns Y.  The call is asynchronous on `stream` (default: torch's current stream)."""
     import torch
+    if static and (workspace is not None or transposed):
+        raise ValueError("static=True takes neither a workspace nor transposed factors")
     Y, args, with_ws, _fptr = _marshal(X, Fs, Y, workspace, transposed)
     if stream is None:
         stream = torch.cuda.current_stream(X.device).cuda_stream
-    name = _entry_name(with_ws, transposed)
+    name = _entry_name(with_ws, transposed, static)
     with torch.cuda.device(X.device):
         _check(getattr(lib(), name)(*args, ctypes.c_void_p(stream)), name)
     return Y

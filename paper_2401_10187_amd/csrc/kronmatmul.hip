@@ -107,6 +107,7 @@ static hipError_t launch_rows(const LaunchArgs& a)
 struct DeviceState {
     void* ws = nullptr;
     size_t ws_bytes = 0;
+    void* scratch_ptr = nullptr;     // this device's copy of `scratch`, resolved once
     // Profiling history since KM_OPT_PROFILE was last switched on: call c with n launches owns
     // events [first[c], first[c] + n].  Events are pooled and reused after the history is cleared.
     std::vector<hipEvent_t> events;
@@ -114,6 +115,11 @@ struct DeviceState {
     int events_used = 0;
 };
 constexpr int MAX_PROFILED_CALLS = 4096;
+
+// Workspace of kronmatmul_static: one array per GPU, held from the moment the library's code is
+// loaded on that GPU until the process ends.  In host code the array's name is only a handle for
+// hipGetSymbolAddress; kernels are given the address that call returns on the device in use.
+static __device__ __align__(256) unsigned char scratch[KM_STATIC_SCRATCH_BYTES];
 
 static std::mutex g_mutex;
 static Options g_options;
@@ -532,9 +538,29 @@ static km_status library_workspace(size_t need, void** ws)
     return KM_OK;
 }
 
-// The body of every compute entry point.  own_ws: the caller passed a workspace (else the library's).
+// Address of the current device's copy of `scratch` (resolved on first use, then remembered).
+static km_status static_scratch(void** ptr)
+{
+    *ptr = nullptr;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return KM_ELAUNCH;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    DeviceState& ds = g_dev[dev];
+    if (!ds.scratch_ptr) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) { (void)hipGetLastError(); return KM_ELAUNCH; }
+        ds.scratch_ptr = p;
+    }
+    *ptr = ds.scratch_ptr;
+    return KM_OK;
+}
+
+// Where a call's workspace comes from: the library's cached allocation, the caller, or the static array.
+enum WsKind { WS_LIBRARY, WS_CALLER, WS_STATIC };
+
+// The body of every compute entry point.
 static km_status execute(int M, int N, const int* P, const int* Q, const void* X, const void* const* F, void* Y,
-                         km_dtype dtype, bool own_ws, void* workspace, size_t workspace_bytes, void* stream,
+                         km_dtype dtype, WsKind kind, void* workspace, size_t workspace_bytes, void* stream,
                          bool transposed)
 {
     Problem pr;
@@ -549,10 +575,16 @@ static km_status execute(int M, int N, const int* P, const int* Q, const void* X
     const size_t plan_need = round_up(plan.ws0_bytes + plan.ws1_bytes, 256);
     const size_t need = transposed ? plan_need + factor_copy_bytes(pr) : plan.ws0_bytes + plan.ws1_bytes;
     void* ws = workspace;
-    if (own_ws) {
+    if (kind == WS_CALLER) {
         if (need > 0 && (!workspace || workspace_bytes < need)) return KM_ENOMEM;
         if (need > 0 && !aligned(workspace, 16)) return KM_EINVAL;
         if (need > 0 && check_workspace(pr, X, Y, workspace, need) != KM_OK) return KM_EINVAL;
+    } else if (kind == WS_STATIC) {
+        // sizes are checked before anything touches the device; nothing on this path allocates
+        if (need > KM_STATIC_SCRATCH_BYTES) return KM_ENOMEM;
+        s = static_scratch(&ws);
+        if (s != KM_OK) return s;
+        return run(pr, plan, X, F, Y, ws, (hipStream_t)stream, false);     // unprofiled: events would be created
     } else {
         s = library_workspace(need, &ws);
         if (s != KM_OK) return s;
@@ -602,13 +634,19 @@ km_status kronmatmul_workspace_size(int M, int N, const int* P, const int* Q, km
 km_status kronmatmul_ws(int M, int N, const int* P, const int* Q, const void* X, const void* const* F,
                         void* Y, km_dtype dtype, void* workspace, size_t workspace_bytes, void* stream)
 {
-    return execute(M, N, P, Q, X, F, Y, dtype, true, workspace, workspace_bytes, stream, false);
+    return execute(M, N, P, Q, X, F, Y, dtype, WS_CALLER, workspace, workspace_bytes, stream, false);
 }
 
 km_status kronmatmul(int M, int N, const int* P, const int* Q, const void* X, const void* const* F,
                      void* Y, km_dtype dtype, void* stream)
 {
-    return execute(M, N, P, Q, X, F, Y, dtype, false, nullptr, 0, stream, false);
+    return execute(M, N, P, Q, X, F, Y, dtype, WS_LIBRARY, nullptr, 0, stream, false);
+}
+
+km_status kronmatmul_static(int M, int N, const int* P, const int* Q, const void* X, const void* const* F,
+                            void* Y, km_dtype dtype, void* stream)
+{
+    return execute(M, N, P, Q, X, F, Y, dtype, WS_STATIC, nullptr, 0, stream, false);
 }
 
 km_status kronmatmul_transposed_workspace_size(int M, int N, const int* P, const int* Q, km_dtype dtype,
@@ -631,13 +669,13 @@ km_status kronmatmul_transposed_ws(int M, int N, const int* P, const int* Q, con
                                    const void* const* Ft, void* Y, km_dtype dtype, void* workspace,
                                    size_t workspace_bytes, void* stream)
 {
-    return execute(M, N, P, Q, X, Ft, Y, dtype, true, workspace, workspace_bytes, stream, true);
+    return execute(M, N, P, Q, X, Ft, Y, dtype, WS_CALLER, workspace, workspace_bytes, stream, true);
 }
 
 km_status kronmatmul_transposed(int M, int N, const int* P, const int* Q, const void* X,
                                 const void* const* Ft, void* Y, km_dtype dtype, void* stream)
 {
-    return execute(M, N, P, Q, X, Ft, Y, dtype, false, nullptr, 0, stream, true);
+    return execute(M, N, P, Q, X, Ft, Y, dtype, WS_LIBRARY, nullptr, 0, stream, true);
 }
 
 km_status kronmatmul_tune(int M, int N, const int* P, const int* Q, km_dtype dtype, void* stream,
@@ -676,7 +714,8 @@ km_status kronmatmul_prepare(int M, int N, const int* P, const int* Q, km_dtype 
     std::vector<const void*> none(pr.N, nullptr);
     for (const km_plan_step& st : plan.steps)
         if (launch_step(pr, st, nullptr, nullptr, none.data(), nullptr, true) != hipSuccess) return KM_ELAUNCH;
-    return KM_OK;
+    void* unused;
+    return static_scratch(&unused);          // kronmatmul_static finds its array's address resolved
 }
 
 km_status kronmatmul_plan(int M, int N, const int* P, const int* Q, km_dtype dtype,

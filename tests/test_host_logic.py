@@ -374,6 +374,21 @@ def test_overlapping_buffers_are_refused():
     assert L.kronmatmul(4, n, p, q, base, f, base + 64, 0, None) == km.KM_EINVAL
 
 
+def test_static_entry_point_refuses_what_does_not_fit():
+    """kronmatmul_static takes its workspace from an array of KM_STATIC_SCRATCH_BYTES: a problem whose
+    intermediates need more (1024 x 8^6: 1 GiB) is refused with KM_ENOMEM before anything touches a device;
+    its other argument checks are those of kronmatmul_ws."""
+    L = km.lib()
+    base, n = 0x10000000, 6
+    p = (ctypes.c_int * n)(*[8] * n)
+    f = ctypes.cast((ctypes.c_void_p * n)(*[0x1000] * n), ctypes.c_void_p)
+    assert km.workspace_size(1024, [8] * n, [8] * n, "float32") > km.KM_STATIC_SCRATCH_BYTES
+    assert L.kronmatmul_static(1024, n, p, p, base, f, base + (1 << 40), km.KM_F32, None) == km.KM_ENOMEM
+    assert L.kronmatmul_static(1024, n, p, p, base, f, base, km.KM_F32, None) == km.KM_EINVAL          # Y is X
+    assert L.kronmatmul_static(1024, n, p, p, None, f, base, km.KM_F32, None) == km.KM_EINVAL
+    assert L.kronmatmul_static(0, n, p, p, None, f, None, km.KM_F32, None) == km.KM_OK
+
+
 def test_empty_problems_plan_to_nothing():
     """M == 0 is a successful no-op for every entry point, the planning ones included."""
     assert km.plan(0, [8, 8], [8, 8], "float32") == []
