@@ -189,9 +189,10 @@ km_status kronmatmul_cost(int M, int N, const int* P, const int* Q, km_dtype dty
  * KM_OPT_TILES_PER_WG: tuning aid; consecutive tiles per workgroup of the MFMA kernels (0 = automatic).
  * KM_OPT_PAIR_INTERLEAVE: tuning aid (default 1); MFMA kernels whose output runs are shorter than a
  * cache line give alternate tiles to pairs of workgroups that share an XCD.
- * KM_OPT_TILE_ORDER: tuning aid (default 2); persistent MFMA kernels walk over a contiguous range of
+ * KM_OPT_TILE_ORDER: tuning aid (default -1); persistent MFMA kernels walk over a contiguous range of
  * tiles (0), over tiles strided by the grid size (2), or strided inside a contiguous eighth of the
- * tiles per XCD (3; taken as 2 when tiles or grid do not split by 8).
+ * tiles per XCD (3; taken as 2 when tiles or grid do not split by 8); -1 leaves the choice between 2
+ * and 3 to the compiled instance.
  * KM_OPT_PREFER_INSTANCE: tuning aid; k > 0 makes the planner take compiled instance k - 1 (the
  * `variant` of a plan step) wherever it fits the shape (0 = automatic); k = instance count + 1
  * makes it take the whole-row kernel (KM_KERNEL_ROWS) whenever the rows fit LDS.

@@ -3,7 +3,7 @@
 #pragma once
 
 // Fused FMA instances: X(type, dtype code, P, Q, factors per launch, tile_slices, threads).
-// Register-resident MFMA pairs: Z(P, tile_slices, wavefronts, units fetched ahead) (fp32, Q = 32, two factors).
+// Register-resident MFMA pairs: Z(P, tile_slices, wavefronts, units fetched ahead, output passes) (fp32, Q = 32, two factors).
 // Small-factor instances with several factors per LDS pass and a run-time tile length:
 // W(type, dtype code, P, Q, G0, G1, G2, largest tile_slices, threads).
 // The same for rows of exactly P*P elements, ST rows per tile: R(P, rows per tile, wavefronts).
@@ -27,7 +27,8 @@
     X(float, KM_F32, 6, 6, 2, 288, 256)                 \
     X(double, KM_F64, 6, 6, 3, 16, 256)                 \
     R(32, 32, 4)                                        \
-    Z(32, 32, 4, 1)                                     \
+    Z(32, 32, 16, 1, 1)                                 \
+    Z(32, 32, 4, 1, 2)                                  \
     Y(MfmaF32x32, KM_F32, 32, 32, 2, 32, 8, 1)          \
     Y(MfmaF32x32, KM_F32, 32, 32, 2, 32, 16, 1)         \
     Y(MfmaF32x32, KM_F32, 32, 32, 2, 16, 4, 1)          \
@@ -35,7 +36,8 @@
     Y(MfmaF32x32, KM_F32, 32, 32, 1, 128, 4, 1)         \
     Y(MfmaF32x32, KM_F32, 32, 32, 1, 32, 1, 1)          \
     R(16, 32, 4)                                        \
-    Z(16, 32, 4, 1)                                     \
+    Z(16, 32, 8, 1, 1)                                  \
+    Z(16, 32, 4, 1, 2)                                  \
     Y(MfmaF32x32, KM_F32, 16, 32, 2, 32, 4, 1)          \
     Y(MfmaF32x32, KM_F32, 16, 32, 2, 16, 4, 1)          \
     Y(MfmaF32x32, KM_F32, 16, 32, 1, 256, 4, 1)         \

@@ -7,12 +7,12 @@
 
 namespace km {
 
-template <int P, int ST, int NW, int PD>
+template <int P, int ST, int NW, int PD, int NPASS>
 hipError_t launch_mfma_pair(const LaunchArgs& a)
 {
-    typedef MfmaPairShape<P, ST, NW, PD> Sh;
+    typedef MfmaPairShape<P, ST, NW, PD, NPASS> Sh;
     const km_plan_step& st = *a.st;
-    auto kern = mfma_pair_sliced_multiply<P, ST, NW, PD>;
+    auto kern = mfma_pair_sliced_multiply<P, ST, NW, PD, NPASS>;
     static unsigned char lds_ok[64];
     hipError_t e = allow_lds((const void*)kern, Sh::LDS_BYTES, lds_ok);
     if (e != hipSuccess || a.prepare_only) return e;

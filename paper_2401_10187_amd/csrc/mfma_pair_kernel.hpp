@@ -27,7 +27,7 @@
 
 namespace km {
 
-template <int P, int ST, int NW, int PD = 1>
+template <int P, int ST, int NW, int PD = 1, int NPASS = 2>
 struct MfmaPairShape {
     static constexpr int Q = 32;
     static constexpr int NT = NW * 64;
@@ -38,10 +38,16 @@ struct MfmaPairShape {
     static constexpr int APW = UPW * AP;              // values of `a` per wavefront
     static constexpr int TK = ST * P * P;
     static constexpr int STP = ST + 4;                // padded row of the output staging buffer
-    static constexpr int PASS_ROWS = 16 * Q;          // rows (q1_local, q2) of one output pass
+    // The output goes through the staging buffer in NPASS passes over the q1 range: with two passes
+    // (72 KB) two workgroups fit a compute unit and each keeps the second half of its accumulators in
+    // registers meanwhile; with one pass (144 KB) a single large workgroup keeps nothing.
+    static constexpr int PASS_Q1 = Q / NPASS;         // q1 values per pass
+    static constexpr int PASS_ROWS = PASS_Q1 * Q;     // rows (q1_local, q2) of one output pass
     static constexpr int LDS_BYTES = PASS_ROWS * STP * 4;
     static constexpr int RD = PASS_ROWS * (ST / 4) / NT;   // 16-byte reads per thread and pass
+    static constexpr int WPS = NW >= 8 ? 4 : 2;       // wavefronts per SIMD the register budget is set for
     static_assert(P == 16 || P == 32, "P must be 16 or 32");
+    static_assert(NPASS == 1 || NPASS == 2, "one or two output passes");
     static_assert(ST % (AP * NW) == 0 && ST % 4 == 0, "tile must split evenly over the wavefronts");
     static_assert((PASS_ROWS * (ST / 4)) % NT == 0, "output pass must split evenly over the threads");
     static constexpr int RING = PD + 1;               // operand buffers: PD units in flight + the one in use
@@ -52,14 +58,14 @@ struct MfmaPairShape {
 typedef float pair_f32x16 __attribute__((ext_vector_type(16)));
 typedef float pair_f32x4 __attribute__((ext_vector_type(4)));
 
-template <int P, int ST, int NW, int PD>
-__global__ __launch_bounds__(NW * 64, 2)
+template <int P, int ST, int NW, int PD, int NPASS>
+__global__ __launch_bounds__(NW * 64, (MfmaPairShape<P, ST, NW, PD, NPASS>::WPS))
 void mfma_pair_sliced_multiply(const float* __restrict__ Xg, float* __restrict__ Yg,
                                const float* __restrict__ F0, const float* __restrict__ F1,   // in order of application
                                int64_t k_in, int64_t k_out, int64_t tiles_per_row, int64_t num_tiles,
                                int64_t tiles_per_wg, int tile_order)
 {
-    typedef MfmaPairShape<P, ST, NW, PD> Sh;
+    typedef MfmaPairShape<P, ST, NW, PD, NPASS> Sh;
     constexpr int Q = Sh::Q, KS = Sh::KS, AP = Sh::AP, UPW = Sh::UPW, STP = Sh::STP, NT = Sh::NT, RING = Sh::RING;
     extern __shared__ __attribute__((aligned(16))) unsigned char pair_lds[];
     float* stage = reinterpret_cast<float*>(pair_lds);
@@ -127,7 +133,7 @@ void mfma_pair_sliced_multiply(const float* __restrict__ Xg, float* __restrict__
         // Registers 0-7 of a stage-1 accumulator hold q1 < 16 and go to the staging buffer at once
         // (it is free: the previous tile's last pass ended with a barrier); registers 8-15 (q1 >= 16)
         // wait here for the second pass.
-        float keep[Sh::APW][8];
+        float keep[NPASS == 2 ? Sh::APW : 1][8];
 #pragma unroll
         for (int u = 0; u < UPW; ++u) {
             // fetch unit u + PD (of this tile, or of the next one)
@@ -164,7 +170,8 @@ void mfma_pair_sliced_multiply(const float* __restrict__ Xg, float* __restrict__
                 for (int w = 0; w < 8; ++w) {
                     const int q1l = 8 * (w / 4) + 4 * g + (w % 4);           // q1 of register w (and of 8 + w, minus 16)
                     stage[(q1l * Q + col) * STP + a] = acc[w];
-                    keep[u * AP + al][w] = acc[8 + w];
+                    if constexpr (NPASS == 2) keep[u * AP + al][w] = acc[8 + w];
+                    else stage[((16 + q1l) * Q + col) * STP + a] = acc[8 + w];
                 }
             }
         }
@@ -172,7 +179,7 @@ void mfma_pair_sliced_multiply(const float* __restrict__ Xg, float* __restrict__
         const int64_t row = uniform(t / tiles_per_row), h = uniform(t % tiles_per_row);
         float* Yrow = Yg + row * k_out + h * ST;
 #pragma unroll
-        for (int pass = 0; pass < 2; ++pass) {
+        for (int pass = 0; pass < NPASS; ++pass) {
             if (pass == 1) {
 #pragma unroll
                 for (int u = 0; u < UPW; ++u)
@@ -187,8 +194,8 @@ void mfma_pair_sliced_multiply(const float* __restrict__ Xg, float* __restrict__
                     }
             }
             __syncthreads();
-            // row r = (q1l, q2) of the staging buffer -> output column ((16*pass + q1l)*Q + q2)*s_row + h*ST + a
-            float* Ypass = Yrow + (int64_t)(16 * pass * Q) * s_row;
+            // row r = (q1l, q2) of the staging buffer -> output column ((PASS_Q1*pass + q1l)*Q + q2)*s_row + h*ST + a
+            float* Ypass = Yrow + (int64_t)(Sh::PASS_Q1 * pass * Q) * s_row;
 #pragma unroll
             for (int i0 = 0; i0 < Sh::RD; i0 += 4) {
                 pair_f32x4 v[4];
@@ -224,7 +231,7 @@ void mfma_pair_rows_sliced_multiply(const float* __restrict__ Xg, float* __restr
                                     const float* __restrict__ F0, const float* __restrict__ F1,   // in order of application
                                     int64_t M, int64_t num_tiles, int64_t tiles_per_wg, int tile_order)
 {
-    typedef MfmaPairShape<P, ST, NW, 1> Sh;
+    typedef MfmaPairShape<P, ST, NW, 1, 2> Sh;
     constexpr int Q = Sh::Q, KS = Sh::KS, AP = Sh::AP, UPW = Sh::UPW;
     constexpr int KIN = P * P, KOUT = Q * Q;
 

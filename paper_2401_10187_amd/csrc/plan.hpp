@@ -28,6 +28,9 @@ struct Variant {
     int lds_per_slice; // flexible instances: LDS bytes per slice of the tile (lds_bytes is the maximum)
     int thread_elems;  // flexible instances: contiguous elements of a tile that one thread multiplies first
     int max_srow;      // > 0: only for rows of at most this many slices of the group (K / prod P)
+    int min_tiles;     // > 0: only planned for launches of at least this many tiles (the tuner still tries it)
+    int walk;          // > 0: tiles per workgroup of a persistent instance, instead of the rule of tiles_per_wg()
+    int xcd_order;     // 1: persistent instance that prefers tile order 3 (each XCD walks its own eighth of the tiles)
 };
 
 // LDS a launch of the instance asks for when its tiles hold `tile_slices` slices.
@@ -47,7 +50,7 @@ inline int launch_lds_bytes(const Variant& c, int tile_slices)
 // Instances that fill most of a compute unit's LDS run one or two workgroups per unit and need the
 // walk to overlap their loads with their stores: at least 4 tiles above 64 KB, 32 above 80 KB.
 inline int64_t tiles_per_wg(int64_t num_tiles, int hint, int64_t factor_elems, int64_t tile_elems,
-                            int lds_bytes, size_t esize)
+                            int lds_bytes, size_t esize, int instance_walk = 0)
 {
     if (hint > 0) return hint;
     const int64_t want = (10 * factor_elems + tile_elems - 1) / tile_elems;
@@ -56,6 +59,7 @@ inline int64_t tiles_per_wg(int64_t num_tiles, int hint, int64_t factor_elems, i
     if ((size_t)factor_elems * esize >= 16 * 1024) t = 32;
     if (lds_bytes > 64 * 1024 && t < 4) t = 4;
     if (lds_bytes > 80 * 1024) t = 32;
+    if (instance_walk > 0) t = instance_walk;          // measured per instance
     // two workgroups per compute unit at least; four when the instance is light (small factor, at most
     // 64 KB of LDS): 1024 x 64x64^2 is 28 % faster with 1024 workgroups than with 512; but one per unit
     // is enough when loading the factor costs a workgroup as much as a tile does (16 x 64x64^3 fp64:
@@ -89,8 +93,9 @@ struct Options {
     int tiles_per_wg = 0;     // tuning: tiles per workgroup of persistent instances (0 = automatic)
     int pair_interleave = 1;  // neighbouring tiles with short output runs go to workgroup pairs
     int prefer_instance = 0;  // tuning: k > 0 = take compiled instance k - 1 wherever it fits
-    int tile_order = 2;       // persistent kernels: 0 = contiguous tile ranges, 2 = tiles strided by the grid,
-                              // 3 = strided inside the XCD's own eighth of the tiles
+    int tile_order = -1;      // persistent kernels: 0 = contiguous tile ranges, 2 = tiles strided by the grid,
+                              // 3 = strided inside the XCD's own eighth of the tiles, -1 = the instance's
+                              // preference (3 where it asks for it and the tiles split by 8, else 2)
 };
 
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -319,6 +324,8 @@ inline Choice find_variant(const Variant* table, int count, const Problem& pr, i
         if (c.P != pr.P[f] || c.Q != pr.Q[f]) continue;
         if (c.max_srow > 0 && s_row > c.max_srow) continue;
         if (c.rows_per_tile > 1 && s_row != c.tile_slices) continue;      // tiles of several rows hold whole rows
+        if (c.min_tiles > 0 && !c.flexible && pr.M * (s_row / c.tile_slices) < c.min_tiles && opt.prefer_instance != v + 1)
+            continue;                                     // too few tiles for this instance (unless it is asked for)
         // slices per tile: fixed, or the best divisor of s_row up to the instance's limit
         int cand[3] = {0, 0, 0};
         int rows = c.rows_per_tile;
@@ -459,11 +466,11 @@ inline km_plan_step build_step(const Problem& pr, const Options& opt, const Vari
         if (var->persistent) {
             const int hint = ch.tiles_per_wg > 0 ? ch.tiles_per_wg : opt.tiles_per_wg;
             const int64_t tpw = tiles_per_wg(st.grid, hint, (int64_t)nf * var->P * var->Q,
-                                             (int64_t)ch.tile_slices * ch.tile_rows * pg, var->lds_bytes, pr.esize);
+                                             (int64_t)ch.tile_slices * ch.tile_rows * pg, var->lds_bytes, pr.esize, var->walk);
             const int64_t num_tiles = st.grid;
             st.tiles_per_wg = (int)tpw;
             st.grid = (num_tiles + tpw - 1) / tpw;
-            st.tile_order = ch.tile_order >= 0 ? ch.tile_order : opt.tile_order;
+            st.tile_order = ch.tile_order >= 0 ? ch.tile_order : (opt.tile_order >= 0 ? opt.tile_order : (var->xcd_order ? 3 : 2));
             // output runs shorter than a 128-byte line: neighbouring tiles go to a pair of workgroups
             // that run side by side (order 1), when the tiles split evenly that way
             if (ch.tile_order < 0 && var->persistent == 1 && opt.pair_interleave &&
