@@ -58,8 +58,9 @@ typedef enum {
     KM_KERNEL_FUSED = 1,    /* up to 12 consecutive small factors, tile resident in LDS (section 4.2) */
     KM_KERNEL_MFMA = 2,     /* factors with P and Q multiples of 16: slice contraction on MFMA     */
     KM_KERNEL_SHUFFLE = 3,  /* one 8x8 fp32 factor, no LDS: P-reduction by wavefront lane exchanges */
-    KM_KERNEL_ROWS = 4      /* every factor of a short row in one launch, any shapes: the row and its
+    KM_KERNEL_ROWS = 4,     /* every factor of a short row in one launch, any shapes: the row and its
                                intermediates stay in LDS (section 4.2's fusion with the row as tile) */
+    KM_KERNEL_MFMA_ANY = 5  /* one factor with P and Q any multiples of 16 (run-time shapes) on MFMA      */
 } km_kernel;
 
 /* Buffers a plan step reads or writes. */
@@ -181,7 +182,7 @@ km_status kronmatmul_cost(int M, int N, const int* P, const int* Q, km_dtype dty
 /* Options (process-wide).  KM_OPT_KERNELS, KM_OPT_MAX_FUSE and KM_OPT_PROFILE are for users; the
  * options called "tuning aid" force the planner's hand and exist for tests and sweeps only: they are
  * not meant to be changed while other threads are making calls.  KM_OPT_KERNELS: bit mask of km_kernel families the planner may use (bit k = family k;
- * the generic family is always allowed; default 23: the shuffle family is off because the LDS-tiled
+ * the generic family is always allowed; default 55: the shuffle family is off because the LDS-tiled
  * kernels measured faster).  KM_OPT_MAX_FUSE: upper limit on factors per launch (default 12).
  * KM_OPT_PROFILE: when 1, every launch is bracketed by HIP events on the caller's stream.
  * KM_OPT_PREFER_TILE / KM_OPT_PREFER_THREADS: tuning aids; when non-zero the planner prefers compiled

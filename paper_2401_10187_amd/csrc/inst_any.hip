@@ -1,0 +1,7 @@
+// Compiled instances: the MFMA kernel for factors whose P and Q are any multiples of 16 (fp32 and fp64).
+#include "launch_any.hpp"
+
+namespace km {
+template hipError_t launch_mfma_any<float>(const LaunchArgs&);
+template hipError_t launch_mfma_any<double>(const LaunchArgs&);
+}  // namespace km

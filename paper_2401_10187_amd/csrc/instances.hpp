@@ -62,6 +62,9 @@
     Y(MfmaF32x32, KM_F32, 64, 128, 1, 128, 8, 2)        \
     Y(MfmaF32x32, KM_F32, 128, 32, 1, 64, 2, 1)         \
     Y(MfmaF32x32, KM_F32, 32, 128, 1, 256, 4, 2)        \
+    Y(MfmaF32x16, KM_F32, 48, 48, 1, 128, 4, 1)         \
+    Y(MfmaF32x32, KM_F32, 96, 96, 1, 64, 6, 3)          \
+    Y(MfmaF64x16, KM_F64, 48, 48, 1, 64, 4, 1)          \
     Y(MfmaF64x16, KM_F64, 32, 16, 1, 128, 4, 1)         \
     Y(MfmaF64x16, KM_F64, 16, 32, 1, 128, 4, 1)         \
     Y(MfmaF64x16, KM_F64, 64, 32, 1, 64, 4, 1)          \

@@ -16,6 +16,7 @@
 #include "mfma_kernel.hpp"
 #include "mfma_pair_kernel.hpp"
 #include "shuffle_kernel.hpp"
+#include "mfma_any_kernel.hpp"
 
 namespace km {
 
@@ -134,7 +135,8 @@ static DeviceState g_dev[64];
 static GenericKernel generic_kernel(int dtype)
 {
     return GenericKernel{GEN_THREADS, GEN_TS, GEN_TQ, dtype == KM_F32 ? gen_lds_bytes<float>() : gen_lds_bytes<double>(),
-                         ROW_THREADS_MANY, ROW_THREADS_FEW, ROW_FEW_ROWS, ROW_LDS_LIMIT, ROW_MAXF};
+                         ROW_THREADS_MANY, ROW_THREADS_FEW, ROW_FEW_ROWS, ROW_LDS_LIMIT, ROW_MAXF,
+                         ANY_THREADS, ANY_TS, ANY_ROW_BYTES};
 }
 
 // Plans are memoised: iterative callers repeat the same small problem thousands of times and the
@@ -223,6 +225,8 @@ static hipError_t launch_step(const Problem& pr, const km_plan_step& st, const v
         return pr.dtype == KM_F32 ? launch_generic<float>(a) : launch_generic<double>(a);
     if (st.kernel == KM_KERNEL_ROWS)
         return pr.dtype == KM_F32 ? launch_rows<float>(a) : launch_rows<double>(a);
+    if (st.kernel == KM_KERNEL_MFMA_ANY)
+        return pr.dtype == KM_F32 ? launch_mfma_any<float>(a) : launch_mfma_any<double>(a);
     if (st.variant < 0 || st.variant >= g_num_variants) return hipErrorInvalidValue;
     return g_launchers[st.variant](a);
 }
@@ -419,6 +423,11 @@ static km_status tune(const Problem& pr, const Options& opt, hipStream_t stream,
         for (int nf = 1; nf <= r && nf <= opt.max_fuse; ++nf) {
             enumerate_choices(g_variants, g_num_variants, pr, r - 1, nf, width[r], opt, cands);
             if (nf == 1) cands.push_back(Choice());            // the generic kernel
+            if (nf == 1 && any_mfma_fits(pr, r - 1, opt)) {     // the run-time-shape MFMA kernel
+                Choice any;
+                any.any_mfma = true;
+                cands.push_back(any);
+            }
             float group_best = -1.f;
             Choice group_pick;
             for (const Choice& ch : cands) {
@@ -770,7 +779,7 @@ km_status kronmatmul_set_option(km_option option, int value)
     std::lock_guard<std::mutex> lock(g_mutex);
     switch (option) {
         case KM_OPT_KERNELS:
-            if (value < 0 || value > 31) return KM_EINVAL;
+            if (value < 0 || value > 63) return KM_EINVAL;
             g_options.kernels = value | 1;
             return KM_OK;
         case KM_OPT_MAX_FUSE:
@@ -915,6 +924,7 @@ const char* kronmatmul_kernel_name(int kernel)
         case KM_KERNEL_MFMA: return "mfma";
         case KM_KERNEL_SHUFFLE: return "shuffle";
         case KM_KERNEL_ROWS: return "rows";
+        case KM_KERNEL_MFMA_ANY: return "mfma-any";
     }
     return "unknown";
 }

@@ -37,5 +37,6 @@ template <class OP, int P, int Q, int NF, int ST, int NW, int QSPLIT> hipError_t
 template <int P, int ST, int NW, int PD, int NPASS> hipError_t launch_mfma_pair(const LaunchArgs& a);
 template <int P, int ST, int NW> hipError_t launch_mfma_pair_rows(const LaunchArgs& a);
 hipError_t launch_shuffle(const LaunchArgs& a);
+template <typename T> hipError_t launch_mfma_any(const LaunchArgs& a);
 
 }  // namespace km

@@ -86,7 +86,7 @@ struct Plan {
 };
 
 struct Options {
-    int kernels = 0x17;   // bit mask of km_kernel families
+    int kernels = 0x37;   // bit mask of km_kernel families
     int max_fuse = 12;
     int prefer_tile = 0;      // tuning: choose instances with this tile_slices when one fits
     int prefer_threads = 0;   // tuning: ... with this workgroup size
@@ -157,6 +157,20 @@ inline int64_t store_column(int64_t k_in, int64_t p_group, int64_t tile_k, int64
     return qq * s_row + tile_index * s_tile + r;
 }
 
+// Column blocks (of 16) per unit of the run-time-shape MFMA kernel for a factor with Q columns: the
+// width among 4, 5 and 3 that leaves the fewest padded columns.
+inline int any_column_blocks(int Q)
+{
+    const int blocks = Q / 16;
+    int best = 4, waste = (4 - blocks % 4) % 4 * 1000 / ((blocks + 3) / 4 * 4);
+    const int others[2] = {5, 3};
+    for (int cb : others) {
+        const int w = (cb - blocks % cb) % cb * 1000 / ((blocks + cb - 1) / cb * cb);
+        if (w < waste) { waste = w; best = cb; }
+    }
+    return best;
+}
+
 // A compiled instance chosen for one group of factors, with the slices per tile it will run with.
 // What the planner needs to know of the generic kernel: a workgroup of `threads` work-items takes
 // `tile_slices` slices and `tile_cols` factor columns at a time.
@@ -166,9 +180,19 @@ struct GenericKernel {
     // are at most row_few_rows rows) applies up to row_max_factors factors to one row held, with the
     // factors, in at most row_lds_limit bytes of LDS
     int row_threads_many, row_threads_few, row_few_rows, row_lds_limit, row_max_factors;
+    // the run-time-shape MFMA kernel (P and Q multiples of 16): a workgroup of any_threads work-items takes
+    // any_tile_slices slices and 16 * any_column_blocks(Q) factor columns at a time, chunks of
+    // any_row_bytes per slice in LDS rows padded by one 16-byte unit
+    int any_threads, any_tile_slices, any_row_bytes;
 };
 
+inline int any_lds_bytes(const GenericKernel& gen, int Q, size_t)
+{
+    return (gen.any_tile_slices + 16 * any_column_blocks(Q)) * (gen.any_row_bytes + 16);
+}
+
 struct Choice {
+    bool any_mfma = false;   // with var == nullptr: the run-time-shape MFMA kernel instead of the generic one
     const Variant* var = nullptr;
     int tile_slices = 0;
     int64_t grid = 0;        // tiles (before the persistent-walk division)
@@ -414,7 +438,7 @@ inline Choice find_variant(const Variant* table, int count, const Problem& pr, i
 inline double launch_cost(const Problem& pr, int64_t k_in, int64_t k_out, const Choice& ch, int generic_P = 0)
 {
     const double bytes = (double)pr.M * ((double)k_in + (double)k_out) * (double)pr.esize;
-    double slow = 3.0;                                   // generic kernel
+    double slow = ch.any_mfma ? 1.5 : 3.0;               // generic kernel; run-time-shape MFMA kernel
     if (ch.var) {
         int64_t run = (int64_t)ch.tile_slices * (int64_t)pr.esize;
         // a tile that holds a whole row writes the whole output row: its runs join up
@@ -429,7 +453,7 @@ inline double launch_cost(const Problem& pr, int64_t k_in, int64_t k_out, const 
     // the generic kernel walks the slice elements in chunks of 16, a barrier apart: a launch of it
     // takes about 2 us + 0.7 us per chunk even when it moves next to nothing (measured: 5.5 us for
     // P = 65, 4.8 us for P = 52 on ten rows)
-    if (!ch.var) fixed += 1.0e7 + 3.5e6 * (double)((generic_P + 15) / 16);
+    if (!ch.var && !ch.any_mfma) fixed += 1.0e7 + 3.5e6 * (double)((generic_P + 15) / 16);
     return bytes * slow + fixed;
 }
 
@@ -479,6 +503,18 @@ inline km_plan_step build_step(const Problem& pr, const Options& opt, const Vari
             if (st.tile_order == 1 && (var->persistent != 1 || !pair_order_fits(num_tiles, tpw))) st.tile_order = 0;
             if (st.tile_order == 3 && !xcd_order_fits(num_tiles, st.grid)) st.tile_order = 2;
         }
+    } else if (ch.any_mfma) {
+        st.kernel = KM_KERNEL_MFMA_ANY;
+        st.variant = -1;
+        st.tile_rows = 1;
+        st.tile_slices = gen.any_tile_slices;
+        st.block = gen.any_threads;
+        st.lds_bytes = any_lds_bytes(gen, pr.Q[f], pr.esize);
+        const int64_t S = st.k_in / pr.P[f];
+        const int cols = 16 * any_column_blocks(pr.Q[f]);
+        st.grid = ((pr.M * S + gen.any_tile_slices - 1) / gen.any_tile_slices) * ((pr.Q[f] + cols - 1) / cols);
+        const int64_t most = ((int64_t)1 << 32) / gen.any_threads - 1;     // the kernel strides over its units
+        if (st.grid > most) st.grid = most;
     } else {
         st.kernel = KM_KERNEL_GENERIC;
         st.variant = -1;
@@ -494,6 +530,12 @@ inline km_plan_step build_step(const Problem& pr, const Options& opt, const Vari
         if (st.grid > most) st.grid = most;
     }
     return st;
+}
+
+// The run-time-shape MFMA kernel takes single factors whose P and Q are multiples of 16.
+inline bool any_mfma_fits(const Problem& pr, int f, const Options& opt)
+{
+    return (opt.kernels >> KM_KERNEL_MFMA_ANY & 1) && pr.P[f] % 16 == 0 && pr.Q[f] % 16 == 0;
 }
 
 inline void row_widths(const Problem& pr, std::vector<int64_t>& width)
@@ -560,8 +602,9 @@ inline km_status make_plan(const Problem& pr, const Options& opt, const Variant*
     for (int r = 1; r <= N; ++r) {
         best[r] = -1;
         for (int nf = 1; nf <= r && nf <= opt.max_fuse; ++nf) {
-            const Choice ch = find_variant(table, count, pr, r - 1, nf, width[r], opt);
-            if (nf > 1 && !ch.var) continue;             // only single factors fall back to the generic kernel
+            Choice ch = find_variant(table, count, pr, r - 1, nf, width[r], opt);
+            if (nf > 1 && !ch.var) continue;             // only single factors fall back to the kernels without compiled shapes
+            if (!ch.var) ch.any_mfma = any_mfma_fits(pr, r - 1, opt);
             const double c = launch_cost(pr, width[r], width[r - nf], ch, pr.P[r - 1]) + best[r - nf];
             if (best[r] < 0 || c <= best[r] * (1 + 1e-9)) { best[r] = c; take[r] = nf; pick[r] = ch; }
         }

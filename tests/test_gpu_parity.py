@@ -148,6 +148,19 @@ SMALL_CASES = [
     ("float64", 1, [(10, 10)] * 4),
     ("float32", 2, [(12, 12)] * 4),
     ("float64", 3, [(12, 12)] * 3),
+    # P and Q multiples of 16 without compiled instances: the run-time-shape MFMA kernel (ragged last
+    # unit, slices of a unit in different rows, 3/4/5 column blocks, partial last column group, several
+    # LDS chunks with a short last one)
+    ("float32", 3, [(48, 48)] * 2),
+    ("float32", 5, [(96, 96)] * 2),
+    ("float32", 2, [(80, 112), (48, 80)]),
+    ("float64", 3, [(48, 48)] * 2),
+    ("float64", 2, [(112, 80), (96, 48)]),
+    ("float32", 7, [(144, 16)]),
+    ("float32", 301, [(48, 96)]),
+    ("float64", 67, [(80, 160)]),
+    ("float32", 2, [(48, 48)] * 3),
+    ("float32", 3, [(8, 8), (48, 48), (8, 8), (8, 8)]),
 ]
 
 
@@ -169,6 +182,27 @@ def test_small_integer_bit_exact(dtype, M, shapes):
         pytest.skip("sums not exactly representable in fp32")
     X, Fs = kron_inputs.make_problem(M, shapes, dtype, "int2", fdist, seed=7)
     assert_close(run_gpu(X, Fs), X, Fs, exact=True)
+
+
+@pytest.mark.parametrize("dtype,M,shapes", [("float32", 5, [(48, 80), (96, 48)]), ("float64", 3, [(48, 48)] * 2),
+                                            ("float32", 4, [(8, 8)] * 3), ("float32", 3, [(32, 32)] * 3),
+                                            ("float64", 2, [(5, 3), (16, 16), (7, 9)])],
+                         ids=lambda v: str(v).replace(" ", ""))
+def test_factors_need_only_their_elements_alignment(dtype, M, shapes):
+    """X and Y must start on 16-byte boundaries, factors need not: each factor here starts one element
+    into its allocation."""
+    X, Fs = kron_inputs.make_problem(M, shapes, dtype, seed=41)
+    Xd = torch.from_numpy(X).cuda()
+    Fd = []
+    for F in Fs:
+        buf = torch.empty(F.size + 1, dtype=Xd.dtype, device="cuda")
+        view = buf[1:].view(F.shape)
+        view.copy_(torch.from_numpy(F))
+        assert view.data_ptr() % 16 != 0 and view.is_contiguous()
+        Fd.append(view)
+    Y = km.kronmatmul(Xd, Fd)
+    torch.cuda.synchronize()
+    assert_close(Y.cpu().numpy(), X, Fs)
 
 
 # every compiled instance and launch mode, forced through the tuning options, on mid-size inputs
@@ -291,6 +325,8 @@ EVERY_INSTANCE = [
     ("float32", 8, [(16, 16)] * 4), ("float64", 8, [(16, 16)] * 4),
     ("float32", 8, [(64, 64)] * 3), ("float64", 8, [(64, 64)] * 3),
     ("float32", 4, [(128, 128)] * 2), ("float64", 8, [(128, 128)] * 2),
+    ("float32", 8, [(48, 48)] * 3), ("float64", 4, [(48, 48)] * 3),
+    ("float32", 2, [(96, 96)] * 3), ("float64", 8, [(96, 96)] * 2),
     ("float32", 2, [(2, 2)] * 14), ("float64", 2, [(2, 2)] * 13),
     ("float32", 3, [(3, 3)] * 9), ("float64", 3, [(3, 3)] * 9),
     ("float32", 4, [(4, 4)] * 8), ("float64", 4, [(4, 4)] * 7),
