@@ -240,6 +240,8 @@ def measure(name, args, headline):
                    "shader_clock_mhz_under_load": shader_mhz,
                    "launch_events_in_timed_region": not separate_profile,
                    "steps_replayed_from_one_graph": bool(args.graph),
+                   "planner_options": {"kernels": km.get_option(km.KM_OPT_KERNELS),
+                                       "max_fuse": km.get_option(km.KM_OPT_MAX_FUSE)},
                    "autotuned": ({"kept_ms": round(tuned[0], 4), "cost_model_ms": round(tuned[1], 4)}
                                  if tuned else False),
                    "paper_context": ({"hardware": "one V100, the paper's Table 1",
@@ -308,6 +310,10 @@ def main():
                          "calls of an iterative solver; implies --separate-profile)")
     ap.add_argument("--tune", action="store_true",
                     help="run the library's autotuner for the workload before the warm-up (set-up, not timed)")
+    ap.add_argument("--kernels", type=int, default=None,
+                    help="bit mask of kernel families the planner may use (the library's KM_OPT_KERNELS), to measure a "
+                         "family that is not planned by default, e.g. 9 = generic + the lane-exchange 8x8 kernel")
+    ap.add_argument("--max-fuse", type=int, default=None, help="upper limit on factors per launch (KM_OPT_MAX_FUSE)")
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain elementwise copy of X's size (for scaling rocprofv3 byte counters)")
@@ -322,6 +328,10 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     km.lib()
+    if args.kernels is not None:
+        km.set_option(km.KM_OPT_KERNELS, args.kernels)
+    if args.max_fuse is not None:
+        km.set_option(km.KM_OPT_MAX_FUSE, args.max_fuse)
     if args.shape:
         parse_shape(args.shape)
         args.workload = "shape_" + args.shape

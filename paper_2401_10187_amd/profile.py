@@ -57,18 +57,25 @@ def bench_args(workload):
     return ["--shape", workload[len("shape_"):]] if workload.startswith("shape_") else ["--workload", workload]
 
 
+EXTRA = []      # further benchmark options for every run of this invocation (--extra)
+
+
 def pass_command(workload, name, outdir):
     opts, extra, limit = PASSES[name]
     kill = ["timeout", "-s", "KILL", str(limit)]
     return kill + ["rocprofv3"] + opts + ["--output-format", "csv", "-d", os.path.join(outdir, name), "-o", "p", "--",
-                                          "python3", BENCH] + bench_args(workload) + extra
+                                          "python3", BENCH] + bench_args(workload) + extra + EXTRA
 
 
-def collect(workload, base, passes):
-    outdir = os.path.join(base, workload)
+def run_dir(base, workload, tag):
+    return os.path.join(base, workload + ("__" + tag if tag else ""))
+
+
+def collect(workload, base, passes, tag=""):
+    outdir = run_dir(base, workload, tag)
     os.makedirs(outdir, exist_ok=True)
     env = dict(os.environ, TMPDIR="/tmp")
-    plain = ["timeout", "-k", "10", "300", "python3", BENCH] + bench_args(workload) + ["--only-headline"]
+    plain = ["timeout", "-k", "10", "300", "python3", BENCH] + bench_args(workload) + ["--only-headline"] + EXTRA
     print("profile: " + " ".join(plain), flush=True)
     proc = subprocess.run(plain, cwd="/tmp", env=env, stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True)
     open(os.path.join(outdir, "bench.json"), "w").write(proc.stdout)
@@ -136,8 +143,8 @@ def problem_of(workload):
     return M, shapes, dtype
 
 
-def summarise(workload, base, out_folder):
-    d = os.path.join(base, workload)
+def summarise(workload, base, out_folder, tag=""):
+    d = run_dir(base, workload, tag)
     bj = json.loads([l for l in open(os.path.join(d, "bench.json")) if l.startswith("{")][-1])
     rf, cfg = bj["roofline"], bj["config"]
     M, shapes, dtype = problem_of(workload)
@@ -148,7 +155,7 @@ def summarise(workload, base, out_folder):
     # ---- kernel-trace statistics
     stats_csv, trace_csv = find_csv(os.path.join(d, "stats"), "kernel_stats.csv"), find_csv(os.path.join(d, "stats"), "kernel_trace.csv")
     add("## Kernel time: `rocprofv3 --kernel-trace --stats`\n")
-    add("    " + " ".join(pass_command(workload, "stats", os.path.join(base, workload))).replace(ROOT + "/", "") + "\n")
+    add("    " + " ".join(pass_command(workload, "stats", d)).replace(ROOT + "/", "") + "\n")
     dom_grid, dom_mean_us = None, None
     if stats_csv and trace_csv:
         add("| Name | Calls | TotalDurationNs | AverageNs | Percentage | MinNs | MaxNs | StdDev |\n|---|---|---|---|---|---|---|---|")
@@ -193,7 +200,7 @@ def summarise(workload, base, out_folder):
     write, _ = read_counters(os.path.join(d, "write"))
     add("## HBM traffic: `rocprofv3 --pmc FETCH_SIZE`, `--pmc WRITE_SIZE` (one counter per run)\n")
     for n in ("fetch", "write"):
-        add("    " + " ".join(pass_command(workload, n, os.path.join(base, workload))).replace(ROOT + "/", ""))
+        add("    " + " ".join(pass_command(workload, n, d)).replace(ROOT + "/", ""))
     if fetch and write:
         add("\n`--calibrate-copy` adds one plain elementwise kernel (torch `mul(X, 1.0, out=...)`) that reads X once and writes as "
             "many bytes; its readings give each counter's scale.\n")
@@ -230,7 +237,7 @@ def summarise(workload, base, out_folder):
     # ---- pipes
     pipes, info = read_counters(os.path.join(d, "pipes"))
     add("## Matrix cores and LDS: `rocprofv3 --pmc` (one run)\n")
-    add("    " + " ".join(pass_command(workload, "pipes", os.path.join(base, workload))).replace(ROOT + "/", "") + "\n")
+    add("    " + " ".join(pass_command(workload, "pipes", d)).replace(ROOT + "/", "") + "\n")
     if pipes:
         add("Counter means per dispatch, summed over the chip by the profiler.  Derived figures:\n"
             "- MFMA busy = SQ_VALU_MFMA_BUSY_CYCLES / (GRBM_GUI_ACTIVE x 1024 SIMDs): the profiler's own MfmaUtil expression "
@@ -270,7 +277,7 @@ def summarise(workload, base, out_folder):
         if not st:
             continue
         add("## %s: `rocprofv3 --pmc` (one run)\n" % title)
-        add("    " + " ".join(pass_command(workload, pname, os.path.join(base, workload))).replace(ROOT + "/", "") + "\n")
+        add("    " + " ".join(pass_command(workload, pname, d)).replace(ROOT + "/", "") + "\n")
         add("| kernel | grid | " + " | ".join(n.replace("_sum", "") for n in names) + " |")
         add("|---|---|" + "---|" * len(names))
         for k in sorted(st):
@@ -279,14 +286,15 @@ def summarise(workload, base, out_folder):
         add("")
 
     head = ["# %s on workload %s" % (rf["kernel"], workload), "",
-            "workload: %s" % workload, "kernel: %s" % rf["kernel"],
+            "workload: %s" % (workload + (" (%s: %s)" % (tag, " ".join(EXTRA)) if tag else "")), "kernel: %s" % rf["kernel"],
             "hbm_traffic_bytes_per_launch: %s" % (traffic if traffic is not None else "unmeasured"),
             "algorithmic_bytes_per_launch: %d" % rf["algorithmic_bytes_per_launch"], "",
             "Launches per Kron-Matmul: %s; per-launch ms from HIP events inside `bench.py`: %s."
             % (cfg["launches"], cfg["per_launch_ms"]),
             "Collected with `python3 -m paper_2401_10187_amd.profile collect --workload %s`, written by its `summarise` "
             "(commands are relative to the repository root; the harness runs them from /tmp with TMPDIR=/tmp).\n" % workload]
-    name = re.sub(r"[^A-Za-z0-9]+", "_", rf["kernel"]).strip("_") + "__" + workload.replace(":", "_").replace("^", "p").replace(",", "_") + ".md"
+    name = (re.sub(r"[^A-Za-z0-9]+", "_", rf["kernel"]).strip("_") + "__" + workload.replace(":", "_").replace("^", "p").replace(",", "_")
+            + ("__" + tag if tag else "") + ".md")
     os.makedirs(out_folder, exist_ok=True)
     path = os.path.join(out_folder, name)
     open(path, "w").write("\n".join(head + L) + "\n")
@@ -302,16 +310,21 @@ def main():
     ap.add_argument("--dir", default=os.path.join(ROOT, "gpurun_out", "prof"))
     ap.add_argument("--passes", default=DEFAULT_PASSES, help="comma-separated; known: " + ",".join(PASSES))
     ap.add_argument("--out", default=os.path.join(ROOT, "profiles"))
+    ap.add_argument("--extra", default="", help="further bench.py options for every run, e.g. \"--kernels 9 --max-fuse 1\"")
+    ap.add_argument("--tag", default="", help="suffix for the result folder and the summary's name when --extra is used")
     args = ap.parse_args()
+    EXTRA.extend(args.extra.split())
+    if EXTRA and not args.tag:
+        sys.exit("profile: --extra needs a --tag to keep its results apart")
     passes = [p for p in args.passes.split(",") if p]
     for p in passes:
         if p not in PASSES:
             sys.exit("profile: unknown pass %r" % p)
     for w in args.workload:
         if args.mode == "collect":
-            collect(w, args.dir, passes)
+            collect(w, args.dir, passes, args.tag)
         else:
-            summarise(w, args.dir, args.out)
+            summarise(w, args.dir, args.out, args.tag)
 
 
 if __name__ == "__main__":

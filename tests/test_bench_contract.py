@@ -1,7 +1,9 @@
 """The benchmark's command-line contract: one JSON line with the agreed keys; more than one GPU is
 refused with a message (this build measures one GPU)."""
+import glob
 import json
 import os
+import re
 import subprocess
 import sys
 
@@ -46,3 +48,27 @@ def test_one_json_line_with_the_agreed_keys(workload, extra):
         assert key in cpu, key
     assert cpu["kind"] == "oracle" and cpu["cores"] >= 1
     assert cpu["max_rel_err_gpu_vs_oracle"] <= (1e-5 if out["dtype"] == "f32" else 1e-12)
+
+
+def test_measured_traffic_comes_from_the_profile_summaries():
+    """roofline.traffic is not a constant in bench.py: it is read from the rocprofv3 summary under
+    profiles/ whose header names the workload.  Every summary's header figure must be the one its own
+    counter table gives, bench.py must find it, and the five measured workloads must each have one."""
+    import bench
+    files = sorted(glob.glob(os.path.join(ROOT, "profiles", "*.md")))
+    assert files
+    for path in files:
+        text = open(path).read()
+        workload = re.search(r"^workload: (.+)$", text, re.M)
+        traffic = re.search(r"^hbm_traffic_bytes_per_launch: (\d+)$", text, re.M)
+        algorithmic = re.search(r"^algorithmic_bytes_per_launch: (\d+)$", text, re.M)
+        table = re.search(r"^Dominant kernel: ([\d,]+) B measured against ([\d,]+) B algorithmic", text, re.M)
+        assert workload and traffic and algorithmic and table, path
+        t, a = int(traffic.group(1)), int(algorithmic.group(1))
+        assert t == int(table.group(1).replace(",", "")) and a == int(table.group(2).replace(",", "")), path
+        # measured traffic well above the algorithmic bytes would mean wasted re-reads
+        assert 0.95 * a <= t <= (1.1 * a if a > 1 << 24 else 2 * a), (path, t, a)
+        if " " not in workload.group(1):          # summaries of non-default planner options carry a tag after the name
+            assert bench.profile_traffic(workload.group(1)) == (t, os.path.relpath(path, ROOT)), path
+    for w in [bench.HEADLINE] + bench.OTHERS:
+        assert bench.profile_traffic(w)[0] is not None, w
