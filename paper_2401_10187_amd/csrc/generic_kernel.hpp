@@ -2,8 +2,9 @@
 // the kernel in section 4: global->LDS, LDS->registers, multiply-accumulate, permuted store).
 //
 // A unit of work is GEN_TS consecutive slices times GEN_TQ consecutive factor columns; workgroups
-// stride over the units, units of the same slices being neighbours (they share the slices through
-// the L2 cache), so that small problems still spread over many compute units.  Within a unit the
+// stride over the units, units of the same slices being numbered so that they run on the same XCD
+// (they share the slices through its L2 cache), so that small problems still spread over many
+// compute units.  Within a unit the
 // slice elements are walked in chunks of GEN_TP: the next chunk of X and F is fetched into registers
 // while the current one is multiplied out of LDS, and two LDS buffers leave one barrier per chunk.
 // Slices are numbered through all rows (row r, slice s is slice r*S + s and starts at element
@@ -17,6 +18,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include "fused_kernel.hpp"   // Vec16
+#include "plan.hpp"           // unit_of
 
 namespace km {
 
@@ -58,8 +60,11 @@ void sliced_multiply_generic(const T* __restrict__ Xg, const T* __restrict__ Fg,
 
     // the grid may be smaller than the number of units (launches are limited to 2^32 work-items)
     for (int64_t unit = blockIdx.x; unit < num_units; unit += gridDim.x) {
-        const int64_t g0 = (unit / q_groups) * GEN_TS;   // first slice of the unit, counted through all rows
-        const int q0 = (int)(unit % q_groups) * GEN_TQ;
+        int64_t tile;
+        int group;
+        unit_of(unit, num_units / q_groups, q_groups, tile, group);
+        const int64_t g0 = tile * GEN_TS;                // first slice of the unit, counted through all rows
+        const int q0 = group * GEN_TQ;
         const bool live = g0 + xs < num_slices;
         const T* xsrc = Xg + (g0 + xs) * P + xp;
 

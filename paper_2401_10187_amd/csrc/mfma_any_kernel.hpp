@@ -10,7 +10,7 @@
 //
 // A unit of work is ANY_TS = 128 consecutive slices, numbered through all rows as in the generic
 // kernel, times CB*16 factor columns; workgroups stride over the units, units of the same slices being
-// neighbours (they share the slices through the L2 cache).  P is walked in chunks of 256 bytes per
+// numbered so that they run on the same XCD (they share the slices through its L2 cache).  P is walked in chunks of 256 bytes per
 // slice (64 floats, 32 doubles; the last one may be shorter): a chunk of the slices and the matching rows of the factor,
 // transposed, sit in LDS, rows padded to an odd number of 16-byte units so that the 16-byte operand
 // reads of 16 consecutive lanes fall into different banks.  Each of the four wavefronts owns 32 slices (two MFMA blocks,
@@ -75,8 +75,11 @@ void mfma_any_sliced_multiply(const T* __restrict__ Xg, const T* __restrict__ Fg
     const int xrow = tid / 16, xcol = (tid % 16) * VN; // fetch duty: column xcol of slices xrow, xrow + 16, ...
 
     for (int64_t unit = blockIdx.x; unit < num_units; unit += gridDim.x) {
-        const int64_t g0 = (unit / q_groups) * ANY_TS;   // first slice of the unit, counted through all rows
-        const int q0 = (int)(unit % q_groups) * QG;
+        int64_t tile;
+        int group;
+        unit_of(unit, num_units / q_groups, q_groups, tile, group);
+        const int64_t g0 = tile * ANY_TS;                // first slice of the unit, counted through all rows
+        const int q0 = group * QG;
 
         typename OP::Acc acc[ANY_SB][CB];
 #pragma unroll

@@ -171,6 +171,23 @@ inline int any_column_blocks(int Q)
     return best;
 }
 
+// Units of work of the kernels without compiled shapes: (tile t of `tiles` slice tiles, group c of
+// `groups` factor-column groups).  The groups of one tile read the same slices, so they should meet in
+// one L2: workgroup b runs on XCD b % 8, hence within each run of 8 tiles the unit number is
+// b = (8 * (t / 8) * groups) + c * 8 + t % 8; the last tiles % 8 tiles are numbered plainly.
+KM_HOST_DEVICE inline void unit_of(int64_t b, int64_t tiles, int groups, int64_t& t, int& c)
+{
+    const int64_t full = tiles / 8 * 8 * groups;
+    if (b < full) {
+        t = b / (8 * groups) * 8 + b % 8;
+        c = (int)(b / 8 % groups);
+    } else {
+        b -= full;
+        t = tiles / 8 * 8 + b / groups;
+        c = (int)(b % groups);
+    }
+}
+
 // A compiled instance chosen for one group of factors, with the slices per tile it will run with.
 // What the planner needs to know of the generic kernel: a workgroup of `threads` work-items takes
 // `tile_slices` slices and `tile_cols` factor columns at a time.

@@ -504,3 +504,37 @@ def test_oracle_and_product_do_not_import_each_other():
     assert "import oracle" not in gen and "paper_2401_10187_amd" not in gen
     for needle in ("kron_matmul(", "sliced_multiply(", " @ ", "np.kron", "matmul"):
         assert needle not in gen
+
+
+def test_unit_numbering_is_a_bijection_that_keeps_a_tile_on_one_xcd(tmp_path):
+    """The kernels without compiled shapes number their units (slice tile, column group) so that the
+    groups of a tile run on the same XCD (workgroup b runs on XCD b % 8): every unit must occur exactly
+    once, and inside the whole runs of 8 tiles all groups of a tile must share b % 8."""
+    src = tmp_path / "units.cpp"
+    src.write_text(r"""
+#include "paper_2401_10187_amd/csrc/plan.hpp"
+#include <stdio.h>
+#include <vector>
+int main() {
+    for (int64_t tiles = 1; tiles <= 70; ++tiles)
+        for (int groups = 1; groups <= 9; ++groups) {
+            std::vector<int> seen(tiles * groups, 0), xcd(tiles, -1);
+            for (int64_t b = 0; b < tiles * groups; ++b) {
+                int64_t t; int c;
+                km::unit_of(b, tiles, groups, t, c);
+                if (t < 0 || t >= tiles || c < 0 || c >= groups) return 1;
+                if (seen[t * groups + c]++) return 2;
+                if (t < tiles / 8 * 8) {
+                    if (xcd[t] >= 0 && xcd[t] != b % 8) return 3;
+                    xcd[t] = (int)(b % 8);
+                }
+            }
+        }
+    puts("ok");
+    return 0;
+}
+""")
+    exe = tmp_path / "units"
+    import subprocess
+    subprocess.run(["g++", "-std=c++17", "-I", ROOT, "-o", str(exe), str(src)], check=True)
+    assert subprocess.run([str(exe)], capture_output=True, text=True).stdout.strip() == "ok"
