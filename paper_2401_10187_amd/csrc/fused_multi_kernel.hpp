@@ -66,7 +66,9 @@ struct MultiShape {
         }
         return m;
     }
-    static constexpr int LDS_BYTES = (lds_elems() * (int)sizeof(T) + 15) / 16 * 16;
+    // 32 bytes of slack: a tile that starts off a 16-byte boundary is held shifted by up to VN - 1 elements
+    static constexpr int LDS_SLACK = 32;
+    static constexpr int LDS_BYTES = (lds_elems() * (int)sizeof(T) + 15) / 16 * 16 + LDS_SLACK;
     // the tile only occupies what its st slices need, so short tiles leave LDS to more workgroups
     static constexpr int LDS_PER_SLICE = lds_elems() / STMAX * (int)sizeof(T);
     static constexpr bool VEC_ROWS = pg(0) % VN == 0;
@@ -282,7 +284,7 @@ void fused_multi_sliced_multiply(const T* __restrict__ Xg, T* __restrict__ Yg,
     typedef typename Vec16<T>::type V;
     constexpr int VN = Sh::VN;
     extern __shared__ __attribute__((aligned(16))) unsigned char multi_lds[];
-    T* tile = reinterpret_cast<T*>(multi_lds);
+    T* tile = reinterpret_cast<T*>(multi_lds);           // (moved up by a few elements below for unaligned tiles)
 
     // XCD-aware order: workgroup b runs on XCD b % 8; give each XCD a contiguous range of tiles
     int64_t t = blockIdx.x;
@@ -328,31 +330,37 @@ void fused_multi_sliced_multiply(const T* __restrict__ Xg, T* __restrict__ Yg,
         const V* vsrc = reinterpret_cast<const V*>(src - mis);
         const int nv = unaligned_vectors(valid, mis, VN), nfull = unaligned_whole_vectors(valid, mis, VN);
         constexpr int UN = 4;
-        for (int base = 0; base < nv; base += UN * NT) {
+        // With odd P nothing downstream reads LDS in vectors (every group length is odd) and no row is
+        // padded, so the tile may sit in LDS shifted by `mis` elements: vector v of global memory then is
+        // vector v of LDS and goes in with one 16-byte write, foreign elements at both ends included
+        // (they fall outside the tile and are never read).  Otherwise the elements are placed one by one.
+        constexpr bool SHIFT = P % 2 == 1 && PAD0 == 0;
+        if constexpr (SHIFT) tile += mis;
+        for (int base = 0; base < nfull; base += UN * NT) {
             V tmp[UN];
 #pragma unroll
             for (int i = 0; i < UN; ++i) {
                 const int v = base + tid + i * NT;
                 if (v < nfull) tmp[i] = stream_load(&vsrc[v]);
-                else if (v < nv) {
-#pragma unroll
-                    for (int k = 0; k < VN; ++k) {
-                        const int e = v * VN + k - mis;
-                        tmp[i][k] = (e >= 0 && e < valid) ? src[e] : T(0);
-                    }
-                }
             }
 #pragma unroll
             for (int i = 0; i < UN; ++i) {
                 const int v = base + tid + i * NT;
-                if (v < nv) {
+                if (v < nfull) {
+                    if constexpr (SHIFT) {
+                        reinterpret_cast<V*>(multi_lds)[v] = tmp[i];
+                    } else {
 #pragma unroll
-                    for (int k = 0; k < VN; ++k) {
-                        const int e = v * VN + k - mis;
-                        if (e >= 0 && e < valid) tile[multi_lds_index<PG0, PAD0>(e)] = tmp[i][k];
+                        for (int k = 0; k < VN; ++k) {
+                            const int e = v * VN + k - mis;
+                            if (e >= 0 && e < valid) tile[multi_lds_index<PG0, PAD0>(e)] = tmp[i][k];
+                        }
                     }
                 }
             }
+        }
+        if (nfull < nv && tid == NT - 1) {               // the tile's share of the last, partial vector
+            for (int e = nfull * VN - mis < 0 ? 0 : nfull * VN - mis; e < valid; ++e) tile[multi_lds_index<PG0, PAD0>(e)] = src[e];
         }
     }
     __syncthreads();

@@ -28,7 +28,7 @@ hipError_t launch_multi(const LaunchArgs& a)
     if (rows > 1 && tiles_per_row != 1) return hipErrorInvalidValue;
     const int64_t tiles = rows > 1 ? (a.pr->M + rows - 1) / rows : a.pr->M * tiles_per_row;
     if (tiles != st.grid) return hipErrorInvalidValue;
-    if (st.lds_bytes < Sh::LDS_PER_SLICE * slices || st.lds_bytes > Sh::LDS_BYTES) return hipErrorInvalidValue;
+    if (st.lds_bytes < Sh::LDS_PER_SLICE * slices + Sh::LDS_SLACK || st.lds_bytes > Sh::LDS_BYTES) return hipErrorInvalidValue;
     hipLaunchKernelGGL(kern, dim3((unsigned)st.grid), dim3(NT), (size_t)st.lds_bytes, a.stream,
                        (const T*)a.src, (T*)a.dst, fp, st.k_in, st.k_out, tiles_per_row, (int64_t)st.grid,
                        slices, rows, a.pr->M);

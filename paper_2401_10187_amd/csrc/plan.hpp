@@ -37,7 +37,7 @@ struct Variant {
 inline int launch_lds_bytes(const Variant& c, int tile_slices)
 {
     if (!c.flexible || c.lds_per_slice <= 0) return c.lds_bytes;
-    const int64_t b = ((int64_t)c.lds_per_slice * tile_slices + 15) / 16 * 16;
+    const int64_t b = ((int64_t)c.lds_per_slice * tile_slices + 15) / 16 * 16 + 32;   // 32: slack for tiles held shifted
     return b < c.lds_bytes ? (int)b : c.lds_bytes;
 }
 
