@@ -380,9 +380,9 @@ inline Choice find_variant(const Variant* table, int count, const Problem& pr, i
             // 1296), then tiles of at most 48 KB of LDS (three and more workgroups per compute unit are
             // 10-30 % faster than two) unless that would cut runs that are not whole lines below 256
             // bytes (6^6: 288-byte runs in 62 KB tiles are 50 % faster than 96-byte runs in 21 KB
-            // tiles; rows of odd length, where no run is ever aligned, from 128 bytes: 5^8 with 500-byte
-            // runs in 62 KB tiles is 34 % faster than with 100-byte runs in 12 KB tiles), then the
-            // longest tile.
+            // tiles; rows of odd length, where no run is ever aligned, below 64 bytes: since such tiles
+            // are fetched with 16-byte loads and LDS writes, 5^8 with 100-byte runs in 12 KB tiles is
+            // 20 % faster than with 500-byte runs in 62 KB tiles), then the longest tile.
             const int64_t lim = s_row < c.tile_slices ? s_row : c.tile_slices;
             const int64_t fit = c.lds_per_slice > 0 ? (48 * 1024) / c.lds_per_slice : lim;
             const int64_t row_bytes = s_row * (int64_t)pr.esize;
@@ -394,7 +394,7 @@ inline Choice find_variant(const Variant* table, int count, const Problem& pr, i
                 const int64_t run = d * (int64_t)pr.esize;
                 int64_t align = run & -run;                          // largest power of two dividing the run
                 if (align > 128) align = 128;
-                const bool small_enough = d <= fit && (align >= 128 || run >= 256 || (!alignable && run >= 128));
+                const bool small_enough = d <= fit && (align >= 128 || run >= 256 || (!alignable && run >= 64));
                 const int64_t key = (align * 2 + (small_enough ? 1 : 0)) * (lim + 1) + d;
                 if (key > best_key[0]) { best_key[0] = key; cand[0] = (int)d; }
                 // ... that leaves enough workgroups: 512 with at least 16 busy threads, else 96 with at
@@ -461,6 +461,12 @@ inline double launch_cost(const Problem& pr, int64_t k_in, int64_t k_out, const 
         // a tile that holds a whole row writes the whole output row: its runs join up
         if (ch.tile_rows > 1 || ch.grid == pr.M) run = k_out * (int64_t)pr.esize;
         slow = run >= 128 ? 1.0 : (run >= 64 ? 1.25 : (run >= 32 ? 2.5 : 4.0));
+        // Rows of odd length: no run ever fills whole lines, so short runs cost less on top (measured
+        // with the autotuner: 1024 x 7^6 as 3+3 factors with 28-byte runs is 12 % faster than 2+2+2 with
+        // 196-byte runs, 9^5 as 2+3 with 36-byte runs 19 % faster than 2+2+1, 3^11 as 7+4 with 12-byte
+        // runs 3 % faster than 4+4+3)
+        const int64_t row_bytes = k_out * (int64_t)pr.esize;
+        if ((row_bytes & -row_bytes) < 16) slow = run >= 64 ? 1.0 : (run >= 32 ? 1.15 : (run >= 16 ? 1.3 : 1.9));
         slow *= ch.var->slowdown;
     }
     // fewer workgroups than compute units: the launch streams at a matching fraction of the chip's

@@ -802,7 +802,9 @@ def test_tuned_plan_matches_the_oracle(dtype, M, shapes):
 # are not launch-bound.  Exceptions (shape: reason) are listed in the design notes; none at present.
 PLANNER_CHECK = ([(c["dtype"], c["M"], c["shapes"]) for c in kron_inputs.CONFIGS.values()]
                  + [("float32", t[1], t[2]) for t in kron_inputs.TABLE4 if t[0] in (17, 18, 19, 24, 25, 26, 27, 28)]
-                 + [("float64", t[1], t[2]) for t in kron_inputs.TABLE4 if t[0] in (25, 28)])
+                 + [("float64", t[1], t[2]) for t in kron_inputs.TABLE4 if t[0] in (25, 28)]
+                 + [("float32", 1024, [(p, p)] * n) for p, n in ((3, 11), (5, 8), (7, 6), (9, 5))]      # rows of odd length
+                 + [("float32", 1024, [(48, 48)] * 3), ("float32", 256, [(80, 80)] * 3)])               # other multiples of 16
 
 
 @pytest.mark.parametrize("dtype,M,shapes", PLANNER_CHECK, ids=lambda v: str(v).replace(" ", "")[:40])

@@ -215,7 +215,7 @@ def test_walk_lengths_follow_the_measured_rule():
 
 def test_tile_lengths_for_small_problems_and_odd_rows():
     """Small problems keep several threads of a workgroup busy instead of cutting one-slice tiles to
-    reach more workgroups; rows of odd length take tiles whose output runs reach 128 bytes; long
+    reach more workgroups; rows of odd length take tiles whose output runs reach 64 bytes; long
     rows that do not start on 16-byte boundaries are not joined into tiles of several rows."""
     old = km.get_option(km.KM_OPT_KERNELS)
     try:
@@ -227,7 +227,7 @@ def test_tile_lengths_for_small_problems_and_odd_rows():
     finally:
         km.set_option(km.KM_OPT_KERNELS, old)
     first = km.plan(1024, [5] * 8, [5] * 8, "float32")[0]
-    assert first["num_factors"] == 3 and first["tile_slices"] == 125
+    assert first["num_factors"] == 3 and first["tile_slices"] == 25       # 100-byte runs, 12 KB tiles
     assert all(st["tile_rows"] == 1 for st in km.plan(1024, [3] * 7, [3] * 7, "float32"))
     assert all(st["tile_rows"] == 2 for st in km.plan(1526, [4] * 6, [4] * 6, "float32"))
     assert km.plan(1 << 20, [4] * 4, [4] * 4, "float32")[0]["tile_rows"] > 8
