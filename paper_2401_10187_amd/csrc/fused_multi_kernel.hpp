@@ -66,8 +66,9 @@ struct MultiShape {
         }
         return m;
     }
-    // 32 bytes of slack: a tile that starts off a 16-byte boundary is held shifted by up to VN - 1 elements
-    static constexpr int LDS_SLACK = 32;
+    // 32 bytes of slack where a tile that starts off a 16-byte boundary is held shifted by up to VN - 1
+    // elements (odd P only; tiles of exactly 64 KB must not grow: two of them no longer share a compute unit)
+    static constexpr int LDS_SLACK = P % 2 == 1 ? 32 : 0;
     static constexpr int LDS_BYTES = (lds_elems() * (int)sizeof(T) + 15) / 16 * 16 + LDS_SLACK;
     // the tile only occupies what its st slices need, so short tiles leave LDS to more workgroups
     static constexpr int LDS_PER_SLICE = lds_elems() / STMAX * (int)sizeof(T);

@@ -39,7 +39,8 @@ namespace km {
     {KM_KERNEL_FUSED, DT, P, Q, G0 + G1 + G2, ST, NT, MultiShape<T, P, Q, G0, G1, G2, ST, NT>::LDS_BYTES, 1, 0, 1, \
      (G0 == 1 && P < 8) ? 1.6f                           /* one tiny factor per LDS pass is instruction-bound */ \
      : (P == 3 && G0 + G1 + G2 >= 5) ? 1.2f : 1.0f,      /* 3^5 and more elements per slice: long runs need tiles that leave two workgroups per compute unit */ \
-     "fused-multi", MultiShape<T, P, Q, G0, G1, G2, ST, NT>::LDS_PER_SLICE, (int)ipow(P, G0)},
+     "fused-multi", MultiShape<T, P, Q, G0, G1, G2, ST, NT>::LDS_PER_SLICE, (int)ipow(P, G0), 0, 0, 0, 0, \
+     MultiShape<T, P, Q, G0, G1, G2, ST, NT>::LDS_SLACK},
 #define KM_ROWS_ROW(P, ST, NW) \
     {KM_KERNEL_MFMA, KM_F32, P, 32, 2, 1, NW * 64, 0, ST, 2, 0, 1.0f, "mfma-pair-rows"},
 #define KM_ROWS_FN(P, ST, NW) launch_mfma_pair_rows<P, ST, NW>,

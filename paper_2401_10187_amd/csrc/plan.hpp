@@ -31,13 +31,14 @@ struct Variant {
     int min_tiles;     // > 0: only planned for launches of at least this many tiles (the tuner still tries it)
     int walk;          // > 0: tiles per workgroup of a persistent instance, instead of the rule of tiles_per_wg()
     int xcd_order;     // 1: persistent instance that prefers tile order 3 (each XCD walks its own eighth of the tiles)
+    int lds_slack;     // flexible instances: LDS bytes a launch needs on top of lds_per_slice * tile_slices
 };
 
 // LDS a launch of the instance asks for when its tiles hold `tile_slices` slices.
 inline int launch_lds_bytes(const Variant& c, int tile_slices)
 {
     if (!c.flexible || c.lds_per_slice <= 0) return c.lds_bytes;
-    const int64_t b = ((int64_t)c.lds_per_slice * tile_slices + 15) / 16 * 16 + 32;   // 32: slack for tiles held shifted
+    const int64_t b = ((int64_t)c.lds_per_slice * tile_slices + 15) / 16 * 16 + c.lds_slack;
     return b < c.lds_bytes ? (int)b : c.lds_bytes;
 }
 
