@@ -314,6 +314,9 @@ def main():
                     help="bit mask of kernel families the planner may use (the library's KM_OPT_KERNELS), to measure a "
                          "family that is not planned by default, e.g. 9 = generic + the lane-exchange 8x8 kernel")
     ap.add_argument("--max-fuse", type=int, default=None, help="upper limit on factors per launch (KM_OPT_MAX_FUSE)")
+    ap.add_argument("--instance", type=int, default=None,
+                    help="make the planner take compiled instance number N (a plan step's `variant`) wherever it fits "
+                         "(KM_OPT_PREFER_INSTANCE), to measure an instance that is not the planner's choice")
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain elementwise copy of X's size (for scaling rocprofv3 byte counters)")
@@ -332,6 +335,8 @@ def main():
         km.set_option(km.KM_OPT_KERNELS, args.kernels)
     if args.max_fuse is not None:
         km.set_option(km.KM_OPT_MAX_FUSE, args.max_fuse)
+    if args.instance is not None:
+        km.set_option(km.KM_OPT_PREFER_INSTANCE, args.instance + 1)
     if args.shape:
         parse_shape(args.shape)
         args.workload = "shape_" + args.shape
