@@ -2,8 +2,8 @@
 counters, matrix-core (MFMA) utilisation and LDS bank-conflict rate of a workload's kernels, against
 the chip's published peaks.
 
-    python3 -m paper_2401_10187_amd.profile collect   --workload c3_f32_m1024_32x32x4 [--dir gpurun_out/prof]
-    python3 -m paper_2401_10187_amd.profile summarise --workload c3_f32_m1024_32x32x4 [--dir gpurun_out/prof]
+    python3 -m paper_2401_10187_amd.profile collect   --workload c3_f32_m1024_32x32x4 [--dir DIR]
+    python3 -m paper_2401_10187_amd.profile summarise --workload c3_f32_m1024_32x32x4 [--dir DIR]
 
 `collect` needs the GPU: it runs the benchmark once plainly and then once under rocprofv3 per pass (the
 profiler collects one counter set per run), the program after `--` always being `python3 bench.py ...`
