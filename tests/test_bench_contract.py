@@ -72,3 +72,26 @@ def test_measured_traffic_comes_from_the_profile_summaries():
             assert bench.profile_traffic(workload.group(1)) == (t, os.path.relpath(path, ROOT)), path
     for w in [bench.HEADLINE] + bench.OTHERS:
         assert bench.profile_traffic(w)[0] is not None, w
+
+
+def test_profiler_commands_keep_to_what_the_profiler_can_collect():
+    """Every rocprofv3 command of the harness runs `python3 bench.py ...` directly after `--`, collects
+    counters in runs of their own (never together with a trace), and asks for no more counters of one
+    hardware block than a single run can hold (8 SQ, 4 TCC, 4 TCP, 2 TA, 2 GRBM)."""
+    from paper_2401_10187_amd import profile
+    limits = {"SQ_": 8, "TCC_": 4, "TCP_": 4, "TA_": 2, "TD_": 2, "GRBM_": 2}
+    for name in profile.PASSES:
+        cmd = profile.pass_command("c2_f32_m1024_8x8x6", name, "/tmp/out")
+        assert cmd[:3] == ["timeout", "-s", "KILL"] and cmd[4] == "rocprofv3"
+        split = cmd.index("--")
+        assert cmd[split + 1] == "python3" and cmd[split + 2].endswith("bench.py")
+        opts = cmd[5:split]
+        if "--pmc" in opts:
+            assert not any(o in opts for o in ("--kernel-trace", "--stats", "--sys-trace", "--hip-trace", "--hsa-trace"))
+            counters = opts[opts.index("--pmc") + 1:opts.index("--output-format")]
+            for block, most in limits.items():
+                stems = {re.sub(r"_(sum|avr|min|max)$", "", c) for c in counters if c.startswith(block)}
+                cost = sum(3 if c == "FETCH_SIZE" else 2 if c == "WRITE_SIZE" else 1 for c in stems)
+                assert cost <= most, (name, block, sorted(stems))
+        else:
+            assert "--kernel-trace" in opts
