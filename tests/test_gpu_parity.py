@@ -821,6 +821,51 @@ def test_cost_model_plan_is_close_to_the_tuned_plan(dtype, M, shapes):
         torch.cuda.empty_cache()
 
 
+def test_concurrent_callers_on_their_own_streams_and_workspaces():
+    """Entry points are thread-safe with respect to each other: four host threads, each with its own
+    stream, workspace and problem (profiling switched on, so that the shared event pool grows under
+    them), call kronmatmul_ws repeatedly; every result must be the oracle's."""
+    import threading
+    problems = [("float32", 16, [(8, 8)] * 5), ("float64", 3, [(16, 16)] * 3),
+                ("float32", 6, [(32, 32)] * 3), ("float32", 5, [(48, 80), (96, 48)])]
+    data, errors = [], []
+    for k, (dtype, M, shapes) in enumerate(problems):
+        X, Fs = kron_inputs.make_problem(M, shapes, dtype, seed=300 + k)
+        P, Q = [s[0] for s in shapes], [s[1] for s in shapes]
+        Xd = torch.from_numpy(X).cuda()
+        Fd = [torch.from_numpy(F).cuda() for F in Fs]
+        ws = torch.empty(max(km.workspace_size(M, P, Q, dtype), 1), dtype=torch.uint8, device="cuda")
+        Yd = torch.empty((M, int(np.prod(Q))), dtype=Xd.dtype, device="cuda")
+        km.prepare(M, P, Q, dtype)
+        data.append((X, Fs, Xd, Fd, ws, Yd, torch.cuda.Stream()))
+    torch.cuda.synchronize()
+
+    def worker(item):
+        try:
+            X, Fs, Xd, Fd, ws, Yd, stream = item
+            call = km.Prepared(Xd, Fd, Y=Yd, workspace=ws)
+            for _ in range(25):
+                call(stream.cuda_stream)
+            stream.synchronize()
+        except Exception as exc:          # noqa: BLE001 - reported in the main thread
+            errors.append(exc)
+
+    km.set_option(km.KM_OPT_PROFILE, 1)
+    try:
+        threads = [threading.Thread(target=worker, args=(item,)) for item in data]
+        for t in threads:
+            t.start()
+        for t in threads:
+            t.join()
+    finally:
+        km.set_option(km.KM_OPT_PROFILE, 0)
+    torch.cuda.synchronize()
+    assert not errors, errors
+    for X, Fs, _Xd, _Fd, _ws, Yd, _stream in data:
+        assert_close(Yd.cpu().numpy(), X, Fs)
+    km.release()
+
+
 def test_clock_probe_reports_both_clocks():
     """The probe sleeps for the asked time and reports how far the shader clock and the constant
     100 MHz clock advanced; next to a Kron-Matmul on another stream it neither disturbs the result
