@@ -197,10 +197,14 @@ km_status kronmatmul_cost(int M, int N, const int* P, const int* Q, km_dtype dty
  * KM_OPT_PREFER_INSTANCE: tuning aid; k > 0 makes the planner take compiled instance k - 1 (the
  * `variant` of a plan step) wherever it fits the shape (0 = automatic); k = instance count + 1
  * makes it take the whole-row kernel (KM_KERNEL_ROWS) whenever the rows fit LDS.
- * KM_OPT_INSTANCE_COUNT: read-only; the number of compiled instances. */
+ * KM_OPT_INSTANCE_COUNT: read-only; the number of compiled instances.
+ * KM_OPT_KEEP_MIB: tuning aid (default 320); a launch that is not a call's last and writes between 48
+ * and this many MiB uses ordinary instead of non-temporal stores, so that the next launch finds
+ * part of the intermediate in the chip's last-level cache (256 MB); 0 = non-temporal always.  It takes
+ * effect on the next call and changes no result. */
 typedef enum { KM_OPT_KERNELS = 0, KM_OPT_MAX_FUSE = 1, KM_OPT_PROFILE = 2, KM_OPT_PREFER_TILE = 3,
                KM_OPT_PREFER_THREADS = 4, KM_OPT_TILES_PER_WG = 5, KM_OPT_PAIR_INTERLEAVE = 6, KM_OPT_TILE_ORDER = 7,
-               KM_OPT_PREFER_INSTANCE = 8, KM_OPT_INSTANCE_COUNT = 9 } km_option;
+               KM_OPT_PREFER_INSTANCE = 8, KM_OPT_INSTANCE_COUNT = 9, KM_OPT_KEEP_MIB = 10 } km_option;
 km_status kronmatmul_set_option(km_option option, int value);
 km_status kronmatmul_get_option(km_option option, int* value);
 

@@ -11,7 +11,7 @@ KM_OK, KM_EINVAL, KM_ENOMEM, KM_ELAUNCH, KM_EUNSUPPORTED = 0, 1, 2, 3, 4
 KM_KERNEL_GENERIC, KM_KERNEL_FUSED, KM_KERNEL_MFMA, KM_KERNEL_SHUFFLE, KM_KERNEL_ROWS, KM_KERNEL_MFMA_ANY = 0, 1, 2, 3, 4, 5
 KM_BUF_X, KM_BUF_Y, KM_BUF_WS0, KM_BUF_WS1 = 0, 1, 2, 3
 KM_OPT_KERNELS, KM_OPT_MAX_FUSE, KM_OPT_PROFILE, KM_OPT_PREFER_TILE, KM_OPT_PREFER_THREADS, KM_OPT_TILES_PER_WG, KM_OPT_PAIR_INTERLEAVE, KM_OPT_TILE_ORDER = 0, 1, 2, 3, 4, 5, 6, 7
-KM_OPT_PREFER_INSTANCE, KM_OPT_INSTANCE_COUNT = 8, 9
+KM_OPT_PREFER_INSTANCE, KM_OPT_INSTANCE_COUNT, KM_OPT_KEEP_MIB = 8, 9, 10
 
 EXPORTS = [
     "kronmatmul_workspace_size", "kronmatmul", "kronmatmul_ws", "kronmatmul_plan",

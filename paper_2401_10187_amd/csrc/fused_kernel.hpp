@@ -34,6 +34,15 @@ template <> struct Vec16<double> { typedef double type __attribute__((ext_vector
 // default caching on the 8x8 workload).
 template <typename V> __device__ __forceinline__ V stream_load(const V* p) { return __builtin_nontemporal_load(p); }
 template <typename V> __device__ __forceinline__ void stream_store(V v, V* p) { __builtin_nontemporal_store(v, p); }
+// Output that the next launch reads back and that fits the chip's last-level cache (256 MB) is
+// written with ordinary stores instead (KEEP): the next launch then finds part of it on chip
+// (measured: 16 x 128x128^3 fp64 0.462 -> 0.437 ms, 256 x 8x8^6 0.198 -> 0.190; beyond 400 MB per
+// launch ordinary stores are 2-8 % slower than non-temporal ones).
+template <bool KEEP, typename V> __device__ __forceinline__ void out_store(V v, V* p)
+{
+    if constexpr (KEEP) *p = v;
+    else __builtin_nontemporal_store(v, p);
+}
 
 // read-only data that is uniform across a wavefront: scalar loads
 #pragma clang diagnostic push
@@ -62,7 +71,7 @@ struct FusedShape {
 };
 
 // One stage: factor `Fc` applied to the tile held in `tile` (size(J) elements).
-template <typename T, int P, int Q, int NF, int ST, int NT, int J>
+template <typename T, int P, int Q, int NF, int ST, int NT, int J, bool KEEP>
 __device__ __forceinline__ void fused_stage(T* __restrict__ tile, const T* Fg, T* __restrict__ Yrow,
                                             int64_t s_row, int64_t h)
 {
@@ -128,13 +137,13 @@ __device__ __forceinline__ void fused_stage(T* __restrict__ tile, const T* Fg, T
             if (FULL || s < SJ) {
                 T* dst = Yrow + (int64_t)(s / ST) * s_row + h * ST + (s % ST);
 #pragma unroll
-                for (int q = 0; q < Q; ++q) stream_store(out[i][q], &dst[(int64_t)(q * QREST) * s_row]);
+                for (int q = 0; q < Q; ++q) out_store<KEEP>(out[i][q], &dst[(int64_t)(q * QREST) * s_row]);
             }
         }
     }
 }
 
-template <typename T, int P, int Q, int NF, int ST, int NT>
+template <typename T, int P, int Q, int NF, int ST, int NT, bool KEEP>
 __global__ __launch_bounds__(NT)
 void fused_sliced_multiply(const T* __restrict__ Xg, T* __restrict__ Yg,
                            const T* F0, const T* F1, const T* F2,   // in order of application
@@ -175,9 +184,9 @@ void fused_sliced_multiply(const T* __restrict__ Xg, T* __restrict__ Yg,
     }
     __syncthreads();
 
-    fused_stage<T, P, Q, NF, ST, NT, 0>(tile, F0, Yrow, s_row, h);
-    if constexpr (NF > 1) fused_stage<T, P, Q, NF, ST, NT, 1>(tile, F1, Yrow, s_row, h);
-    if constexpr (NF > 2) fused_stage<T, P, Q, NF, ST, NT, 2>(tile, F2, Yrow, s_row, h);
+    fused_stage<T, P, Q, NF, ST, NT, 0, KEEP>(tile, F0, Yrow, s_row, h);
+    if constexpr (NF > 1) fused_stage<T, P, Q, NF, ST, NT, 1, KEEP>(tile, F1, Yrow, s_row, h);
+    if constexpr (NF > 2) fused_stage<T, P, Q, NF, ST, NT, 2, KEEP>(tile, F2, Yrow, s_row, h);
 }
 
 }  // namespace km

@@ -14,7 +14,20 @@ struct LaunchArgs {
     const km_plan_step* st;
     hipStream_t stream;
     bool prepare_only;            // set the kernel's attributes on the current device, launch nothing
+    bool keep_output;             // the next launch reads dst back and it fits the last-level cache: ordinary
+                                  // instead of non-temporal stores (kernels that have both forms)
 };
+
+// Launchers of kernels with both store forms: prepares both, launches the one the arguments ask for.
+template <class Impl>
+inline hipError_t launch_either(const LaunchArgs& a)
+{
+    if (a.prepare_only) {
+        hipError_t e = Impl::template run<false>(a);
+        return e != hipSuccess ? e : Impl::template run<true>(a);
+    }
+    return a.keep_output ? Impl::template run<true>(a) : Impl::template run<false>(a);
+}
 typedef hipError_t (*LaunchFn)(const LaunchArgs&);
 
 // Kernels that need more than 48 KB of dynamic LDS must raise their limit once per device.

@@ -9,11 +9,13 @@
 namespace km {
 
 template <typename T, int P, int Q, int NF, int ST, int NT>
-hipError_t launch_fused(const LaunchArgs& a)
+struct FusedLauncher {
+template <bool KEEP>
+static hipError_t run(const LaunchArgs& a)
 {
     typedef FusedShape<T, P, Q, NF, ST, NT> Sh;
     const km_plan_step& st = *a.st;
-    auto kern = fused_sliced_multiply<T, P, Q, NF, ST, NT>;
+    auto kern = fused_sliced_multiply<T, P, Q, NF, ST, NT, KEEP>;
     static unsigned char lds_ok[64];
     hipError_t e = allow_lds((const void*)kern, Sh::LDS_BYTES, lds_ok);
     if (e != hipSuccess || a.prepare_only) return e;
@@ -25,6 +27,10 @@ hipError_t launch_fused(const LaunchArgs& a)
                        (int64_t)st.grid);
     return hipGetLastError();
 }
+};
+
+template <typename T, int P, int Q, int NF, int ST, int NT>
+hipError_t launch_fused(const LaunchArgs& a) { return launch_either<FusedLauncher<T, P, Q, NF, ST, NT>>(a); }
 
 inline hipError_t launch_shuffle_impl(const LaunchArgs& a)
 {

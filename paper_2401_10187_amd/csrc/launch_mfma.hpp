@@ -8,12 +8,14 @@
 namespace km {
 
 template <class OP, int P, int Q, int NF, int ST, int NW, int QSPLIT>
-hipError_t launch_mfma(const LaunchArgs& a)
+struct MfmaLauncher {
+template <bool KEEP>
+static hipError_t run(const LaunchArgs& a)
 {
     typedef MfmaShape<OP, P, Q, NF, ST, NW, QSPLIT> Sh;
     typedef typename OP::T T;
     const km_plan_step& st = *a.st;
-    auto kern = mfma_sliced_multiply<OP, P, Q, NF, ST, NW, QSPLIT>;
+    auto kern = mfma_sliced_multiply<OP, P, Q, NF, ST, NW, QSPLIT, KEEP>;
     static unsigned char lds_ok[64];
     hipError_t e = allow_lds((const void*)kern, Sh::LDS_BYTES, lds_ok);
     if (e != hipSuccess || a.prepare_only) return e;
@@ -31,5 +33,9 @@ hipError_t launch_mfma(const LaunchArgs& a)
                        st.tile_order);
     return hipGetLastError();
 }
+};
+
+template <class OP, int P, int Q, int NF, int ST, int NW, int QSPLIT>
+hipError_t launch_mfma(const LaunchArgs& a) { return launch_either<MfmaLauncher<OP, P, Q, NF, ST, NW, QSPLIT>>(a); }
 
 }  // namespace km

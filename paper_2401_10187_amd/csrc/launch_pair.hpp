@@ -8,11 +8,13 @@
 namespace km {
 
 template <int P, int ST, int NW, int PD, int NPASS>
-hipError_t launch_mfma_pair(const LaunchArgs& a)
+struct PairLauncher {
+template <bool KEEP>
+static hipError_t run(const LaunchArgs& a)
 {
     typedef MfmaPairShape<P, ST, NW, PD, NPASS> Sh;
     const km_plan_step& st = *a.st;
-    auto kern = mfma_pair_sliced_multiply<P, ST, NW, PD, NPASS>;
+    auto kern = mfma_pair_sliced_multiply<P, ST, NW, PD, NPASS, KEEP>;
     static unsigned char lds_ok[64];
     hipError_t e = allow_lds((const void*)kern, Sh::LDS_BYTES, lds_ok);
     if (e != hipSuccess || a.prepare_only) return e;
@@ -29,6 +31,10 @@ hipError_t launch_mfma_pair(const LaunchArgs& a)
                        st.tile_order);
     return hipGetLastError();
 }
+};
+
+template <int P, int ST, int NW, int PD, int NPASS>
+hipError_t launch_mfma_pair(const LaunchArgs& a) { return launch_either<PairLauncher<P, ST, NW, PD, NPASS>>(a); }
 
 template <int P, int ST, int NW>
 hipError_t launch_mfma_pair_rows(const LaunchArgs& a)

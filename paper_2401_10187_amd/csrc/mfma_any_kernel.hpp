@@ -1,5 +1,6 @@
-// One sliced-multiply iteration on the matrix cores for any factor whose P and Q are multiples of 16
-// (run-time shapes: 48, 80, 96, 112, 144, ... and rectangles of them), fp32 and fp64.
+// One sliced-multiply iteration on the matrix cores for a factor of any shape whose slices start on
+// 16-byte boundaries (P a multiple of 4 floats or 2 doubles; run-time shapes: 20, 48, 80, 96, 100, ...
+// and rectangles), fp32 and fp64.  P and Q are padded with zeros to multiples of 16 on the way into LDS.
 //
 // The contraction of a slice with the factor (Algorithm 1's inner loop) is the dense product
 //     D[q][s] = sum_p F[p][q] * X[s*P + p]
@@ -8,15 +9,16 @@
 // and stores are runs of the output row (the output column of (s, q) is q*(K/P)+s; section 4 of the
 // paper, with the matrix cores in place of its thread tiles).
 //
-// A unit of work is ANY_TS = 128 consecutive slices, numbered through all rows as in the generic
+// A unit of work is 128 consecutive slices (256 in the narrow shape, see AnyShape), numbered through all rows as in the generic
 // kernel, times CB*16 factor columns; workgroups stride over the units, units of the same slices being
 // numbered so that they run on the same XCD (they share the slices through its L2 cache).  P is walked in chunks of 256 bytes per
 // slice (64 floats, 32 doubles; the last one may be shorter): a chunk of the slices and the matching rows of the factor,
 // transposed, sit in LDS, rows padded to an odd number of 16-byte units so that the 16-byte operand
 // reads of 16 consecutive lanes fall into different banks.  Each of the four wavefronts owns 32 slices (two MFMA blocks,
 // joined before the store in fp32 so that a half wavefront writes a whole 128-byte line) and all
-// CB column blocks.  Loads and stores are bounds-checked against the slice and column counts, so
-// nothing but P % 16 == 0 and Q % 16 == 0 is assumed.
+// CB column blocks.  Loads and stores are bounds-checked against the slice, element and column counts;
+// the factor is read with 16-byte loads when its rows start on 16-byte boundaries (f_aligned: base
+// aligned and Q a whole number of vectors), element by element otherwise.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -28,43 +30,48 @@ namespace km {
 
 constexpr int ANY_NW = 4;                   // wavefronts per workgroup
 constexpr int ANY_THREADS = 64 * ANY_NW;
-constexpr int ANY_SB = 2;                   // 16-slice blocks per wavefront
-constexpr int ANY_TS = 16 * ANY_SB * ANY_NW;   // slices per unit
-constexpr int ANY_ROW_BYTES = 256;          // bytes of a slice per LDS chunk (64 floats, 32 doubles)
+constexpr int ANY_TS = 32 * ANY_NW;         // slices per unit of the wide shape (two 16-slice blocks per wavefront)
+constexpr int ANY_ROW_BYTES = 256;          // bytes of a slice per LDS chunk of the wide shape (64 floats, 32 doubles)
 
 template <typename T> struct AnyOp;
 template <> struct AnyOp<float> { typedef MfmaF32x16 OP; };
 template <> struct AnyOp<double> { typedef MfmaF64x16 OP; };
 
-template <typename T, int CB>
+// NARROW (slices of at most 128 bytes): chunks of half the bytes and units of twice the slices, so
+// that a unit still moves enough bytes to keep the memory system busy and fewer lanes idle in the loads.
+template <typename T, int CB, bool NARROW>
 struct AnyShape {
     static constexpr int VN = Vec16<T>::N;
-    static constexpr int KT = ANY_ROW_BYTES / (int)sizeof(T);   // slice elements per LDS chunk
+    static constexpr int SB = NARROW ? 4 : 2;                   // 16-slice blocks per wavefront
+    static constexpr int TS = 16 * SB * ANY_NW;                 // slices per unit
+    static constexpr int KT = ANY_ROW_BYTES / (NARROW ? 2 : 1) / (int)sizeof(T);   // slice elements per LDS chunk
     static constexpr int ROW = KT + VN;                         // padded LDS row: an odd number of 16-byte units
     static constexpr int QG = CB * 16;                          // factor columns per unit
-    static constexpr int X_ELEMS = ANY_TS * ROW, F_ELEMS = QG * ROW;
+    static constexpr int X_ELEMS = TS * ROW, F_ELEMS = QG * ROW;
     static constexpr int LDS_BYTES = (X_ELEMS + F_ELEMS) * (int)sizeof(T);
     static constexpr int VPR = KT / VN;                         // 16-byte vectors per chunk row of a slice
-    static constexpr int XV = ANY_TS * VPR / ANY_THREADS;       // vectors of the slice chunk per thread
+    static constexpr int RP = ANY_THREADS / VPR;                // slices the workgroup fetches per pass
+    static constexpr int XV = TS / RP;                          // vectors of the slice chunk per thread
     static constexpr int FVR = QG / VN;                         // 16-byte vectors per chunk row of the factor
     static constexpr int FV = (KT * FVR + ANY_THREADS - 1) / ANY_THREADS;   // vectors of the factor chunk per thread
-    static_assert(VPR == 16 && XV == ANY_TS / 16, "a thread fetches one 16-byte column of every 16th slice");
+    static_assert(TS == (NARROW ? 2 : 1) * ANY_TS && XV * RP == TS && KT % 16 == 0, "fetch passes cover the unit");
     static_assert(((ROW * sizeof(T)) / 16) % 2 == 1, "row stride must be an odd number of 16-byte units");
 };
 
 // (the second launch bound, wavefronts per SIMD, caps the registers: left alone the compiler spends
 // several hundred of them on scheduling freedom and one workgroup fills a compute unit)
-template <typename T, int CB>
-__global__ __launch_bounds__(ANY_THREADS, (CB >= 5 ? 2 : 3))
+template <typename T, int CB, bool NARROW, bool KEEP>
+__global__ __launch_bounds__(ANY_THREADS, (CB >= 5 || (NARROW && sizeof(T) == 8 && CB >= 3) ? 2 : 3))
 void mfma_any_sliced_multiply(const T* __restrict__ Xg, const T* __restrict__ Fg, T* __restrict__ Yg,
                               int64_t K, int P, int Q, int64_t num_slices, int64_t num_units, int f_aligned)
 {
-    typedef AnyShape<T, CB> Sh;
+    typedef AnyShape<T, CB, NARROW> Sh;
     typedef typename AnyOp<T>::OP OP;
     typedef typename Vec16<T>::type V;
     constexpr int VN = Sh::VN, KT = Sh::KT, ROW = Sh::ROW, QG = Sh::QG, XV = Sh::XV, FVR = Sh::FVR, FV = Sh::FV;
+    constexpr int SB = Sh::SB, TS = Sh::TS, RP = Sh::RP;
     extern __shared__ __attribute__((aligned(16))) unsigned char any_lds[];
-    T* Xs = reinterpret_cast<T*>(any_lds);            // [ANY_TS][ROW]: slice i, chunk element k
+    T* Xs = reinterpret_cast<T*>(any_lds);            // [TS][ROW]: slice i, chunk element k
     T* Fs = Xs + Sh::X_ELEMS;                          // [QG][ROW]: factor column q (transposed), chunk element k
 
     const int64_t S = K / P;
@@ -72,18 +79,18 @@ void mfma_any_sliced_multiply(const T* __restrict__ Xg, const T* __restrict__ Fg
     const int lane = tid % 64, wave = tid / 64;
     const int j = lane % 16, g = lane / 16;            // operand row/column inside a block, k group
     const int q_groups = (Q + QG - 1) / QG;
-    const int xrow = tid / 16, xcol = (tid % 16) * VN; // fetch duty: column xcol of slices xrow, xrow + 16, ...
+    const int xrow = tid / Sh::VPR, xcol = (tid % Sh::VPR) * VN;   // fetch duty: column xcol of slices xrow, xrow + RP, ...
 
     for (int64_t unit = blockIdx.x; unit < num_units; unit += gridDim.x) {
         int64_t tile;
         int group;
         unit_of(unit, num_units / q_groups, q_groups, tile, group);
-        const int64_t g0 = tile * ANY_TS;                // first slice of the unit, counted through all rows
+        const int64_t g0 = tile * TS;                // first slice of the unit, counted through all rows
         const int q0 = group * QG;
 
-        typename OP::Acc acc[ANY_SB][CB];
+        typename OP::Acc acc[SB][CB];
 #pragma unroll
-        for (int sb = 0; sb < ANY_SB; ++sb)
+        for (int sb = 0; sb < SB; ++sb)
 #pragma unroll
             for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
@@ -99,7 +106,7 @@ void mfma_any_sliced_multiply(const T* __restrict__ Xg, const T* __restrict__ Fg
             const T* xsrc = Xg + g0 * P + k0;            // uniform part of the slice addresses
 #pragma unroll
             for (int i = 0; i < XV; ++i) {
-                const int row = xrow + 16 * i;
+                const int row = xrow + RP * i;
                 if (g0 + row < num_slices && xcol < kt) {
                     const V* src = reinterpret_cast<const V*>(xsrc + row * P + xcol);
                     xr[i] = q_groups == 1 ? stream_load(src) : *src;
@@ -113,18 +120,14 @@ void mfma_any_sliced_multiply(const T* __restrict__ Xg, const T* __restrict__ Fg
             for (int i = 0; i < FV; ++i) {
                 const int e = tid + i * ANY_THREADS;
                 const int p = e / FVR, q = (e % FVR) * VN;
-                if (p < kt && q0 + q < Q) {
-                    if (f_aligned) fr[i] = *reinterpret_cast<const V*>(fsrc + p * Q + q);
-                    else                                 // a factor that does not start on a 16-byte boundary
+                if (f_aligned && p < kt && q0 + q < Q) fr[i] = *reinterpret_cast<const V*>(fsrc + p * Q + q);
+                else                                     // factor rows that do not start on 16-byte boundaries, padding
 #pragma unroll
-                        for (int k = 0; k < VN; ++k) fr[i][k] = fsrc[p * Q + q + k];
-                } else
-#pragma unroll
-                    for (int k = 0; k < VN; ++k) fr[i][k] = T(0);
+                    for (int k = 0; k < VN; ++k) fr[i][k] = (p < kt && q0 + q + k < Q) ? fsrc[p * Q + q + k] : T(0);
             }
             __syncthreads();                             // the previous chunk (or unit) has been read by everybody
 #pragma unroll
-            for (int i = 0; i < XV; ++i) *reinterpret_cast<V*>(Xs + (xrow + 16 * i) * ROW + xcol) = xr[i];
+            for (int i = 0; i < XV; ++i) *reinterpret_cast<V*>(Xs + (xrow + RP * i) * ROW + xcol) = xr[i];
 #pragma unroll
             for (int i = 0; i < FV; ++i) {
                 const int e = tid + i * ANY_THREADS;
@@ -137,10 +140,10 @@ void mfma_any_sliced_multiply(const T* __restrict__ Xg, const T* __restrict__ Fg
             // 16 chunk elements per trip: lane group g takes elements 4g .. 4g+3 of them, one MFMA step each
 #pragma unroll 1
             for (int kc = 0; kc < kt; kc += 16) {
-                T b[ANY_SB][4], a[CB][4];
+                T b[SB][4], a[CB][4];
 #pragma unroll
-                for (int sb = 0; sb < ANY_SB; ++sb) {
-                    const T* src = Xs + (wave * 16 * ANY_SB + sb * 16 + j) * ROW + kc + 4 * g;
+                for (int sb = 0; sb < SB; ++sb) {
+                    const T* src = Xs + (wave * 16 * SB + sb * 16 + j) * ROW + kc + 4 * g;
 #pragma unroll
                     for (int c = 0; c < 4 / VN; ++c) {
                         const V v = reinterpret_cast<const V*>(src)[c];
@@ -161,7 +164,7 @@ void mfma_any_sliced_multiply(const T* __restrict__ Xg, const T* __restrict__ Fg
 #pragma unroll
                 for (int t = 0; t < 4; ++t)
 #pragma unroll
-                    for (int sb = 0; sb < ANY_SB; ++sb)
+                    for (int sb = 0; sb < SB; ++sb)
 #pragma unroll
                         for (int cb = 0; cb < CB; ++cb) acc[sb][cb] = OP::mma(a[cb][t], b[sb][t], acc[sb][cb]);
             }
@@ -169,25 +172,28 @@ void mfma_any_sliced_multiply(const T* __restrict__ Xg, const T* __restrict__ Fg
 
         // permuted store: (slice s of row r, column q) -> Y[r*(S*Q) + q*S + s]
         if constexpr (OP::JOIN_BLOCKS) {
-            static_assert(ANY_SB == 2, "joined stores take the two slice blocks of a wavefront");
-            // after the exchange, register v of the first block holds column 8*(lane/32) + v of its column
+            static_assert(SB % 2 == 0, "joined stores take the slice blocks of a wavefront in pairs");
+            // after the exchange, register v of a pair's first block holds column 8*(lane/32) + v of its column
             // block and the second block's register column 8*(lane/32) + 4 + v, both for slice lane % 32
-            const int64_t slice = g0 + wave * 32 + lane % 32;
-            const bool live = slice < num_slices;
-            T* Ycol = Yg + (live ? (slice / S) * (S * (int64_t)Q) + slice % S : 0);
 #pragma unroll
-            for (int cb = 0; cb < CB; ++cb)
+            for (int sb = 0; sb < SB; sb += 2) {
+                const int64_t slice = g0 + wave * 16 * SB + sb * 16 + lane % 32;
+                const bool live = slice < num_slices;
+                T* Ycol = Yg + (live ? (slice / S) * (S * (int64_t)Q) + slice % S : 0);
 #pragma unroll
-                for (int v = 0; v < OP::NACC; ++v) {
-                    join_blocks(acc[0][cb], acc[1][cb], v);
-                    const int q = q0 + cb * 16 + 8 * (lane / 32) + v;
-                    if (live && q < Q) stream_store(acc[0][cb][v], &Ycol[(int64_t)q * S]);
-                    if (live && q + 4 < Q) stream_store(acc[1][cb][v], &Ycol[(int64_t)(q + 4) * S]);
-                }
+                for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+                    for (int v = 0; v < OP::NACC; ++v) {
+                        join_blocks(acc[sb][cb], acc[sb + 1][cb], v);
+                        const int q = q0 + cb * 16 + 8 * (lane / 32) + v;
+                        if (live && q < Q) out_store<KEEP>(acc[sb][cb][v], &Ycol[(int64_t)q * S]);
+                        if (live && q + 4 < Q) out_store<KEEP>(acc[sb + 1][cb][v], &Ycol[(int64_t)(q + 4) * S]);
+                    }
+            }
         } else {
 #pragma unroll
-            for (int sb = 0; sb < ANY_SB; ++sb) {
-                const int64_t slice = g0 + wave * 16 * ANY_SB + sb * 16 + j;
+            for (int sb = 0; sb < SB; ++sb) {
+                const int64_t slice = g0 + wave * 16 * SB + sb * 16 + j;
                 const bool live = slice < num_slices;
                 T* Ycol = Yg + (live ? (slice / S) * (S * (int64_t)Q) + slice % S : 0);
 #pragma unroll
@@ -195,7 +201,7 @@ void mfma_any_sliced_multiply(const T* __restrict__ Xg, const T* __restrict__ Fg
 #pragma unroll
                     for (int v = 0; v < OP::NACC; ++v) {
                         const int q = q0 + cb * 16 + OP::row_lane(lane) + OP::row_reg(v);
-                        if (live && q < Q) stream_store(acc[sb][cb][v], &Ycol[(int64_t)q * S]);
+                        if (live && q < Q) out_store<KEEP>(acc[sb][cb][v], &Ycol[(int64_t)q * S]);
                     }
             }
         }

@@ -114,7 +114,7 @@ struct MfmaShape {
     static_assert(TK % (VN * NT) == 0, "tile must be a whole number of vectors per thread");
 };
 
-template <class OP, int P, int Q, int NF, int ST, int NW, int QSPLIT, int J>
+template <class OP, int P, int Q, int NF, int ST, int NW, int QSPLIT, int J, bool KEEP>
 __device__ __forceinline__ void mfma_stage(typename OP::T* __restrict__ tile,
                                            const typename OP::T (&a)[MfmaShape<OP, P, Q, NF, ST, NW, QSPLIT>::QTW][MfmaShape<OP, P, Q, NF, ST, NW, QSPLIT>::PL],
                                            typename OP::T* __restrict__ Yrow, int64_t s_row, int64_t h)
@@ -168,8 +168,8 @@ __device__ __forceinline__ void mfma_stage(typename OP::T* __restrict__ tile,
 #pragma unroll
                         for (int v = 0; v < OP::NACC; ++v) {
                             join_blocks(acc[0][qt], acc[1][qt], v);
-                            stream_store(acc[0][qt][v], &Yrow[off + (qt * OP::MB + v) * QREST * sr]);
-                            stream_store(acc[1][qt][v], &Yrow[off + (qt * OP::MB + 4 + v) * QREST * sr]);
+                            out_store<KEEP>(acc[0][qt][v], &Yrow[off + (qt * OP::MB + v) * QREST * sr]);
+                            out_store<KEEP>(acc[1][qt][v], &Yrow[off + (qt * OP::MB + 4 + v) * QREST * sr]);
                         }
                 }
             } else {
@@ -179,7 +179,7 @@ __device__ __forceinline__ void mfma_stage(typename OP::T* __restrict__ tile,
                 for (int qt = 0; qt < QTW; ++qt)
 #pragma unroll
                     for (int v = 0; v < OP::NACC; ++v)
-                        stream_store(acc[0][qt][v], &Yrow[off + (qt * OP::MB + OP::row_reg(v)) * QREST * sr]);
+                        out_store<KEEP>(acc[0][qt][v], &Yrow[off + (qt * OP::MB + OP::row_reg(v)) * QREST * sr]);
             }
         }
     }
@@ -240,7 +240,7 @@ __device__ __forceinline__ void mfma_single_compute(
 }
 
 // ... then the permuted store: (q, s) -> column q*s_row + h*ST + s.
-template <class OP, int P, int Q, int ST, int NW, int QSPLIT>
+template <class OP, int P, int Q, int ST, int NW, int QSPLIT, bool KEEP>
 __device__ __forceinline__ void mfma_single_store(
     typename OP::T* __restrict__ Yrow, int64_t s_row, int64_t h,
     typename OP::Acc (&acc)[ST / OP::NB / MfmaShape<OP, P, Q, 1, ST, NW, QSPLIT>::SG][MfmaShape<OP, P, Q, 1, ST, NW, QSPLIT>::QTW])
@@ -263,8 +263,8 @@ __device__ __forceinline__ void mfma_single_store(
 #pragma unroll
                 for (int v = 0; v < OP::NACC; ++v) {
                     join_blocks(acc[bi][qt], acc[bi + 1][qt], v);
-                    stream_store(acc[bi][qt][v], &Yrow[off + (qt * OP::MB + v) * sr]);
-                    stream_store(acc[bi + 1][qt][v], &Yrow[off + (qt * OP::MB + 4 + v) * sr]);
+                    out_store<KEEP>(acc[bi][qt][v], &Yrow[off + (qt * OP::MB + v) * sr]);
+                    out_store<KEEP>(acc[bi + 1][qt][v], &Yrow[off + (qt * OP::MB + 4 + v) * sr]);
                 }
         }
     } else {
@@ -276,12 +276,12 @@ __device__ __forceinline__ void mfma_single_store(
             for (int qt = 0; qt < QTW; ++qt)
 #pragma unroll
                 for (int v = 0; v < OP::NACC; ++v)
-                    stream_store(acc[bi][qt][v], &Yrow[off + (qt * OP::MB + OP::row_reg(v)) * sr]);
+                    out_store<KEEP>(acc[bi][qt][v], &Yrow[off + (qt * OP::MB + OP::row_reg(v)) * sr]);
         }
     }
 }
 
-template <class OP, int P, int Q, int NF, int ST, int NW, int QSPLIT>
+template <class OP, int P, int Q, int NF, int ST, int NW, int QSPLIT, bool KEEP>
 __global__ __launch_bounds__(NW * 64, (NW >= 16 ? 4 : 2))   // second bound: wavefronts per SIMD to fit
 void mfma_sliced_multiply(const typename OP::T* __restrict__ Xg, typename OP::T* __restrict__ Yg,
                           const typename OP::T* __restrict__ F0, const typename OP::T* __restrict__ F1,
@@ -389,7 +389,7 @@ void mfma_sliced_multiply(const typename OP::T* __restrict__ Xg, typename OP::T*
                 }
             }
             const int64_t row = t / tiles_per_row, h = t % tiles_per_row;
-            mfma_single_store<OP, P, Q, ST, NW, QSPLIT>(Yg + row * k_out, s_row, h, acc);
+            mfma_single_store<OP, P, Q, ST, NW, QSPLIT, KEEP>(Yg + row * k_out, s_row, h, acc);
             __syncthreads();      // the other buffer is complete; this one has been read by everybody
             cur ^= 1;
         }
@@ -413,15 +413,15 @@ void mfma_sliced_multiply(const typename OP::T* __restrict__ Xg, typename OP::T*
 #pragma unroll
                     for (int i = 0; i < RV; ++i) pf[i] = stream_load(&src[tid + i * NT]);
                 }
-                mfma_stage<OP, P, Q, NF, ST, NW, QSPLIT, 0>(tile, a0, Yrow, s_row, h);
+                mfma_stage<OP, P, Q, NF, ST, NW, QSPLIT, 0, KEEP>(tile, a0, Yrow, s_row, h);
             } else {
-                mfma_stage<OP, P, Q, NF, ST, NW, QSPLIT, 0>(tile, a0, Yrow, s_row, h);
+                mfma_stage<OP, P, Q, NF, ST, NW, QSPLIT, 0, KEEP>(tile, a0, Yrow, s_row, h);
                 if (t + t_step < t_end) {
                     const V* src = tile_ptr(t + t_step);
 #pragma unroll
                     for (int i = 0; i < RV; ++i) pf[i] = stream_load(&src[tid + i * NT]);
                 }
-                mfma_stage<OP, P, Q, NF, ST, NW, QSPLIT, 1>(tile, a1, Yrow, s_row, h);
+                mfma_stage<OP, P, Q, NF, ST, NW, QSPLIT, 1, KEEP>(tile, a1, Yrow, s_row, h);
             }
             __syncthreads();                           // tile fully consumed before it is overwritten
         }

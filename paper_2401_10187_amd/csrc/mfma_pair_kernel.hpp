@@ -58,7 +58,7 @@ struct MfmaPairShape {
 typedef float pair_f32x16 __attribute__((ext_vector_type(16)));
 typedef float pair_f32x4 __attribute__((ext_vector_type(4)));
 
-template <int P, int ST, int NW, int PD, int NPASS>
+template <int P, int ST, int NW, int PD, int NPASS, bool KEEP>
 __global__ __launch_bounds__(NW * 64, (MfmaPairShape<P, ST, NW, PD, NPASS>::WPS))
 void mfma_pair_sliced_multiply(const float* __restrict__ Xg, float* __restrict__ Yg,
                                const float* __restrict__ F0, const float* __restrict__ F1,   // in order of application
@@ -207,7 +207,7 @@ void mfma_pair_sliced_multiply(const float* __restrict__ Xg, float* __restrict__
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const int idx = tid + (i0 + i) * NT;
-                    stream_store(v[i], reinterpret_cast<pair_f32x4*>(Ypass + (int64_t)(idx / (ST / 4)) * s_row + 4 * (idx % (ST / 4))));
+                    out_store<KEEP>(v[i], reinterpret_cast<pair_f32x4*>(Ypass + (int64_t)(idx / (ST / 4)) * s_row + 4 * (idx % (ST / 4))));
                 }
             }
             __syncthreads();

@@ -159,12 +159,12 @@ inline int64_t store_column(int64_t k_in, int64_t p_group, int64_t tile_k, int64
 }
 
 // Column blocks (of 16) per unit of the run-time-shape MFMA kernel for a factor with Q columns: the
-// width among 4, 5 and 3 that leaves the fewest padded columns.
+// width among 4, 5, 3, 2 and 1 (tried in this order) that leaves the fewest padded blocks.
 inline int any_column_blocks(int Q)
 {
-    const int blocks = Q / 16;
+    const int blocks = (Q + 15) / 16;
     int best = 4, waste = (4 - blocks % 4) % 4 * 1000 / ((blocks + 3) / 4 * 4);
-    const int others[2] = {5, 3};
+    const int others[4] = {5, 3, 2, 1};
     for (int cb : others) {
         const int w = (cb - blocks % cb) % cb * 1000 / ((blocks + cb - 1) / cb * cb);
         if (w < waste) { waste = w; best = cb; }
@@ -198,15 +198,22 @@ struct GenericKernel {
     // are at most row_few_rows rows) applies up to row_max_factors factors to one row held, with the
     // factors, in at most row_lds_limit bytes of LDS
     int row_threads_many, row_threads_few, row_few_rows, row_lds_limit, row_max_factors;
-    // the run-time-shape MFMA kernel (P and Q multiples of 16): a workgroup of any_threads work-items takes
+    // the run-time-shape MFMA kernel: a workgroup of any_threads work-items takes
     // any_tile_slices slices and 16 * any_column_blocks(Q) factor columns at a time, chunks of
-    // any_row_bytes per slice in LDS rows padded by one 16-byte unit
+    // any_row_bytes per slice in LDS rows padded by one 16-byte unit; slices of at most half a chunk
+    // take the narrow shape: twice the slices, chunks of half the bytes
     int any_threads, any_tile_slices, any_row_bytes;
 };
 
-inline int any_lds_bytes(const GenericKernel& gen, int Q, size_t)
+inline bool any_narrow(const GenericKernel& gen, int P, size_t esize) { return (size_t)P * esize * 2 <= (size_t)gen.any_row_bytes; }
+inline int any_unit_slices(const GenericKernel& gen, int P, size_t esize)
 {
-    return (gen.any_tile_slices + 16 * any_column_blocks(Q)) * (gen.any_row_bytes + 16);
+    return any_narrow(gen, P, esize) ? 2 * gen.any_tile_slices : gen.any_tile_slices;
+}
+inline int any_lds_bytes(const GenericKernel& gen, int P, int Q, size_t esize)
+{
+    const int row = any_narrow(gen, P, esize) ? gen.any_row_bytes / 2 : gen.any_row_bytes;
+    return (any_unit_slices(gen, P, esize) + 16 * any_column_blocks(Q)) * (row + 16);
 }
 
 struct Choice {
@@ -531,12 +538,12 @@ inline km_plan_step build_step(const Problem& pr, const Options& opt, const Vari
         st.kernel = KM_KERNEL_MFMA_ANY;
         st.variant = -1;
         st.tile_rows = 1;
-        st.tile_slices = gen.any_tile_slices;
+        st.tile_slices = any_unit_slices(gen, pr.P[f], pr.esize);
         st.block = gen.any_threads;
-        st.lds_bytes = any_lds_bytes(gen, pr.Q[f], pr.esize);
+        st.lds_bytes = any_lds_bytes(gen, pr.P[f], pr.Q[f], pr.esize);
         const int64_t S = st.k_in / pr.P[f];
         const int cols = 16 * any_column_blocks(pr.Q[f]);
-        st.grid = ((pr.M * S + gen.any_tile_slices - 1) / gen.any_tile_slices) * ((pr.Q[f] + cols - 1) / cols);
+        st.grid = ((pr.M * S + st.tile_slices - 1) / st.tile_slices) * ((pr.Q[f] + cols - 1) / cols);
         const int64_t most = ((int64_t)1 << 32) / gen.any_threads - 1;     // the kernel strides over its units
         if (st.grid > most) st.grid = most;
     } else {
@@ -556,10 +563,21 @@ inline km_plan_step build_step(const Problem& pr, const Options& opt, const Vari
     return st;
 }
 
-// The run-time-shape MFMA kernel takes single factors whose P and Q are multiples of 16.
+// The run-time-shape MFMA kernel takes single factors whose slices start on 16-byte boundaries
+// (P a multiple of 4 floats or 2 doubles).  It pads P and Q to multiples of 16 with zeros, so a factor
+// is given to it only while the padded product stays below a multiple of the real one: 3 in fp32
+// (measured against the generic kernel, 3 factors each: 20x20 4 % faster at 2.56x padding, 36x36 19 %
+// at 1.78x, 40x40 18 %, 52x52 10 %, 100x100 level), 1.5 in fp64, whose MFMA rate is half as far from
+// the generic kernel's multiply-adds (14x14 15 %, 40x40 17 %, 44x44 15 % faster; 20x20 at 2.56x and
+// 24x24 at 1.78x 6 % slower, 50x50 at 1.64x 7 % slower).
 inline bool any_mfma_fits(const Problem& pr, int f, const Options& opt)
 {
-    return (opt.kernels >> KM_KERNEL_MFMA_ANY & 1) && pr.P[f] % 16 == 0 && pr.Q[f] % 16 == 0;
+    const int P = pr.P[f], Q = pr.Q[f];
+    const int vn = 16 / (int)pr.esize;
+    if (!(opt.kernels >> KM_KERNEL_MFMA_ANY & 1) || P % vn) return false;
+    const int cols = 16 * any_column_blocks(Q);
+    const double padded = (double)((P + 15) / 16 * 16) * (double)((Q + cols - 1) / cols * cols);
+    return padded <= (pr.esize == 4 ? 3.0 : 1.5) * (double)P * (double)Q;
 }
 
 inline void row_widths(const Problem& pr, std::vector<int64_t>& width)

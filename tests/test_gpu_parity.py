@@ -34,11 +34,11 @@ class options:
     """Temporarily restrict the planner (kernel families bit mask, fusion depth)."""
 
     def __init__(self, kernels=None, max_fuse=None, tile=None, threads=None, tiles_per_wg=None, pair=None,
-                 order=None, instance=None):
+                 order=None, instance=None, keep_mib=None):
         self.new = {km.KM_OPT_KERNELS: kernels, km.KM_OPT_MAX_FUSE: max_fuse, km.KM_OPT_PREFER_TILE: tile,
                     km.KM_OPT_PREFER_THREADS: threads, km.KM_OPT_TILES_PER_WG: tiles_per_wg,
                     km.KM_OPT_PAIR_INTERLEAVE: pair, km.KM_OPT_TILE_ORDER: order,
-                    km.KM_OPT_PREFER_INSTANCE: instance}
+                    km.KM_OPT_PREFER_INSTANCE: instance, km.KM_OPT_KEEP_MIB: keep_mib}
 
     def __enter__(self):
         self.old = {k: km.get_option(k) for k in self.new}
@@ -161,6 +161,22 @@ SMALL_CASES = [
     ("float64", 67, [(80, 160)]),
     ("float32", 2, [(48, 48)] * 3),
     ("float32", 3, [(8, 8), (48, 48), (8, 8), (8, 8)]),
+    # the same kernel on shapes it pads to multiples of 16 with zeros (P a whole number of 16-byte
+    # vectors, Q anything): narrow units for slices of up to 128 bytes, factors read element by element
+    # when Q is not a whole number of vectors, output runs that start off 64-byte boundaries
+    ("float32", 3, [(20, 20)] * 3),
+    ("float32", 5, [(36, 36)] * 2),
+    ("float32", 2, [(24, 28), (28, 20)]),
+    ("float32", 7, [(20, 15)] * 3),
+    ("float32", 1, [(100, 100)] * 2),
+    ("float32", 3, [(36, 50), (52, 33)]),
+    ("float32", 300, [(32, 20)]),
+    ("float32", 2, [(16, 80)] * 2),
+    ("float64", 3, [(14, 14)] * 3),
+    ("float64", 2, [(40, 40)] * 2),
+    ("float64", 5, [(30, 30)] * 2),
+    ("float64", 3, [(16, 48), (44, 41)]),
+    ("float64", 129, [(90, 90)]),
 ]
 
 
@@ -185,6 +201,7 @@ def test_small_integer_bit_exact(dtype, M, shapes):
 
 
 @pytest.mark.parametrize("dtype,M,shapes", [("float32", 5, [(48, 80), (96, 48)]), ("float64", 3, [(48, 48)] * 2),
+                                            ("float32", 3, [(20, 20)] * 2), ("float64", 2, [(14, 40), (40, 14)]),
                                             ("float32", 4, [(8, 8)] * 3), ("float32", 3, [(32, 32)] * 3),
                                             ("float64", 2, [(5, 3), (16, 16), (7, 9)])],
                          ids=lambda v: str(v).replace(" ", ""))
@@ -570,6 +587,36 @@ def test_full_size_every_element(name):
     for r0 in range(0, M, 64):
         assert_close(Y[r0:r0 + 64].cpu().numpy(), X[r0:r0 + 64], Fs)
     del Y, Xd, ws
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("dtype,M,shapes", [
+    ("float32", 64, [(8, 8)] * 6),          # small-factor kernel, 64 MiB intermediate
+    ("float32", 64, [(64, 64)] * 3),        # single-factor fp32 MFMA instances, 64 MiB
+    ("float64", 4, [(128, 128)] * 3),       # fp64 MFMA instances, 64 MiB
+    ("float32", 16, [(32, 32)] * 4),        # pair kernel, 64 MiB
+    ("float32", 64, [(80, 80)] * 3),        # run-time-shape MFMA kernel, 125 MiB
+    ("float64", 128, [(40, 40)] * 3),       # the same, padded shape, 62 MiB
+], ids=lambda v: str(v).replace(" ", ""))
+def test_intermediates_kept_in_cache_change_no_result(dtype, M, shapes):
+    """Intermediates of 48 to 320 MiB are written with ordinary stores so that they stay in the
+    last-level cache for the next launch, others (and every final result) with non-temporal ones: the
+    two forms of each kernel give the same bits, and sampled rows match the oracle."""
+    X, Fs = kron_inputs.make_problem(M, shapes, dtype, seed=77)
+    Xd = torch.from_numpy(X).cuda()
+    Fd = [torch.from_numpy(F).cuda() for F in Fs]
+    assert km.get_option(km.KM_OPT_KEEP_MIB) == 320
+    assert len(km.plan(M, [p for p, _ in shapes], [q for _, q in shapes], dtype)) > 1
+    Y = km.kronmatmul(Xd, Fd)
+    with options(keep_mib=0):
+        Y0 = km.kronmatmul(Xd, Fd)
+    with options(keep_mib=1 << 20):
+        Y1 = km.kronmatmul(Xd, Fd)
+    torch.cuda.synchronize()
+    assert torch.equal(Y, Y0) and torch.equal(Y, Y1)
+    rows = _sample_rows(M)[:4]
+    assert_close(Y[rows].cpu().numpy(), X[rows], Fs)
+    del Y, Y0, Y1, Xd
     torch.cuda.empty_cache()
 
 

@@ -173,7 +173,7 @@ def test_workspace_follows_algorithm_1_buffers():
 def test_tuning_options_round_trip():
     for opt, good, bad in ((km.KM_OPT_PREFER_TILE, 16, -1), (km.KM_OPT_PREFER_THREADS, 256, 5000),
                            (km.KM_OPT_TILES_PER_WG, 8, -2), (km.KM_OPT_PAIR_INTERLEAVE, 0, 2),
-                           (km.KM_OPT_PROFILE, 1, 3)):
+                           (km.KM_OPT_PROFILE, 1, 3), (km.KM_OPT_KEEP_MIB, 0, -1)):
         old = km.get_option(opt)
         try:
             km.set_option(opt, good)
@@ -183,6 +183,24 @@ def test_tuning_options_round_trip():
             assert km.get_option(opt) == good
         finally:
             km.set_option(opt, old)
+
+
+def test_padded_shapes_go_to_the_run_time_shape_mfma_kernel_within_its_padding_limits():
+    """Slices that start on 16-byte boundaries and a padded product of at most 3x (fp32) or 1.5x (fp64)
+    the real one; everything else without a compiled instance stays with the generic kernel.  The
+    narrow shape (slices of up to 128 bytes) takes 256 slices per unit, the wide one 128."""
+    def kernels(dtype, M, shapes):
+        return [(s["kernel"], s["tile_slices"]) for s in km.plan(M, [p for p, _ in shapes], [q for _, q in shapes], dtype)]
+    any_, gen = km.KM_KERNEL_MFMA_ANY, km.KM_KERNEL_GENERIC
+    assert kernels("float32", 4096, [(20, 20)] * 3) == [(any_, 256)] * 3          # 32*32 / 400 = 2.56
+    assert kernels("float32", 4096, [(36, 50)] * 3) == [(any_, 128)] * 3
+    assert kernels("float32", 4096, [(20, 15)] * 3) == [(any_, 256)] * 3          # Q need not be a whole vector
+    assert [k for k, _ in kernels("float32", 4096, [(20, 7)] * 4)] == [gen] * 4    # 32*16 / 140 = 3.7
+    assert [k for k, _ in kernels("float32", 4096, [(18, 18)] * 4)] == [gen] * 4   # slices not 16-byte aligned
+    assert kernels("float64", 4096, [(14, 14)] * 4) == [(any_, 256)] * 4          # 16*16 / 196 = 1.31
+    assert kernels("float64", 4096, [(40, 40)] * 3) == [(any_, 128)] * 3          # 48*48 / 1600 = 1.44
+    assert [k for k, _ in kernels("float64", 4096, [(20, 20)] * 3)] == [gen] * 3   # 2.56 > 1.5
+    assert [k for k, _ in kernels("float64", 4096, [(15, 16)] * 4)] == [gen] * 4   # odd P
 
 
 def test_planner_prefers_fusion_and_mfma_for_the_measured_workloads():
