@@ -1,4 +1,4 @@
-// Compiled instances: the MFMA kernel for factors whose P and Q are any multiples of 16 (fp32 and fp64).
+// Compiled instances: the MFMA kernel with run-time factor shapes (fp32 and fp64).
 #include "launch_any.hpp"
 
 namespace km {
