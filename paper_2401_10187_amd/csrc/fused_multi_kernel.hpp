@@ -8,7 +8,10 @@
 // Q^G columns: (group s, column qq) -> qq*S + s.  With P = 2 three factors cost one LDS round trip
 // instead of three; with P = 4 two factors do.
 //
-// Up to three super-stages (G0, G1, G2 factors; 0 = unused) per launch.  Factor elements are read
+// Up to three super-stages (G0, G1, G2 factors; 0 = unused) per launch.  Nothing in the rule needs
+// the stages to share a factor shape: stage j has its own (Pj, Qj), so neighbouring runs of different
+// small shapes (2x2 beside 4x4, 5x5 beside 2x2) are one launch too; within a stage the factors are
+// equal-shaped.  Factor elements are read
 // with scalar loads, as in fused_kernel.hpp.  LDS rows (one group each) are padded when their
 // length is an even number of 16-byte units above two, which would otherwise put the 16-byte reads
 // of eight consecutive lanes into the same banks.
@@ -28,23 +31,29 @@ template <int N> struct FactorPtrs { const void* f[N]; };
 // STMAX bounds the tile (LDS, registers, unrolled trip counts); the number of slices actually in a
 // tile, st <= STMAX, is a launch parameter so that one instance serves every row length whose
 // K/P^NF has a divisor in range (rows of 3^7 or 6^7 elements, M = 1 problems, ...).
-template <typename T, int P, int Q, int G0, int G1, int G2, int STMAX, int NT>
-struct MultiShape {
+template <typename T_, int P0, int Q0, int G0, int P1, int Q1, int G1, int P2, int Q2, int G2, int STMAX_, int NT_>
+struct MixedShape {
+    typedef T_ T;
+    static constexpr int STMAX = STMAX_, NT = NT_;
     static constexpr int NS = (G0 > 0) + (G1 > 0) + (G2 > 0);
     static constexpr int NF = G0 + G1 + G2;
     static constexpr int VN = Vec16<T>::N;
     static constexpr int g(int j) { return j == 0 ? G0 : (j == 1 ? G1 : G2); }
+    static constexpr int p(int j) { return j == 0 ? P0 : (j == 1 ? P1 : P2); }      // factor shape of stage j
+    static constexpr int q(int j) { return j == 0 ? Q0 : (j == 1 ? Q1 : Q2); }
     static constexpr int done(int j) { return (j > 0 ? G0 : 0) + (j > 1 ? G1 : 0) + (j > 2 ? G2 : 0); }
-    static constexpr int per_slice(int j) { return (int)(ipow(P, NF - done(j)) * ipow(Q, done(j))); }   // tile elements per unit of st
-    static constexpr int pg(int j) { return (int)ipow(P, g(j)); }      // elements a thread reads per group
-    static constexpr int qg(int j) { return (int)ipow(Q, g(j)); }      // elements it produces
-    static constexpr int wmax(int j) { return (int)ipow(P > Q ? P : Q, g(j)); }
-    static constexpr int qchunk()       // columns of one factor whose elements fit 64 scalar registers
+    static constexpr int pg(int j) { return (int)ipow(p(j), g(j)); }      // elements a thread reads per group
+    static constexpr int qg(int j) { return (int)ipow(q(j), g(j)); }      // elements it produces
+    static constexpr int qdone(int j) { return (j > 0 ? qg(0) : 1) * (j > 1 ? qg(1) : 1) * (j > 2 ? qg(2) : 1); }   // columns of the stages before j
+    static constexpr int ptodo(int j) { return (j <= 0 ? pg(0) : 1) * (j <= 1 ? pg(1) : 1) * (j <= 2 ? pg(2) : 1); } // elements per slice still to contract
+    static constexpr int per_slice(int j) { return ptodo(j) * qdone(j); }   // tile elements per unit of st
+    static constexpr int wmax(int j) { return (int)ipow(p(j) > q(j) ? p(j) : q(j), g(j)); }
+    static constexpr int qchunk(int j)  // columns of one factor whose elements fit 64 scalar registers
     {
-        int c = Q;
-        while (c > 1 && (P * c * (int)sizeof(T)) / 4 > 64) {
+        int c = q(j);
+        while (c > 1 && (p(j) * c * (int)sizeof(T)) / 4 > 64) {
             --c;
-            while (c > 1 && Q % c) --c;
+            while (c > 1 && q(j) % c) --c;
         }
         return c;
     }
@@ -66,15 +75,21 @@ struct MultiShape {
         }
         return m;
     }
+    // every stage's groups have odd length: nothing reads LDS in 16-byte vectors
+    static constexpr bool ALL_ODD = P0 % 2 == 1 && (G1 == 0 || P1 % 2 == 1) && (G2 == 0 || P2 % 2 == 1);
     // 32 bytes of slack where a tile that starts off a 16-byte boundary is held shifted by up to VN - 1
     // elements (odd P only; tiles of exactly 64 KB must not grow: two of them no longer share a compute unit)
-    static constexpr int LDS_SLACK = P % 2 == 1 ? 32 : 0;
+    static constexpr int LDS_SLACK = ALL_ODD ? 32 : 0;
     static constexpr int LDS_BYTES = (lds_elems() * (int)sizeof(T) + 15) / 16 * 16 + LDS_SLACK;
     // the tile only occupies what its st slices need, so short tiles leave LDS to more workgroups
     static constexpr int LDS_PER_SLICE = lds_elems() / STMAX * (int)sizeof(T);
     static constexpr bool VEC_ROWS = pg(0) % VN == 0;
     static_assert(G0 > 0 && (G1 > 0 || G2 == 0), "super-stages are filled from the first");
 };
+
+// every stage with the same factor shape
+template <typename T, int P, int Q, int G0, int G1, int G2, int STMAX, int NT>
+using MultiShape = MixedShape<T, P, Q, G0, P, Q, G1, P, Q, G2, STMAX, NT>;
 
 // Tiles of whole rows: the final stage leaves the tile's output rows in LDS, unpadded and in
 // memory order (they are contiguous in Y), and this writes them out with contiguous stores.
@@ -114,14 +129,14 @@ __device__ __forceinline__ void multi_store_rows(const T* __restrict__ tile, T* 
 template <int PGN, int PADN>
 __device__ __forceinline__ int multi_lds_index(int c) { return PADN == 0 ? c : c + (c / PGN) * PADN; }
 
-template <typename T, int P, int Q, int G0, int G1, int G2, int STMAX, int NT, int J>
-__device__ __forceinline__ void multi_stage(T* __restrict__ tile, const FactorPtrs<G0 + G1 + G2>& fp,
-                                            T* __restrict__ Yrow, int64_t s_row, int64_t h, int st,
+template <class Sh, int J>
+__device__ __forceinline__ void multi_stage(typename Sh::T* __restrict__ tile, const FactorPtrs<Sh::NF>& fp,
+                                            typename Sh::T* __restrict__ Yrow, int64_t s_row, int64_t h, int st,
                                             int sr_tile, int64_t k_out, int rows_here, int tile_rows)
 {
-    typedef MultiShape<T, P, Q, G0, G1, G2, STMAX, NT> Sh;
+    typedef typename Sh::T T;
     typedef typename Vec16<T>::type V;
-    constexpr int VN = Sh::VN;
+    constexpr int VN = Sh::VN, NT = Sh::NT, P = Sh::p(J), Q = Sh::q(J);
     constexpr int GJ = Sh::g(J), PGJ = Sh::pg(J), QGJ = Sh::qg(J), PADJ = Sh::pad(J), WMAX = Sh::wmax(J);
     constexpr int R = (Sh::max_rows(J) + NT - 1) / NT;
     constexpr bool LAST = J == Sh::NS - 1;
@@ -133,7 +148,7 @@ __device__ __forceinline__ void multi_stage(T* __restrict__ tile, const FactorPt
         // One factor whose elements do not fit the scalar registers at once (8x8 doubles): take its
         // columns in chunks that do, and run every slice of the thread against one chunk before the
         // next chunk is fetched.
-        constexpr int QCH = Sh::qchunk();
+        constexpr int QCH = Sh::qchunk(J);
         T xs[R][P];
 #pragma unroll
         for (int i = 0; i < R; ++i) {
@@ -160,7 +175,7 @@ __device__ __forceinline__ void multi_stage(T* __restrict__ tile, const FactorPt
         // deliberately not unrolled (unrolled, all of the factor would be fetched up front again).
         const auto Fc = as_constant(static_cast<const T*>(fp.f[Sh::done(J)]));
         if (!LAST || tile_rows > 1) __syncthreads();     // every slice has been read
-        constexpr int QREST1 = (int)ipow(Q, Sh::done(J));
+        constexpr int QREST1 = Sh::qdone(J);
 #pragma unroll 1
         for (int q0 = 0; q0 < Q; q0 += QCH) {
 #pragma unroll
@@ -249,9 +264,10 @@ __device__ __forceinline__ void multi_stage(T* __restrict__ tile, const FactorPt
         __syncthreads();
     } else {
         if (tile_rows > 1) __syncthreads();              // every group has been read; LDS is reused for the rows
-        // local (qq, s) with s = qrest*st + r  ->  column (qq*Q^done + qrest)*s_row + h*st + r; when the
+        // local (qq, s) with s = qrest*st + r  ->  column (qq*QREST + qrest)*s_row + h*st + r, QREST the
+        // columns of the earlier stages; when the
         // tile holds several whole rows, r = m*s_row + r' and the element belongs to row m of the tile
-        constexpr int QREST = (int)ipow(Q, Sh::done(J));
+        constexpr int QREST = Sh::qdone(J);
 #pragma unroll
         for (int i = 0; i < R; ++i) {
             const int s = tid + i * NT;
@@ -274,16 +290,16 @@ __device__ __forceinline__ void multi_stage(T* __restrict__ tile, const FactorPt
     }
 }
 
-template <typename T, int P, int Q, int G0, int G1, int G2, int STMAX, int NT>
-__global__ __launch_bounds__(NT)
-void fused_multi_sliced_multiply(const T* __restrict__ Xg, T* __restrict__ Yg,
-                                 const FactorPtrs<G0 + G1 + G2> fp,     // in order of application
+template <class Sh>
+__global__ __launch_bounds__(Sh::NT)
+void fused_multi_sliced_multiply(const typename Sh::T* __restrict__ Xg, typename Sh::T* __restrict__ Yg,
+                                 const FactorPtrs<Sh::NF> fp,           // in order of application
                                  int64_t k_in, int64_t k_out, int64_t tiles_per_row, int64_t num_tiles, int st,
                                  int tile_rows, int64_t M)
 {
-    typedef MultiShape<T, P, Q, G0, G1, G2, STMAX, NT> Sh;
+    typedef typename Sh::T T;
     typedef typename Vec16<T>::type V;
-    constexpr int VN = Sh::VN;
+    constexpr int VN = Sh::VN, NT = Sh::NT, STMAX = Sh::STMAX;
     extern __shared__ __attribute__((aligned(16))) unsigned char multi_lds[];
     T* tile = reinterpret_cast<T*>(multi_lds);           // (moved up by a few elements below for unaligned tiles)
 
@@ -335,7 +351,7 @@ void fused_multi_sliced_multiply(const T* __restrict__ Xg, T* __restrict__ Yg,
         // padded, so the tile may sit in LDS shifted by `mis` elements: vector v of global memory then is
         // vector v of LDS and goes in with one 16-byte write, foreign elements at both ends included
         // (they fall outside the tile and are never read).  Otherwise the elements are placed one by one.
-        constexpr bool SHIFT = P % 2 == 1 && PAD0 == 0;
+        constexpr bool SHIFT = Sh::ALL_ODD && PAD0 == 0;
         if constexpr (SHIFT) tile += mis;
         for (int base = 0; base < nfull; base += UN * NT) {
             V tmp[UN];
@@ -366,9 +382,9 @@ void fused_multi_sliced_multiply(const T* __restrict__ Xg, T* __restrict__ Yg,
     }
     __syncthreads();
 
-    multi_stage<T, P, Q, G0, G1, G2, STMAX, NT, 0>(tile, fp, Yrow, s_row, h, st, sr_tile, k_out, rows_here, tile_rows);
-    if constexpr (Sh::NS > 1) multi_stage<T, P, Q, G0, G1, G2, STMAX, NT, 1>(tile, fp, Yrow, s_row, h, st, sr_tile, k_out, rows_here, tile_rows);
-    if constexpr (Sh::NS > 2) multi_stage<T, P, Q, G0, G1, G2, STMAX, NT, 2>(tile, fp, Yrow, s_row, h, st, sr_tile, k_out, rows_here, tile_rows);
+    multi_stage<Sh, 0>(tile, fp, Yrow, s_row, h, st, sr_tile, k_out, rows_here, tile_rows);
+    if constexpr (Sh::NS > 1) multi_stage<Sh, 1>(tile, fp, Yrow, s_row, h, st, sr_tile, k_out, rows_here, tile_rows);
+    if constexpr (Sh::NS > 2) multi_stage<Sh, 2>(tile, fp, Yrow, s_row, h, st, sr_tile, k_out, rows_here, tile_rows);
 }
 
 }  // namespace km

@@ -8,8 +8,13 @@
 // W(type, dtype code, P, Q, G0, G1, G2, largest tile_slices, threads).
 // The same for rows of exactly P*P elements, ST rows per tile: R(P, rows per tile, wavefronts).
 // MFMA instances: Y(op, dtype code, P, Q, factors per launch, tile_slices, wavefronts, q split).
+// The same with a factor shape per stage, for neighbouring runs of different small shapes, stages in
+// order of application (the group's last factors first):
+// V(type, dtype code, P0, Q0, G0, P1, Q1, G1, P2, Q2, G2, largest tile_slices, threads); the comment
+// behind a row gives the factors in the order of the Kronecker product.  A curated list (neighbouring
+// runs of 2x2, 4x4 and 8x8, 5x5 beside 2x2, 3x3 beside 2x2): a further combination is one more row.
 // Order = preference among instances that fit a shape.
-#define KM_INSTANCES(X, Y, Z, W, R)                          \
+#define KM_INSTANCES(X, Y, Z, W, R, V)                       \
     X(float, KM_F32, 8, 8, 3, 32, 1024)                 \
     X(float, KM_F32, 8, 8, 3, 32, 256)                  \
     X(float, KM_F32, 8, 8, 3, 16, 256)                  \
@@ -189,4 +194,22 @@
     W(double, KM_F64, 4, 8, 2, 0, 0, 64, 256)           \
     W(double, KM_F64, 4, 8, 1, 0, 0, 512, 256)          \
     W(double, KM_F64, 8, 4, 1, 1, 0, 64, 256)           \
-    W(double, KM_F64, 8, 4, 1, 0, 0, 512, 256)
+    W(double, KM_F64, 8, 4, 1, 0, 0, 512, 256)          \
+    V(float, KM_F32, 2, 2, 4, 4, 4, 3, 4, 4, 2, 1, 256)    /* 4x4^5, 2x2^4 */ \
+    V(float, KM_F32, 2, 2, 4, 4, 4, 2, 4, 4, 2, 4, 256)    /* 4x4^4, 2x2^4 */ \
+    V(float, KM_F32, 2, 2, 4, 4, 4, 2, 0, 0, 0, 64, 256)   /* 4x4^2, 2x2^4 */ \
+    V(float, KM_F32, 2, 2, 3, 4, 4, 2, 0, 0, 0, 128, 256)  /* 4x4^2, 2x2^3 */ \
+    V(float, KM_F32, 4, 4, 2, 2, 2, 4, 2, 2, 4, 4, 256)    /* 2x2^8, 4x4^2 */ \
+    V(float, KM_F32, 4, 4, 2, 2, 2, 4, 0, 0, 0, 64, 256)   /* 2x2^4, 4x4^2 */ \
+    V(float, KM_F32, 4, 4, 2, 8, 8, 1, 8, 8, 1, 16, 256)   /* 8x8^2, 4x4^2 */ \
+    V(float, KM_F32, 8, 8, 1, 8, 8, 1, 4, 4, 2, 16, 256)   /* 4x4^2, 8x8^2 */ \
+    V(float, KM_F32, 2, 2, 3, 8, 8, 1, 8, 8, 1, 32, 256)   /* 8x8^2, 2x2^3 */ \
+    V(float, KM_F32, 8, 8, 1, 8, 8, 1, 2, 2, 3, 32, 256)   /* 2x2^3, 8x8^2 */ \
+    V(float, KM_F32, 2, 2, 1, 5, 5, 2, 0, 0, 0, 256, 256)  /* 5x5^2, 2x2 */ \
+    V(float, KM_F32, 5, 5, 2, 2, 2, 1, 0, 0, 0, 256, 256)  /* 2x2, 5x5^2 */ \
+    V(float, KM_F32, 2, 2, 2, 3, 3, 2, 0, 0, 0, 432, 256)  /* 3x3^2, 2x2^2 */ \
+    V(double, KM_F64, 2, 2, 4, 4, 4, 2, 4, 4, 2, 2, 256)   /* 4x4^4, 2x2^4 */ \
+    V(double, KM_F64, 2, 2, 4, 4, 4, 2, 0, 0, 0, 32, 256)  /* 4x4^2, 2x2^4 */ \
+    V(double, KM_F64, 4, 4, 2, 2, 2, 4, 0, 0, 0, 32, 256)  /* 2x2^4, 4x4^2 */ \
+    V(double, KM_F64, 4, 4, 2, 8, 8, 1, 8, 8, 1, 8, 256)   /* 8x8^2, 4x4^2 */ \
+    V(double, KM_F64, 2, 2, 1, 5, 5, 2, 0, 0, 0, 128, 256) /* 5x5^2, 2x2 */

@@ -40,21 +40,28 @@ namespace km {
      (G0 == 1 && P < 8) ? 1.6f                           /* one tiny factor per LDS pass is instruction-bound */ \
      : (P == 3 && G0 + G1 + G2 >= 5) ? 1.2f : 1.0f,      /* 3^5 and more elements per slice: long runs need tiles that leave two workgroups per compute unit */ \
      "fused-multi", MultiShape<T, P, Q, G0, G1, G2, ST, NT>::LDS_PER_SLICE, (int)ipow(P, G0), 0, 0, 0, 0, \
-     MultiShape<T, P, Q, G0, G1, G2, ST, NT>::LDS_SLACK},
+     MultiShape<T, P, Q, G0, G1, G2, ST, NT>::LDS_SLACK, {0, 0, 0, 0, 0, 0, 0, 0, 0}},
+#define KM_MIXED_SHAPE(T, P0, Q0, G0, P1, Q1, G1, P2, Q2, G2, ST, NT) MixedShape<T, P0, Q0, G0, P1, Q1, G1, P2, Q2, G2, ST, NT>
+#define KM_MIXED_ROW(T, DT, P0, Q0, G0, P1, Q1, G1, P2, Q2, G2, ST, NT) \
+    {KM_KERNEL_FUSED, DT, P0, Q0, G0 + G1 + G2, ST, NT, KM_MIXED_SHAPE(T, P0, Q0, G0, P1, Q1, G1, P2, Q2, G2, ST, NT)::LDS_BYTES, 1, 0, 1, \
+     (G0 == 1 && P0 < 8) ? 1.6f : 1.0f, "fused-mixed", \
+     KM_MIXED_SHAPE(T, P0, Q0, G0, P1, Q1, G1, P2, Q2, G2, ST, NT)::LDS_PER_SLICE, (int)ipow(P0, G0), 0, 0, 0, 0, \
+     KM_MIXED_SHAPE(T, P0, Q0, G0, P1, Q1, G1, P2, Q2, G2, ST, NT)::LDS_SLACK, {P0, Q0, G0, P1, Q1, G1, P2, Q2, G2}},
+#define KM_MIXED_FN(T, DT, P0, Q0, G0, P1, Q1, G1, P2, Q2, G2, ST, NT) launch_multi<KM_MIXED_SHAPE(T, P0, Q0, G0, P1, Q1, G1, P2, Q2, G2, ST, NT)>,
 #define KM_ROWS_ROW(P, ST, NW) \
     {KM_KERNEL_MFMA, KM_F32, P, 32, 2, 1, NW * 64, 0, ST, 2, 0, 1.0f, "mfma-pair-rows"},
 #define KM_ROWS_FN(P, ST, NW) launch_mfma_pair_rows<P, ST, NW>,
-#define KM_MULTI_FN(T, DT, P, Q, G0, G1, G2, ST, NT) launch_multi<T, P, Q, G0, G1, G2, ST, NT>,
+#define KM_MULTI_FN(T, DT, P, Q, G0, G1, G2, ST, NT) launch_multi<MultiShape<T, P, Q, G0, G1, G2, ST, NT>>,
 #define KM_PAIR_FN(P, ST, NW, PD, NPASS) launch_mfma_pair<P, ST, NW, PD, NPASS>,
 #define KM_FUSED_FN(T, DT, P, Q, NF, ST, NT) launch_fused<T, P, Q, NF, ST, NT>,
 #define KM_MFMA_FN(OP, DT, P, Q, NF, ST, NW, QS) launch_mfma<OP, P, Q, NF, ST, NW, QS>,
 
 static const Variant g_variants[] = {
     {KM_KERNEL_SHUFFLE, KM_F32, SHF_P, SHF_Q, 1, SHF_ST, SHF_NT, 0, 1, 0, 0, 1.0f, "shuffle"},
-    KM_INSTANCES(KM_FUSED_ROW, KM_MFMA_ROW, KM_PAIR_ROW, KM_MULTI_ROW, KM_ROWS_ROW) };
+    KM_INSTANCES(KM_FUSED_ROW, KM_MFMA_ROW, KM_PAIR_ROW, KM_MULTI_ROW, KM_ROWS_ROW, KM_MIXED_ROW) };
 static const LaunchFn g_launchers[] = {
     launch_shuffle,
-    KM_INSTANCES(KM_FUSED_FN, KM_MFMA_FN, KM_PAIR_FN, KM_MULTI_FN, KM_ROWS_FN) };
+    KM_INSTANCES(KM_FUSED_FN, KM_MFMA_FN, KM_PAIR_FN, KM_MULTI_FN, KM_ROWS_FN, KM_MIXED_FN) };
 static const int g_num_variants = (int)(sizeof(g_variants) / sizeof(g_variants[0]));
 
 template <typename T>

@@ -45,7 +45,7 @@ inline hipError_t allow_lds(const void* kernel, int bytes, unsigned char (&done)
 }
 
 template <typename T, int P, int Q, int NF, int ST, int NT> hipError_t launch_fused(const LaunchArgs& a);
-template <typename T, int P, int Q, int G0, int G1, int G2, int STMAX, int NT> hipError_t launch_multi(const LaunchArgs& a);
+template <class Sh> hipError_t launch_multi(const LaunchArgs& a);      // Sh: a MixedShape of fused_multi_kernel.hpp
 template <class OP, int P, int Q, int NF, int ST, int NW, int QSPLIT> hipError_t launch_mfma(const LaunchArgs& a);
 template <int P, int ST, int NW, int PD, int NPASS> hipError_t launch_mfma_pair(const LaunchArgs& a);
 template <int P, int ST, int NW> hipError_t launch_mfma_pair_rows(const LaunchArgs& a);

@@ -7,20 +7,28 @@
 
 namespace km {
 
-template <typename T, int P, int Q, int G0, int G1, int G2, int STMAX, int NT>
+template <class Sh>
 hipError_t launch_multi(const LaunchArgs& a)
 {
-    typedef MultiShape<T, P, Q, G0, G1, G2, STMAX, NT> Sh;
+    typedef typename Sh::T T;
+    constexpr int STMAX = Sh::STMAX, NT = Sh::NT;
     const km_plan_step& st = *a.st;
-    auto kern = fused_multi_sliced_multiply<T, P, Q, G0, G1, G2, STMAX, NT>;
+    auto kern = fused_multi_sliced_multiply<Sh>;
     static unsigned char lds_ok[64];
     hipError_t e = allow_lds((const void*)kern, Sh::LDS_BYTES, lds_ok);
     if (e != hipSuccess || a.prepare_only) return e;
     const int rows = st.tile_rows;
     if (rows < 1 || st.tile_slices < 1 || (int64_t)st.tile_slices * rows > STMAX) return hipErrorInvalidValue;
     const int slices = st.tile_slices * rows;            // what the kernel treats as one tile
+    if (st.num_factors != Sh::NF) return hipErrorInvalidValue;
     FactorPtrs<Sh::NF> fp;
     for (int j = 0; j < Sh::NF; ++j) fp.f[j] = a.factors[st.first_factor + Sh::NF - 1 - j];   // order of application
+    // stage j takes the next g(j) factors in that order: each must have the shape the stage is compiled for
+    for (int j = 0, at = 0; j < Sh::NS; ++j)
+        for (int k = 0; k < Sh::g(j); ++k, ++at) {
+            const int f = st.first_factor + Sh::NF - 1 - at;
+            if (a.pr->P[f] != Sh::p(j) || a.pr->Q[f] != Sh::q(j)) return hipErrorInvalidValue;
+        }
     const int64_t tk_row = (int64_t)st.tile_slices * Sh::per_slice(0);
     if (st.k_in % tk_row) return hipErrorInvalidValue;
     const int64_t tiles_per_row = st.k_in / tk_row;

@@ -32,7 +32,25 @@ struct Variant {
     int walk;          // > 0: tiles per workgroup of a persistent instance, instead of the rule of tiles_per_wg()
     int xcd_order;     // 1: persistent instance that prefers tile order 3 (each XCD walks its own eighth of the tiles)
     int lds_slack;     // flexible instances: LDS bytes a launch needs on top of lds_per_slice * tile_slices
+    int mix[9];        // instances whose stages have their own factor shapes: (P, Q, factors) of up to three
+                       // stages in order of application (P, Q above are the first stage's); all 0 otherwise
 };
+
+// Do factors [f - nf + 1, f] (applied from f downwards) have the shapes instance c is compiled for?
+inline bool shapes_match(const Variant& c, const std::vector<int>& P, const std::vector<int>& Q, int f, int nf)
+{
+    if (c.num_factors != nf) return false;
+    if (c.mix[2] == 0) {                                  // one shape for every factor of the group
+        for (int i = f - nf + 1; i <= f; ++i)
+            if (P[i] != c.P || Q[i] != c.Q) return false;
+        return true;
+    }
+    int at = f;
+    for (int j = 0; j < 3; ++j)
+        for (int k = 0; k < c.mix[3 * j + 2]; ++k, --at)
+            if (at < f - nf + 1 || P[at] != c.mix[3 * j] || Q[at] != c.mix[3 * j + 1]) return false;
+    return at == f - nf;
+}
 
 // LDS a launch of the instance asks for when its tiles hold `tile_slices` slices.
 inline int launch_lds_bytes(const Variant& c, int tile_slices)
@@ -281,7 +299,6 @@ inline bool group_shape(const Problem& pr, int f, int nf, int64_t k_cur, int64_t
     int64_t qg = 1;
     pg = 1;
     for (int i = f - nf + 1; i <= f; ++i) {
-        if (pr.P[i] != pr.P[f] || pr.Q[i] != pr.Q[f]) return false;   // equal shapes within a group
         pg *= pr.P[i];
         qg *= pr.Q[i];
         if (pg > ((int64_t)1 << 40) || qg > ((int64_t)1 << 40)) return false;
@@ -305,8 +322,7 @@ inline void enumerate_choices(const Variant* table, int count, const Problem& pr
     for (int v = 0; v < count; ++v) {
         const Variant& c = table[v];
         if (!(opt.kernels >> c.kernel & 1)) continue;
-        if (c.dtype != pr.dtype || c.num_factors != nf) continue;
-        if (c.P != pr.P[f] || c.Q != pr.Q[f]) continue;
+        if (c.dtype != pr.dtype || !shapes_match(c, pr.P, pr.Q, f, nf)) continue;
         if (c.max_srow > 0 && s_row > c.max_srow) continue;
         if (c.rows_per_tile > 1 && s_row != c.tile_slices) continue;      // tiles of several rows hold whole rows
         tile_lengths(c, s_row, lens, 5);
@@ -369,8 +385,7 @@ inline Choice find_variant(const Variant* table, int count, const Problem& pr, i
     for (int v = 0; v < count; ++v) {
         const Variant& c = table[v];
         if (!(opt.kernels >> c.kernel & 1)) continue;
-        if (c.dtype != pr.dtype || c.num_factors != nf) continue;
-        if (c.P != pr.P[f] || c.Q != pr.Q[f]) continue;
+        if (c.dtype != pr.dtype || !shapes_match(c, pr.P, pr.Q, f, nf)) continue;
         if (c.max_srow > 0 && s_row > c.max_srow) continue;
         if (c.rows_per_tile > 1 && s_row != c.tile_slices) continue;      // tiles of several rows hold whole rows
         if (c.min_tiles > 0 && !c.flexible && pr.M * (s_row / c.tile_slices) < c.min_tiles && opt.prefer_instance != v + 1)

@@ -177,6 +177,13 @@ SMALL_CASES = [
     ("float64", 5, [(30, 30)] * 2),
     ("float64", 3, [(16, 48), (44, 41)]),
     ("float64", 129, [(90, 90)]),
+    # neighbouring runs of different small shapes fused into one launch
+    ("float32", 5, [(4, 4)] * 5 + [(2, 2)] * 4),
+    ("float32", 3, [(3, 3)] + [(4, 4)] * 2 + [(2, 2)] * 4),
+    ("float64", 4, [(8, 8)] * 2 + [(4, 4)] * 2),
+    ("float32", 1100, [(5, 5)] * 2 + [(2, 2)]),
+    ("float32", 7, [(2, 2)] + [(5, 5)] * 2 + [(9, 9)]),
+    ("float64", 2, [(7, 7)] + [(2, 2)] * 4 + [(4, 4)] * 2),
 ]
 
 
@@ -388,6 +395,22 @@ EVERY_INSTANCE = [
     ("float64", 64, [(8, 8)] * 6),
     # rows of 6^7 elements, for the 6x6 instances with fixed tiles of 48, 288 and 16 slices
     ("float32", 24, [(6, 6)] * 7), ("float64", 12, [(6, 6)] * 7),
+    # neighbouring runs of different small shapes in one launch (a factor shape per stage): whole rows as
+    # tiles, several tiles per row behind other factors, many short rows per tile
+    ("float32", 300, [(4, 4)] * 5 + [(2, 2)] * 4), ("float32", 300, [(4, 4)] * 4 + [(2, 2)] * 4),
+    ("float32", 300, [(2, 2)] * 8 + [(4, 4)] * 2), ("float32", 300, [(8, 8)] * 2 + [(4, 4)] * 2),
+    ("float32", 300, [(4, 4)] * 2 + [(8, 8)] * 2), ("float64", 300, [(4, 4)] * 4 + [(2, 2)] * 4),
+    ("float64", 300, [(8, 8)] * 2 + [(4, 4)] * 2),
+    ("float32", 300, [(6, 6)] * 2 + [(4, 4)] * 2 + [(2, 2)] * 4),
+    ("float32", 300, [(6, 6)] * 2 + [(4, 4)] * 2 + [(2, 2)] * 3),
+    ("float32", 300, [(6, 6)] * 2 + [(2, 2)] * 4 + [(4, 4)] * 2),
+    ("float32", 300, [(6, 6)] * 2 + [(8, 8)] * 2 + [(2, 2)] * 3),
+    ("float32", 300, [(6, 6)] * 2 + [(2, 2)] * 3 + [(8, 8)] * 2), ("float32", 300, [(6, 6)] * 3 + [(5, 5)] * 2 + [(2, 2)]),
+    ("float32", 300, [(6, 6)] * 3 + [(2, 2)] + [(5, 5)] * 2), ("float32", 300, [(7, 7)] * 3 + [(3, 3)] * 2 + [(2, 2)] * 2),
+    ("float64", 300, [(6, 6)] * 2 + [(4, 4)] * 2 + [(2, 2)] * 4),
+    ("float64", 300, [(6, 6)] * 2 + [(2, 2)] * 4 + [(4, 4)] * 2),
+    ("float64", 300, [(6, 6)] * 3 + [(5, 5)] * 2 + [(2, 2)]),
+    ("float32", 1100, [(4, 4)] * 2 + [(2, 2)] * 3), ("float32", 1100, [(5, 5)] * 2 + [(2, 2)]), ("float64", 1100, [(5, 5)] * 2 + [(2, 2)]),
 ]
 FUSE_LIMITS = (12, 11, 10, 9, 8, 7, 6, 5, 4, 3, 2, 1)
 
