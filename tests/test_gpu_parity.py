@@ -230,11 +230,12 @@ def test_factors_need_only_their_elements_alignment(dtype, M, shapes):
 
 
 # every compiled instance and launch mode, forced through the tuning options, on mid-size inputs
-def _random_problems(count, seed):
+def _random_problems(count, seed, pool=(1, 2, 2, 3, 4, 4, 5, 6, 7, 8, 8, 9, 12, 16, 16, 17, 32, 32, 33, 64),
+                     max_m=40):
     """Seeded random problems: any mix of factor shapes (runs of equal shapes are likely, so fused
     groups, single launches and the generic kernel all occur), rows of at most 2^17 elements."""
     rng = np.random.default_rng(seed)
-    pool = [1, 2, 2, 3, 4, 4, 5, 6, 7, 8, 8, 9, 12, 16, 16, 17, 32, 32, 33, 64]
+    pool = list(pool)
     out = []
     while len(out) < count:
         n = int(rng.integers(1, 7))
@@ -249,7 +250,7 @@ def _random_problems(count, seed):
             widths.append(widths[-1] // p * q)
         if max(widths) > 2 ** 17:
             continue
-        out.append(("float32" if rng.random() < 0.6 else "float64", int(rng.integers(1, 41)), shapes))
+        out.append(("float32" if rng.random() < 0.6 else "float64", int(rng.integers(1, max_m + 1)), shapes))
     return out
 
 
@@ -258,6 +259,18 @@ def test_random_shapes(dtype, M, shapes):
     X, Fs = kron_inputs.make_problem(M, shapes, dtype, seed=300 + M + len(shapes))
     assert_close(run_gpu(X, Fs), X, Fs)
     Xi, Fi = kron_inputs.make_problem(M, shapes, dtype, x="int2", f="int1", seed=400 + M)
+    if 2.0 * np.prod([s[0] for s in shapes], dtype=np.float64) < (2 ** 24 if dtype == "float32" else 2 ** 53):
+        assert_close(run_gpu(Xi, Fi, use_ws=True), Xi, Fi, exact=True)
+
+
+@pytest.mark.parametrize("dtype,M,shapes", _random_problems(32, 31, pool=(2, 2, 2, 4, 4, 4, 8, 8, 5, 3, 20, 36, 40, 14, 48, 100),
+                                                          max_m=600), ids=lambda v: str(v).replace(" ", ""))
+def test_random_shapes_of_mixed_small_and_padded_factors(dtype, M, shapes):
+    """Random problems from the shapes the per-stage small-factor instances and the zero-padding MFMA
+    kernel take, with up to 600 rows so that the planner finds enough workgroups to fuse."""
+    X, Fs = kron_inputs.make_problem(M, shapes, dtype, seed=500 + M + len(shapes))
+    assert_close(run_gpu(X, Fs), X, Fs)
+    Xi, Fi = kron_inputs.make_problem(M, shapes, dtype, x="int2", f="int1", seed=600 + M)
     if 2.0 * np.prod([s[0] for s in shapes], dtype=np.float64) < (2 ** 24 if dtype == "float32" else 2 ** 53):
         assert_close(run_gpu(Xi, Fi, use_ws=True), Xi, Fi, exact=True)
 
@@ -846,6 +859,8 @@ TUNED = [
     ("float32", 6, [(4, 4)] * 7),
     ("float64", 4, [(8, 8)] * 4),
     ("float32", 5, [(3, 5), (7, 2), (8, 8), (8, 8)]),
+    ("float32", 40, [(4, 4)] * 4 + [(2, 2)] * 4),        # runs of different small shapes: per-stage instances compete
+    ("float64", 24, [(20, 20)] * 2 + [(40, 40)]),        # the run-time-shape MFMA kernel against the generic one
 ]
 
 
@@ -874,7 +889,9 @@ PLANNER_CHECK = ([(c["dtype"], c["M"], c["shapes"]) for c in kron_inputs.CONFIGS
                  + [("float32", t[1], t[2]) for t in kron_inputs.TABLE4 if t[0] in (17, 18, 19, 24, 25, 26, 27, 28)]
                  + [("float64", t[1], t[2]) for t in kron_inputs.TABLE4 if t[0] in (25, 28)]
                  + [("float32", 1024, [(p, p)] * n) for p, n in ((3, 11), (5, 8), (7, 6), (9, 5))]      # rows of odd length
-                 + [("float32", 1024, [(48, 48)] * 3), ("float32", 256, [(80, 80)] * 3)])               # other multiples of 16
+                 + [("float32", 1024, [(48, 48)] * 3), ("float32", 256, [(80, 80)] * 3)]                # other multiples of 16
+                 + [("float32", 1024, [(36, 36)] * 3), ("float32", 512, [(20, 20)] * 4)]                # padded to multiples of 16
+                 + [("float32", 1024, [(4, 4)] * 5 + [(2, 2)] * 4), ("float32", 4096, [(8, 8)] * 2 + [(4, 4)] * 2)])   # mixed small shapes
 
 
 @pytest.mark.parametrize("dtype,M,shapes", PLANNER_CHECK, ids=lambda v: str(v).replace(" ", "")[:40])
