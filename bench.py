@@ -77,6 +77,17 @@ def make_workload(name, seed):
     return (kron_inputs.CONFIGS[name]["dtype"],) + kron_inputs.make_config(name, seed=seed)
 
 
+def shape_runs(P, Q):
+    """Factor shapes as runs of equal ones: "3x(8x8)", "5x(4x4)+4x(2x2)"."""
+    runs = []
+    for pq in zip(P, Q):
+        if runs and runs[-1][0] == pq:
+            runs[-1][1] += 1
+        else:
+            runs.append([pq, 1])
+    return "+".join("%dx(%dx%d)" % (n, p, q) for (p, q), n in runs)
+
+
 def measure(name, args, headline):
     """Runs one workload: warm-up, settling, the timed steps, per-launch durations, the clock probe,
     and the comparison with the CPU oracle.  Returns the full result dictionary."""
@@ -196,10 +207,7 @@ def measure(name, args, headline):
             k = k // P[i] * Q[i]
         key = (st["kernel"], st["variant"], st["k_in"], st["k_out"])
         launches.append(dict(key=key, ms=ms, bytes=nb, flops=fl,
-                             name=("%s[%dx(%dx%d)]" % (km.kernel_name(st["kernel"]), nf, P[f0], Q[f0])
-                                   if len(set(zip(P[f0:f0 + nf], Q[f0:f0 + nf]))) == 1 else
-                                   "%s[%s]" % (km.kernel_name(st["kernel"]),
-                                               ",".join("%dx%d" % pq for pq in zip(P[f0:f0 + nf], Q[f0:f0 + nf]))))))
+                             name="%s[%s]" % (km.kernel_name(st["kernel"]), shape_runs(P[f0:f0 + nf], Q[f0:f0 + nf]))))
     groups = {}
     for l in launches:
         g = groups.setdefault(l["key"], dict(ms=0.0, n=0, bytes=l["bytes"], flops=l["flops"], name=l["name"]))

@@ -199,9 +199,10 @@ km_status kronmatmul_cost(int M, int N, const int* P, const int* Q, km_dtype dty
  * makes it take the whole-row kernel (KM_KERNEL_ROWS) whenever the rows fit LDS.
  * KM_OPT_INSTANCE_COUNT: read-only; the number of compiled instances.
  * KM_OPT_KEEP_MIB: tuning aid (default 320); a launch that is not a call's last and writes between 48
- * and this many MiB uses ordinary instead of non-temporal stores, so that the next launch finds
- * part of the intermediate in the chip's last-level cache (256 MB); 0 = non-temporal always.  It takes
- * effect on the next call and changes no result. */
+ * and this many MiB (four times as many for the KM_KERNEL_FUSED family) uses ordinary instead of
+ * non-temporal stores, so that the next launch finds part of the intermediate in the chip's
+ * last-level cache (256 MB); 0 = non-temporal always.  It takes effect on the next call and changes
+ * no result. */
 typedef enum { KM_OPT_KERNELS = 0, KM_OPT_MAX_FUSE = 1, KM_OPT_PROFILE = 2, KM_OPT_PREFER_TILE = 3,
                KM_OPT_PREFER_THREADS = 4, KM_OPT_TILES_PER_WG = 5, KM_OPT_PAIR_INTERLEAVE = 6, KM_OPT_TILE_ORDER = 7,
                KM_OPT_PREFER_INSTANCE = 8, KM_OPT_INSTANCE_COUNT = 9, KM_OPT_KEEP_MIB = 10 } km_option;

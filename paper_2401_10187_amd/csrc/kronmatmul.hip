@@ -286,7 +286,11 @@ static km_status run(const Problem& pr, const Plan& plan, const void* X, const v
         };
         // an intermediate that fits the last-level cache is written so that it stays there for the next launch
         const double out_mib = (double)pr.M * (double)st.k_out * (double)pr.esize / 1048576.0;
-        const bool keep = i + 1 < n && out_mib >= KEEP_MIN_MIB && out_mib <= (double)g_keep_mib;
+        // (the small-factor kernel still gains 1-2 % at 1 GiB, where a quarter of the intermediate stays on
+        // chip: 1024 x 8x8^6 0.724 -> 0.715 ms, 16 x 8x8^8 1.255 -> 1.225, 65536 x 8x8^4 0.714 -> 0.697; level at
+        // 2 GiB, 1.6 % slower at 4 GiB; the MFMA kernels lose from 400 MB on)
+        const double keep_max = (double)g_keep_mib * (st.kernel == KM_KERNEL_FUSED ? 4.0 : 1.0);
+        const bool keep = i + 1 < n && out_mib >= KEEP_MIN_MIB && out_mib <= keep_max;
         if (launch_step(pr, st, buf(st.src), buf(st.dst), F, stream, false, keep) != hipSuccess) return KM_ELAUNCH;
         if (profile && hipEventRecord(ev[i + 1], stream) != hipSuccess) return KM_ELAUNCH;
     }
