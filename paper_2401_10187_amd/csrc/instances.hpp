@@ -69,7 +69,15 @@
     Y(MfmaF32x32, KM_F32, 32, 128, 1, 256, 4, 2)        \
     Y(MfmaF32x16, KM_F32, 48, 48, 1, 128, 4, 1)         \
     Y(MfmaF32x32, KM_F32, 96, 96, 1, 64, 6, 3)          \
+    Y(MfmaF32x16, KM_F32, 80, 80, 1, 128, 10, 5)        \
+    Y(MfmaF32x16, KM_F32, 80, 80, 1, 64, 10, 5)         \
+    Y(MfmaF32x16, KM_F32, 112, 112, 1, 64, 7, 7)        \
+    Y(MfmaF32x16, KM_F32, 144, 144, 1, 64, 9, 9)        \
     Y(MfmaF64x16, KM_F64, 48, 48, 1, 64, 4, 1)          \
+    Y(MfmaF64x16, KM_F64, 80, 80, 1, 64, 10, 5)         \
+    Y(MfmaF64x16, KM_F64, 96, 96, 1, 64, 6, 6)          \
+    Y(MfmaF64x16, KM_F64, 112, 112, 1, 64, 7, 7)        \
+    Y(MfmaF64x16, KM_F64, 144, 144, 1, 64, 9, 9)        \
     Y(MfmaF64x16, KM_F64, 32, 16, 1, 128, 4, 1)         \
     Y(MfmaF64x16, KM_F64, 16, 32, 1, 128, 4, 1)         \
     Y(MfmaF64x16, KM_F64, 64, 32, 1, 64, 4, 1)          \

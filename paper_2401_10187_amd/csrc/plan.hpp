@@ -29,7 +29,8 @@ struct Variant {
     int thread_elems;  // flexible instances: contiguous elements of a tile that one thread multiplies first
     int max_srow;      // > 0: only for rows of at most this many slices of the group (K / prod P)
     int min_tiles;     // > 0: only planned for launches of at least this many tiles (the tuner still tries it)
-    int walk;          // > 0: tiles per workgroup of a persistent instance, instead of the rule of tiles_per_wg()
+    int walk;          // > 0: tiles per workgroup of a persistent instance, instead of the rule of tiles_per_wg();
+                       // -1: as many as make the grid one round of the workgroups the chip holds at once
     int xcd_order;     // 1: persistent instance that prefers tile order 3 (each XCD walks its own eighth of the tiles)
     int lds_slack;     // flexible instances: LDS bytes a launch needs on top of lds_per_slice * tile_slices
     int mix[9];        // instances whose stages have their own factor shapes: (P, Q, factors) of up to three
@@ -176,13 +177,15 @@ inline int64_t store_column(int64_t k_in, int64_t p_group, int64_t tile_k, int64
     return qq * s_row + tile_index * s_tile + r;
 }
 
-// Column blocks (of 16) per unit of the run-time-shape MFMA kernel for a factor with Q columns: the
-// width among 4, 5, 3, 2 and 1 (tried in this order) that leaves the fewest padded blocks.
+// Column blocks (of 16) per unit of the run-time-shape MFMA kernel for a factor with Q columns: one or
+// two for factors that narrow, else the width among 4, 5 and 3 that leaves the fewest padded blocks
+// (narrower units would re-read the slices once per 16 or 32 columns).
 inline int any_column_blocks(int Q)
 {
     const int blocks = (Q + 15) / 16;
+    if (blocks <= 2) return blocks < 1 ? 1 : blocks;
     int best = 4, waste = (4 - blocks % 4) % 4 * 1000 / ((blocks + 3) / 4 * 4);
-    const int others[4] = {5, 3, 2, 1};
+    const int others[2] = {5, 3};
     for (int cb : others) {
         const int w = (cb - blocks % cb) % cb * 1000 / ((blocks + cb - 1) / cb * cb);
         if (w < waste) { waste = w; best = cb; }
@@ -535,8 +538,17 @@ inline km_plan_step build_step(const Problem& pr, const Options& opt, const Vari
         st.grid = ch.grid;
         if (var->persistent) {
             const int hint = ch.tiles_per_wg > 0 ? ch.tiles_per_wg : opt.tiles_per_wg;
-            const int64_t tpw = tiles_per_wg(st.grid, hint, (int64_t)nf * var->P * var->Q,
-                                             (int64_t)ch.tile_slices * ch.tile_rows * pg, var->lds_bytes, pr.esize, var->walk);
+            int64_t tpw = tiles_per_wg(st.grid, hint, (int64_t)nf * var->P * var->Q,
+                                       (int64_t)ch.tile_slices * ch.tile_rows * pg, var->lds_bytes, pr.esize, var->walk);
+            if (hint <= 0 && var->walk == -1) {
+                // every workgroup resident from the start and each with the same share of the tiles
+                // (measured with the autotuner: 256 x 80x80^3 walks of 17 instead of 8 tiles 0.809 -> 0.721 ms,
+                // 256 x 112x112^3 49 instead of 32 2.68 -> 2.38, 64 x 144x144^3 27 instead of 32 2.07 -> 1.76)
+                const int64_t resident = 256 * resident_per_cu(*var);
+                tpw = (st.grid + resident - 1) / resident;
+                if (tpw > 4096) tpw = 4096;
+                while (tpw > 1 && st.grid / tpw < 256) --tpw;
+            }
             const int64_t num_tiles = st.grid;
             st.tiles_per_wg = (int)tpw;
             st.grid = (num_tiles + tpw - 1) / tpw;
