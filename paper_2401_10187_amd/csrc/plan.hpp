@@ -573,6 +573,11 @@ inline km_plan_step build_step(const Problem& pr, const Options& opt, const Vari
         st.grid = ((pr.M * S + st.tile_slices - 1) / st.tile_slices) * ((pr.Q[f] + cols - 1) / cols);
         const int64_t most = ((int64_t)1 << 32) / gen.any_threads - 1;     // the kernel strides over its units
         if (st.grid > most) st.grid = most;
+        // two rounds of the workgroups the chip holds at once (three per compute unit, two with five column
+        // blocks), each striding over its share of the units: 2-11 % faster than one workgroup per unit
+        // (512 x 40x40^3 fp64 0.458 -> 0.409 ms, 512 x 20x20^4 0.729 -> 0.691, 64 x 100x100^3 0.822 -> 0.789)
+        const int64_t rounds2 = 2 * 256 * (any_column_blocks(pr.Q[f]) >= 5 ? 2 : 3);
+        if (st.grid > rounds2) st.grid = rounds2;
     } else {
         st.kernel = KM_KERNEL_GENERIC;
         st.variant = -1;
