@@ -891,7 +891,7 @@ PLANNER_CHECK = ([(c["dtype"], c["M"], c["shapes"]) for c in kron_inputs.CONFIGS
                  + [("float64", t[1], t[2]) for t in kron_inputs.TABLE4 if t[0] in (25, 28)]
                  + [("float32", 1024, [(p, p)] * n) for p, n in ((3, 11), (5, 8), (7, 6), (9, 5))]      # rows of odd length
                  + [("float32", 1024, [(48, 48)] * 3), ("float32", 256, [(80, 80)] * 3), ("float32", 256, [(112, 112)] * 3),
-                    ("float64", 64, [(96, 96)] * 3), ("float32", 256, [(160, 160)] * 2)]                                 # other multiples of 16
+                    ("float64", 64, [(96, 96)] * 3), ("float32", 2048, [(160, 160)] * 2)]                                 # other multiples of 16
                  + [("float32", 1024, [(36, 36)] * 3), ("float32", 512, [(20, 20)] * 4)]                # padded to multiples of 16
                  + [("float32", 1024, [(4, 4)] * 5 + [(2, 2)] * 4), ("float32", 4096, [(8, 8)] * 2 + [(4, 4)] * 2)])   # mixed small shapes
 
