@@ -9,16 +9,18 @@
 // and stores are runs of the output row (the output column of (s, q) is q*(K/P)+s; section 4 of the
 // paper, with the matrix cores in place of its thread tiles).
 //
-// A unit of work is 128 consecutive slices (256 in the narrow shape, see AnyShape), numbered through all rows as in the generic
-// kernel, times CB*16 factor columns; workgroups stride over the units, units of the same slices being
-// numbered so that they run on the same XCD (they share the slices through its L2 cache).  P is walked in chunks of 256 bytes per
-// slice (64 floats, 32 doubles; the last one may be shorter): a chunk of the slices and the matching rows of the factor,
-// transposed, sit in LDS, rows padded to an odd number of 16-byte units so that the 16-byte operand
-// reads of 16 consecutive lanes fall into different banks.  Each of the four wavefronts owns 32 slices (two MFMA blocks,
-// joined before the store in fp32 so that a half wavefront writes a whole 128-byte line) and all
-// CB column blocks.  Loads and stores are bounds-checked against the slice, element and column counts;
-// the factor is read with 16-byte loads when its rows start on 16-byte boundaries (f_aligned: base
-// aligned and Q a whole number of vectors), element by element otherwise.
+// A unit of work is 128 consecutive slices (256 in the narrow shape, see AnyShape), numbered through
+// all rows as in the generic kernel, times CB*16 factor columns; workgroups stride over the units,
+// units of the same slices being numbered so that they run on the same XCD (they share the slices
+// through its L2 cache).  P is walked in chunks of 256 bytes per slice (64 floats, 32 doubles; narrow:
+// 128 bytes; the last chunk may be shorter): a chunk of the slices and the matching rows of the
+// factor, transposed, sit in LDS, rows padded to an odd number of 16-byte units so that the 16-byte
+// operand reads of 16 consecutive lanes fall into different banks.  Each of the four wavefronts owns
+// 32 slices (narrow: 64), MFMA blocks of 16 that are joined in pairs before the store in fp32 so that
+// a half wavefront writes a whole 128-byte line, and all CB column blocks.  Loads and stores are
+// bounds-checked against the slice, element and column counts; the factor is read with 16-byte loads
+// when its rows start on 16-byte boundaries (f_aligned: base aligned and Q a whole number of vectors),
+// element by element otherwise.  KEEP selects ordinary instead of non-temporal stores (out_store).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
