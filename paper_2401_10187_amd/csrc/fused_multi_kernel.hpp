@@ -91,9 +91,11 @@ struct MixedShape {
 template <typename T, int P, int Q, int G0, int G1, int G2, int STMAX, int NT>
 using MultiShape = MixedShape<T, P, Q, G0, P, Q, G1, P, Q, G2, STMAX, NT>;
 
+// (KEEP: ordinary instead of non-temporal stores, for output the next launch reads back out of the
+// last-level cache; see out_store.)
 // Tiles of whole rows: the final stage leaves the tile's output rows in LDS, unpadded and in
 // memory order (they are contiguous in Y), and this writes them out with contiguous stores.
-template <typename T, int NT>
+template <typename T, int NT, bool KEEP>
 __device__ __forceinline__ void multi_store_rows(const T* __restrict__ tile, T* __restrict__ dst, int n, bool vec_ok)
 {
     typedef typename Vec16<T>::type V;
@@ -111,7 +113,7 @@ __device__ __forceinline__ void multi_store_rows(const T* __restrict__ tile, T* 
 #pragma unroll
             for (int i = 0; i < UN; ++i) {
                 const int v = base + tid + i * NT;
-                if (v < nv) stream_store(tmp[i], &reinterpret_cast<V*>(dst)[v]);
+                if (v < nv) out_store<KEEP>(tmp[i], &reinterpret_cast<V*>(dst)[v]);
             }
         }
     } else {
@@ -119,7 +121,7 @@ __device__ __forceinline__ void multi_store_rows(const T* __restrict__ tile, T* 
 #pragma unroll
             for (int i = 0; i < UN; ++i) {
                 const int e = base + tid + i * NT;
-                if (e < n) stream_store(tile[e], &dst[e]);
+                if (e < n) out_store<KEEP>(tile[e], &dst[e]);
             }
         }
     }
@@ -129,7 +131,7 @@ __device__ __forceinline__ void multi_store_rows(const T* __restrict__ tile, T* 
 template <int PGN, int PADN>
 __device__ __forceinline__ int multi_lds_index(int c) { return PADN == 0 ? c : c + (c / PGN) * PADN; }
 
-template <class Sh, int J>
+template <class Sh, int J, bool KEEP>
 __device__ __forceinline__ void multi_stage(typename Sh::T* __restrict__ tile, const FactorPtrs<Sh::NF>& fp,
                                             typename Sh::T* __restrict__ Yrow, int64_t s_row, int64_t h, int st,
                                             int sr_tile, int64_t k_out, int rows_here, int tile_rows)
@@ -195,7 +197,7 @@ __device__ __forceinline__ void multi_stage(typename Sh::T* __restrict__ tile, c
                             const int m = (s % st) / sr_tile;        // row of the tile (0 unless it holds whole rows)
                             const int64_t at = m * k_out + (int64_t)(s / st + q * QREST1) * s_row + h * sr_tile + (s % st) % sr_tile;
                             if (tile_rows > 1) tile[at] = acc;       // whole rows: collected in LDS, stored below
-                            else stream_store(acc, &Yrow[at]);
+                            else out_store<KEEP>(acc, &Yrow[at]);
                         }
                     }
                 }
@@ -203,7 +205,7 @@ __device__ __forceinline__ void multi_stage(typename Sh::T* __restrict__ tile, c
         }
         if (!LAST || tile_rows > 1) __syncthreads();
         if constexpr (LAST) {
-            if (tile_rows > 1) multi_store_rows<T, NT>(tile, Yrow, (int)(rows_here * k_out), k_out % VN == 0);
+            if (tile_rows > 1) multi_store_rows<T, NT, KEEP>(tile, Yrow, (int)(rows_here * k_out), k_out % VN == 0);
         }
         return;
     } else {
@@ -279,18 +281,18 @@ __device__ __forceinline__ void multi_stage(typename Sh::T* __restrict__ tile, c
                     for (int qq = 0; qq < QGJ; ++qq) tile[at + (int64_t)(qq * QREST) * s_row] = out[i][qq];
                 } else {
 #pragma unroll
-                    for (int qq = 0; qq < QGJ; ++qq) stream_store(out[i][qq], &Yrow[at + (int64_t)(qq * QREST) * s_row]);
+                    for (int qq = 0; qq < QGJ; ++qq) out_store<KEEP>(out[i][qq], &Yrow[at + (int64_t)(qq * QREST) * s_row]);
                 }
             }
         }
         if (tile_rows > 1) {
             __syncthreads();
-            multi_store_rows<T, NT>(tile, Yrow, (int)(rows_here * k_out), k_out % VN == 0);
+            multi_store_rows<T, NT, KEEP>(tile, Yrow, (int)(rows_here * k_out), k_out % VN == 0);
         }
     }
 }
 
-template <class Sh>
+template <class Sh, bool KEEP>
 __global__ __launch_bounds__(Sh::NT)
 void fused_multi_sliced_multiply(const typename Sh::T* __restrict__ Xg, typename Sh::T* __restrict__ Yg,
                                  const FactorPtrs<Sh::NF> fp,           // in order of application
@@ -382,9 +384,9 @@ void fused_multi_sliced_multiply(const typename Sh::T* __restrict__ Xg, typename
     }
     __syncthreads();
 
-    multi_stage<Sh, 0>(tile, fp, Yrow, s_row, h, st, sr_tile, k_out, rows_here, tile_rows);
-    if constexpr (Sh::NS > 1) multi_stage<Sh, 1>(tile, fp, Yrow, s_row, h, st, sr_tile, k_out, rows_here, tile_rows);
-    if constexpr (Sh::NS > 2) multi_stage<Sh, 2>(tile, fp, Yrow, s_row, h, st, sr_tile, k_out, rows_here, tile_rows);
+    multi_stage<Sh, 0, KEEP>(tile, fp, Yrow, s_row, h, st, sr_tile, k_out, rows_here, tile_rows);
+    if constexpr (Sh::NS > 1) multi_stage<Sh, 1, KEEP>(tile, fp, Yrow, s_row, h, st, sr_tile, k_out, rows_here, tile_rows);
+    if constexpr (Sh::NS > 2) multi_stage<Sh, 2, KEEP>(tile, fp, Yrow, s_row, h, st, sr_tile, k_out, rows_here, tile_rows);
 }
 
 }  // namespace km

@@ -8,12 +8,14 @@
 namespace km {
 
 template <class Sh>
-hipError_t launch_multi(const LaunchArgs& a)
+struct MultiLauncher {
+template <bool KEEP>
+static hipError_t run(const LaunchArgs& a)
 {
     typedef typename Sh::T T;
     constexpr int STMAX = Sh::STMAX, NT = Sh::NT;
     const km_plan_step& st = *a.st;
-    auto kern = fused_multi_sliced_multiply<Sh>;
+    auto kern = fused_multi_sliced_multiply<Sh, KEEP>;
     static unsigned char lds_ok[64];
     hipError_t e = allow_lds((const void*)kern, Sh::LDS_BYTES, lds_ok);
     if (e != hipSuccess || a.prepare_only) return e;
@@ -42,5 +44,9 @@ hipError_t launch_multi(const LaunchArgs& a)
                        slices, rows, a.pr->M);
     return hipGetLastError();
 }
+};
+
+template <class Sh>
+hipError_t launch_multi(const LaunchArgs& a) { return launch_either<MultiLauncher<Sh>>(a); }
 
 }  // namespace km

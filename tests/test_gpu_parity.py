@@ -634,6 +634,8 @@ def test_full_size_every_element(name):
     ("float32", 16, [(32, 32)] * 4),        # pair kernel, 64 MiB
     ("float32", 64, [(80, 80)] * 3),        # run-time-shape MFMA kernel, 125 MiB
     ("float64", 128, [(40, 40)] * 3),       # the same, padded shape, 62 MiB
+    ("float32", 64, [(4, 4)] * 9),          # several small factors per LDS pass, 64 MiB
+    ("float64", 48, [(3, 3)] * 11),         # the same on rows of odd length (element-sized stores), 65 MiB
 ], ids=lambda v: str(v).replace(" ", ""))
 def test_intermediates_kept_in_cache_change_no_result(dtype, M, shapes):
     """Intermediates of 48 to 320 MiB are written with ordinary stores so that they stay in the
