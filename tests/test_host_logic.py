@@ -203,6 +203,36 @@ def test_padded_shapes_go_to_the_run_time_shape_mfma_kernel_within_its_padding_l
     assert [k for k, _ in kernels("float64", 4096, [(15, 16)] * 4)] == [gen] * 4   # odd P
 
 
+def test_neighbouring_runs_of_different_small_shapes_are_one_launch_where_an_instance_is_compiled():
+    """The small-factor kernel has a factor shape per stage; the planner matches a group's shapes against
+    the stages in order of application (the group's last factors first)."""
+    def steps(M, shapes, dtype="float32"):
+        return [(s["kernel"], s["num_factors"]) for s in km.plan(M, [p for p, _ in shapes], [q for _, q in shapes], dtype)]
+    fused = km.KM_KERNEL_FUSED
+    assert steps(1024, [(4, 4)] * 5 + [(2, 2)] * 4) == [(fused, 9)]
+    assert steps(1024, [(4, 4)] * 4 + [(2, 2)] * 4, "float64") == [(fused, 8)]
+    assert steps(4096, [(5, 5)] * 2 + [(2, 2)]) == [(fused, 3)]
+    assert steps(4096, [(2, 2)] + [(5, 5)] * 2) == [(fused, 3)]
+    assert steps(1024, [(8, 8)] * 2 + [(4, 4)] * 2) == [(fused, 4)]
+    # no instance for this order of the same factors: one launch per run of equal shapes
+    assert steps(1024, [(2, 2)] * 4 + [(4, 4)] * 5) == [(fused, 5), (fused, 4)]
+    # a run-time check on the launch side too: the plan of one shape sequence is refused for another
+    assert len(steps(1024, [(4, 4)] * 5 + [(2, 2)] * 3 + [(3, 3)])) > 1
+
+
+def test_square_mfma_instances_between_the_powers_of_two_walk_one_round_of_resident_workgroups():
+    """80, 112 and 144 (and 96 in fp64): the grid is the number of workgroups the chip holds at once
+    (three of 640 threads, four of 448, three of 576, three with 49 KB of LDS each per compute unit), each walking its share."""
+    for P, M, dtype, per_cu in ((80, 256, "float32", 3), (112, 256, "float32", 4), (144, 64, "float32", 3),
+                                (96, 64, "float64", 3)):
+        plan = km.plan(M, [P] * 3, [P] * 3, dtype)
+        assert [s["kernel"] for s in plan] == [km.KM_KERNEL_MFMA] * 3
+        for s in plan:
+            tiles = M * (P * P * P // P // s["tile_slices"])
+            assert s["grid"] == -(-tiles // s["tiles_per_wg"])
+            assert 256 * per_cu * 0.9 <= s["grid"] <= 256 * per_cu, (P, s["grid"], s["tiles_per_wg"])
+
+
 def test_planner_prefers_fusion_and_mfma_for_the_measured_workloads():
     import kron_inputs
     want = {"c1_f32_m16_8x8x3": [(km.KM_KERNEL_FUSED, 3)],
