@@ -196,6 +196,7 @@ def measure(name, args, headline):
     gflops = flops / (ms_per_step * 1e-3) / 1e9
 
     # dominant kernel = the launch kind with the largest share of the step
+    keep_mib = km.get_option(km.KM_OPT_KEEP_MIB)
     launches = []
     for st, ms in zip(steps, per_launch_ms):
         nb = es * M * (st["k_in"] + st["k_out"])
@@ -206,11 +207,18 @@ def measure(name, args, headline):
             fl += 2 * M * k * Q[i]
             k = k // P[i] * Q[i]
         key = (st["kernel"], st["variant"], st["k_in"], st["k_out"])
-        launches.append(dict(key=key, ms=ms, bytes=nb, flops=fl,
+        # did the launch before this one leave its output (this one's input) in the last-level cache?
+        # (the library's rule: not a call's last launch, 48 MiB to KM_OPT_KEEP_MIB, four times as much
+        # for the small-factor family)
+        prev = steps[len(launches) - 1] if launches else None
+        in_mib = es * M * st["k_in"] / 2.0 ** 20
+        kept_in = bool(prev and 48.0 <= in_mib <= keep_mib * (4 if prev["kernel"] == km.KM_KERNEL_FUSED else 1))
+        launches.append(dict(key=key, ms=ms, bytes=nb, flops=fl, kept_in=kept_in,
                              name="%s[%s]" % (km.kernel_name(st["kernel"]), shape_runs(P[f0:f0 + nf], Q[f0:f0 + nf]))))
     groups = {}
     for l in launches:
-        g = groups.setdefault(l["key"], dict(ms=0.0, n=0, bytes=l["bytes"], flops=l["flops"], name=l["name"]))
+        g = groups.setdefault(l["key"], dict(ms=0.0, n=0, bytes=l["bytes"], flops=l["flops"], name=l["name"],
+                                             kept_in=l["kept_in"]))
         g["ms"] += l["ms"]
         g["n"] += 1
     dom = max(groups.values(), key=lambda g: g["ms"])
@@ -228,7 +236,10 @@ def measure(name, args, headline):
     roofline.update(traffic=traffic, traffic_source=traffic_file, kernel=dom["name"],
                     kernel_ms=round(dom_ms, 4), launches_per_step=dom["n"],
                     algorithmic_bytes_per_launch=dom["bytes"], flops_per_launch=dom["flops"],
-                    alt_frac_hbm=round(gbs / HBM_PEAK_GBS, 4), alt_frac_flops=round(tfl / peak_tf, 4))
+                    alt_frac_hbm=round(gbs / HBM_PEAK_GBS, 4), alt_frac_flops=round(tfl / peak_tf, 4),
+                    # True: the kernel's input is an intermediate that the launch before it wrote with
+                    # cacheable stores, so part of the algorithmic bytes come from the last-level cache
+                    input_partly_cache_resident=dom["kept_in"])
 
     out = {
         "metric": "kron_matmul_gflops", "value": round(gflops, 1), "unit": "GFLOP/s",
@@ -288,6 +299,7 @@ def brief(res):
     return {"workload": c["workload"], "dtype": res["dtype"], "ms_per_step": res["ms_per_step"],
             "gflops": res["value"], "launches": c["launches"], "kernel": r["kernel"], "kernel_ms": r["kernel_ms"],
             "bound": r["bound"], "frac": r["frac"], "frac_hbm": r["alt_frac_hbm"], "frac_flops": r["alt_frac_flops"],
+            "input_partly_cache_resident": r["input_partly_cache_resident"],
             "traffic": r["traffic"], "algorithmic_bytes_per_launch": r["algorithmic_bytes_per_launch"],
             "settle_steps": c["settle_steps"], "shader_clock_mhz_under_load": c["shader_clock_mhz_under_load"],
             "max_rel_err": res.get("cpu_baseline", {}).get("max_rel_err_gpu_vs_oracle"),
