@@ -83,7 +83,16 @@ void mfma_any_sliced_multiply(const T* __restrict__ Xg, const T* __restrict__ Fg
     const int q_groups = (Q + QG - 1) / QG;
     const int xrow = tid / Sh::VPR, xcol = (tid % Sh::VPR) * VN;   // fetch duty: column xcol of slices xrow, xrow + RP, ...
 
+    // A factor of one column group and one chunk is the same LDS content for every unit of this
+    // workgroup: it is staged with the first unit only (2048 x 36x36^3 0.700 -> 0.567 ms, 512 x 52x52^3
+    // 0.580 -> 0.481, 512 x 60x60^3 0.814 -> 0.667, 1024 x 24x24^4 2.47 -> 2.23: the scalar, bank-conflicting LDS
+    // writes of the transposition cost as much as staging the slices.  Variants measured slower: the
+    // same as a compile-time form of the kernel that stages the factor ahead of the loop (0.620 for
+    // 36x36^3), and a whole factor of several chunks in rows of run-time length, 3-5 % only).
+    const bool f_stays = q_groups == 1 && P <= KT;
+
     for (int64_t unit = blockIdx.x; unit < num_units; unit += gridDim.x) {
+        const bool stage_f = !f_stays || unit == blockIdx.x;
         int64_t tile;
         int group;
         unit_of(unit, num_units / q_groups, q_groups, tile, group);
@@ -118,6 +127,7 @@ void mfma_any_sliced_multiply(const T* __restrict__ Xg, const T* __restrict__ Fg
                 }
             }
             const T* fsrc = Fg + (int64_t)k0 * Q + q0;   // uniform part of the factor addresses
+            if (stage_f)
 #pragma unroll
             for (int i = 0; i < FV; ++i) {
                 const int e = tid + i * ANY_THREADS;
@@ -130,6 +140,7 @@ void mfma_any_sliced_multiply(const T* __restrict__ Xg, const T* __restrict__ Fg
             __syncthreads();                             // the previous chunk (or unit) has been read by everybody
 #pragma unroll
             for (int i = 0; i < XV; ++i) *reinterpret_cast<V*>(Xs + (xrow + RP * i) * ROW + xcol) = xr[i];
+            if (stage_f)
 #pragma unroll
             for (int i = 0; i < FV; ++i) {
                 const int e = tid + i * ANY_THREADS;
