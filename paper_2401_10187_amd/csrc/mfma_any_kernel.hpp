@@ -72,6 +72,7 @@ void mfma_any_sliced_multiply(const T* __restrict__ Xg, const T* __restrict__ Fg
     typedef typename Vec16<T>::type V;
     constexpr int VN = Sh::VN, KT = Sh::KT, ROW = Sh::ROW, QG = Sh::QG, XV = Sh::XV, FVR = Sh::FVR, FV = Sh::FV;
     constexpr int SB = Sh::SB, TS = Sh::TS, RP = Sh::RP;
+    constexpr bool GATHER = sizeof(T) == 8 || CB >= 5;  // how the factor chunk is transposed into LDS (below)
     extern __shared__ __attribute__((aligned(16))) unsigned char any_lds[];
     T* Xs = reinterpret_cast<T*>(any_lds);            // [TS][ROW]: slice i, chunk element k
     T* Fs = Xs + Sh::X_ELEMS;                          // [QG][ROW]: factor column q (transposed), chunk element k
@@ -126,16 +127,29 @@ void mfma_any_sliced_multiply(const T* __restrict__ Xg, const T* __restrict__ Fg
                     for (int k = 0; k < VN; ++k) xr[i][k] = T(0);
                 }
             }
+            // The factor chunk goes into LDS transposed.  GATHER: a thread gathers VN consecutive rows p of
+            // one column q (element-sized loads; lanes run along q, so each load instruction reads stretches
+            // of factor rows) and writes them as one 16-byte vector of row q of Fs, free of bank conflicts
+            // (512 x 40x40^3 fp64 0.413 -> 0.373 ms, 1024 x 44x44^3 fp64 1.016 -> 0.901, 128 x 72x72^3 0.490 -> 0.450).
+            // Otherwise it loads a 16-byte vector of one factor row and scatters its elements over VN rows
+            // of Fs with element-sized writes, four to a bank: the gathering form needs more address
+            // registers, and the fp32 kernels of three and four column blocks spill with it (36x36^3 +30 %).
             const T* fsrc = Fg + (int64_t)k0 * Q + q0;   // uniform part of the factor addresses
             if (stage_f)
 #pragma unroll
             for (int i = 0; i < FV; ++i) {
                 const int e = tid + i * ANY_THREADS;
-                const int p = e / FVR, q = (e % FVR) * VN;
-                if (f_aligned && p < kt && q0 + q < Q) fr[i] = *reinterpret_cast<const V*>(fsrc + p * Q + q);
-                else                                     // factor rows that do not start on 16-byte boundaries, padding
+                if constexpr (GATHER) {
+                    const int q = e % QG, p = (e / QG) * VN;
 #pragma unroll
-                    for (int k = 0; k < VN; ++k) fr[i][k] = (p < kt && q0 + q + k < Q) ? fsrc[p * Q + q + k] : T(0);
+                    for (int k = 0; k < VN; ++k) fr[i][k] = (p + k < kt && q0 + q < Q) ? fsrc[(p + k) * Q + q] : T(0);
+                } else {
+                    const int p = e / FVR, q = (e % FVR) * VN;
+                    if (f_aligned && p < kt && q0 + q < Q) fr[i] = *reinterpret_cast<const V*>(fsrc + p * Q + q);
+                    else                                 // factor rows that do not start on 16-byte boundaries, padding
+#pragma unroll
+                        for (int k = 0; k < VN; ++k) fr[i][k] = (p < kt && q0 + q + k < Q) ? fsrc[p * Q + q + k] : T(0);
+                }
             }
             __syncthreads();                             // the previous chunk (or unit) has been read by everybody
 #pragma unroll
@@ -144,10 +158,15 @@ void mfma_any_sliced_multiply(const T* __restrict__ Xg, const T* __restrict__ Fg
 #pragma unroll
             for (int i = 0; i < FV; ++i) {
                 const int e = tid + i * ANY_THREADS;
-                const int p = e / FVR, q = (e % FVR) * VN;
-                if (p < KT)
+                if constexpr (GATHER) {
+                    const int q = e % QG, p = (e / QG) * VN;
+                    if (p < KT) *reinterpret_cast<V*>(Fs + q * ROW + p) = fr[i];     // column q, elements p .. p + VN - 1
+                } else {
+                    const int p = e / FVR, q = (e % FVR) * VN;
+                    if (p < KT)
 #pragma unroll
-                    for (int k = 0; k < VN; ++k) Fs[(q + k) * ROW + p] = fr[i][k];     // transposed: column q, element p
+                        for (int k = 0; k < VN; ++k) Fs[(q + k) * ROW + p] = fr[i][k];     // transposed: column q, element p
+                }
             }
             __syncthreads();
             // 16 chunk elements per trip: lane group g takes elements 4g .. 4g+3 of them, one MFMA step each
