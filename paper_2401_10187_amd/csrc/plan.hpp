@@ -597,11 +597,10 @@ inline km_plan_step build_step(const Problem& pr, const Options& opt, const Vari
 
 // The run-time-shape MFMA kernel takes single factors whose slices start on 16-byte boundaries
 // (P a multiple of 4 floats or 2 doubles).  It pads P and Q to multiples of 16 with zeros, so a factor
-// is given to it only while the padded product stays below a multiple of the real one: 3 in fp32
-// (measured against the generic kernel, 3 factors each: 20x20 4 % faster at 2.56x padding, 36x36 19 %
-// at 1.78x, 40x40 18 %, 52x52 10 %, 100x100 level), 1.5 in fp64, whose MFMA rate is half as far from
-// the generic kernel's multiply-adds (14x14 15 %, 40x40 17 %, 44x44 15 % faster; 20x20 at 2.56x and
-// 24x24 at 1.78x 6 % slower, 50x50 at 1.64x 7 % slower).
+// is given to it only while the padded product is at most 3 times the real one (measured against the
+// generic kernel, 3 factors each: fp32 20x20 4 % faster at 2.56x padding, 36x36 19 % at 1.78x, 40x40
+// 18 %, 52x52 10 %, 100x100 level; fp64 20x20 9 % faster, 36x36 31 %, 34x34 26 %, 84x84 14 %, 50x50 and
+// 22x22 level, 30x30 4 % slower).
 inline bool any_mfma_fits(const Problem& pr, int f, const Options& opt)
 {
     const int P = pr.P[f], Q = pr.Q[f];
@@ -609,7 +608,7 @@ inline bool any_mfma_fits(const Problem& pr, int f, const Options& opt)
     if (!(opt.kernels >> KM_KERNEL_MFMA_ANY & 1) || P % vn) return false;
     const int cols = 16 * any_column_blocks(Q);
     const double padded = (double)((P + 15) / 16 * 16) * (double)((Q + cols - 1) / cols * cols);
-    return padded <= (pr.esize == 4 ? 3.0 : 1.5) * (double)P * (double)Q;
+    return padded <= 3.0 * (double)P * (double)Q;
 }
 
 inline void row_widths(const Problem& pr, std::vector<int64_t>& width)

@@ -186,8 +186,7 @@ def test_tuning_options_round_trip():
 
 
 def test_padded_shapes_go_to_the_run_time_shape_mfma_kernel_within_its_padding_limits():
-    """Slices that start on 16-byte boundaries and a padded product of at most 3x (fp32) or 1.5x (fp64)
-    the real one; everything else without a compiled instance stays with the generic kernel.  The
+    """Slices that start on 16-byte boundaries and a padded product of at most 3x the real one; everything else without a compiled instance stays with the generic kernel.  The
     narrow shape (slices of up to 128 bytes) takes 256 slices per unit, the wide one 128."""
     def kernels(dtype, M, shapes):
         return [(s["kernel"], s["tile_slices"]) for s in km.plan(M, [p for p, _ in shapes], [q for _, q in shapes], dtype)]
@@ -199,7 +198,8 @@ def test_padded_shapes_go_to_the_run_time_shape_mfma_kernel_within_its_padding_l
     assert [k for k, _ in kernels("float32", 4096, [(18, 18)] * 4)] == [gen] * 4   # slices not 16-byte aligned
     assert kernels("float64", 4096, [(14, 14)] * 4) == [(any_, 256)] * 4          # 16*16 / 196 = 1.31
     assert kernels("float64", 4096, [(40, 40)] * 3) == [(any_, 128)] * 3          # 48*48 / 1600 = 1.44
-    assert [k for k, _ in kernels("float64", 4096, [(20, 20)] * 3)] == [gen] * 3   # 2.56 > 1.5
+    assert kernels("float64", 4096, [(20, 20)] * 3) == [(any_, 128)] * 3          # 32*32 / 400 = 2.56
+    assert [k for k, _ in kernels("float64", 4096, [(6, 50)] * 3)] == [gen] * 3    # 16*64 / 300 = 3.4
     assert [k for k, _ in kernels("float64", 4096, [(15, 16)] * 4)] == [gen] * 4   # odd P
 
 
