@@ -5,17 +5,18 @@
 
 namespace km {
 
-template <typename T, int CB, bool NARROW, bool KEEP>
+template <typename T, int CB, bool NARROW, bool KEEP, bool FLAT>
 static hipError_t launch_mfma_any_shape(const LaunchArgs& a, int64_t slices)
 {
     typedef AnyShape<T, CB, NARROW> Sh;
     const km_plan_step& st = *a.st;
     const int f = st.first_factor;
-    auto kern = mfma_any_sliced_multiply<T, CB, NARROW, KEEP>;
+    auto kern = mfma_any_sliced_multiply<T, CB, NARROW, KEEP, FLAT>;
     static unsigned char lds_ok[64];
     hipError_t e = allow_lds((const void*)kern, Sh::LDS_BYTES, lds_ok);
     if (e != hipSuccess || a.prepare_only) return e;
     const int Q = a.pr->Q[f];
+    if (FLAT ? a.pr->P[f] > Sh::KT : a.pr->P[f] % Sh::VN != 0) return hipErrorInvalidValue;
     const int64_t units = ((slices + Sh::TS - 1) / Sh::TS) * ((Q + Sh::QG - 1) / Sh::QG);
     if (st.lds_bytes != Sh::LDS_BYTES || st.tile_slices != Sh::TS || st.grid < 1 || st.grid > units) return hipErrorInvalidValue;
     hipLaunchKernelGGL(kern, dim3((unsigned)st.grid), dim3(ANY_THREADS), Sh::LDS_BYTES, a.stream,
@@ -33,11 +34,16 @@ static hipError_t launch_mfma_any_cb(const LaunchArgs& a, int64_t slices)
     // boundaries would reach memory as partial lines if they bypassed the cache: ordinary stores
     // (measured: 1024 x 30x30^3 fp64 0.417 -> 0.348 ms, 8192 x 20x15^3 0.302 -> 0.237)
     const bool keep = a.keep_output || (a.st->k_in / a.pr->P[a.st->first_factor]) * (int64_t)sizeof(T) % 64 != 0;
+    // slices that do not start on 16-byte boundaries: the form that fetches a unit as one contiguous run
+    const bool flat = a.pr->P[a.st->first_factor] % (16 / (int)sizeof(T)) != 0;
     hipError_t e = hipSuccess;
-    for (int k = 0; k < 2 && e == hipSuccess; ++k) {
-        if (!a.prepare_only && (k == 1) != keep) continue;     // preparing takes both store forms
-        if (narrow) e = k ? launch_mfma_any_shape<T, CB, true, true>(a, slices) : launch_mfma_any_shape<T, CB, true, false>(a, slices);
-        else e = k ? launch_mfma_any_shape<T, CB, false, true>(a, slices) : launch_mfma_any_shape<T, CB, false, false>(a, slices);
+    for (int k = 0; k < 4 && e == hipSuccess; ++k) {
+        const bool kp = (k & 1) != 0, fl = (k >> 1) != 0;
+        if (!a.prepare_only && (kp != keep || fl != flat)) continue;     // preparing takes every form
+        if (narrow) e = fl ? (kp ? launch_mfma_any_shape<T, CB, true, true, true>(a, slices) : launch_mfma_any_shape<T, CB, true, false, true>(a, slices))
+                           : (kp ? launch_mfma_any_shape<T, CB, true, true, false>(a, slices) : launch_mfma_any_shape<T, CB, true, false, false>(a, slices));
+        else e = fl ? (kp ? launch_mfma_any_shape<T, CB, false, true, true>(a, slices) : launch_mfma_any_shape<T, CB, false, false, true>(a, slices))
+                    : (kp ? launch_mfma_any_shape<T, CB, false, true, false>(a, slices) : launch_mfma_any_shape<T, CB, false, false, false>(a, slices));
     }
     return e;
 }
@@ -48,7 +54,7 @@ hipError_t launch_mfma_any(const LaunchArgs& a)
     const km_plan_step& st = *a.st;
     const int f = st.first_factor;
     const int P = a.pr->P[f], Q = a.pr->Q[f];
-    if (st.num_factors != 1 || P % (16 / (int)sizeof(T)) || st.k_in % P || st.block != ANY_THREADS) return hipErrorInvalidValue;
+    if (st.num_factors != 1 || st.k_in % P || st.block != ANY_THREADS) return hipErrorInvalidValue;
     const int64_t slices = a.pr->M * (st.k_in / P);      // counted through all rows
     const int cb = any_column_blocks(Q);
     switch (cb) {

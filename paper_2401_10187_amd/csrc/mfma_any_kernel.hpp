@@ -1,6 +1,6 @@
 // One sliced-multiply iteration on the matrix cores for a factor of any shape whose slices start on
 // 16-byte boundaries (P a multiple of 4 floats or 2 doubles; run-time shapes: 20, 48, 80, 96, 100, ...
-// and rectangles), fp32 and fp64.  P and Q are padded with zeros to multiples of 16 on the way into LDS.
+// and rectangles) or are at most one chunk long (FLAT below: 13, 22, 33, 50, ...), fp32 and fp64.  P and Q are padded with zeros to multiples of 16 on the way into LDS.
 //
 // The contraction of a slice with the factor (Algorithm 1's inner loop) is the dense product
 //     D[q][s] = sum_p F[p][q] * X[s*P + p]
@@ -62,7 +62,11 @@ struct AnyShape {
 
 // (the second launch bound, wavefronts per SIMD, caps the registers: left alone the compiler spends
 // several hundred of them on scheduling freedom and one workgroup fills a compute unit)
-template <typename T, int CB, bool NARROW, bool KEEP>
+// FLAT: for slices that do not start on 16-byte boundaries (P not a whole number of vectors) and fit
+// one chunk (P <= KT).  The TS slices of a unit are contiguous in memory and the unit starts on a
+// 16-byte boundary (TS * P elements per unit), so the unit is fetched as one run of 16-byte vectors and
+// the elements are dealt to their LDS rows one by one (consecutive elements, consecutive banks).
+template <typename T, int CB, bool NARROW, bool KEEP, bool FLAT>
 __global__ __launch_bounds__(ANY_THREADS, (CB >= 5 || (NARROW && sizeof(T) == 8 && CB >= 3) ? 2 : 3))
 void mfma_any_sliced_multiply(const T* __restrict__ Xg, const T* __restrict__ Fg, T* __restrict__ Yg,
                               int64_t K, int P, int Q, int64_t num_slices, int64_t num_units, int f_aligned)
@@ -92,6 +96,13 @@ void mfma_any_sliced_multiply(const T* __restrict__ Xg, const T* __restrict__ Fg
     // 36x36^3), and a whole factor of several chunks in rows of run-time length, 3-5 % only).
     const bool f_stays = q_groups == 1 && P <= KT;
 
+    if constexpr (FLAT) {
+        // elements P .. KT - 1 of every LDS row are read by the products (up to the next multiple of 16)
+        // and never written by the unit loop: zeros, once
+        const int pad = KT - P;
+        for (int e = tid; e < TS * pad; e += ANY_THREADS) Xs[(e / pad) * ROW + P + e % pad] = T(0);
+    }
+
     for (int64_t unit = blockIdx.x; unit < num_units; unit += gridDim.x) {
         const bool stage_f = !f_stays || unit == blockIdx.x;
         int64_t tile;
@@ -116,6 +127,22 @@ void mfma_any_sliced_multiply(const T* __restrict__ Xg, const T* __restrict__ Fg
             // groups they stay for the neighbouring units.
             V xr[XV], fr[FV];
             const T* xsrc = Xg + g0 * P + k0;            // uniform part of the slice addresses
+            if constexpr (FLAT) {
+                // vector v of the unit's TS * P contiguous elements; the last unit may hold fewer slices
+                const int64_t left = (num_slices - g0) * P;
+                const int valid = left < (int64_t)TS * P ? (int)left : TS * P;
+#pragma unroll
+                for (int i = 0; i < XV; ++i) {
+                    const int e0 = (tid + i * ANY_THREADS) * VN;
+                    if (e0 + VN <= valid) {
+                        const V* src = reinterpret_cast<const V*>(xsrc + e0);
+                        xr[i] = q_groups == 1 ? stream_load(src) : *src;
+                    } else {
+#pragma unroll
+                        for (int k = 0; k < VN; ++k) xr[i][k] = e0 + k < valid ? xsrc[e0 + k] : T(0);
+                    }
+                }
+            } else {
 #pragma unroll
             for (int i = 0; i < XV; ++i) {
                 const int row = xrow + RP * i;
@@ -126,6 +153,7 @@ void mfma_any_sliced_multiply(const T* __restrict__ Xg, const T* __restrict__ Fg
 #pragma unroll
                     for (int k = 0; k < VN; ++k) xr[i][k] = T(0);
                 }
+            }
             }
             // The factor chunk goes into LDS transposed.  GATHER: a thread gathers VN consecutive rows p of
             // one column q (element-sized loads; lanes run along q, so each load instruction reads stretches
@@ -152,8 +180,23 @@ void mfma_any_sliced_multiply(const T* __restrict__ Xg, const T* __restrict__ Fg
                 }
             }
             __syncthreads();                             // the previous chunk (or unit) has been read by everybody
+            if constexpr (FLAT) {
 #pragma unroll
-            for (int i = 0; i < XV; ++i) *reinterpret_cast<V*>(Xs + (xrow + RP * i) * ROW + xcol) = xr[i];
+                for (int i = 0; i < XV; ++i) {
+                    const int e0 = (tid + i * ANY_THREADS) * VN;
+                    if (e0 < TS * P) {
+                        int row = e0 / P, col = e0 - row * P;
+#pragma unroll
+                        for (int k = 0; k < VN; ++k) {
+                            Xs[row * ROW + col] = xr[i][k];
+                            if (++col == P) { col = 0; ++row; }
+                        }
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < XV; ++i) *reinterpret_cast<V*>(Xs + (xrow + RP * i) * ROW + xcol) = xr[i];
+            }
             if (stage_f)
 #pragma unroll
             for (int i = 0; i < FV; ++i) {

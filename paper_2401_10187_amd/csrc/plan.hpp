@@ -596,7 +596,7 @@ inline km_plan_step build_step(const Problem& pr, const Options& opt, const Vari
 }
 
 // The run-time-shape MFMA kernel takes single factors whose slices start on 16-byte boundaries
-// (P a multiple of 4 floats or 2 doubles).  It pads P and Q to multiples of 16 with zeros, so a factor
+// (P a multiple of 4 floats or 2 doubles) or are at most 256 bytes long.  It pads P and Q to multiples of 16 with zeros, so a factor
 // is given to it only while the padded product is at most 3 times the real one (measured against the
 // generic kernel, 3 factors each: fp32 20x20 4 % faster at 2.56x padding, 36x36 19 % at 1.78x, 40x40
 // 18 %, 52x52 10 %, 100x100 level; fp64 20x20 9 % faster, 36x36 31 %, 34x34 26 %, 84x84 14 %, 50x50 and
@@ -605,7 +605,10 @@ inline bool any_mfma_fits(const Problem& pr, int f, const Options& opt)
 {
     const int P = pr.P[f], Q = pr.Q[f];
     const int vn = 16 / (int)pr.esize;
-    if (!(opt.kernels >> KM_KERNEL_MFMA_ANY & 1) || P % vn) return false;
+    if (!(opt.kernels >> KM_KERNEL_MFMA_ANY & 1)) return false;
+    // slices that do not start on 16-byte boundaries are fetched as one contiguous run per unit, which
+    // needs the whole slice in one LDS chunk (256 bytes)
+    if (P % vn && (size_t)P * pr.esize > 256) return false;
     const int cols = 16 * any_column_blocks(Q);
     const double padded = (double)((P + 15) / 16 * 16) * (double)((Q + cols - 1) / cols * cols);
     return padded <= 3.0 * (double)P * (double)Q;

@@ -177,6 +177,17 @@ SMALL_CASES = [
     ("float64", 5, [(30, 30)] * 2),
     ("float64", 3, [(16, 48), (44, 41)]),
     ("float64", 129, [(90, 90)]),
+    # ... and on slices that do not start on 16-byte boundaries (a unit fetched as one contiguous run):
+    # odd P, P = 2 mod 4, narrow and wide units, ragged last unit, more slices than one unit per row
+    ("float32", 3, [(13, 13)] * 4),
+    ("float32", 5, [(22, 22)] * 3),
+    ("float32", 2, [(33, 40), (50, 33)]),
+    ("float32", 700, [(19, 19)]),
+    ("float32", 1, [(63, 63)] * 2),
+    ("float64", 3, [(15, 15)] * 3),
+    ("float64", 2, [(27, 27)] * 2),
+    ("float64", 301, [(31, 20)]),
+    ("float64", 4, [(11, 11)] * 4),
     # neighbouring runs of different small shapes fused into one launch
     ("float32", 5, [(4, 4)] * 5 + [(2, 2)] * 4),
     ("float32", 3, [(3, 3)] + [(4, 4)] * 2 + [(2, 2)] * 4),
@@ -209,6 +220,7 @@ def test_small_integer_bit_exact(dtype, M, shapes):
 
 @pytest.mark.parametrize("dtype,M,shapes", [("float32", 5, [(48, 80), (96, 48)]), ("float64", 3, [(48, 48)] * 2),
                                             ("float32", 3, [(20, 20)] * 2), ("float64", 2, [(14, 40), (40, 14)]),
+                                            ("float32", 3, [(13, 13)] * 4), ("float64", 2, [(15, 22), (27, 15)]),
                                             ("float32", 4, [(8, 8)] * 3), ("float32", 3, [(32, 32)] * 3),
                                             ("float64", 2, [(5, 3), (16, 16), (7, 9)])],
                          ids=lambda v: str(v).replace(" ", ""))
