@@ -786,6 +786,41 @@ def test_rows_beyond_32_bit_offsets_use_the_generic_kernel_and_stay_exact():
     km.release()
 
 
+def test_rows_beyond_32_bit_offsets_on_the_run_time_shape_mfma_kernel():
+    """One row of 16^8 floats (16 GiB): the compiled 16x16 instances address inside a row with 32-bit
+    offsets and are not planned, the run-time-shape MFMA kernel (64-bit indexing, slices counted
+    through all rows) takes every factor.  Cyclic-shift factors make Y an exactly known column
+    permutation of X, checked bit for bit on sampled columns, among them the ones around 2^31 and 2^32
+    bytes."""
+    n, P = 8, 16
+    steps = km.plan(1, [P] * n, [P] * n, "float32")
+    assert all(st["kernel"] == km.KM_KERNEL_MFMA_ANY for st in steps)
+    K = P ** n
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(4321)
+    Xd = torch.rand((1, K), dtype=torch.float32, device="cuda", generator=gen)
+    F = np.zeros((P, P), dtype=np.float32)
+    F[np.arange(P), (np.arange(P) + 1) % P] = 1
+    Fd = [torch.from_numpy(F).cuda() for _ in range(n)]
+    Y = km.kronmatmul(Xd, Fd)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(98)
+    special = [0, 1, K - 1, K - 2, K // 2, 2 ** 31 // 4 - 1, 2 ** 31 // 4, 2 ** 32 // 4 - 1, 2 ** 32 // 4, 2 ** 32 // 4 + 1]
+    cols = np.unique(np.concatenate([rng.integers(0, K, 200000), special])).astype(np.int64)
+    src = np.zeros_like(cols)
+    rem = cols.copy()
+    for i in range(n):                       # peel digits from the fastest
+        q = rem % P
+        rem //= P
+        src += ((q - 1) % P) * P ** i
+    got = Y[0, torch.from_numpy(cols).cuda()].cpu().numpy()
+    want = Xd[0, torch.from_numpy(src).cuda()].cpu().numpy()
+    assert np.array_equal(got, want)
+    del Y, Xd
+    torch.cuda.empty_cache()
+    km.release()
+
+
 @pytest.mark.parametrize("dtype,M,shapes", [
     ("float32", 4099, [(4, 4)] * 4),          # ragged last tile
     ("float32", 2048, [(2, 2)] * 8),
