@@ -503,6 +503,10 @@ inline double launch_cost(const Problem& pr, int64_t k_in, int64_t k_out, const 
     // takes about 2 us + 0.7 us per chunk even when it moves next to nothing (measured: 5.5 us for
     // P = 65, 4.8 us for P = 52 on ten rows)
     if (!ch.var && !ch.any_mfma) fixed += 1.0e7 + 3.5e6 * (double)((generic_P + 15) / 16);
+    // a launch of the run-time-shape MFMA kernel that moves next to nothing takes 6-8 us (measured on the
+    // paper's Table 4 sizes: two such launches 12.5 us for 50 x (32x8, 64x128), 15.4 us for 10 x (52x65,
+    // 50x20), where the whole-row kernel takes 17 and 13.4)
+    if (ch.any_mfma) fixed += 1.25e7;
     return bytes * slow + fixed;
 }
 
