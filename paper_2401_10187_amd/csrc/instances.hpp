@@ -73,11 +73,16 @@
     Y(MfmaF32x16, KM_F32, 80, 80, 1, 64, 10, 5)         \
     Y(MfmaF32x16, KM_F32, 112, 112, 1, 64, 7, 7)        \
     Y(MfmaF32x16, KM_F32, 144, 144, 1, 64, 9, 9)        \
+    Y(MfmaF32x16, KM_F32, 160, 160, 1, 64, 10, 10)      \
+    Y(MfmaF32x16, KM_F32, 192, 192, 1, 64, 12, 12)      \
+    Y(MfmaF32x16, KM_F32, 256, 256, 1, 64, 16, 16)      \
     Y(MfmaF64x16, KM_F64, 48, 48, 1, 64, 4, 1)          \
     Y(MfmaF64x16, KM_F64, 80, 80, 1, 64, 10, 5)         \
     Y(MfmaF64x16, KM_F64, 96, 96, 1, 64, 6, 6)          \
     Y(MfmaF64x16, KM_F64, 112, 112, 1, 64, 7, 7)        \
     Y(MfmaF64x16, KM_F64, 144, 144, 1, 64, 9, 9)        \
+    Y(MfmaF64x16, KM_F64, 160, 160, 1, 64, 10, 10)      \
+    Y(MfmaF64x16, KM_F64, 192, 192, 1, 64, 12, 12)      \
     Y(MfmaF64x16, KM_F64, 32, 16, 1, 128, 4, 1)         \
     Y(MfmaF64x16, KM_F64, 16, 32, 1, 128, 4, 1)         \
     Y(MfmaF64x16, KM_F64, 64, 32, 1, 64, 4, 1)          \

@@ -28,7 +28,7 @@ namespace km {
      sizeof(T) == 8 ? 8192 : 0},   /* fp64: 10-20 % faster than the several-factors-per-pass kernel up to 4096 slices per row, 10 % slower at 32768 */
 #define KM_MFMA_ROW(OP, DT, P, Q, NF, ST, NW, QS) \
     {KM_KERNEL_MFMA, DT, P, Q, NF, ST, NW * 64, MfmaShape<OP, P, Q, NF, ST, NW, QS>::LDS_BYTES, 1, 1, 0, 1.0f, "mfma", \
-     0, 0, 0, 0, (P == 80 || P == 96 || P == 112 || P == 144) ? -1 : 0 /* walk: one round of resident workgroups */},
+     0, 0, 0, 0, (P == 80 || P == 96 || P == 112 || P >= 144) ? -1 : 0 /* walk: one round of resident workgroups */},
 /* One workgroup per compute unit with the whole output tile staged at once (NPASS == 1): 7-12 % faster
    than two 4-wave workgroups where output rows lie up to 8 KB apart and every compute unit gets 8 tiles
    and more (1024 x 32x32^4: 1.75 -> 1.54 ms per launch); 15 % slower on rows of 32^5 elements (128 KB

@@ -377,6 +377,8 @@ EVERY_INSTANCE = [
     ("float32", 8, [(48, 48)] * 3), ("float64", 4, [(48, 48)] * 3),
     ("float32", 2, [(96, 96)] * 3), ("float32", 2, [(80, 80)] * 3), ("float32", 2, [(112, 112)] * 3), ("float32", 1, [(144, 144)] * 3),
     ("float64", 2, [(80, 80)] * 3), ("float64", 1, [(96, 96)] * 3), ("float64", 1, [(112, 112)] * 3), ("float64", 1, [(144, 144)] * 3),
+    ("float32", 1, [(160, 160)] * 3), ("float32", 1, [(192, 192)] * 3), ("float32", 1, [(256, 256)] * 3),
+    ("float64", 1, [(160, 160)] * 3), ("float64", 1, [(192, 192)] * 3),
     ("float32", 2, [(2, 2)] * 14), ("float64", 2, [(2, 2)] * 13),
     ("float32", 3, [(3, 3)] * 9), ("float64", 3, [(3, 3)] * 9),
     ("float32", 4, [(4, 4)] * 8), ("float64", 4, [(4, 4)] * 7),
