@@ -25,7 +25,9 @@ namespace km {
 // ---------------------------------------------------------------------------------------------
 #define KM_FUSED_ROW(T, DT, P, Q, NF, ST, NT) \
     {KM_KERNEL_FUSED, DT, P, Q, NF, ST, NT, FusedShape<T, P, Q, NF, ST, NT>::LDS_BYTES, 1, 0, 0, 1.0f, "fused", 0, 0, \
-     sizeof(T) == 8 ? 8192 : 0},   /* fp64: 10-20 % faster than the several-factors-per-pass kernel up to 4096 slices per row, 10 % slower at 32768 */
+     sizeof(T) == 8 ? 8192 : 0,    /* fp64: 10-20 % faster than the several-factors-per-pass kernel up to 4096 slices per row, 10 % slower at 32768 */ \
+     NT == 1024 ? 8192 : 0},       /* 1024-thread workgroups only from 8192 tiles up: below, the 256-thread instance of the same tile is \
+                                      2-5 % faster (128 x 8x8^6 0.110 vs 0.104 ms), above 1-2 % slower (2048 x 8x8^6 1.426 vs 1.454) */
 #define KM_MFMA_ROW(OP, DT, P, Q, NF, ST, NW, QS) \
     {KM_KERNEL_MFMA, DT, P, Q, NF, ST, NW * 64, MfmaShape<OP, P, Q, NF, ST, NW, QS>::LDS_BYTES, 1, 1, 0, 1.0f, "mfma", \
      0, 0, 0, 0, (P == 80 || P == 96 || P == 112 || P >= 144) ? -1 : 0 /* walk: one round of resident workgroups */},
