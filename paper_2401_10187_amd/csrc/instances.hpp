@@ -123,6 +123,7 @@
     W(float, KM_F32, 3, 3, 2, 1, 0, 243, 256)           \
     W(float, KM_F32, 3, 3, 2, 0, 0, 729, 256)           \
     W(float, KM_F32, 3, 3, 1, 0, 0, 2187, 256)          \
+    W(float, KM_F32, 5, 5, 2, 2, 0, 25, 256)            \
     W(float, KM_F32, 5, 5, 2, 1, 0, 125, 256)           \
     W(float, KM_F32, 5, 5, 2, 0, 0, 625, 256)           \
     W(float, KM_F32, 5, 5, 1, 0, 0, 3125, 256)          \

@@ -278,7 +278,9 @@ def test_tile_lengths_for_small_problems_and_odd_rows():
     finally:
         km.set_option(km.KM_OPT_KERNELS, old)
     first = km.plan(1024, [5] * 8, [5] * 8, "float32")[0]
-    assert first["num_factors"] == 3 and first["tile_slices"] == 25       # 100-byte runs, 12 KB tiles
+    assert first["num_factors"] == 4 and first["tile_slices"] == 25       # 100-byte runs, 62 KB tiles, two launches of four factors
+    first = km.plan(1024, [5] * 7, [5] * 7, "float64")[0]
+    assert first["num_factors"] == 3 and first["tile_slices"] == 25       # 200-byte runs, 25 KB tiles
     assert all(st["tile_rows"] == 1 for st in km.plan(1024, [3] * 7, [3] * 7, "float32"))
     assert all(st["tile_rows"] == 2 for st in km.plan(1526, [4] * 6, [4] * 6, "float32"))
     assert km.plan(1 << 20, [4] * 4, [4] * 4, "float32")[0]["tile_rows"] > 8
