@@ -15,6 +15,10 @@ namespace km {
 #define KM_W_F32_P9 KM_SKIP
 #define KM_W_F32_P10 KM_SKIP
 #define KM_W_F32_P12 KM_SKIP
+#define KM_W_F32_P11 KM_SKIP
+#define KM_W_F32_P13 KM_SKIP
+#define KM_W_F32_P14 KM_SKIP
+#define KM_W_F32_P15 KM_SKIP
 #define KM_W_KM_F32(T, P, Q, G0, G1, G2, ST, NT) KM_W_F32_P##P(T, P, Q, G0, G1, G2, ST, NT)
 #define KM_W_KM_F64(...)
 #define KM_W(T, DT, P, Q, G0, G1, G2, ST, NT) KM_W_##DT(T, P, Q, G0, G1, G2, ST, NT)

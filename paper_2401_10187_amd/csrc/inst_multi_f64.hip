@@ -1,9 +1,25 @@
-// Compiled instances: several small factors per LDS pass, fp64.
+// Compiled instances: several small factors per LDS pass, fp64, factors with P of 2, 3 and 4.
 #include "launch_multi.hpp"
 #include "instances.hpp"
 
 namespace km {
-#define KM_W_KM_F64(T, P, Q, G0, G1, G2, ST, NT) template hipError_t launch_multi<MultiShape<T, P, Q, G0, G1, G2, ST, NT>>(const LaunchArgs&);
+#define KM_INST(T, P, Q, G0, G1, G2, ST, NT) template hipError_t launch_multi<MultiShape<T, P, Q, G0, G1, G2, ST, NT>>(const LaunchArgs&);
+#define KM_SKIP(...)
+#define KM_W_F64_P2 KM_INST
+#define KM_W_F64_P3 KM_INST
+#define KM_W_F64_P4 KM_INST
+#define KM_W_F64_P5 KM_SKIP
+#define KM_W_F64_P6 KM_SKIP
+#define KM_W_F64_P7 KM_SKIP
+#define KM_W_F64_P8 KM_SKIP
+#define KM_W_F64_P9 KM_SKIP
+#define KM_W_F64_P10 KM_SKIP
+#define KM_W_F64_P11 KM_SKIP
+#define KM_W_F64_P12 KM_SKIP
+#define KM_W_F64_P13 KM_SKIP
+#define KM_W_F64_P14 KM_SKIP
+#define KM_W_F64_P15 KM_SKIP
+#define KM_W_KM_F64(T, P, Q, G0, G1, G2, ST, NT) KM_W_F64_P##P(T, P, Q, G0, G1, G2, ST, NT)
 #define KM_W_KM_F32(...)
 #define KM_W(T, DT, P, Q, G0, G1, G2, ST, NT) KM_W_##DT(T, P, Q, G0, G1, G2, ST, NT)
 #define KM_NONE(...)

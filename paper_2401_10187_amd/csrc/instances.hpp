@@ -178,6 +178,22 @@
     W(float, KM_F32, 10, 10, 1, 0, 0, 1000, 256)        \
     W(float, KM_F32, 12, 12, 1, 1, 0, 72, 256)          \
     W(float, KM_F32, 12, 12, 1, 0, 0, 864, 256)         \
+    W(float, KM_F32, 11, 11, 1, 1, 0, 100, 256)         \
+    W(float, KM_F32, 11, 11, 1, 0, 0, 1000, 256)        \
+    W(float, KM_F32, 13, 13, 1, 1, 0, 64, 256)          \
+    W(float, KM_F32, 13, 13, 1, 0, 0, 832, 256)         \
+    W(float, KM_F32, 14, 14, 1, 1, 0, 64, 256)          \
+    W(float, KM_F32, 14, 14, 1, 0, 0, 832, 256)         \
+    W(float, KM_F32, 15, 15, 1, 1, 0, 64, 256)          \
+    W(float, KM_F32, 15, 15, 1, 0, 0, 800, 256)         \
+    W(double, KM_F64, 11, 11, 1, 1, 0, 50, 256)         \
+    W(double, KM_F64, 11, 11, 1, 0, 0, 500, 256)        \
+    W(double, KM_F64, 13, 13, 1, 1, 0, 32, 256)         \
+    W(double, KM_F64, 13, 13, 1, 0, 0, 416, 256)        \
+    W(double, KM_F64, 14, 14, 1, 1, 0, 32, 256)         \
+    W(double, KM_F64, 14, 14, 1, 0, 0, 416, 256)        \
+    W(double, KM_F64, 15, 15, 1, 1, 0, 32, 256)         \
+    W(double, KM_F64, 15, 15, 1, 0, 0, 400, 256)        \
     W(double, KM_F64, 7, 7, 2, 1, 0, 16, 256)           \
     W(double, KM_F64, 7, 7, 2, 0, 0, 128, 256)          \
     W(double, KM_F64, 7, 7, 1, 0, 0, 1024, 256)         \

@@ -388,6 +388,8 @@ EVERY_INSTANCE = [
     ("float32", 2, [(9, 9)] * 5), ("float64", 2, [(9, 9)] * 4),
     ("float32", 2, [(10, 10)] * 5), ("float64", 2, [(10, 10)] * 4),
     ("float32", 2, [(12, 12)] * 4), ("float64", 2, [(12, 12)] * 4),
+    ("float32", 3, [(11, 11)] * 4), ("float64", 3, [(11, 11)] * 4), ("float32", 3, [(13, 13)] * 4), ("float64", 3, [(13, 13)] * 4),
+    ("float32", 2, [(14, 14)] * 4), ("float64", 2, [(14, 14)] * 4), ("float32", 2, [(15, 15)] * 4), ("float64", 2, [(15, 15)] * 4),
     # short rows, for the instances with short tiles
     ("float32", 16, [(8, 8)] * 3), ("float32", 5, [(8, 8)] * 4), ("float32", 3, [(8, 8)] * 2), ("float32", 2, [(8, 8)]),
     ("float32", 6, [(32, 32)] * 2), ("float32", 8, [(16, 32)] * 3), ("float32", 5, [(16, 16)] * 2),

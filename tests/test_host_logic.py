@@ -198,7 +198,8 @@ def test_padded_shapes_go_to_the_run_time_shape_mfma_kernel_within_its_padding_l
     assert [k for k, _ in kernels("float32", 4096, [(20, 7)] * 4)] == [gen] * 4    # 32*16 / 140 = 3.7
     assert kernels("float32", 4096, [(22, 22)] * 4) == [(any_, 256)] * 4          # slices not 16-byte aligned, but one chunk
     assert [k for k, _ in kernels("float32", 4096, [(66, 66)] * 3)] == [gen] * 3   # ... and longer than a chunk (264 bytes)
-    assert kernels("float64", 4096, [(14, 14)] * 4) == [(any_, 256)] * 4          # 16*16 / 196 = 1.31
+    assert kernels("float64", 4096, [(16, 20)] * 4) == [(any_, 256)] * 4          # 16*32 / 320 = 1.6, 128-byte slices
+    assert kernels("float64", 4096, [(26, 26)] * 3) == [(any_, 128)] * 3          # 32*32 / 676 = 1.5
     assert kernels("float64", 4096, [(40, 40)] * 3) == [(any_, 128)] * 3          # 48*48 / 1600 = 1.44
     assert kernels("float64", 4096, [(20, 20)] * 3) == [(any_, 128)] * 3          # 32*32 / 400 = 2.56
     assert [k for k, _ in kernels("float64", 4096, [(6, 50)] * 3)] == [gen] * 3    # 16*64 / 300 = 3.4
