@@ -142,6 +142,7 @@
     W(double, KM_F64, 2, 2, 4, 0, 0, 512, 256)          \
     W(double, KM_F64, 2, 2, 3, 0, 0, 1024, 256)         \
     W(double, KM_F64, 2, 2, 1, 0, 0, 4096, 256)         \
+    W(double, KM_F64, 4, 4, 3, 2, 2, 1, 512)            \
     W(double, KM_F64, 4, 4, 2, 2, 2, 2, 256)            \
     W(double, KM_F64, 4, 4, 2, 2, 1, 8, 256)            \
     W(double, KM_F64, 4, 4, 2, 2, 0, 32, 256)           \

@@ -116,6 +116,7 @@ SMALL_CASES = [
     ("float32", 4, [(2, 2)] * 12),
     ("float64", 2, [(2, 2)] * 10),
     ("float64", 3, [(4, 4)] * 5),
+    ("float64", 5, [(4, 4)] * 7),
     ("float64", 2, [(8, 8)] * 4),
     ("float32", 7, [(4, 4), (4, 4), (2, 2), (2, 2), (2, 2), (3, 3)]),
     ("float64", 3, [(3, 3)] * 8),
@@ -381,7 +382,7 @@ EVERY_INSTANCE = [
     ("float64", 1, [(160, 160)] * 3), ("float64", 1, [(192, 192)] * 3),
     ("float32", 2, [(2, 2)] * 14), ("float64", 2, [(2, 2)] * 13),
     ("float32", 3, [(3, 3)] * 9), ("float64", 3, [(3, 3)] * 9),
-    ("float32", 4, [(4, 4)] * 8), ("float64", 4, [(4, 4)] * 7),
+    ("float32", 4, [(4, 4)] * 8), ("float64", 4, [(4, 4)] * 7), ("float64", 64, [(4, 4)] * 7),
     ("float32", 2, [(5, 5)] * 6), ("float64", 2, [(5, 5)] * 6), ("float32", 300, [(5, 5)] * 6),
     ("float32", 2, [(6, 6)] * 6), ("float64", 2, [(6, 6)] * 6),
     ("float32", 2, [(7, 7)] * 5), ("float64", 2, [(7, 7)] * 5),
