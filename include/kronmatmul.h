@@ -60,7 +60,7 @@ typedef enum {
     KM_KERNEL_SHUFFLE = 3,  /* one 8x8 fp32 factor, no LDS: P-reduction by wavefront lane exchanges */
     KM_KERNEL_ROWS = 4,     /* every factor of a short row in one launch, any shapes: the row and its
                                intermediates stay in LDS (section 4.2's fusion with the row as tile) */
-    KM_KERNEL_MFMA_ANY = 5  /* one factor of run-time shape on MFMA (slices 16-byte aligned or <= 256 bytes; zero-padded to 16s) */
+    KM_KERNEL_MFMA_ANY = 5  /* one factor of run-time shape on MFMA (zero-padded to 16s; slices of any alignment) */
 } km_kernel;
 
 /* Buffers a plan step reads or writes. */

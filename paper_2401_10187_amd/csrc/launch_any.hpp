@@ -5,7 +5,7 @@
 
 namespace km {
 
-template <typename T, int CB, bool NARROW, bool KEEP, bool FLAT>
+template <typename T, int CB, bool NARROW, bool KEEP, int FLAT>
 static hipError_t launch_mfma_any_shape(const LaunchArgs& a, int64_t slices)
 {
     typedef AnyShape<T, CB, NARROW> Sh;
@@ -16,7 +16,7 @@ static hipError_t launch_mfma_any_shape(const LaunchArgs& a, int64_t slices)
     hipError_t e = allow_lds((const void*)kern, Sh::LDS_BYTES, lds_ok);
     if (e != hipSuccess || a.prepare_only) return e;
     const int Q = a.pr->Q[f];
-    if (FLAT ? a.pr->P[f] > Sh::KT : a.pr->P[f] % Sh::VN != 0) return hipErrorInvalidValue;
+    if (FLAT == 0 ? a.pr->P[f] % Sh::VN != 0 : (FLAT == 1 && a.pr->P[f] > Sh::KT)) return hipErrorInvalidValue;
     const int64_t units = ((slices + Sh::TS - 1) / Sh::TS) * ((Q + Sh::QG - 1) / Sh::QG);
     if (st.lds_bytes != Sh::LDS_BYTES || st.tile_slices != Sh::TS || st.grid < 1 || st.grid > units) return hipErrorInvalidValue;
     hipLaunchKernelGGL(kern, dim3((unsigned)st.grid), dim3(ANY_THREADS), Sh::LDS_BYTES, a.stream,
@@ -35,15 +35,23 @@ static hipError_t launch_mfma_any_cb(const LaunchArgs& a, int64_t slices)
     // (measured: 1024 x 30x30^3 fp64 0.417 -> 0.348 ms, 8192 x 20x15^3 0.302 -> 0.237)
     const bool keep = a.keep_output || (a.st->k_in / a.pr->P[a.st->first_factor]) * (int64_t)sizeof(T) % 64 != 0;
     // slices that do not start on 16-byte boundaries: the form that fetches a unit as one contiguous run
-    const bool flat = a.pr->P[a.st->first_factor] % (16 / (int)sizeof(T)) != 0;
+    // when a slice is one chunk, the form of skewed chunk rows otherwise
+    const int P = a.pr->P[a.st->first_factor];
+    const int flat = P % (16 / (int)sizeof(T)) == 0 ? 0 : ((size_t)P * sizeof(T) <= (size_t)ANY_ROW_BYTES ? 1 : 2);
     hipError_t e = hipSuccess;
-    for (int k = 0; k < 4 && e == hipSuccess; ++k) {
-        const bool kp = (k & 1) != 0, fl = (k >> 1) != 0;
+    for (int k = 0; k < 6 && e == hipSuccess; ++k) {
+        const bool kp = (k & 1) != 0;
+        const int fl = k >> 1;
         if (!a.prepare_only && (kp != keep || fl != flat)) continue;     // preparing takes every form
-        if (narrow) e = fl ? (kp ? launch_mfma_any_shape<T, CB, true, true, true>(a, slices) : launch_mfma_any_shape<T, CB, true, false, true>(a, slices))
-                           : (kp ? launch_mfma_any_shape<T, CB, true, true, false>(a, slices) : launch_mfma_any_shape<T, CB, true, false, false>(a, slices));
-        else e = fl ? (kp ? launch_mfma_any_shape<T, CB, false, true, true>(a, slices) : launch_mfma_any_shape<T, CB, false, false, true>(a, slices))
-                    : (kp ? launch_mfma_any_shape<T, CB, false, true, false>(a, slices) : launch_mfma_any_shape<T, CB, false, false, false>(a, slices));
+        if (narrow) {
+            if (fl == 2) continue;                                       // (no skewed form of the narrow shape: its slices are one chunk)
+            e = fl ? (kp ? launch_mfma_any_shape<T, CB, true, true, 1>(a, slices) : launch_mfma_any_shape<T, CB, true, false, 1>(a, slices))
+                   : (kp ? launch_mfma_any_shape<T, CB, true, true, 0>(a, slices) : launch_mfma_any_shape<T, CB, true, false, 0>(a, slices));
+        } else {
+            e = fl == 2 ? (kp ? launch_mfma_any_shape<T, CB, false, true, 2>(a, slices) : launch_mfma_any_shape<T, CB, false, false, 2>(a, slices))
+              : fl == 1 ? (kp ? launch_mfma_any_shape<T, CB, false, true, 1>(a, slices) : launch_mfma_any_shape<T, CB, false, false, 1>(a, slices))
+                        : (kp ? launch_mfma_any_shape<T, CB, false, true, 0>(a, slices) : launch_mfma_any_shape<T, CB, false, false, 0>(a, slices));
+        }
     }
     return e;
 }

@@ -1,6 +1,8 @@
 // One sliced-multiply iteration on the matrix cores for a factor of any shape whose slices start on
 // 16-byte boundaries (P a multiple of 4 floats or 2 doubles; run-time shapes: 20, 48, 80, 96, 100, ...
-// and rectangles) or are at most one chunk long (FLAT below: 13, 22, 33, 50, ...), fp32 and fp64.  P and Q are padded with zeros to multiples of 16 on the way into LDS.
+// and rectangles), are at most one chunk long (FLAT == 1 below: 13, 22, 33, 50, ...) or neither
+// (FLAT == 2: 65, 99, 127, fp64 33, 45, ...), fp32 and fp64.  P and Q are padded with zeros to
+// multiples of 16 on the way into LDS.
 //
 // The contraction of a slice with the factor (Algorithm 1's inner loop) is the dense product
 //     D[q][s] = sum_p F[p][q] * X[s*P + p]
@@ -62,11 +64,17 @@ struct AnyShape {
 
 // (the second launch bound, wavefronts per SIMD, caps the registers: left alone the compiler spends
 // several hundred of them on scheduling freedom and one workgroup fills a compute unit)
-// FLAT: for slices that do not start on 16-byte boundaries (P not a whole number of vectors) and fit
-// one chunk (P <= KT).  The TS slices of a unit are contiguous in memory and the unit starts on a
+// FLAT == 1: for slices that do not start on 16-byte boundaries (P not a whole number of vectors) and
+// fit one chunk (P <= KT).  The TS slices of a unit are contiguous in memory and the unit starts on a
 // 16-byte boundary (TS * P elements per unit), so the unit is fetched as one run of 16-byte vectors and
 // the elements are dealt to their LDS rows one by one (consecutive elements, consecutive banks).
-template <typename T, int CB, bool NARROW, bool KEEP, bool FLAT>
+// FLAT == 2: such slices of several chunks (wide shape only).  A chunk row of a slice then starts
+// anywhere inside a 16-byte vector, so VPR + 1 aligned vectors cover it: that many threads fetch one
+// row (15 rows per pass instead of 16), and every element is written to its LDS column on its own;
+// elements of the vectors that belong to the neighbouring chunk or slice are dropped, columns past the
+// end of the slice are zeroed.  Nothing outside X is read: a vector that would pass its end is fetched
+// element by element.
+template <typename T, int CB, bool NARROW, bool KEEP, int FLAT>
 __global__ __launch_bounds__(ANY_THREADS, (CB >= 5 || (NARROW && sizeof(T) == 8 && CB >= 3) ? 2 : 3))
 void mfma_any_sliced_multiply(const T* __restrict__ Xg, const T* __restrict__ Fg, T* __restrict__ Yg,
                               int64_t K, int P, int Q, int64_t num_slices, int64_t num_units, int f_aligned)
@@ -77,6 +85,12 @@ void mfma_any_sliced_multiply(const T* __restrict__ Xg, const T* __restrict__ Fg
     constexpr int VN = Sh::VN, KT = Sh::KT, ROW = Sh::ROW, QG = Sh::QG, XV = Sh::XV, FVR = Sh::FVR, FV = Sh::FV;
     constexpr int SB = Sh::SB, TS = Sh::TS, RP = Sh::RP;
     constexpr bool GATHER = sizeof(T) == 8 || CB >= 5;  // how the factor chunk is transposed into LDS (below)
+    constexpr bool SKEW = FLAT == 2;
+    constexpr int VPX = Sh::VPR + 1;                   // aligned vectors that cover a chunk row starting anywhere
+    constexpr int RPX = ANY_THREADS / VPX;             // rows per pass of the skewed fetch (the last threads idle)
+    constexpr int XVX = (TS + RPX - 1) / RPX;
+    constexpr int XN = SKEW ? XVX : XV;
+    static_assert(!SKEW || !NARROW, "slices of several chunks take the wide shape");
     extern __shared__ __attribute__((aligned(16))) unsigned char any_lds[];
     T* Xs = reinterpret_cast<T*>(any_lds);            // [TS][ROW]: slice i, chunk element k
     T* Fs = Xs + Sh::X_ELEMS;                          // [QG][ROW]: factor column q (transposed), chunk element k
@@ -87,6 +101,7 @@ void mfma_any_sliced_multiply(const T* __restrict__ Xg, const T* __restrict__ Fg
     const int j = lane % 16, g = lane / 16;            // operand row/column inside a block, k group
     const int q_groups = (Q + QG - 1) / QG;
     const int xrow = tid / Sh::VPR, xcol = (tid % Sh::VPR) * VN;   // fetch duty: column xcol of slices xrow, xrow + RP, ...
+    const int srow = tid / VPX, svec = tid % VPX;      // skewed fetch: vector svec of slices srow, srow + RPX, ...
 
     // A factor of one column group and one chunk is the same LDS content for every unit of this
     // workgroup: it is staged with the first unit only (2048 x 36x36^3 0.700 -> 0.567 ms, 512 x 52x52^3
@@ -96,7 +111,7 @@ void mfma_any_sliced_multiply(const T* __restrict__ Xg, const T* __restrict__ Fg
     // 36x36^3), and a whole factor of several chunks in rows of run-time length, 3-5 % only).
     const bool f_stays = q_groups == 1 && P <= KT;
 
-    if constexpr (FLAT) {
+    if constexpr (FLAT == 1) {
         // elements P .. KT - 1 of every LDS row are read by the products (up to the next multiple of 16)
         // and never written by the unit loop: zeros, once
         const int pad = KT - P;
@@ -125,9 +140,30 @@ void mfma_any_sliced_multiply(const T* __restrict__ Xg, const T* __restrict__ Fg
             // with the other wavefronts' products; further overlap comes from the three workgroups that
             // share a compute unit.  Slices only this unit reads bypass the caches; with several column
             // groups they stay for the neighbouring units.
-            V xr[XV], fr[FV];
+            V xr[XN], fr[FV];
             const T* xsrc = Xg + g0 * P + k0;            // uniform part of the slice addresses
-            if constexpr (FLAT) {
+            if constexpr (SKEW) {
+                const int64_t total = num_slices * P;    // elements of X
+#pragma unroll
+                for (int i = 0; i < XVX; ++i) {
+                    const int row = srow + RPX * i;
+#pragma unroll
+                    for (int k = 0; k < VN; ++k) xr[i][k] = T(0);
+                    if (srow < RPX && row < TS && g0 + row < num_slices) {
+                        const int64_t o = (g0 + row) * P + k0;                        // first element of the chunk row
+                        const int64_t a = (o & ~(int64_t)(VN - 1)) + svec * VN;       // this thread's aligned vector
+                        if (a - o < kt) {                                             // some of it lies inside the chunk row
+                            if (a + VN <= total) {
+                                const V* src = reinterpret_cast<const V*>(Xg + a);
+                                xr[i] = q_groups == 1 ? stream_load(src) : *src;
+                            } else {
+#pragma unroll
+                                for (int k = 0; k < VN; ++k) xr[i][k] = a + k < total ? Xg[a + k] : T(0);
+                            }
+                        }
+                    }
+                }
+            } else if constexpr (FLAT == 1) {
                 // vector v of the unit's TS * P contiguous elements; the last unit may hold fewer slices
                 const int64_t left = (num_slices - g0) * P;
                 const int valid = left < (int64_t)TS * P ? (int)left : TS * P;
@@ -180,7 +216,20 @@ void mfma_any_sliced_multiply(const T* __restrict__ Xg, const T* __restrict__ Fg
                 }
             }
             __syncthreads();                             // the previous chunk (or unit) has been read by everybody
-            if constexpr (FLAT) {
+            if constexpr (SKEW) {
+#pragma unroll
+                for (int i = 0; i < XVX; ++i) {
+                    const int row = srow + RPX * i;
+                    if (srow < RPX && row < TS) {
+                        const int mis = (int)(((g0 + row) * P + k0) & (VN - 1));
+#pragma unroll
+                        for (int k = 0; k < VN; ++k) {
+                            const int col = svec * VN + k - mis;                      // column of the chunk row
+                            if (col >= 0 && col < KT) Xs[row * ROW + col] = col < kt ? xr[i][k] : T(0);
+                        }
+                    }
+                }
+            } else if constexpr (FLAT == 1) {
 #pragma unroll
                 for (int i = 0; i < XV; ++i) {
                     const int e0 = (tid + i * ANY_THREADS) * VN;

@@ -608,11 +608,7 @@ inline km_plan_step build_step(const Problem& pr, const Options& opt, const Vari
 inline bool any_mfma_fits(const Problem& pr, int f, const Options& opt)
 {
     const int P = pr.P[f], Q = pr.Q[f];
-    const int vn = 16 / (int)pr.esize;
     if (!(opt.kernels >> KM_KERNEL_MFMA_ANY & 1)) return false;
-    // slices that do not start on 16-byte boundaries are fetched as one contiguous run per unit, which
-    // needs the whole slice in one LDS chunk (256 bytes)
-    if (P % vn && (size_t)P * pr.esize > 256) return false;
     const int cols = 16 * any_column_blocks(Q);
     const double padded = (double)((P + 15) / 16 * 16) * (double)((Q + cols - 1) / cols * cols);
     return padded <= 3.0 * (double)P * (double)Q;

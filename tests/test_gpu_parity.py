@@ -189,6 +189,17 @@ SMALL_CASES = [
     ("float64", 2, [(27, 27)] * 2),
     ("float64", 301, [(31, 20)]),
     ("float64", 4, [(11, 11)] * 4),
+    # ... and on such slices of several 256-byte chunks (a chunk row starts anywhere inside a 16-byte
+    # vector): ragged last unit, last chunks of 1 to 15 elements, X that ends inside a vector
+    ("float32", 3, [(65, 65)] * 2),
+    ("float32", 1, [(99, 70), (67, 33)]),
+    ("float32", 130, [(127, 20)]),
+    ("float32", 1, [(65, 16)]),
+    ("float32", 7, [(129, 24)]),
+    ("float64", 2, [(33, 33)] * 3),
+    ("float64", 5, [(45, 37), (35, 50)]),
+    ("float64", 200, [(81, 17)]),
+    ("float64", 1, [(33, 16)]),
     # neighbouring runs of different small shapes fused into one launch
     ("float32", 5, [(4, 4)] * 5 + [(2, 2)] * 4),
     ("float32", 3, [(3, 3)] + [(4, 4)] * 2 + [(2, 2)] * 4),

@@ -186,9 +186,9 @@ def test_tuning_options_round_trip():
 
 
 def test_padded_shapes_go_to_the_run_time_shape_mfma_kernel_within_its_padding_limits():
-    """Slices that start on 16-byte boundaries or fit one 256-byte chunk, and a padded product of at most 3x
-    the real one; everything else without a compiled instance stays with the generic kernel.  The
-    narrow shape (slices of up to 128 bytes) takes 256 slices per unit, the wide one 128."""
+    """A padded product of at most 3x the real one, whatever the alignment of the slices; everything else
+    without a compiled instance stays with the generic kernel.  The narrow shape (slices of up to 128
+    bytes) takes 256 slices per unit, the wide one 128."""
     def kernels(dtype, M, shapes):
         return [(s["kernel"], s["tile_slices"]) for s in km.plan(M, [p for p, _ in shapes], [q for _, q in shapes], dtype)]
     any_, gen = km.KM_KERNEL_MFMA_ANY, km.KM_KERNEL_GENERIC
@@ -197,14 +197,14 @@ def test_padded_shapes_go_to_the_run_time_shape_mfma_kernel_within_its_padding_l
     assert kernels("float32", 4096, [(20, 15)] * 3) == [(any_, 256)] * 3          # Q need not be a whole vector
     assert [k for k, _ in kernels("float32", 4096, [(20, 7)] * 4)] == [gen] * 4    # 32*16 / 140 = 3.7
     assert kernels("float32", 4096, [(22, 22)] * 4) == [(any_, 256)] * 4          # slices not 16-byte aligned, but one chunk
-    assert [k for k, _ in kernels("float32", 4096, [(66, 66)] * 3)] == [gen] * 3   # ... and longer than a chunk (264 bytes)
+    assert kernels("float32", 1024, [(66, 66)] * 3) == [(any_, 128)] * 3          # ... or longer than a chunk (264 bytes)
     assert kernels("float64", 4096, [(16, 20)] * 4) == [(any_, 256)] * 4          # 16*32 / 320 = 1.6, 128-byte slices
     assert kernels("float64", 4096, [(26, 26)] * 3) == [(any_, 128)] * 3          # 32*32 / 676 = 1.5
     assert kernels("float64", 4096, [(40, 40)] * 3) == [(any_, 128)] * 3          # 48*48 / 1600 = 1.44
     assert kernels("float64", 4096, [(20, 20)] * 3) == [(any_, 128)] * 3          # 32*32 / 400 = 2.56
     assert [k for k, _ in kernels("float64", 4096, [(6, 50)] * 3)] == [gen] * 3    # 16*64 / 300 = 3.4
     assert kernels("float64", 4096, [(15, 16)] * 4) == [(any_, 256)] * 4          # odd P, 120-byte slices
-    assert [k for k, _ in kernels("float64", 4096, [(33, 33)] * 3)] == [gen] * 3   # odd P, 264-byte slices
+    assert kernels("float64", 4096, [(33, 33)] * 3) == [(any_, 128)] * 3          # odd P, 264-byte slices
 
 
 def test_neighbouring_runs_of_different_small_shapes_are_one_launch_where_an_instance_is_compiled():
@@ -289,9 +289,9 @@ def test_tile_lengths_for_small_problems_and_odd_rows():
 
 def test_generic_launches_cover_slices_times_column_groups():
     """The generic kernel's units of work are 128 slices by 32 factor columns."""
-    st = km.plan(10, [65], [20], "float32")[0]
+    st = km.plan(300, [5], [40], "float32")[0]
     assert st["kernel"] == km.KM_KERNEL_GENERIC
-    assert st["grid"] == -(-10 // 128) * -(-20 // 32)
+    assert st["grid"] == -(-300 // 128) * -(-40 // 32)
     old = km.get_option(km.KM_OPT_KERNELS)
     try:
         km.set_option(km.KM_OPT_KERNELS, 1)              # generic kernel only
