@@ -251,7 +251,11 @@ struct Choice {
 // contiguous in memory, so several of them pass through the stages as one long tile): as many as
 // fit 48 KB of LDS (three and more workgroups per compute unit, see find_variant), within the
 // instance's limit, leaving at least 512 tiles when there are that many rows.
-inline int whole_rows_per_tile(const Variant& c, int64_t s_row, int64_t M, int64_t row_bytes)
+// (the autotuner's finding on 2^6 ... 2^10, 3^5, 4^4, 4^5 and 5^3 with 16 K to 1 M rows: fp32 tiles of
+// 24 KB are 5-20 % faster than tiles of 48 KB, fp64 tiles are best at 48 KB: about 6000 elements either way)
+inline int64_t whole_rows_lds_budget(size_t esize) { return esize == 4 ? 24 * 1024 : 48 * 1024; }
+
+inline int whole_rows_per_tile(const Variant& c, int64_t s_row, int64_t M, int64_t row_bytes, int64_t lds_budget)
 {
     if (!c.flexible || s_row > c.tile_slices / 2 || M < 1024) return 1;   // few rows: one workgroup each
     if (c.P != c.Q) return 1;       // the output rows are collected in the tile's own LDS: same size needed
@@ -260,7 +264,7 @@ inline int whole_rows_per_tile(const Variant& c, int64_t s_row, int64_t M, int64
     if (row_bytes >= 8192 && row_bytes % 16 != 0) return 1;
     int64_t most = c.tile_slices / s_row;
     if (c.lds_per_slice > 0) {
-        const int64_t fit = (48 * 1024) / c.lds_per_slice / s_row;
+        const int64_t fit = lds_budget / c.lds_per_slice / s_row;
         if (fit >= 1 && fit < most) most = fit;
     }
     if (most > M) most = M;
@@ -329,9 +333,9 @@ inline void enumerate_choices(const Variant* table, int count, const Problem& pr
         if (c.max_srow > 0 && s_row > c.max_srow) continue;
         if (c.rows_per_tile > 1 && s_row != c.tile_slices) continue;      // tiles of several rows hold whole rows
         tile_lengths(c, s_row, lens, 5);
-        const int rows = whole_rows_per_tile(c, s_row, pr.M, s_row * pg * (int64_t)pr.esize);
-        if (rows > 1) {                                   // whole rows, several per tile, and half as many
-            for (int r = rows; r >= 2 && r >= rows / 2; r = (r == rows && rows / 2 >= 2) ? rows / 2 : 1) {
+        const int rows = whole_rows_per_tile(c, s_row, pr.M, s_row * pg * (int64_t)pr.esize, 48 * 1024);
+        if (rows > 1) {                                   // whole rows, several per tile, then half and a quarter as many
+            for (int r = rows; r >= 2 && r >= rows / 4; r /= 2) {
                 Choice ch;
                 ch.var = &c;
                 ch.tile_slices = (int)s_row;
@@ -436,7 +440,7 @@ inline Choice find_variant(const Variant* table, int count, const Problem& pr, i
             }
             if (opt.prefer_tile > 0 && opt.prefer_tile <= c.tile_slices && s_row % opt.prefer_tile == 0) cand[2] = opt.prefer_tile;
             // rows much shorter than the tile: whole rows, several per tile
-            rows = whole_rows_per_tile(c, s_row, pr.M, s_row * pg * (int64_t)pr.esize);
+            rows = whole_rows_per_tile(c, s_row, pr.M, s_row * pg * (int64_t)pr.esize, whole_rows_lds_budget(pr.esize));
             if (rows > 1) { cand[0] = (int)s_row; cand[1] = cand[2] = 0; }
         }
         for (int k = 0; k < 3; ++k) {

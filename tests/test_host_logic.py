@@ -283,7 +283,9 @@ def test_tile_lengths_for_small_problems_and_odd_rows():
     first = km.plan(1024, [5] * 7, [5] * 7, "float64")[0]
     assert first["num_factors"] == 3 and first["tile_slices"] == 25       # 200-byte runs, 25 KB tiles
     assert all(st["tile_rows"] == 1 for st in km.plan(1024, [3] * 7, [3] * 7, "float32"))
-    assert all(st["tile_rows"] == 2 for st in km.plan(1526, [4] * 6, [4] * 6, "float32"))
+    assert all(st["tile_rows"] == 1 for st in km.plan(1526, [4] * 6, [4] * 6, "float32"))   # 16 KB rows: fp32 tiles hold 24 KB
+    assert all(24 < st["tile_rows"] * 8 <= 48 for st in km.plan(4096, [4] * 5, [4] * 5, "float64"))   # ... fp64 tiles 48 KB (rows of 8 KB)
+    assert all(st["tile_rows"] == 4 for st in km.plan(4096, [4] * 5, [4] * 5, "float32"))
     assert km.plan(1 << 20, [4] * 4, [4] * 4, "float32")[0]["tile_rows"] > 8
 
 
