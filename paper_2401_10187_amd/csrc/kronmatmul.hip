@@ -41,7 +41,8 @@ namespace km {
 #define KM_MULTI_ROW(T, DT, P, Q, G0, G1, G2, ST, NT) \
     {KM_KERNEL_FUSED, DT, P, Q, G0 + G1 + G2, ST, NT, MultiShape<T, P, Q, G0, G1, G2, ST, NT>::LDS_BYTES, 1, 0, 1, \
      (G0 == 1 && P < 8) ? 1.6f                           /* one tiny factor per LDS pass is instruction-bound */ \
-     : (P == 3 && G0 + G1 + G2 >= 5) ? 1.2f : 1.0f,      /* 3^5 and more elements per slice: long runs need tiles that leave two workgroups per compute unit */ \
+     : (P == 3 && G0 + G1 + G2 >= 5) ? 1.2f              /* 3^5 and more elements per slice: long runs need tiles that leave two workgroups per compute unit */ \
+     : (P == 5 && G0 + G1 + G2 >= 4) ? 1.1f : 1.0f,      /* 62 KB tiles: 5^6 as 3 + 3 factors 7 % faster than as 4 + 2, 5^8 as 4 + 4 still 7 % faster than as 3 + 3 + 2 */ \
      "fused-multi", MultiShape<T, P, Q, G0, G1, G2, ST, NT>::LDS_PER_SLICE, (int)ipow(P, G0), 0, 0, 0, 0, \
      MultiShape<T, P, Q, G0, G1, G2, ST, NT>::LDS_SLACK, {0, 0, 0, 0, 0, 0, 0, 0, 0}},
 #define KM_MIXED_SHAPE(T, P0, Q0, G0, P1, Q1, G1, P2, Q2, G2, ST, NT) MixedShape<T, P0, Q0, G0, P1, Q1, G1, P2, Q2, G2, ST, NT>

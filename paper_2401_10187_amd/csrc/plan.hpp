@@ -85,7 +85,9 @@ inline int64_t tiles_per_wg(int64_t num_tiles, int hint, int64_t factor_elems, i
     // is enough when loading the factor costs a workgroup as much as a tile does (16 x 64x64^3 fp64:
     // 256 workgroups walking 4 tiles each are 28 % faster than 1024 with one tile)
     const bool heavy = (size_t)factor_elems * esize >= 64 * 1024 || lds_bytes > 64 * 1024;
-    const int64_t fewest = heavy ? 512 : (factor_elems >= tile_elems ? 256 : 1024);
+    // (factors of 16 KB and more: with 32x32 factors, whose tiles are as large as the factor too, four
+    // workgroups per unit win again: 4096 x 32x32^2 fp64 0.044 -> 0.027 ms, 16 x 32x32^3 0.014 -> 0.011)
+    const int64_t fewest = heavy ? 512 : ((size_t)factor_elems * esize >= 16 * 1024 && factor_elems >= tile_elems ? 256 : 1024);
     while (t > 1 && num_tiles / t < fewest) t /= 2;
     return t;
 }
@@ -379,15 +381,20 @@ inline void enumerate_choices(const Variant* table, int count, const Problem& pr
 // that fits the shape and still gives the chip enough workgroups wins; failing that, the fitting
 // instance with the most workgroups among those whose output runs are at least 32 bytes.  The tuning
 // options override both.
+inline double launch_cost(const Problem& pr, int64_t k_in, int64_t k_out, const Choice& ch, int generic_P);
+
 inline Choice find_variant(const Variant* table, int count, const Problem& pr, int f, int nf,
                            int64_t k_cur, const Options& opt)
 {
     Choice none;
     int64_t pg, s_row;
     if (!group_shape(pr, f, nf, k_cur, pg, s_row)) return none;
+    int64_t k_out = s_row;
+    for (int i = f - nf + 1; i <= f; ++i) k_out *= pr.Q[i];
 
     const int64_t enough = 2 * 256;
-    Choice first_big, first_tiny, most, wanted;
+    Choice first_big, first_tiny, most, wanted, cheapest;
+    double cheapest_cost = 0;
     int64_t wanted_score = 0;
     for (int v = 0; v < count; ++v) {
         const Variant& c = table[v];
@@ -414,9 +421,11 @@ inline Choice find_variant(const Variant* table, int count, const Problem& pr, i
             // are fetched with 16-byte loads and LDS writes, 5^8 with 100-byte runs in 12 KB tiles is
             // 20 % faster than with 500-byte runs in 62 KB tiles), then the longest tile.
             const int64_t lim = s_row < c.tile_slices ? s_row : c.tile_slices;
-            const int64_t fit = c.lds_per_slice > 0 ? (48 * 1024) / c.lds_per_slice : lim;
             const int64_t row_bytes = s_row * (int64_t)pr.esize;
             const bool alignable = (row_bytes & -row_bytes) >= 32;      // some tile length gives 32-byte aligned runs
+            // (rows of odd length: 40 KB, four workgroups per compute unit; 1024 x 15^4 fp64 in tiles of 15
+            // slices, 27 KB, 0.363 ms, of 25 slices, 45 KB, 0.429)
+            const int64_t fit = c.lds_per_slice > 0 ? ((alignable ? 48 : 40) * 1024) / c.lds_per_slice : lim;
             int64_t best_key[2] = {-1, -1};
             int best_tier = 0;
             for (int64_t d = lim; d >= 1; --d) {
@@ -437,11 +446,23 @@ inline Choice find_variant(const Variant* table, int count, const Problem& pr, i
                 if (tier > 0 && (tier > best_tier || (tier == best_tier && key > best_key[1]))) {
                     best_tier = tier; best_key[1] = key; cand[1] = (int)d;
                 }
+                // ... and the tile length the cost estimate likes best (small problems, see below)
+                if ((busy >= 4 || d == lim) && (c.persistent || (double)wgs * (double)c.threads < 4294967296.0)) {
+                    Choice t;
+                    t.var = &c;
+                    t.tile_slices = (int)d;
+                    t.grid = wgs;
+                    const double tc = launch_cost(pr, k_cur, k_out, t, 0);
+                    if (!cheapest.var || tc < cheapest_cost) { cheapest = t; cheapest_cost = tc; }
+                }
             }
             if (opt.prefer_tile > 0 && opt.prefer_tile <= c.tile_slices && s_row % opt.prefer_tile == 0) cand[2] = opt.prefer_tile;
             // rows much shorter than the tile: whole rows, several per tile
             rows = whole_rows_per_tile(c, s_row, pr.M, s_row * pg * (int64_t)pr.esize, whole_rows_lds_budget(pr.esize));
-            if (rows > 1) { cand[0] = (int)s_row; cand[1] = cand[2] = 0; }
+            if (rows > 1) {
+                cand[0] = (int)s_row; cand[1] = cand[2] = 0;
+                if (cheapest.var == &c) cheapest = Choice();
+            }
         }
         for (int k = 0; k < 3; ++k) {
             if (!cand[k]) continue;
@@ -476,13 +497,19 @@ inline Choice find_variant(const Variant* table, int count, const Problem& pr, i
         }
     }
     if (wanted.var) return wanted;
-    if (first_big.var) return first_big;
-    return first_tiny.var ? first_tiny : most;
+    const Choice base = first_big.var ? first_big : (first_tiny.var ? first_tiny : most);
+    // The rules above are made for launches that fill the chip.  On small problems they would cut a
+    // row into tiles with runs of 16 bytes to reach 512 workgroups, where a hundred workgroups with
+    // decent runs finish sooner (16 rows of 6^6: three launches of two factors in 1296 tiles 0.024 ms,
+    // two of three factors in 144 tiles of 24 slices 0.013): when the cost estimate rates another
+    // tile length of a fitting flexible instance a fifth cheaper than the rules' choice, that one is taken.
+    if (base.var && cheapest.var && cheapest_cost < 0.8 * launch_cost(pr, k_cur, k_out, base, 0)) return cheapest;
+    return base;
 }
 
 // Estimated cost of one launch in "bytes moved at full speed": rows read and written, scaled up for
 // short output runs and for the generic kernel, plus a constant per launch.
-inline double launch_cost(const Problem& pr, int64_t k_in, int64_t k_out, const Choice& ch, int generic_P = 0)
+inline double launch_cost(const Problem& pr, int64_t k_in, int64_t k_out, const Choice& ch, int generic_P)
 {
     const double bytes = (double)pr.M * ((double)k_in + (double)k_out) * (double)pr.esize;
     double slow = ch.any_mfma ? 1.5 : 3.0;               // generic kernel; run-time-shape MFMA kernel

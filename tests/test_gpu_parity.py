@@ -394,7 +394,7 @@ EVERY_INSTANCE = [
     ("float32", 2, [(2, 2)] * 14), ("float64", 2, [(2, 2)] * 13),
     ("float32", 3, [(3, 3)] * 9), ("float64", 3, [(3, 3)] * 9),
     ("float32", 4, [(4, 4)] * 8), ("float64", 4, [(4, 4)] * 7), ("float64", 64, [(4, 4)] * 7),
-    ("float32", 2, [(5, 5)] * 6), ("float64", 2, [(5, 5)] * 6), ("float32", 300, [(5, 5)] * 6),
+    ("float32", 2, [(5, 5)] * 6), ("float64", 2, [(5, 5)] * 6), ("float32", 300, [(5, 5)] * 6), ("float32", 300, [(5, 5)] * 8), ("float32", 300, [(4, 4)] * 7),
     ("float32", 2, [(6, 6)] * 6), ("float64", 2, [(6, 6)] * 6),
     ("float32", 2, [(7, 7)] * 5), ("float64", 2, [(7, 7)] * 5),
     ("float32", 2, [(9, 9)] * 5), ("float64", 2, [(9, 9)] * 4),
