@@ -28,9 +28,12 @@ namespace km {
      sizeof(T) == 8 ? 8192 : 0,    /* fp64: 10-20 % faster than the several-factors-per-pass kernel up to 4096 slices per row, 10 % slower at 32768 */ \
      NT == 1024 ? 8192 : 0},       /* 1024-thread workgroups only from 8192 tiles up: below, the 256-thread instance of the same tile is \
                                       2-5 % faster (128 x 8x8^6 0.110 vs 0.104 ms), above 1-2 % slower (2048 x 8x8^6 1.426 vs 1.454) */
+/* (walk -1, one round of resident workgroups: measured for every single-factor instance; it pays for the
+   shapes named here, e.g. 4096 x 64x64^2 0.100 -> 0.071 ms, 20000 x 64x64^2 0.327 -> 0.275, 1024 x 48x48^3 fp64
+   1.08 -> 1.02, and costs on others: 200000 x 16x16^2 0.148 -> 0.181, 1024 x 64x64^2 fp64 0.038 -> 0.048) */
 #define KM_MFMA_ROW(OP, DT, P, Q, NF, ST, NW, QS) \
     {KM_KERNEL_MFMA, DT, P, Q, NF, ST, NW * 64, MfmaShape<OP, P, Q, NF, ST, NW, QS>::LDS_BYTES, 1, 1, 0, 1.0f, "mfma", \
-     0, 0, 0, 0, (P == 80 || P == 96 || P == 112 || P >= 144) ? -1 : 0 /* walk: one round of resident workgroups */},
+     0, 0, 0, 0, (P == 80 || P == 96 || P == 112 || P >= 144 || (P == 64 && Q == 64 && DT == KM_F32) || (P == 48 && DT == KM_F64)) ? -1 : 0 /* walk: one round of resident workgroups */},
 /* One workgroup per compute unit with the whole output tile staged at once (NPASS == 1): 7-12 % faster
    than two 4-wave workgroups where output rows lie up to 8 KB apart and every compute unit gets 8 tiles
    and more (1024 x 32x32^4: 1.75 -> 1.54 ms per launch); 15 % slower on rows of 32^5 elements (128 KB
