@@ -585,6 +585,15 @@ inline km_plan_step build_step(const Problem& pr, const Options& opt, const Vari
                 // 256 x 112x112^3 49 instead of 32 2.68 -> 2.38, 64 x 144x144^3 27 instead of 32 2.07 -> 1.76)
                 const int64_t resident = 256 * resident_per_cu(*var);
                 tpw = (st.grid + resident - 1) / resident;
+                // ... or up to a third longer walks when that lowers the tiles the busiest compute unit
+                // gets (workgroups on it times walk; 16 x 80x80^3 fp64, 1600 tiles: walks of 3 in 534
+                // workgroups 0.140 ms, walks of 4 in 400 workgroups 0.122)
+                auto busiest = [&](int64_t t) { return (((st.grid + t - 1) / t + 255) / 256) * t; };
+                // (by 5 % at least: fewer workgroups per unit cost more than a tile: 256 x 96x96^3 in 1272
+                // workgroups of 29 tiles 1.59 ms, in 1024 of 36 1.78)
+                const int64_t first = tpw;
+                for (int64_t t = first + 1, last = first + (first + 2) / 3; t <= last; ++t)
+                    if (busiest(t) * 20 <= busiest(tpw) * 19) tpw = t;
                 if (tpw > 4096) tpw = 4096;
                 while (tpw > 1 && st.grid / tpw < 256) --tpw;
             }
