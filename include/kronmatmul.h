@@ -183,7 +183,7 @@ km_status kronmatmul_cost(int M, int N, const int* P, const int* Q, km_dtype dty
  * options called "tuning aid" force the planner's hand and exist for tests and sweeps only: they are
  * not meant to be changed while other threads are making calls.  KM_OPT_KERNELS: bit mask of km_kernel families the planner may use (bit k = family k;
  * the generic family is always allowed; default 55: the shuffle family is off because the LDS-tiled
- * kernels measured faster).  KM_OPT_MAX_FUSE: upper limit on factors per launch (default 12).
+ * kernels measured faster).  KM_OPT_MAX_FUSE: upper limit on factors per launch (1 to 16, default 16).
  * KM_OPT_PROFILE: when 1, every launch is bracketed by HIP events on the caller's stream.
  * KM_OPT_PREFER_TILE / KM_OPT_PREFER_THREADS: tuning aids; when non-zero the planner prefers compiled
  * instances with that tile_slices / workgroup size where one fits the shape (0 = automatic).

@@ -31,21 +31,23 @@ template <int N> struct FactorPtrs { const void* f[N]; };
 // STMAX bounds the tile (LDS, registers, unrolled trip counts); the number of slices actually in a
 // tile, st <= STMAX, is a launch parameter so that one instance serves every row length whose
 // K/P^NF has a divisor in range (rows of 3^7 or 6^7 elements, M = 1 problems, ...).
-template <typename T_, int P0, int Q0, int G0, int P1, int Q1, int G1, int P2, int Q2, int G2, int STMAX_, int NT_>
+// (A fourth super-stage, G3 factors of the third stage's shape, serves rows of P^4 elements that fit
+// LDS whole: one launch instead of two.)
+template <typename T_, int P0, int Q0, int G0, int P1, int Q1, int G1, int P2, int Q2, int G2, int STMAX_, int NT_, int G3 = 0>
 struct MixedShape {
     typedef T_ T;
     static constexpr int STMAX = STMAX_, NT = NT_;
-    static constexpr int NS = (G0 > 0) + (G1 > 0) + (G2 > 0);
-    static constexpr int NF = G0 + G1 + G2;
+    static constexpr int NS = (G0 > 0) + (G1 > 0) + (G2 > 0) + (G3 > 0);
+    static constexpr int NF = G0 + G1 + G2 + G3;
     static constexpr int VN = Vec16<T>::N;
-    static constexpr int g(int j) { return j == 0 ? G0 : (j == 1 ? G1 : G2); }
+    static constexpr int g(int j) { return j == 0 ? G0 : (j == 1 ? G1 : (j == 2 ? G2 : G3)); }
     static constexpr int p(int j) { return j == 0 ? P0 : (j == 1 ? P1 : P2); }      // factor shape of stage j
     static constexpr int q(int j) { return j == 0 ? Q0 : (j == 1 ? Q1 : Q2); }
     static constexpr int done(int j) { return (j > 0 ? G0 : 0) + (j > 1 ? G1 : 0) + (j > 2 ? G2 : 0); }
     static constexpr int pg(int j) { return (int)ipow(p(j), g(j)); }      // elements a thread reads per group
     static constexpr int qg(int j) { return (int)ipow(q(j), g(j)); }      // elements it produces
     static constexpr int qdone(int j) { return (j > 0 ? qg(0) : 1) * (j > 1 ? qg(1) : 1) * (j > 2 ? qg(2) : 1); }   // columns of the stages before j
-    static constexpr int ptodo(int j) { return (j <= 0 ? pg(0) : 1) * (j <= 1 ? pg(1) : 1) * (j <= 2 ? pg(2) : 1); } // elements per slice still to contract
+    static constexpr int ptodo(int j) { return (j <= 0 ? pg(0) : 1) * (j <= 1 ? pg(1) : 1) * (j <= 2 ? pg(2) : 1) * (j <= 3 ? pg(3) : 1); } // elements per slice still to contract
     static constexpr int per_slice(int j) { return ptodo(j) * qdone(j); }   // tile elements per unit of st
     static constexpr int wmax(int j) { return (int)ipow(p(j) > q(j) ? p(j) : q(j), g(j)); }
     static constexpr int qchunk(int j)  // columns of one factor whose elements fit 64 scalar registers
@@ -84,12 +86,12 @@ struct MixedShape {
     // the tile only occupies what its st slices need, so short tiles leave LDS to more workgroups
     static constexpr int LDS_PER_SLICE = lds_elems() / STMAX * (int)sizeof(T);
     static constexpr bool VEC_ROWS = pg(0) % VN == 0;
-    static_assert(G0 > 0 && (G1 > 0 || G2 == 0), "super-stages are filled from the first");
+    static_assert(G0 > 0 && (G1 > 0 || G2 == 0) && (G2 > 0 || G3 == 0), "super-stages are filled from the first");
 };
 
 // every stage with the same factor shape
-template <typename T, int P, int Q, int G0, int G1, int G2, int STMAX, int NT>
-using MultiShape = MixedShape<T, P, Q, G0, P, Q, G1, P, Q, G2, STMAX, NT>;
+template <typename T, int P, int Q, int G0, int G1, int G2, int STMAX, int NT, int G3 = 0>
+using MultiShape = MixedShape<T, P, Q, G0, P, Q, G1, P, Q, G2, STMAX, NT, G3>;
 
 // (KEEP: ordinary instead of non-temporal stores, for output the next launch reads back out of the
 // last-level cache; see out_store.)
@@ -387,6 +389,7 @@ void fused_multi_sliced_multiply(const typename Sh::T* __restrict__ Xg, typename
     multi_stage<Sh, 0, KEEP>(tile, fp, Yrow, s_row, h, st, sr_tile, k_out, rows_here, tile_rows);
     if constexpr (Sh::NS > 1) multi_stage<Sh, 1, KEEP>(tile, fp, Yrow, s_row, h, st, sr_tile, k_out, rows_here, tile_rows);
     if constexpr (Sh::NS > 2) multi_stage<Sh, 2, KEEP>(tile, fp, Yrow, s_row, h, st, sr_tile, k_out, rows_here, tile_rows);
+    if constexpr (Sh::NS > 3) multi_stage<Sh, 3, KEEP>(tile, fp, Yrow, s_row, h, st, sr_tile, k_out, rows_here, tile_rows);
 }
 
 }  // namespace km

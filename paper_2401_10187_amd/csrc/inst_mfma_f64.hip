@@ -7,5 +7,5 @@ namespace km {
 #define KM_Y_KM_F32(...)
 #define KM_Y(OP, DT, P, Q, NF, ST, NW, QS) KM_Y_##DT(OP, P, Q, NF, ST, NW, QS)
 #define KM_NONE(...)
-KM_INSTANCES(KM_NONE, KM_Y, KM_NONE, KM_NONE, KM_NONE, KM_NONE)
+KM_INSTANCES(KM_NONE, KM_Y, KM_NONE, KM_NONE, KM_NONE, KM_NONE, KM_NONE)
 }  // namespace km

@@ -6,5 +6,5 @@ namespace km {
 #define KM_V(T, DT, P0, Q0, G0, P1, Q1, G1, P2, Q2, G2, ST, NT) \
     template hipError_t launch_multi<MixedShape<T, P0, Q0, G0, P1, Q1, G1, P2, Q2, G2, ST, NT>>(const LaunchArgs&);
 #define KM_NONE(...)
-KM_INSTANCES(KM_NONE, KM_NONE, KM_NONE, KM_NONE, KM_NONE, KM_V)
+KM_INSTANCES(KM_NONE, KM_NONE, KM_NONE, KM_NONE, KM_NONE, KM_V, KM_NONE)
 }  // namespace km

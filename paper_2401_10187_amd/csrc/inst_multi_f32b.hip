@@ -23,5 +23,5 @@ namespace km {
 #define KM_W_KM_F64(...)
 #define KM_W(T, DT, P, Q, G0, G1, G2, ST, NT) KM_W_##DT(T, P, Q, G0, G1, G2, ST, NT)
 #define KM_NONE(...)
-KM_INSTANCES(KM_NONE, KM_NONE, KM_NONE, KM_W, KM_NONE, KM_NONE)
+KM_INSTANCES(KM_NONE, KM_NONE, KM_NONE, KM_W, KM_NONE, KM_NONE, KM_NONE)
 }  // namespace km

@@ -6,6 +6,8 @@
 // Register-resident MFMA pairs: Z(P, tile_slices, wavefronts, units fetched ahead, output passes) (fp32, Q = 32, two factors).
 // Small-factor instances with several factors per LDS pass and a run-time tile length:
 // W(type, dtype code, P, Q, G0, G1, G2, largest tile_slices, threads).
+// The same with a fourth super-stage (whole rows of P^4 elements in one launch):
+// U(type, dtype code, P, Q, G0, G1, G2, G3, largest tile_slices, threads).
 // The same for rows of exactly P*P elements, ST rows per tile: R(P, rows per tile, wavefronts).
 // MFMA instances: Y(op, dtype code, P, Q, factors per launch, tile_slices, wavefronts, q split).
 // The same with a factor shape per stage, for neighbouring runs of different small shapes, stages in
@@ -14,7 +16,7 @@
 // behind a row gives the factors in the order of the Kronecker product.  A curated list (neighbouring
 // runs of 2x2, 4x4 and 8x8, 5x5 beside 2x2, 3x3 beside 2x2): a further combination is one more row.
 // Order = preference among instances that fit a shape.
-#define KM_INSTANCES(X, Y, Z, W, R, V)                       \
+#define KM_INSTANCES(X, Y, Z, W, R, V, U)                    \
     X(float, KM_F32, 8, 8, 3, 32, 1024)                 \
     X(float, KM_F32, 8, 8, 3, 32, 256)                  \
     X(float, KM_F32, 8, 8, 3, 16, 256)                  \
@@ -243,4 +245,36 @@
     V(double, KM_F64, 2, 2, 4, 4, 4, 2, 0, 0, 0, 32, 256)  /* 4x4^2, 2x2^4 */ \
     V(double, KM_F64, 4, 4, 2, 2, 2, 4, 0, 0, 0, 32, 256)  /* 2x2^4, 4x4^2 */ \
     V(double, KM_F64, 4, 4, 2, 8, 8, 1, 8, 8, 1, 8, 256)   /* 8x8^2, 4x4^2 */ \
-    V(double, KM_F64, 2, 2, 1, 5, 5, 2, 0, 0, 0, 128, 256) /* 5x5^2, 2x2 */
+    V(double, KM_F64, 2, 2, 1, 5, 5, 2, 0, 0, 0, 128, 256) /* 5x5^2, 2x2 */ \
+    U(float, KM_F32, 13, 13, 1, 1, 1, 1, 1, 1024)       \
+    U(float, KM_F32, 12, 12, 1, 1, 1, 1, 1, 1024)       \
+    U(float, KM_F32, 14, 14, 1, 1, 1, 1, 1, 1024)       \
+    U(float, KM_F32, 11, 11, 1, 1, 1, 1, 1, 512)        \
+    U(float, KM_F32, 10, 10, 1, 1, 1, 1, 1, 512)        \
+    U(float, KM_F32, 9, 9, 1, 1, 1, 1, 1, 256)          \
+    U(double, KM_F64, 11, 11, 1, 1, 1, 1, 1, 1024)      \
+    U(double, KM_F64, 10, 10, 1, 1, 1, 1, 1, 512)       \
+    U(double, KM_F64, 9, 9, 1, 1, 1, 1, 1, 512)         \
+    U(float, KM_F32, 8, 8, 1, 1, 1, 1, 2, 512)          \
+    U(float, KM_F32, 7, 7, 2, 1, 1, 1, 1, 512)          \
+    U(float, KM_F32, 7, 7, 1, 1, 1, 1, 4, 256)          \
+    U(float, KM_F32, 6, 6, 2, 1, 1, 1, 1, 512)          \
+    U(float, KM_F32, 5, 5, 2, 2, 1, 1, 1, 512)          \
+    U(float, KM_F32, 5, 5, 2, 1, 1, 1, 2, 256)          \
+    U(float, KM_F32, 3, 3, 3, 2, 2, 2, 1, 512)          \
+    U(float, KM_F32, 3, 3, 2, 2, 2, 2, 1, 256)          \
+    U(float, KM_F32, 2, 2, 4, 4, 4, 3, 1, 1024)         \
+    U(float, KM_F32, 2, 2, 4, 4, 3, 3, 1, 1024)         \
+    U(float, KM_F32, 2, 2, 4, 3, 3, 3, 1, 512)          \
+    U(double, KM_F64, 8, 8, 1, 1, 1, 1, 1, 512)         \
+    U(double, KM_F64, 7, 7, 2, 1, 1, 1, 1, 512)         \
+    U(double, KM_F64, 7, 7, 1, 1, 1, 1, 2, 256)         \
+    U(double, KM_F64, 6, 6, 2, 1, 1, 1, 1, 512)         \
+    U(double, KM_F64, 6, 6, 1, 1, 1, 1, 4, 256)         \
+    U(double, KM_F64, 5, 5, 2, 2, 1, 1, 1, 1024)        \
+    U(double, KM_F64, 5, 5, 2, 1, 1, 1, 1, 256)         \
+    U(double, KM_F64, 5, 5, 2, 1, 1, 0, 8, 256)         \
+    U(double, KM_F64, 3, 3, 3, 2, 2, 2, 1, 1024)        \
+    U(double, KM_F64, 3, 3, 2, 2, 2, 2, 1, 512)         \
+    U(double, KM_F64, 2, 2, 4, 4, 3, 3, 1, 1024)        \
+    U(double, KM_F64, 2, 2, 4, 3, 3, 3, 1, 512)

@@ -48,6 +48,11 @@ namespace km {
      : (P == 5 && G0 + G1 + G2 >= 4) ? 1.1f : 1.0f,      /* 62 KB tiles: 5^6 as 3 + 3 factors 7 % faster than as 4 + 2, 5^8 as 4 + 4 still 7 % faster than as 3 + 3 + 2 */ \
      "fused-multi", MultiShape<T, P, Q, G0, G1, G2, ST, NT>::LDS_PER_SLICE, (int)ipow(P, G0), 0, 0, 0, 0, \
      MultiShape<T, P, Q, G0, G1, G2, ST, NT>::LDS_SLACK, {0, 0, 0, 0, 0, 0, 0, 0, 0}},
+#define KM_MULTI4_ROW(T, DT, P, Q, G0, G1, G2, G3, ST, NT) \
+    {KM_KERNEL_FUSED, DT, P, Q, G0 + G1 + G2 + G3, ST, NT, MultiShape<T, P, Q, G0, G1, G2, ST, NT, G3>::LDS_BYTES, 1, 0, 1, \
+     1.0f, "fused-multi", MultiShape<T, P, Q, G0, G1, G2, ST, NT, G3>::LDS_PER_SLICE, (int)ipow(P, G0), ST /* whole rows only */, 0, 0, 0, \
+     MultiShape<T, P, Q, G0, G1, G2, ST, NT, G3>::LDS_SLACK, {0, 0, 0, 0, 0, 0, 0, 0, 0}},
+#define KM_MULTI4_FN(T, DT, P, Q, G0, G1, G2, G3, ST, NT) launch_multi<MultiShape<T, P, Q, G0, G1, G2, ST, NT, G3>>,
 #define KM_MIXED_SHAPE(T, P0, Q0, G0, P1, Q1, G1, P2, Q2, G2, ST, NT) MixedShape<T, P0, Q0, G0, P1, Q1, G1, P2, Q2, G2, ST, NT>
 #define KM_MIXED_ROW(T, DT, P0, Q0, G0, P1, Q1, G1, P2, Q2, G2, ST, NT) \
     {KM_KERNEL_FUSED, DT, P0, Q0, G0 + G1 + G2, ST, NT, KM_MIXED_SHAPE(T, P0, Q0, G0, P1, Q1, G1, P2, Q2, G2, ST, NT)::LDS_BYTES, 1, 0, 1, \
@@ -65,10 +70,10 @@ namespace km {
 
 static const Variant g_variants[] = {
     {KM_KERNEL_SHUFFLE, KM_F32, SHF_P, SHF_Q, 1, SHF_ST, SHF_NT, 0, 1, 0, 0, 1.0f, "shuffle"},
-    KM_INSTANCES(KM_FUSED_ROW, KM_MFMA_ROW, KM_PAIR_ROW, KM_MULTI_ROW, KM_ROWS_ROW, KM_MIXED_ROW) };
+    KM_INSTANCES(KM_FUSED_ROW, KM_MFMA_ROW, KM_PAIR_ROW, KM_MULTI_ROW, KM_ROWS_ROW, KM_MIXED_ROW, KM_MULTI4_ROW) };
 static const LaunchFn g_launchers[] = {
     launch_shuffle,
-    KM_INSTANCES(KM_FUSED_FN, KM_MFMA_FN, KM_PAIR_FN, KM_MULTI_FN, KM_ROWS_FN, KM_MIXED_FN) };
+    KM_INSTANCES(KM_FUSED_FN, KM_MFMA_FN, KM_PAIR_FN, KM_MULTI_FN, KM_ROWS_FN, KM_MIXED_FN, KM_MULTI4_FN) };
 static const int g_num_variants = (int)(sizeof(g_variants) / sizeof(g_variants[0]));
 
 template <typename T>

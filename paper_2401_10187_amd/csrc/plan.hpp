@@ -109,7 +109,7 @@ struct Plan {
 
 struct Options {
     int kernels = 0x37;   // bit mask of km_kernel families
-    int max_fuse = 12;
+    int max_fuse = 16;
     int prefer_tile = 0;      // tuning: choose instances with this tile_slices when one fits
     int prefer_threads = 0;   // tuning: ... with this workgroup size
     int tiles_per_wg = 0;     // tuning: tiles per workgroup of persistent instances (0 = automatic)

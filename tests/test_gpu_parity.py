@@ -200,6 +200,13 @@ SMALL_CASES = [
     ("float64", 5, [(45, 37), (35, 50)]),
     ("float64", 200, [(81, 17)]),
     ("float64", 1, [(33, 16)]),
+    # whole short rows in one launch: four super-stages, tiles up to the whole LDS, several rows per tile
+    ("float32", 3, [(2, 2)] * 15),
+    ("float64", 2, [(3, 3)] * 9),
+    ("float32", 2, [(7, 7)] * 5),
+    ("float32", 3, [(14, 14)] * 4),
+    ("float64", 1100, [(5, 5)] * 4),
+    ("float32", 1030, [(7, 7)] * 4),
     # neighbouring runs of different small shapes fused into one launch
     ("float32", 5, [(4, 4)] * 5 + [(2, 2)] * 4),
     ("float32", 3, [(3, 3)] + [(4, 4)] * 2 + [(2, 2)] * 4),
@@ -453,8 +460,20 @@ EVERY_INSTANCE = [
     ("float64", 300, [(6, 6)] * 2 + [(2, 2)] * 4 + [(4, 4)] * 2),
     ("float64", 300, [(6, 6)] * 3 + [(5, 5)] * 2 + [(2, 2)]),
     ("float32", 1100, [(4, 4)] * 2 + [(2, 2)] * 3), ("float32", 1100, [(5, 5)] * 2 + [(2, 2)]), ("float64", 1100, [(5, 5)] * 2 + [(2, 2)]),
+    # whole short rows in one launch (four super-stages)
+    ("float32", 300, [(13, 13)] * 4), ("float32", 300, [(12, 12)] * 4), ("float32", 300, [(14, 14)] * 4),
+    ("float32", 300, [(11, 11)] * 4), ("float32", 300, [(10, 10)] * 4), ("float32", 300, [(9, 9)] * 4),
+    ("float64", 300, [(11, 11)] * 4), ("float64", 300, [(10, 10)] * 4), ("float64", 300, [(9, 9)] * 4),
+    ("float32", 300, [(8, 8)] * 4), ("float32", 300, [(7, 7)] * 5), ("float32", 300, [(7, 7)] * 4),
+    ("float32", 300, [(6, 6)] * 5), ("float32", 300, [(5, 5)] * 6), ("float32", 300, [(5, 5)] * 5),
+    ("float32", 300, [(3, 3)] * 9), ("float32", 300, [(3, 3)] * 8), ("float32", 300, [(2, 2)] * 15),
+    ("float32", 300, [(2, 2)] * 14), ("float32", 300, [(2, 2)] * 13), ("float64", 300, [(8, 8)] * 4),
+    ("float64", 300, [(7, 7)] * 5), ("float64", 300, [(7, 7)] * 4), ("float64", 300, [(6, 6)] * 5),
+    ("float64", 300, [(6, 6)] * 4), ("float64", 300, [(5, 5)] * 6), ("float64", 300, [(5, 5)] * 5),
+    ("float64", 300, [(5, 5)] * 4), ("float64", 300, [(3, 3)] * 9), ("float64", 300, [(3, 3)] * 8),
+    ("float64", 300, [(2, 2)] * 14), ("float64", 300, [(2, 2)] * 13),
 ]
-FUSE_LIMITS = (12, 11, 10, 9, 8, 7, 6, 5, 4, 3, 2, 1)
+FUSE_LIMITS = (16, 15, 14, 13, 12, 11, 10, 9, 8, 7, 6, 5, 4, 3, 2, 1)
 
 
 def test_every_instance_is_reached_by_some_shape_of_the_list():

@@ -272,10 +272,14 @@ def test_tile_lengths_for_small_problems_and_odd_rows():
     old = km.get_option(km.KM_OPT_KERNELS)
     try:
         km.set_option(km.KM_OPT_KERNELS, 7)              # the tiled families, not the whole-row kernel
-        for M, P, n, dtype in ((20, 5, 6, "float32"), (100, 5, 5, "float64")):      # 125 or 25 elements per thread
+        for M, P, n, dtype in ((20, 5, 8, "float32"), (50, 5, 7, "float32"), (100, 5, 7, "float64")):      # 25 or 125 elements per thread
             steps = km.plan(M, [P] * n, [P] * n, dtype)
             assert all(st["tile_slices"] * st["tile_rows"] >= 4 for st in steps if st["num_factors"] >= 2), (M, P, n, steps)
             assert all(st["grid"] >= 96 for st in steps), (M, P, n, steps)
+        # ... unless the whole row fits one tile: one launch, one workgroup per row (20 x 5^6: 0.013 ms, two launches 0.016)
+        for M, P, n, dtype in ((20, 5, 6, "float32"), (100, 5, 5, "float64")):
+            steps = km.plan(M, [P] * n, [P] * n, dtype)
+            assert len(steps) == 1 and steps[0]["grid"] == M, (M, P, n, steps)
     finally:
         km.set_option(km.KM_OPT_KERNELS, old)
     first = km.plan(1024, [5] * 8, [5] * 8, "float32")[0]
