@@ -307,9 +307,7 @@ void fused_multi_sliced_multiply(const typename Sh::T* __restrict__ Xg, typename
     extern __shared__ __attribute__((aligned(16))) unsigned char multi_lds[];
     T* tile = reinterpret_cast<T*>(multi_lds);           // (moved up by a few elements below for unaligned tiles)
 
-    // XCD-aware order: workgroup b runs on XCD b % 8; give each XCD a contiguous range of tiles
-    int64_t t = blockIdx.x;
-    if (num_tiles % 8 == 0) t = (t % 8) * (num_tiles / 8) + t / 8;
+    const int64_t t = xcd_contiguous_tile(blockIdx.x, num_tiles);
     // A tile is `st` slices: a stretch of one row (tile_rows == 1), or tile_rows whole rows, which are
     // contiguous in memory and go through the stages as one long tile; only the final store tells
     // the rows apart.

@@ -42,9 +42,7 @@ void shuffle_sliced_multiply_8x8(const float* __restrict__ Xg, float* __restrict
 {
     constexpr int P = SHF_P, Q = SHF_Q, NT = NT_, R = SHF_R;
     static_assert(NT_ == SHF_NT, "one workgroup size");
-    // XCD-aware order: workgroup b runs on XCD b % 8; give each XCD a contiguous range of tiles
-    int64_t t = blockIdx.x;
-    if (num_tiles % 8 == 0) t = (t % 8) * (num_tiles / 8) + t / 8;
+    const int64_t t = xcd_contiguous_tile(blockIdx.x, num_tiles);
     const int64_t row = t / tiles_per_row;
     const int64_t h = t % tiles_per_row;
     const int64_t S = k_in / P;                            // slices per row; k_out = S * Q = k_in
