@@ -596,6 +596,13 @@ inline km_plan_step build_step(const Problem& pr, const Options& opt, const Vari
                     if (busiest(t) * 20 <= busiest(tpw) * 19) tpw = t;
                 if (tpw > 4096) tpw = 4096;
                 while (tpw > 1 && st.grid / tpw < 256) --tpw;
+            } else if (hint <= 0 && var->walk == 0 && tpw > 1 && !var->xcd_order) {
+                // The other walking instances, by the same measure (17 x 128x128^3 fp64, 8704 tiles: walks of
+                // 16 in 544 workgroups, two or three to a compute unit, 0.626 ms; walks of 17 in 512, two to each)
+                auto busiest = [&](int64_t t) { return (((st.grid + t - 1) / t + 255) / 256) * t; };
+                const int64_t first = tpw;
+                for (int64_t t = first + 1, last = first + (first + 2) / 3; t <= last; ++t)
+                    if (busiest(t) * 20 <= busiest(tpw) * 19) tpw = t;
             }
             const int64_t num_tiles = st.grid;
             st.tiles_per_wg = (int)tpw;
