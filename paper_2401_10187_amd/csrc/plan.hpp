@@ -257,16 +257,23 @@ struct Choice {
 // 24 KB are 5-20 % faster than tiles of 48 KB, fp64 tiles are best at 48 KB: about 6000 elements either way)
 inline int64_t whole_rows_lds_budget(size_t esize) { return esize == 4 ? 24 * 1024 : 48 * 1024; }
 
-inline int whole_rows_per_tile(const Variant& c, int64_t s_row, int64_t M, int64_t row_bytes, int64_t lds_budget)
+inline int whole_rows_per_tile(const Variant& c, int64_t s_row, int64_t M, int64_t row_bytes, int64_t row_out_bytes,
+                               int64_t lds_budget)
 {
     if (!c.flexible || s_row > c.tile_slices / 2 || M < 1024) return 1;   // few rows: one workgroup each
-    if (c.P != c.Q) return 1;       // the output rows are collected in the tile's own LDS: same size needed
     // rows of 8 KB that do not start on 16-byte boundaries are tiles of their own: the joined rows
     // would be stored element by element (1024 rows of 3^7: one row per tile 0.014 ms, two 0.018 ms)
     if (row_bytes >= 8192 && row_bytes % 16 != 0) return 1;
     int64_t most = c.tile_slices / s_row;
     if (c.lds_per_slice > 0) {
         const int64_t fit = lds_budget / c.lds_per_slice / s_row;
+        if (fit < most) most = fit < 1 ? 1 : fit;
+    }
+    // the output rows are collected in the tile's own LDS: where they are longer than the input rows
+    // (Q > P) they set the limit, and the launch asks for their size (build_step)
+    if (row_out_bytes > row_bytes) {
+        const int64_t room = lds_budget < c.lds_bytes ? lds_budget : c.lds_bytes;
+        const int64_t fit = room / row_out_bytes;
         if (fit < most) most = fit < 1 ? 1 : fit;
     }
     if (most > M) most = M;
@@ -327,6 +334,8 @@ inline void enumerate_choices(const Variant* table, int count, const Problem& pr
     out.clear();
     int64_t pg, s_row;
     if (!group_shape(pr, f, nf, k_cur, pg, s_row)) return;
+    int64_t qg_all = 1;
+    for (int i = f - nf + 1; i <= f; ++i) qg_all *= pr.Q[i];
     std::vector<int> lens;
     for (int v = 0; v < count; ++v) {
         const Variant& c = table[v];
@@ -335,7 +344,7 @@ inline void enumerate_choices(const Variant* table, int count, const Problem& pr
         if (c.max_srow > 0 && s_row > c.max_srow) continue;
         if (c.rows_per_tile > 1 && s_row != c.tile_slices) continue;      // tiles of several rows hold whole rows
         tile_lengths(c, s_row, lens, 5);
-        const int rows = whole_rows_per_tile(c, s_row, pr.M, s_row * pg * (int64_t)pr.esize, 48 * 1024);
+        const int rows = whole_rows_per_tile(c, s_row, pr.M, s_row * pg * (int64_t)pr.esize, s_row * qg_all * (int64_t)pr.esize, 48 * 1024);
         if (rows > 1) {                                   // whole rows, several per tile, then half and a quarter as many
             for (int r = rows; r >= 2 && r >= rows / 4; r /= 2) {
                 Choice ch;
@@ -462,7 +471,7 @@ inline Choice find_variant(const Variant* table, int count, const Problem& pr, i
             }
             if (opt.prefer_tile > 0 && opt.prefer_tile <= c.tile_slices && s_row % opt.prefer_tile == 0) cand[2] = opt.prefer_tile;
             // rows much shorter than the tile: whole rows, several per tile
-            rows = whole_rows_per_tile(c, s_row, pr.M, s_row * pg * (int64_t)pr.esize, whole_rows_lds_budget(pr.esize));
+            rows = whole_rows_per_tile(c, s_row, pr.M, s_row * pg * (int64_t)pr.esize, k_out * (int64_t)pr.esize, whole_rows_lds_budget(pr.esize));
             if (rows > 1) {
                 cand[0] = (int)s_row; cand[1] = cand[2] = 0;
                 if (cheapest.var == &c) cheapest = Choice();
@@ -574,6 +583,10 @@ inline km_plan_step build_step(const Problem& pr, const Options& opt, const Vari
         st.block = var->threads;
         st.tile_rows = ch.tile_rows;
         st.lds_bytes = launch_lds_bytes(*var, ch.tile_slices * ch.tile_rows);
+        if (ch.tile_rows > 1) {                           // whole rows: the output rows are collected in LDS too
+            const int64_t out_bytes = ((int64_t)ch.tile_rows * st.k_out * (int64_t)pr.esize + 15) / 16 * 16;
+            if (out_bytes > st.lds_bytes) st.lds_bytes = (int)out_bytes;
+        }
         st.grid = ch.grid;
         if (var->persistent) {
             const int hint = ch.tiles_per_wg > 0 ? ch.tiles_per_wg : opt.tiles_per_wg;

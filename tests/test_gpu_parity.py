@@ -207,6 +207,12 @@ SMALL_CASES = [
     ("float32", 3, [(14, 14)] * 4),
     ("float64", 1100, [(5, 5)] * 4),
     ("float32", 1030, [(7, 7)] * 4),
+    # tiles of several whole rows with rectangular factors: output rows longer or shorter than the input rows
+    ("float32", 1100, [(4, 8)]),
+    ("float32", 1500, [(2, 4)] * 2),
+    ("float32", 1030, [(8, 4)] * 2),
+    ("float32", 2050, [(4, 2)] * 3),
+    ("float32", 1025, [(4, 8)] * 3),
     # neighbouring runs of different small shapes fused into one launch
     ("float32", 5, [(4, 4)] * 5 + [(2, 2)] * 4),
     ("float32", 3, [(3, 3)] + [(4, 4)] * 2 + [(2, 2)] * 4),
