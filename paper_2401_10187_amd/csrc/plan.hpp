@@ -777,7 +777,13 @@ inline km_status make_plan(const Problem& pr, const Options& opt, const Variant*
             const int64_t side_by_side = 256 * per_cu;
             const double rounds = (double)((pr.M + side_by_side - 1) / side_by_side);
             const double per_mac = (few ? 50e-9 : 35e-9) * (pr.esize == 4 ? 1.0 : 1.5);
-            const double seconds = rounds * (2.0e-6 + 0.4e-6 * N + macs / threads * per_mac);
+            // ... and rows that share a compute unit share its LDS bandwidth: about 60 ps per multiply-add
+            // and compute unit, whatever the precision (measured with 7 or 8 rows per unit: 103563 x 6^4
+            // 14.9 us per round, 116508 x 24x24^2 fp64 13.6, 37282 x (9x3, 32x100) 13.2)
+            const int64_t rows_per_cu = per_cu < (pr.M + 255) / 256 ? per_cu : (pr.M + 255) / 256;
+            const double alone = 2.0e-6 + 0.4e-6 * N + macs / threads * per_mac;
+            const double shared = 2.0e-6 + (double)rows_per_cu * macs * 60e-12;
+            const double seconds = rounds * (alone > shared ? alone : shared);
             const double bytes = (double)pr.M * ((double)width[N] + (double)width[0]) * (double)pr.esize;
             double c = seconds * 5e12;
             if (c < 2 * bytes) c = 2 * bytes;
