@@ -781,12 +781,19 @@ inline km_status make_plan(const Problem& pr, const Options& opt, const Variant*
             // and compute unit, whatever the precision (measured with 7 or 8 rows per unit: 103563 x 6^4
             // 14.9 us per round, 116508 x 24x24^2 fp64 13.6, 37282 x (9x3, 32x100) 13.2)
             const int64_t rows_per_cu = per_cu < (pr.M + 255) / 256 ? per_cu : (pr.M + 255) / 256;
-            const double alone = 2.0e-6 + 0.4e-6 * N + macs / threads * per_mac;
+            // (long rows: the loops that load and store a row wait for memory about every 0.45 us per trip
+            // of the workgroup; the first trips are part of the fixed cost.  3355 x (10x5)^4, rows of 10000
+            // floats on 256 threads: 34 us per round where the multiply-adds account for 16)
+            const double trips = (double)(width[N] + width[0]) / threads;
+            const double alone = 2.0e-6 + 0.4e-6 * N + macs / threads * per_mac + (trips > 8 ? (trips - 8) * 0.45e-6 : 0.0);
             const double shared = 2.0e-6 + (double)rows_per_cu * macs * 60e-12;
             const double seconds = rounds * (alone > shared ? alone : shared);
             const double bytes = (double)pr.M * ((double)width[N] + (double)width[0]) * (double)pr.esize;
             double c = seconds * 5e12;
-            if (c < 2 * bytes) c = 2 * bytes;
+            // and its row loads and stores, a short loop without loads in flight ahead, stream at about
+            // 1.1 TB/s over the whole chip at best (13107 x (80x5, 64x2), rows of 20 KB: 0.384 ms, the tiled
+            // plan 0.090; 116508 x (16x13, 36x4) fp64 0.628 against 0.228)
+            if (c < 4.5 * bytes) c = 4.5 * bytes;
             c += 2.5e7;
             if (c < best[N] || force_rows) {
                 km_plan_step one{};
