@@ -781,11 +781,12 @@ inline km_status make_plan(const Problem& pr, const Options& opt, const Variant*
             // and compute unit, whatever the precision (measured with 7 or 8 rows per unit: 103563 x 6^4
             // 14.9 us per round, 116508 x 24x24^2 fp64 13.6, 37282 x (9x3, 32x100) 13.2)
             const int64_t rows_per_cu = per_cu < (pr.M + 255) / 256 ? per_cu : (pr.M + 255) / 256;
-            // (long rows: the loops that load and store a row wait for memory about every 0.45 us per trip
-            // of the workgroup; the first trips are part of the fixed cost.  3355 x (10x5)^4, rows of 10000
-            // floats on 256 threads: 34 us per round where the multiply-adds account for 16)
+            // (long rows: about 0.1 us per trip of the workgroup through the loops that load and store a
+            // row, beyond the first trips, which are part of the fixed cost; it was 0.45 us while the row
+            // loader kept no loads in flight: 3355 x (10x5)^4, rows of 10000 floats on 256 threads, took 34 us
+            // per round where the multiply-adds account for 16, and takes 15.5 now)
             const double trips = (double)(width[N] + width[0]) / threads;
-            const double alone = 2.0e-6 + 0.4e-6 * N + macs / threads * per_mac + (trips > 8 ? (trips - 8) * 0.45e-6 : 0.0);
+            const double alone = 2.0e-6 + 0.4e-6 * N + macs / threads * per_mac + (trips > 8 ? (trips - 8) * 0.1e-6 : 0.0);
             const double shared = 2.0e-6 + (double)rows_per_cu * macs * 60e-12;
             const double seconds = rounds * (alone > shared ? alone : shared);
             const double bytes = (double)pr.M * ((double)width[N] + (double)width[0]) * (double)pr.esize;

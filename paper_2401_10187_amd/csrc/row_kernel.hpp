@@ -59,10 +59,52 @@ void row_sliced_multiply(const T* __restrict__ Xg, T* __restrict__ Yg, const Row
     // latency instead of one per factor.  The code is kept short on purpose (run-time loops, one
     // path for full and partial column blocks): for the small problems this kernel serves, fetching
     // instructions costs as much as executing them.
+    // (Only the first ROW_HEAD_TRIPS trips of a long row are part of that list; the rest, and every
+    // further row of the workgroup, is loaded four trips at a time, loads ahead of the LDS writes.)
+    // Rows that are whole 16-byte vectors (they then start on 16-byte boundaries as X does) are loaded as such.
+    typedef T RowVec __attribute__((ext_vector_type(16 / sizeof(T))));
+    constexpr int VN = 16 / (int)sizeof(T);
+    const bool vec_rows = k_in % VN == 0;
+    auto load_row = [&](const T* src, int from) {
+        if (vec_rows) {
+            const int nv = k_in / VN;
+            for (int v0 = from / VN + tid; v0 < nv; v0 += 4 * ROW_THREADS) {
+                RowVec v[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int vi = v0 + j * ROW_THREADS;
+                    if (vi < nv) v[j] = reinterpret_cast<const RowVec*>(src)[vi];
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int vi = v0 + j * ROW_THREADS;
+                    if (vi < nv)
+#pragma unroll
+                        for (int k = 0; k < VN; ++k) buf0[row_pad(vi * VN + k)] = v[j][k];
+                }
+            }
+            return;
+        }
+        for (int e0 = from + tid; e0 < k_in; e0 += 4 * ROW_THREADS) {
+            T v[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int e = e0 + j * ROW_THREADS;
+                v[j] = e < k_in ? src[e] : T(0);
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int e = e0 + j * ROW_THREADS;
+                if (e < k_in) buf0[row_pad(e)] = v[j];
+            }
+        }
+    };
+    constexpr int ROW_HEAD_TRIPS = 4;
+    const int head = k_in < ROW_HEAD_TRIPS * ROW_THREADS ? k_in : ROW_HEAD_TRIPS * ROW_THREADS;
     int nf = 0;
     for (int i = 0; i < fa.n; ++i) nf += fa.P[i] * fa.Q[i];
     {
-        const int total = nf + (blockIdx.x < M ? k_in : 0);
+        const int total = nf + (blockIdx.x < M ? head : 0);
         const T* src = Xg + (int64_t)blockIdx.x * k_in;
         for (int idx = tid; idx < total; idx += ROW_THREADS) {
             const T* from = src;
@@ -76,12 +118,12 @@ void row_sliced_multiply(const T* __restrict__ Xg, T* __restrict__ Yg, const Row
             if (idx < nf) fbuf[idx] = v;
             else buf0[row_pad(idx - nf)] = v;
         }
+        if (blockIdx.x < M && head < k_in) load_row(src, head);
     }
     for (int64_t row = blockIdx.x; row < M; row += gridDim.x) {
         T* Yrow = Yg + row * k_out;
         if (row != blockIdx.x) {
-            const T* src = Xg + row * k_in;
-            for (int e = tid; e < k_in; e += ROW_THREADS) buf0[row_pad(e)] = src[e];
+            load_row(Xg + row * k_in, 0);
         }
         __syncthreads();                                 // the row (and, the first time, the factors) are in LDS
         T* cur = buf0;
