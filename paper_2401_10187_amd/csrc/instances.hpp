@@ -277,4 +277,15 @@
     U(double, KM_F64, 3, 3, 3, 2, 2, 2, 1, 1024)        \
     U(double, KM_F64, 3, 3, 2, 2, 2, 2, 1, 512)         \
     U(double, KM_F64, 2, 2, 4, 4, 3, 3, 1, 1024)        \
-    U(double, KM_F64, 2, 2, 4, 3, 3, 3, 1, 512)
+    U(double, KM_F64, 2, 2, 4, 3, 3, 3, 1, 512)         \
+    U(float, KM_F32, 6, 6, 1, 1, 1, 1, 4, 256)          \
+    U(float, KM_F32, 11, 11, 1, 1, 1, 0, 4, 256)        \
+    U(float, KM_F32, 12, 12, 1, 1, 1, 0, 3, 256)        \
+    U(float, KM_F32, 13, 13, 1, 1, 1, 0, 2, 256)        \
+    U(float, KM_F32, 14, 14, 1, 1, 1, 0, 2, 256)        \
+    U(float, KM_F32, 15, 15, 1, 1, 1, 0, 1, 256)        \
+    U(double, KM_F64, 11, 11, 1, 1, 1, 0, 4, 256)       \
+    U(double, KM_F64, 12, 12, 1, 1, 1, 0, 3, 256)       \
+    U(double, KM_F64, 13, 13, 1, 1, 1, 0, 2, 256)       \
+    U(double, KM_F64, 14, 14, 1, 1, 1, 0, 2, 256)       \
+    U(double, KM_F64, 15, 15, 1, 1, 1, 0, 1, 256)

@@ -207,6 +207,8 @@ SMALL_CASES = [
     ("float32", 3, [(14, 14)] * 4),
     ("float64", 1100, [(5, 5)] * 4),
     ("float32", 1030, [(7, 7)] * 4),
+    ("float32", 1100, [(11, 11)] * 3),
+    ("float64", 1030, [(12, 12)] * 3),
     # tiles of several whole rows with rectangular factors: output rows longer or shorter than the input rows
     ("float32", 1100, [(4, 8)]),
     ("float32", 1500, [(2, 4)] * 2),
@@ -478,6 +480,10 @@ EVERY_INSTANCE = [
     ("float64", 300, [(6, 6)] * 4), ("float64", 300, [(5, 5)] * 6), ("float64", 300, [(5, 5)] * 5),
     ("float64", 300, [(5, 5)] * 4), ("float64", 300, [(3, 3)] * 9), ("float64", 300, [(3, 3)] * 8),
     ("float64", 300, [(2, 2)] * 14), ("float64", 300, [(2, 2)] * 13),
+    ("float32", 300, [(6, 6)] * 4), ("float32", 300, [(11, 11)] * 3), ("float32", 300, [(12, 12)] * 3),
+    ("float32", 300, [(13, 13)] * 3), ("float32", 300, [(14, 14)] * 3), ("float32", 300, [(15, 15)] * 3),
+    ("float64", 300, [(11, 11)] * 3), ("float64", 300, [(12, 12)] * 3), ("float64", 300, [(13, 13)] * 3),
+    ("float64", 300, [(14, 14)] * 3), ("float64", 300, [(15, 15)] * 3),
 ]
 FUSE_LIMITS = (16, 15, 14, 13, 12, 11, 10, 9, 8, 7, 6, 5, 4, 3, 2, 1)
 
