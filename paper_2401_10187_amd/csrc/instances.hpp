@@ -288,4 +288,12 @@
     U(double, KM_F64, 12, 12, 1, 1, 1, 0, 3, 256)       \
     U(double, KM_F64, 13, 13, 1, 1, 1, 0, 2, 256)       \
     U(double, KM_F64, 14, 14, 1, 1, 1, 0, 2, 256)       \
-    U(double, KM_F64, 15, 15, 1, 1, 1, 0, 1, 256)
+    U(double, KM_F64, 15, 15, 1, 1, 1, 0, 1, 256)       \
+    U(float, KM_F32, 2, 4, 2, 2, 2, 0, 1, 256)          \
+    U(float, KM_F32, 2, 4, 2, 2, 2, 1, 1, 512)          \
+    U(float, KM_F32, 4, 2, 2, 2, 2, 0, 1, 256)          \
+    U(float, KM_F32, 4, 2, 2, 2, 2, 1, 1, 512)          \
+    U(float, KM_F32, 4, 8, 2, 1, 1, 0, 1, 256)          \
+    U(float, KM_F32, 4, 8, 2, 1, 1, 1, 1, 512)          \
+    U(float, KM_F32, 8, 4, 1, 1, 1, 1, 1, 256)          \
+    U(float, KM_F32, 8, 4, 2, 1, 1, 1, 1, 1024)
