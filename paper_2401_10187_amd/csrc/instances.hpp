@@ -222,10 +222,14 @@
     W(float, KM_F32, 8, 4, 1, 0, 0, 1024, 256)          \
     W(double, KM_F64, 2, 4, 2, 2, 0, 8, 256)            \
     W(double, KM_F64, 2, 4, 2, 0, 0, 256, 256)          \
+    W(double, KM_F64, 2, 4, 1, 0, 0, 1024, 256)         \
     W(double, KM_F64, 4, 2, 2, 2, 0, 16, 256)           \
     W(double, KM_F64, 4, 2, 2, 0, 0, 256, 256)          \
+    W(double, KM_F64, 4, 2, 1, 0, 0, 1024, 256)         \
+    W(double, KM_F64, 4, 8, 2, 1, 0, 8, 256)            \
     W(double, KM_F64, 4, 8, 2, 0, 0, 64, 256)           \
     W(double, KM_F64, 4, 8, 1, 0, 0, 512, 256)          \
+    W(double, KM_F64, 8, 4, 1, 1, 1, 8, 256)            \
     W(double, KM_F64, 8, 4, 1, 1, 0, 64, 256)           \
     W(double, KM_F64, 8, 4, 1, 0, 0, 512, 256)          \
     V(float, KM_F32, 2, 2, 4, 4, 4, 3, 4, 4, 2, 1, 256)    /* 4x4^5, 2x2^4 */ \

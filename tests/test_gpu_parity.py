@@ -209,6 +209,7 @@ SMALL_CASES = [
     ("float32", 1030, [(7, 7)] * 4),
     ("float32", 1100, [(11, 11)] * 3),
     ("float32", 3, [(2, 4)] * 7),
+    ("float64", 1100, [(4, 8)] * 3),
     ("float32", 2, [(8, 4)] * 5),
     ("float64", 1030, [(12, 12)] * 3),
     # tiles of several whole rows with rectangular factors: output rows longer or shorter than the input rows
@@ -488,6 +489,7 @@ EVERY_INSTANCE = [
     ("float64", 300, [(14, 14)] * 3), ("float64", 300, [(15, 15)] * 3),
     ("float32", 300, [(2, 4)] * 6), ("float32", 300, [(2, 4)] * 7), ("float32", 300, [(4, 2)] * 6), ("float32", 300, [(4, 2)] * 7),
     ("float32", 300, [(4, 8)] * 4), ("float32", 300, [(4, 8)] * 5), ("float32", 300, [(8, 4)] * 4), ("float32", 300, [(8, 4)] * 5),
+    ("float64", 300, [(2, 4)]), ("float64", 300, [(4, 2)]), ("float64", 300, [(4, 8)] * 3), ("float64", 300, [(8, 4)] * 3),
 ]
 FUSE_LIMITS = (16, 15, 14, 13, 12, 11, 10, 9, 8, 7, 6, 5, 4, 3, 2, 1)
 
