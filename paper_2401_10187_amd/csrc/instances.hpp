@@ -300,4 +300,11 @@
     U(float, KM_F32, 4, 8, 2, 1, 1, 0, 1, 256)          \
     U(float, KM_F32, 4, 8, 2, 1, 1, 1, 1, 512)          \
     U(float, KM_F32, 8, 4, 1, 1, 1, 1, 1, 256)          \
-    U(float, KM_F32, 8, 4, 2, 1, 1, 1, 1, 1024)
+    U(float, KM_F32, 8, 4, 2, 1, 1, 1, 1, 1024)         \
+    U(double, KM_F64, 2, 4, 2, 2, 2, 0, 1, 256)         \
+    U(double, KM_F64, 2, 4, 2, 2, 2, 1, 1, 512)         \
+    U(double, KM_F64, 4, 2, 2, 2, 2, 0, 1, 256)         \
+    U(double, KM_F64, 4, 2, 2, 2, 2, 1, 1, 1024)        \
+    U(double, KM_F64, 4, 8, 2, 1, 1, 0, 1, 256)         \
+    U(double, KM_F64, 4, 8, 2, 1, 1, 1, 1, 1024)        \
+    U(double, KM_F64, 8, 4, 1, 1, 1, 1, 1, 256)

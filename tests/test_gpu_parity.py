@@ -490,6 +490,8 @@ EVERY_INSTANCE = [
     ("float32", 300, [(2, 4)] * 6), ("float32", 300, [(2, 4)] * 7), ("float32", 300, [(4, 2)] * 6), ("float32", 300, [(4, 2)] * 7),
     ("float32", 300, [(4, 8)] * 4), ("float32", 300, [(4, 8)] * 5), ("float32", 300, [(8, 4)] * 4), ("float32", 300, [(8, 4)] * 5),
     ("float64", 300, [(2, 4)]), ("float64", 300, [(4, 2)]), ("float64", 300, [(4, 8)] * 3), ("float64", 300, [(8, 4)] * 3),
+    ("float64", 300, [(2, 4)] * 6), ("float64", 300, [(2, 4)] * 7), ("float64", 300, [(4, 2)] * 6), ("float64", 300, [(4, 2)] * 7),
+    ("float64", 300, [(4, 8)] * 4), ("float64", 300, [(4, 8)] * 5), ("float64", 300, [(8, 4)] * 4),
 ]
 FUSE_LIMITS = (16, 15, 14, 13, 12, 11, 10, 9, 8, 7, 6, 5, 4, 3, 2, 1)
 
